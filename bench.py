@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the SwiftKV prefill hot path on one MI355X.
+
+One "step" = one swiftkv_prefill call over the whole batch of the workload
+(layers 1..l on all prompt tokens, fused KV projection of the later layers,
+last-token tail, logits), inputs resident in HBM.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="8b_l16_b8x2048")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="skip the per-launch HIP events (roofline is then null)")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=256)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as WL
+    from paper_2410_03960_amd import binding as B
+
+    torch.cuda.set_device(0)
+    wl = WL.get_workload(args.workload)
+    sh = wl.shape
+    t0 = time.time()
+    store = WL.WeightStore(sh, wl.seed, device="cuda", keep=True).materialize()
+    dev_w = dict(store._cache)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t0
+    batch = WL.build_batch(wl)
+    T, nseq = batch.n_tokens, batch.n_seqs
+    ctx = B.Context(sh, dev_w, wl.l, wl.g)
+    kvd = B.SWIFTKV_KV_FP8_E4M3 if wl.kv_fp8 else B.SWIFTKV_KV_BF16
+    scale_mode = B.SWIFTKV_SCALE_COMPUTE_ABSMAX
+    cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, sh.n_kv_heads, sh.head_dim, batch.block_tables,
+                      batch.context_lens.tolist(), fp8=wl.kv_fp8, scale_mode=scale_mode)
+    if wl.kv_fp8 and wl.n_decode:
+        # pre-existing contexts: seeded codes under fixed scales
+        cache.scale_mode = B.SWIFTKV_SCALE_USE_GIVEN
+        cache.scales.fill_(0.02)
+        cache.data.random_(0, 0x77, generator=torch.Generator(device="cuda").manual_seed(wl.seed))
+    ws = torch.empty(ctx.workspace_bytes(T, nseq, kvd), dtype=torch.uint8, device="cuda")
+    logits = torch.empty((nseq, sh.vocab), dtype=torch.float32, device="cuda")
+    ids = batch.token_ids.cuda()
+    lens = batch.seq_lens.tolist()
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        ctx.prefill(ids, lens, cache, logits, ws, stream)
+    torch.cuda.synchronize()
+    ctx.set_timing(not args.no_kernel_timing)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.prefill(ids, lens, cache, logits, ws, stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    tok_s = T * args.steps / dt
+    assert torch.isfinite(logits).all(), "non-finite logits"
+
+    gemm_fl, attn_fl = ctx.flops(lens, batch.context_lens.tolist())
+    out = {
+        "metric": "prefill tokens/s, 8B-shape SwiftKV-50%; GEMM MFMA TFLOPS as % of bf16 peak",
+        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "n_seqs": nseq, "n_tokens": T, "l": wl.l, "acrosskv_group": wl.g,
+                   "kv_cache": "fp8_e4m3" if wl.kv_fp8 else "bf16", "n_layers": sh.n_layers,
+                   "hidden": sh.hidden},
+        "executed_tflops": (gemm_fl + attn_fl) / (ms_per_step * 1e-3) / 1e12,
+        "executed_frac_of_bf16_peak": (gemm_fl + attn_fl) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "weight_gen_s": t_gen,
+    }
+
+    roof = None
+    if not args.no_kernel_timing:
+        tim = ctx.get_timing()
+        ctx.set_timing(False)
+        d, qd, kvdim, f = sh.hidden, sh.q_dim, sh.kv_dim, sh.ffn
+        P = (sh.n_layers - wl.l) // wl.g
+        per_launch_flops = {"qkv_gemm": 2.0 * T * d * (qd + 2 * kvdim), "o_gemm": 2.0 * T * d * qd,
+                            "gateup_gemm": 4.0 * T * d * f, "down_gemm": 2.0 * T * d * f,
+                            "fused_kv_gemm": 2.0 * T * d * P * 2 * kvdim,
+                            "attn_prefill": attn_fl / max(wl.l, 1) if wl.l else 0.0}
+        classes, gemm_ms, gemm_flops = {}, 0.0, 0.0
+        for name, (ms, n) in tim.items():
+            ent = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps}
+            if name in per_launch_flops and n:
+                avg_ms = ms / n
+                ent["avg_launch_ms"] = avg_ms
+                ent["tflops"] = per_launch_flops[name] / (avg_ms * 1e-3) / 1e12
+                if name.endswith("_gemm"):
+                    gemm_ms += ms
+                    gemm_flops += per_launch_flops[name] * n
+            classes[name] = ent
+        out["kernel_classes"] = classes
+        if gemm_ms > 0:
+            out["gemm_tflops"] = gemm_flops / (gemm_ms * 1e-3) / 1e12
+            out["gemm_frac_of_bf16_peak"] = out["gemm_tflops"] / PEAK_BF16_TFLOPS
+        dom = max((k for k in classes if k.endswith("_gemm") and "tflops" in classes[k]),
+                  key=lambda k: classes[k]["ms_per_step"], default=None)
+        if dom:
+            roof = {"bound": "mfma", "kernel": f"gemm_kernel ({dom})", "achieved": classes[dom]["tflops"],
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": classes[dom]["tflops"] / PEAK_BF16_TFLOPS,
+                    "avg_launch_ms": classes[dom]["avg_launch_ms"],
+                    "flops_per_launch": per_launch_flops[dom], "traffic": None}
+    out["roofline"] = roof
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, store, ctx, args.cpu_sample_tokens)
+    print(json.dumps(out))
+
+
+def cpu_baseline(wl, store, ctx, n_sample):
+    """Time the CPU oracle (float32, as it stands) on a bounded sample of the same
+    workload: the first `n_sample` tokens of sequence 0 as one prompt, all steps
+    of the path.  Also reports how far the GPU result for that prompt is from it."""
+    import torch
+    import workloads as WL
+    from oracle import swiftkv_oracle as O
+    from paper_2410_03960_amd import binding as B
+    sh = wl.shape
+    full = WL.build_batch(wl)
+    n = min(n_sample, int(full.seq_lens[0]))
+    sub = WL.build_batch(wl, lens=[n], ctx=[0], shuffled=False)
+    sub.token_ids = full.token_ids[:n].clone()
+    host = {}
+
+    def wfn(name, j0=None):
+        key = name if j0 is None else f"{name}.{j0}"
+        if key not in host:
+            host[key] = store.get(name, j0).cpu()
+        return host[key]
+    # bring the needed weights to the host before the clock starts
+    for nm in ("embed", "final_norm", "lm_head"):
+        wfn(nm)
+    leaders = set(j - 1 for j in O.leader_layers(sh.n_layers, wl.l, wl.g))
+    for j in range(sh.n_layers):
+        for nm in ("norm1", "wq", "wo", "norm2", "wgate", "wup", "wdown"):
+            wfn(nm, j)
+        if j < wl.l or j in leaders:
+            wfn("wk", j), wfn("wv", j)
+    osh = O.Shape(sh.n_layers, sh.hidden, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.ffn, sh.vocab,
+                  sh.rope_theta, sh.rms_eps)
+    ocache = O.PagedKVCache(ctx.n_cache_layers, sub.n_blocks, sh.n_kv_heads, sh.head_dim, sub.block_tables,
+                            dtype=torch.float32, fp8=wl.kv_fp8)
+    t0 = time.perf_counter()
+    ologits, _ = O.swiftkv_prefill(osh, wfn, sub.token_ids, [n], [0], wl.l, wl.g, ocache, dtype=torch.float32)
+    dt = time.perf_counter() - t0
+    # same prompt through the HIP path, for a parity figure at this shape
+    cache = B.KVCache(ctx.n_cache_layers, sub.n_blocks, sh.n_kv_heads, sh.head_dim, sub.block_tables, [0],
+                      fp8=wl.kv_fp8)
+    kvd = B.SWIFTKV_KV_FP8_E4M3 if wl.kv_fp8 else B.SWIFTKV_KV_BF16
+    ws = torch.empty(ctx.workspace_bytes(n, 1, kvd), dtype=torch.uint8, device="cuda")
+    logits = torch.empty((1, sh.vocab), dtype=torch.float32, device="cuda")
+    ctx.prefill(sub.token_ids.cuda(), [n], cache, logits, ws)
+    torch.cuda.synchronize()
+    a, b = logits[0].double().cpu(), ologits[0].double()
+    rel = float((a - b).abs().max() / b.abs().max())
+    cos = float((a @ b) / (a.norm() * b.norm()))
+    return {"value": n / dt, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"first {n} tokens of sequence 0 of {wl.name} as one prompt, whole path, float32",
+            "seconds": dt, "gpu_vs_oracle_logits_rel_err": rel, "gpu_vs_oracle_logits_cosine": cos}
+
+
+if __name__ == "__main__":
+    main()

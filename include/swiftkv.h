@@ -1,0 +1,191 @@
+/*
+ * swiftkv.h - C ABI of libswiftkv: the SwiftKV prefill forward pass for a
+ * Llama-style grouped-query decoder on one AMD MI355X (gfx950).
+ *
+ * Method (SwiftKV paper): prompt tokens run decoder layers 1..l in full
+ * (Sec. 3.1); the residual stream after layer l then feeds the K/V projections
+ * of every later layer j > l (Sec. 3.2, Eq. 2: KV_j = W_KV^j x_{l+1}), with
+ * AcrossKV letting the first layer of each group of g consecutive later layers
+ * compute the K/V the whole group shares (Sec. 3.3).  Only the last new token of
+ * each sequence (and decode tokens) continues through layers l+1..L to give
+ * logits (footnote of Sec. 3.2; forward-pass order of Sec. 3.5).  The KV cache
+ * is paged (Sec. 3.5 names PagedAttention) and may be stored as FP8 e4m3
+ * (Appendix B.1 combines SwiftKV with FP8 KV quantisation).
+ *
+ * Conventions for every call
+ *  - "dev" pointers are device (HBM) pointers owned by the caller; "host"
+ *    pointers are ordinary host memory read before the call returns.
+ *  - Nothing is synchronised: all work is enqueued on `stream` (a hipStream_t
+ *    passed as void*, NULL = default stream) and the call returns at once.
+ *  - Return value: SWIFTKV_OK (0) or a negative error; swiftkv_last_error()
+ *    then gives a thread-local message.  Outputs are unspecified after an error.
+ *  - The library never allocates device memory in swiftkv_prefill; it allocates
+ *    a few small tables in swiftkv_create and frees them in swiftkv_destroy.
+ *  - All matrices are bf16, row-major [out_features, in_features].
+ */
+#ifndef SWIFTKV_H
+#define SWIFTKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  SWIFTKV_OK = 0,
+  SWIFTKV_EINVAL = -1, /* bad shape / argument                                */
+  SWIFTKV_ENOSPC = -2, /* workspace or block table too small                  */
+  SWIFTKV_EHIP = -3,   /* HIP runtime failure (message carries the HIP error) */
+  SWIFTKV_EDATA = -4   /* device-side input check failed (token id or block id out of range) */
+};
+
+enum { SWIFTKV_KV_BF16 = 0, SWIFTKV_KV_FP8_E4M3 = 1 };
+enum { SWIFTKV_SCALE_COMPUTE_ABSMAX = 0, SWIFTKV_SCALE_USE_GIVEN = 1 };
+
+#define SWIFTKV_BLOCK_SIZE 16 /* tokens per paged KV block (fixed) */
+
+/* Decoder shape.  Constraints checked by swiftkv_create: head_dim is 64 or
+ * 128; n_q_heads is a multiple of n_kv_heads; n_q_heads*head_dim and
+ * n_kv_heads*head_dim are multiples of 128; hidden and ffn are multiples of 16. */
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  float rope_theta; /* RoPE base; rotate-half pairing (i, i + head_dim/2), no frequency rescaling */
+  float rms_eps;
+} swiftkv_model_cfg;
+
+/* Model weights (Sec. 3.1: W_Q, W_K, W_V; plus the rest of a Llama layer).
+ * Per-layer members are HOST arrays of n_layers dev pointers.  wk/wv of a later
+ * layer that is not the first of its AcrossKV group are never read and may be
+ * NULL (the paper discards them after distillation, Sec. 3.4). */
+typedef struct {
+  const void *embed;          /* dev [vocab, hidden]                      */
+  const void *const *norm1;   /* dev [hidden]   input RMSNorm gain        */
+  const void *const *wq;      /* dev [n_q_heads*head_dim, hidden]         */
+  const void *const *wk;      /* dev [n_kv_heads*head_dim, hidden]        */
+  const void *const *wv;      /* dev [n_kv_heads*head_dim, hidden]        */
+  const void *const *wo;      /* dev [hidden, n_q_heads*head_dim]         */
+  const void *const *norm2;   /* dev [hidden]   post-attention RMSNorm    */
+  const void *const *wgate;   /* dev [ffn, hidden]                        */
+  const void *const *wup;     /* dev [ffn, hidden]                        */
+  const void *const *wdown;   /* dev [hidden, ffn]                        */
+  const void *final_norm;     /* dev [hidden]                             */
+  const void *lm_head;        /* dev [vocab, hidden] (not tied to embed)  */
+} swiftkv_weights;
+
+/* Paged KV cache.  Element (cache layer c, kv in {0=K,1=V}, block, offset,
+ * head, dim) lives at index
+ *   ((((c*2 + kv)*n_blocks + block)*16 + offset)*n_kv_heads + head)*head_dim + dim.
+ * Model layer j (1-based) uses cache layer j-1 for j <= l and
+ * l + (j-l-1)/g for j > l, so n_cache_layers = l + (L-l)/g (Sec. 3.3: one
+ * cache layer per AcrossKV group).  K is stored after RoPE.
+ * FP8 mode stores OCP e4m3fn codes; value = code * scales[c][kv][head]. */
+typedef struct {
+  void *data;                  /* dev, bf16 (2 B) or e4m3 (1 B) elements, layout above     */
+  float *scales;               /* dev [n_cache_layers][2][n_kv_heads] fp32; FP8 only       */
+  const int32_t *block_tables; /* dev [n_seqs][max_blocks_per_seq] physical block ids      */
+  const int32_t *context_lens; /* host [n_seqs] tokens of each sequence already cached     */
+  int32_t n_cache_layers, n_blocks, block_size /* must be 16 */, max_blocks_per_seq;
+  int32_t dtype;               /* SWIFTKV_KV_BF16 | SWIFTKV_KV_FP8_E4M3                     */
+  int32_t scale_mode;          /* FP8: COMPUTE_ABSMAX writes scales = absmax/448 over the
+                                  tokens this call stores; USE_GIVEN reads caller's scales */
+} swiftkv_kv_cache;
+
+typedef struct swiftkv_ctx swiftkv_ctx;
+
+/* Bind a model, the SwiftKV split l (1 <= l <= n_layers: number of layers the
+ * prompt runs in full, Sec. 3.2) and the AcrossKV group size g >= 1 with
+ * (n_layers - l) % g == 0 (Sec. 3.3; 1 = off).  Builds the row-pointer tables
+ * that present [W_Q;W_K;W_V], [W_gate;W_up] and the concatenation of the group
+ * leaders' [W_K;W_V] (the single fused KV GEMM of Eq. 2) as one operand each,
+ * without copying weights.  Allocates a few MB on the current device. */
+int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftkv_weights *w,
+                   int32_t l, int32_t acrosskv_group);
+void swiftkv_destroy(swiftkv_ctx *ctx);
+
+/* Bytes of dev workspace swiftkv_prefill needs for up to max_tokens new tokens
+ * in up to max_seqs sequences with the given cache dtype. */
+size_t swiftkv_workspace_bytes(const swiftkv_ctx *ctx, int64_t max_tokens, int32_t max_seqs,
+                               int32_t kv_dtype);
+
+/* SwiftKV prefill of a packed batch (Sec. 3.2 Eq. 2, Sec. 3.3, Sec. 3.5).
+ *  token_ids  dev  int32 [T]  new tokens, sequence after sequence, T = sum(seq_lens)
+ *  seq_lens   host int32 [n_seqs] new tokens per sequence (>= 1)
+ *  kv         cache descriptor; kv->context_lens[b] cached tokens precede the new ones.
+ *             context 0 with any number of new tokens = prompt prefill; context > 0
+ *             with exactly one new token = decode token; context > 0 with more new
+ *             tokens is rejected (SWIFTKV_EINVAL).
+ *  logits_out dev fp32 [n_seqs, vocab]: logits of the last new token of each sequence.
+ * Writes K/V of all T new tokens into every cache layer (layers <= l from their
+ * own layer input, later cache layers from the layer-l output), then runs the
+ * last token of each sequence through layers l+1..L. */
+int swiftkv_prefill(swiftkv_ctx *ctx, const int32_t *token_ids, const int32_t *seq_lens,
+                    int32_t n_seqs, const swiftkv_kv_cache *kv, float *logits_out,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* The signature step alone (Eq. 2 + AcrossKV): from a given layer-l output
+ * hidden_l (dev bf16 [T, hidden]) compute RMSNorm_j, the fused K/V projection of
+ * all group leaders, RoPE on K and the paged scatter into cache layers l..  */
+int swiftkv_kv_from_hidden(swiftkv_ctx *ctx, const void *hidden_l, const int32_t *seq_lens,
+                           int32_t n_seqs, const swiftkv_kv_cache *kv, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/* Copy out the integer plan of the most recent swiftkv_prefill /
+ * swiftkv_kv_from_hidden that used `workspace` (all dev outputs, any may be NULL):
+ * slot_mapping int64 [T] (= block_table[b][p/16]*16 + p%16), positions int32 [T],
+ * cu_seqlens int32 [n_seqs+1], last_rows int32 [n_seqs].  Synchronises the
+ * stream and returns SWIFTKV_EDATA if the device-side input checks failed. */
+int swiftkv_export_plan(swiftkv_ctx *ctx, const void *workspace, int64_t *slot_mapping,
+                        int32_t *positions, int32_t *cu_seqlens, int32_t *last_rows, void *stream);
+
+/* Copy out the layer-l output (dev bf16 [T, hidden]) left in `workspace` by the
+ * most recent swiftkv_prefill. */
+int swiftkv_export_hidden(swiftkv_ctx *ctx, const void *workspace, void *hidden_out, void *stream);
+
+/* ---- single operations, exposed for kernel-level checks and timing -------- */
+
+/* C[M,N] = A[M,K] * W[N,K]^T, bf16 inputs, fp32 accumulation.  out_f32 != 0
+ * stores fp32, else bf16.  variant: 0 = pick by shape, 1 = 256x256 tile, 2 =
+ * 128x128 tile, 3 = weight-streaming kernel for M <= 80 rows.  All dev. */
+int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K,
+                    int32_t out_f32, int32_t variant, void *stream);
+
+/* Causal grouped-query attention over packed fresh sequences (Sec. 3.1):
+ * q dev bf16 [T, Hq*hd], k, v dev bf16 [T, Hkv*hd] (already rotated), out dev
+ * bf16 [T, Hq*hd]; seq_lens host.  workspace as from swiftkv_op_attention_workspace. */
+int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, void *out,
+                                 const int32_t *seq_lens, int32_t n_seqs, int32_t n_q_heads,
+                                 int32_t n_kv_heads, int32_t head_dim, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+size_t swiftkv_op_attention_workspace(int64_t n_tokens, int32_t n_seqs, int32_t n_kv_heads,
+                                      int32_t head_dim);
+
+/* Saturating round-to-nearest-even fp32 -> OCP e4m3fn of x[i]/scale, dev arrays. */
+int swiftkv_op_fp8_quantize(const float *x, float scale, uint8_t *codes, int64_t n, void *stream);
+
+/* Executed floating-point operations of one prefill call of this ctx (GEMM and
+ * attention parts), for throughput accounting. */
+int swiftkv_flops(const swiftkv_ctx *ctx, const int32_t *seq_lens, const int32_t *context_lens,
+                  int32_t n_seqs, double *gemm_flops, double *attn_flops);
+
+/* Per-kernel-class device time of all swiftkv_prefill calls on this ctx since
+ * timing was last switched on with swiftkv_set_timing(ctx, 1) (which also
+ * clears the totals): HIP events are recorded on each call's stream around
+ * every launch.  Classes:
+ * 0 = QKV GEMM, 1 = O GEMM, 2 = gate/up GEMM, 3 = down GEMM (layers 1..l),
+ * 4 = fused KV GEMM (Eq. 2), 5 = prefill attention, 6 = plan/embed/rstd/KV-commit
+ * kernels, 7 = last-token tail.  ms_out / launches_out are host arrays of 8.
+ * Reading waits for the last recorded event. */
+#define SWIFTKV_N_TIME_CLASSES 8
+int swiftkv_set_timing(swiftkv_ctx *ctx, int32_t enable);
+int swiftkv_get_timing(swiftkv_ctx *ctx, double ms_out[SWIFTKV_N_TIME_CLASSES],
+                       int32_t launches_out[SWIFTKV_N_TIME_CLASSES]);
+
+const char *swiftkv_last_error(void);
+const char *swiftkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWIFTKV_H */

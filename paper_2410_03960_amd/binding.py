@@ -1,0 +1,257 @@
+"""ctypes binding of libswiftkv.so: argument marshalling only.
+
+Function names mirror include/swiftkv.h.  Tensors are PyTorch CUDA tensors used
+purely as device-memory handles (`.data_ptr()`); every step of the computation
+runs inside the HIP library.  Loading fails loudly when the library has not
+been built (`python -m paper_2410_03960_amd.build`); there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libswiftkv.so")
+
+SWIFTKV_OK, SWIFTKV_EINVAL, SWIFTKV_ENOSPC, SWIFTKV_EHIP, SWIFTKV_EDATA = 0, -1, -2, -3, -4
+SWIFTKV_KV_BF16, SWIFTKV_KV_FP8_E4M3 = 0, 1
+SWIFTKV_SCALE_COMPUTE_ABSMAX, SWIFTKV_SCALE_USE_GIVEN = 0, 1
+N_TIME_CLASSES = 8
+TIME_CLASS_NAMES = ("qkv_gemm", "o_gemm", "gateup_gemm", "down_gemm", "fused_kv_gemm",
+                    "attn_prefill", "other", "tail")
+
+EXPORTS = (
+    "swiftkv_create", "swiftkv_destroy", "swiftkv_workspace_bytes", "swiftkv_prefill",
+    "swiftkv_kv_from_hidden", "swiftkv_export_plan", "swiftkv_export_hidden", "swiftkv_op_gemm",
+    "swiftkv_op_attention_prefill", "swiftkv_op_attention_workspace", "swiftkv_op_fp8_quantize",
+    "swiftkv_flops", "swiftkv_set_timing", "swiftkv_get_timing", "swiftkv_last_error",
+    "swiftkv_version",
+)
+
+
+class SwiftKVError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libswiftkv error {code}: {msg}")
+        self.code = code
+
+
+class ModelCfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32),
+                ("vocab", C.c_int32), ("rope_theta", C.c_float), ("rms_eps", C.c_float)]
+
+
+class Weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p)] + \
+        [(n, C.POINTER(C.c_void_p)) for n in ("norm1", "wq", "wk", "wv", "wo", "norm2", "wgate", "wup", "wdown")] + \
+        [("final_norm", C.c_void_p), ("lm_head", C.c_void_p)]
+
+
+class KVCacheDesc(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("scales", C.c_void_p), ("block_tables", C.c_void_p),
+                ("context_lens", C.POINTER(C.c_int32)),
+                ("n_cache_layers", C.c_int32), ("n_blocks", C.c_int32), ("block_size", C.c_int32),
+                ("max_blocks_per_seq", C.c_int32), ("dtype", C.c_int32), ("scale_mode", C.c_int32)]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """dlopen libswiftkv.so (built in-tree); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2410_03960_amd.build` "
+            "(or __graft_entry__.build()); there is no CPU fallback")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.swiftkv_create.argtypes = [C.POINTER(vp), C.POINTER(ModelCfg), C.POINTER(Weights), i32, i32]
+    lib.swiftkv_destroy.argtypes = [vp]
+    lib.swiftkv_destroy.restype = None
+    lib.swiftkv_workspace_bytes.argtypes = [vp, i64, i32, i32]
+    lib.swiftkv_workspace_bytes.restype = C.c_size_t
+    lib.swiftkv_prefill.argtypes = [vp, vp, C.POINTER(i32), i32, C.POINTER(KVCacheDesc), vp, vp, C.c_size_t, vp]
+    lib.swiftkv_kv_from_hidden.argtypes = [vp, vp, C.POINTER(i32), i32, C.POINTER(KVCacheDesc), vp, C.c_size_t, vp]
+    lib.swiftkv_export_plan.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.swiftkv_export_hidden.argtypes = [vp, vp, vp, vp]
+    lib.swiftkv_op_gemm.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp]
+    lib.swiftkv_op_attention_prefill.argtypes = [vp, vp, vp, vp, C.POINTER(i32), i32, i32, i32, i32, vp, C.c_size_t, vp]
+    lib.swiftkv_op_attention_workspace.argtypes = [i64, i32, i32, i32]
+    lib.swiftkv_op_attention_workspace.restype = C.c_size_t
+    lib.swiftkv_op_fp8_quantize.argtypes = [vp, C.c_float, vp, i64, vp]
+    lib.swiftkv_flops.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.swiftkv_set_timing.argtypes = [vp, i32]
+    lib.swiftkv_get_timing.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
+    lib.swiftkv_last_error.restype = C.c_char_p
+    lib.swiftkv_version.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise SwiftKVError(rc, load().swiftkv_last_error().decode())
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def _i32_array(vals: Sequence[int]):
+    return (C.c_int32 * len(vals))(*[int(v) for v in vals])
+
+
+def _dev(t: torch.Tensor, dtype=None) -> int:
+    assert t.is_cuda and t.is_contiguous(), "expected a contiguous CUDA tensor"
+    if dtype is not None:
+        assert t.dtype == dtype, f"expected {dtype}, got {t.dtype}"
+    return t.data_ptr()
+
+
+_PER_LAYER = ("norm1", "wq", "wk", "wv", "wo", "norm2", "wgate", "wup", "wdown")
+
+
+class Context:
+    """swiftkv_create / swiftkv_destroy.  `weights` maps "embed", "final_norm",
+    "lm_head" and "<name>.<layer>" to bf16 CUDA tensors; they must outlive the
+    context (a reference is kept here)."""
+
+    def __init__(self, shape, weights: Dict[str, torch.Tensor], l: int, g: int):
+        lib = load()
+        self.shape, self.l, self.g = shape, l, g
+        self._weights = weights
+        cfg = ModelCfg(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                       shape.ffn, shape.vocab, shape.rope_theta, shape.rms_eps)
+        w = Weights()
+        self._arrays = {}
+        for n in _PER_LAYER:
+            arr = (C.c_void_p * shape.n_layers)()
+            for j in range(shape.n_layers):
+                t = weights.get(f"{n}.{j}")
+                arr[j] = _dev(t, torch.bfloat16) if t is not None else None
+            self._arrays[n] = arr
+            setattr(w, n, C.cast(arr, C.POINTER(C.c_void_p)))
+        w.embed = _dev(weights["embed"], torch.bfloat16)
+        w.final_norm = _dev(weights["final_norm"], torch.bfloat16)
+        w.lm_head = _dev(weights["lm_head"], torch.bfloat16)
+        self._h = C.c_void_p()
+        _check(lib.swiftkv_create(C.byref(self._h), C.byref(cfg), C.byref(w), l, g))
+        self.n_cache_layers = l + (shape.n_layers - l) // g
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load().swiftkv_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- thin wrappers, one per C entry point ----
+    def workspace_bytes(self, max_tokens: int, max_seqs: int, kv_dtype: int = SWIFTKV_KV_BF16) -> int:
+        return int(load().swiftkv_workspace_bytes(self._h, max_tokens, max_seqs, kv_dtype))
+
+    def prefill(self, token_ids: torch.Tensor, seq_lens: Sequence[int], kv: "KVCache", logits_out: torch.Tensor,
+                workspace: torch.Tensor, stream=None):
+        desc = kv.desc()
+        _check(load().swiftkv_prefill(self._h, _dev(token_ids, torch.int32), _i32_array(seq_lens), len(seq_lens),
+                                      C.byref(desc), _dev(logits_out, torch.float32), _dev(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+
+    def kv_from_hidden(self, hidden_l: torch.Tensor, seq_lens: Sequence[int], kv: "KVCache",
+                       workspace: torch.Tensor, stream=None):
+        desc = kv.desc()
+        _check(load().swiftkv_kv_from_hidden(self._h, _dev(hidden_l, torch.bfloat16), _i32_array(seq_lens),
+                                             len(seq_lens), C.byref(desc), _dev(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+
+    def export_plan(self, workspace: torch.Tensor, n_tokens: int, n_seqs: int, stream=None):
+        dev = workspace.device
+        slots = torch.empty(n_tokens, dtype=torch.int64, device=dev)
+        pos = torch.empty(n_tokens, dtype=torch.int32, device=dev)
+        cu = torch.empty(n_seqs + 1, dtype=torch.int32, device=dev)
+        last = torch.empty(n_seqs, dtype=torch.int32, device=dev)
+        _check(load().swiftkv_export_plan(self._h, _dev(workspace), _dev(slots), _dev(pos), _dev(cu), _dev(last),
+                                          _stream_ptr(stream)))
+        return slots, pos, cu, last
+
+    def export_hidden(self, workspace: torch.Tensor, n_tokens: int, stream=None) -> torch.Tensor:
+        out = torch.empty((n_tokens, self.shape.hidden), dtype=torch.bfloat16, device=workspace.device)
+        _check(load().swiftkv_export_hidden(self._h, _dev(workspace), _dev(out), _stream_ptr(stream)))
+        return out
+
+    def flops(self, seq_lens: Sequence[int], context_lens: Sequence[int]):
+        g, a = C.c_double(), C.c_double()
+        _check(load().swiftkv_flops(self._h, _i32_array(seq_lens), _i32_array(context_lens), len(seq_lens),
+                                    C.byref(g), C.byref(a)))
+        return g.value, a.value
+
+    def set_timing(self, enable: bool):
+        _check(load().swiftkv_set_timing(self._h, int(enable)))
+
+    def get_timing(self):
+        ms = (C.c_double * N_TIME_CLASSES)()
+        n = (C.c_int32 * N_TIME_CLASSES)()
+        _check(load().swiftkv_get_timing(self._h, ms, n))
+        return {TIME_CLASS_NAMES[i]: (ms[i], n[i]) for i in range(N_TIME_CLASSES)}
+
+
+class KVCache:
+    """Device memory for a paged cache + its descriptor (swiftkv_kv_cache)."""
+
+    def __init__(self, n_cache_layers: int, n_blocks: int, n_kv_heads: int, head_dim: int,
+                 block_tables: torch.Tensor, context_lens: Sequence[int], fp8: bool = False,
+                 scale_mode: int = SWIFTKV_SCALE_COMPUTE_ABSMAX, device="cuda"):
+        self.fp8 = fp8
+        shape = (n_cache_layers, 2, n_blocks * 16, n_kv_heads, head_dim)
+        self.data = torch.zeros(shape, dtype=torch.uint8 if fp8 else torch.bfloat16, device=device)
+        self.scales = torch.zeros((n_cache_layers, 2, n_kv_heads), dtype=torch.float32, device=device) if fp8 else None
+        self.block_tables = block_tables.to(device=device, dtype=torch.int32).contiguous()
+        self.context_lens = _i32_array(context_lens)
+        self.n_cache_layers, self.n_blocks = n_cache_layers, n_blocks
+        self.scale_mode = scale_mode
+
+    def desc(self) -> KVCacheDesc:
+        return KVCacheDesc(self.data.data_ptr(), self.scales.data_ptr() if self.scales is not None else None,
+                           self.block_tables.data_ptr(), C.cast(self.context_lens, C.POINTER(C.c_int32)),
+                           self.n_cache_layers, self.n_blocks, 16, self.block_tables.shape[1],
+                           SWIFTKV_KV_FP8_E4M3 if self.fp8 else SWIFTKV_KV_BF16, self.scale_mode)
+
+
+def op_gemm(A: torch.Tensor, W: torch.Tensor, out_f32: bool = False, variant: int = 0, stream=None,
+            out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    M, K = A.shape
+    N = W.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device=A.device)
+    _check(load().swiftkv_op_gemm(_dev(A, torch.bfloat16), _dev(W, torch.bfloat16), _dev(out), M, N, K,
+                                  int(out_f32), variant, _stream_ptr(stream)))
+    return out
+
+
+def op_attention_prefill(q, k, v, seq_lens, n_q_heads, n_kv_heads, head_dim, stream=None) -> torch.Tensor:
+    T = q.shape[0]
+    lib = load()
+    nbytes = int(lib.swiftkv_op_attention_workspace(T, len(seq_lens), n_kv_heads, head_dim))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=q.device)
+    out = torch.empty_like(q)
+    _check(lib.swiftkv_op_attention_prefill(_dev(q, torch.bfloat16), _dev(k, torch.bfloat16), _dev(v, torch.bfloat16),
+                                            _dev(out), _i32_array(seq_lens), len(seq_lens), n_q_heads, n_kv_heads,
+                                            head_dim, _dev(ws), nbytes, _stream_ptr(stream)))
+    return out
+
+
+def op_fp8_quantize(x: torch.Tensor, scale: float, stream=None) -> torch.Tensor:
+    codes = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    _check(load().swiftkv_op_fp8_quantize(_dev(x, torch.float32), float(scale), _dev(codes), x.numel(),
+                                          _stream_ptr(stream)))
+    return codes

@@ -1,0 +1,730 @@
+// C ABI of libswiftkv: context, workspace layout, and the stream-ordered driver
+// of the SwiftKV prefill forward pass (layers 1..l on all new tokens, fused KV
+// projection of the later layers from the layer-l output, last-token tail).
+#include "../../include/swiftkv.h"
+#include "common.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                     \
+  do {                                                                                    \
+    hipError_t _e = (expr);                                                               \
+    if (_e != hipSuccess) return fail(SWIFTKV_EHIP, "%s: %s", #expr, hipGetErrorString(_e)); \
+  } while (0)
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+enum TimeClass { TC_QKV = 0, TC_O, TC_GATEUP, TC_DOWN, TC_KV, TC_ATTN, TC_OTHER, TC_TAIL, TC_COUNT };
+
+struct Layout {  // byte offsets into the workspace
+  int64_t T = 0;
+  int32_t B = 0;
+  int64_t vt_ld = 0;
+  int32_t n_qblocks = 0, n_kvtiles = 0, n_dec = 0;
+  size_t err, meta, positions, seq_of, last_rows, slots, cos_sin, h, rstd, q, k, v, o, vt, z, stage, amax;
+  size_t th, ta, tq, to, tz, partial, total;
+  // offsets (in int32 units) inside the meta block copied from the host
+  size_t m_cu, m_ctx, m_qblocks, m_kvtiles, m_dec, m_tail, m_words;
+};
+
+}  // namespace
+
+struct swiftkv_ctx {
+  swiftkv_model_cfg cfg;
+  int32_t l, g, P, C;
+  int device;
+  std::vector<const bf16_t *> norm1, wq, wk, wv, wo, norm2, wgate, wup, wdown;
+  const bf16_t *embed, *final_norm, *lm_head;
+  // device tables
+  void *dev_tables = nullptr;
+  std::vector<const bf16_t *const *> qkv_tab, gu_tab, norm1_tab, norm2_tab;
+  const bf16_t *const *kv_tab = nullptr;
+  const bf16_t *const *kv_gain_tab = nullptr;
+  Layout last;
+  bool have_last = false;
+  // timing
+  bool timing = false;
+  std::vector<hipEvent_t> ev;
+  std::vector<int> ev_class;
+  size_t ev_used = 0;
+};
+
+namespace {
+
+constexpr int MAX_SPLIT = 32;
+
+Layout make_layout(const swiftkv_ctx *c, int64_t T, int32_t B, int64_t vt_ld, int32_t nqb, int32_t nkt,
+                   int32_t ndec, bool fp8) {
+  const swiftkv_model_cfg &m = c->cfg;
+  const int64_t d = m.hidden, qd = (int64_t)m.n_q_heads * m.head_dim, kvd = (int64_t)m.n_kv_heads * m.head_dim;
+  Layout L;
+  L.T = T; L.B = B; L.vt_ld = vt_ld; L.n_qblocks = nqb; L.n_kvtiles = nkt; L.n_dec = ndec;
+  size_t w = 0;
+  L.m_cu = w; w += B + 1;
+  L.m_ctx = w; w += B;
+  w = (w + 3) / 4 * 4;
+  L.m_qblocks = w; w += (size_t)nqb * 8;
+  L.m_kvtiles = w; w += (size_t)nkt * 4;
+  w = (w + 3) / 4 * 4;
+  L.m_dec = w; w += (size_t)ndec * 8;
+  L.m_tail = w; w += (size_t)B * 8;
+  L.m_words = w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  L.err = take(256);
+  L.meta = take(L.m_words * 4);
+  L.positions = take(T * 4);
+  L.seq_of = take(T * 4);
+  L.last_rows = take((size_t)B * 4);
+  L.slots = take(T * 8);
+  L.cos_sin = take(T * (m.head_dim / 2) * 8);
+  L.h = take(T * d * 2);
+  L.rstd = take(T * 4);
+  L.q = take(T * qd * 2);
+  L.k = take(T * kvd * 2);
+  L.v = take(T * kvd * 2);
+  L.o = take(T * qd * 2);
+  L.vt = take((size_t)kvd * vt_ld * 2);
+  L.z = take(T * (int64_t)m.ffn * 2);
+  L.stage = take(fp8 ? T * (int64_t)c->P * 2 * kvd * 2 : 0);
+  L.amax = take(fp8 ? (size_t)c->C * 2 * m.n_kv_heads * 4 : 0);
+  L.th = take((size_t)B * d * 2);
+  L.ta = take((size_t)B * std::max<int64_t>(d, qd) * 2);
+  L.tq = take((size_t)B * qd * 2);
+  L.to = take((size_t)B * qd * 2);
+  L.tz = take((size_t)B * m.ffn * 2);
+  L.partial = take((size_t)std::max(B, ndec) * m.n_q_heads * MAX_SPLIT * (m.head_dim + 2) * 4);
+  L.total = off;
+  return L;
+}
+
+struct Timer {
+  swiftkv_ctx *c;
+  hipStream_t st;
+  void begin(int cls) {
+    if (!c->timing) return;
+    if (c->ev_used + 2 > c->ev.size()) {
+      for (int i = 0; i < 64; ++i) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return;
+        c->ev.push_back(e);
+      }
+    }
+    c->ev_class.push_back(cls);
+    (void)hipEventRecord(c->ev[c->ev_used++], st);
+  }
+  void end() {
+    if (!c->timing || (c->ev_used & 1) == 0) return;
+    (void)hipEventRecord(c->ev[c->ev_used++], st);
+  }
+};
+
+int check_launch(const char *what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(SWIFTKV_EHIP, "launch of %s failed: %s", what, hipGetErrorString(e));
+  return 0;
+}
+
+int pick_split(int rows, int n_kv_heads, int max_keys) {
+  int want = (512 + rows * n_kv_heads - 1) / (rows * n_kv_heads);
+  int cap = std::max(1, max_keys / 64);
+  return std::max(1, std::min({want, cap, MAX_SPLIT}));
+}
+
+struct HostPlan {
+  std::vector<int32_t> meta;
+  int64_t T = 0, vt_ld = 0;
+  int32_t nqb = 0, nkt = 0, ndec = 0, max_keys_dec = 0, max_keys_tail = 0;
+};
+
+// Host side of the plan: cumulative lengths, 128-query blocks (longest first),
+// 64-token KV tiles, the decode rows (sequences with cached context) and the
+// tail rows (last new token of every sequence).
+int build_host_plan(const swiftkv_ctx *c, const int32_t *seq_lens, const int32_t *ctx_lens, int32_t B,
+                    int32_t max_blocks_per_seq, HostPlan &hp, Layout &L, bool fp8) {
+  std::vector<int64_t> cu(B + 1, 0);
+  std::vector<int32_t> vt0(B, -1);
+  int64_t vt_cols = 0;
+  struct QB { int32_t row0, q0, n, seq_row0, vt_col0; };
+  std::vector<QB> qbs;
+  std::vector<int32_t> kvt, dec, tail;
+  for (int b = 0; b < B; ++b) {
+    const int64_t n = seq_lens[b], ctx = ctx_lens ? ctx_lens[b] : 0;
+    if (n < 1) return fail(SWIFTKV_EINVAL, "seq_lens[%d] = %lld must be >= 1", b, (long long)n);
+    if (ctx < 0) return fail(SWIFTKV_EINVAL, "context_lens[%d] is negative", b);
+    if (ctx > 0 && n != 1)
+      return fail(SWIFTKV_EINVAL, "sequence %d has cached context and %lld new tokens; only one is supported", b, (long long)n);
+    if ((ctx + n + SKV_BLOCK - 1) / SKV_BLOCK > max_blocks_per_seq)
+      return fail(SWIFTKV_ENOSPC, "sequence %d needs %lld blocks, block table has %d", b,
+                  (long long)((ctx + n + SKV_BLOCK - 1) / SKV_BLOCK), max_blocks_per_seq);
+    cu[b + 1] = cu[b] + n;
+    if (cu[b + 1] > 0x7fffffff / 2) return fail(SWIFTKV_EINVAL, "too many tokens");
+    const int32_t row0 = (int32_t)cu[b];
+    if (ctx == 0) {
+      vt0[b] = (int32_t)vt_cols;
+      vt_cols += (n + 63) / 64 * 64;
+      for (int64_t q0 = 0; q0 < n; q0 += 128) qbs.push_back({(int32_t)(row0 + q0), (int32_t)q0, (int32_t)n, row0, vt0[b]});
+    } else {
+      dec.insert(dec.end(), {row0, row0, b, (int32_t)(ctx + 1), -1, 0, 0, 0});
+      hp.max_keys_dec = std::max<int32_t>(hp.max_keys_dec, (int32_t)(ctx + 1));
+    }
+    for (int64_t p0 = 0; p0 < n; p0 += 64)
+      kvt.insert(kvt.end(), {(int32_t)(row0 + p0), (int32_t)std::min<int64_t>(64, n - p0), ctx == 0 ? (int32_t)(vt0[b] + p0) : -1, 0});
+    // tail row: q row b of the tail buffer, rotated with the last token's angles
+    tail.insert(tail.end(), {b, b, b, (int32_t)(ctx + n), (int32_t)(cu[b + 1] - 1), 0, 0, 0});
+    hp.max_keys_tail = std::max<int32_t>(hp.max_keys_tail, (int32_t)(ctx + n));
+  }
+  std::stable_sort(qbs.begin(), qbs.end(), [](const QB &a, const QB &b) {
+    return std::min(a.q0 + 128, a.n) > std::min(b.q0 + 128, b.n);
+  });
+  hp.T = cu[B];
+  hp.vt_ld = std::max<int64_t>(vt_cols, 64);
+  hp.nqb = (int32_t)qbs.size();
+  hp.nkt = (int32_t)(kvt.size() / 4);
+  hp.ndec = (int32_t)(dec.size() / 8);
+  L = make_layout(c, hp.T, B, hp.vt_ld, hp.nqb, hp.nkt, hp.ndec, fp8);
+  hp.meta.assign(L.m_words, 0);
+  for (int b = 0; b <= B; ++b) hp.meta[L.m_cu + b] = (int32_t)cu[b];
+  for (int b = 0; b < B; ++b) hp.meta[L.m_ctx + b] = ctx_lens ? ctx_lens[b] : 0;
+  for (size_t i = 0; i < qbs.size(); ++i) {
+    int32_t *q = &hp.meta[L.m_qblocks + i * 8];
+    q[0] = qbs[i].row0; q[1] = qbs[i].q0; q[2] = qbs[i].n; q[3] = qbs[i].seq_row0; q[4] = qbs[i].vt_col0;
+  }
+  std::copy(kvt.begin(), kvt.end(), hp.meta.begin() + L.m_kvtiles);
+  std::copy(dec.begin(), dec.end(), hp.meta.begin() + L.m_dec);
+  std::copy(tail.begin(), tail.end(), hp.meta.begin() + L.m_tail);
+  return 0;
+}
+
+int validate_cache(const swiftkv_ctx *c, const swiftkv_kv_cache *kv) {
+  if (!kv || !kv->data || !kv->block_tables) return fail(SWIFTKV_EINVAL, "kv cache descriptor has null pointers");
+  if (kv->block_size != SKV_BLOCK) return fail(SWIFTKV_EINVAL, "block_size must be 16, got %d", kv->block_size);
+  if (kv->n_cache_layers != c->C)
+    return fail(SWIFTKV_EINVAL, "cache has %d layers, l=%d g=%d needs %d", kv->n_cache_layers, c->l, c->g, c->C);
+  if (kv->n_blocks < 1 || kv->max_blocks_per_seq < 1) return fail(SWIFTKV_EINVAL, "empty block pool or table");
+  if (kv->dtype != SWIFTKV_KV_BF16 && kv->dtype != SWIFTKV_KV_FP8_E4M3) return fail(SWIFTKV_EINVAL, "bad kv dtype");
+  if (kv->dtype == SWIFTKV_KV_FP8_E4M3 && !kv->scales) return fail(SWIFTKV_EINVAL, "FP8 cache needs scales");
+  if (kv->dtype == SWIFTKV_KV_FP8_E4M3 && kv->scale_mode != SWIFTKV_SCALE_COMPUTE_ABSMAX && kv->scale_mode != SWIFTKV_SCALE_USE_GIVEN)
+    return fail(SWIFTKV_EINVAL, "bad scale_mode");
+  return 0;
+}
+
+// everything from the plan up to the cache of layers > l; shared by the two entry points
+struct Run {
+  swiftkv_ctx *c;
+  const swiftkv_kv_cache *kv;
+  unsigned char *ws;
+  Layout L;
+  HostPlan hp;
+  hipStream_t st;
+  bool fp8;
+  size_t esz;                 // cache element bytes
+  int64_t plane, layer_stride;  // elements per K (or V) plane / per cache layer
+
+  template <class T> T *at(size_t off) const { return (T *)(ws + off); }
+  const int32_t *meta(size_t word) const { return at<int32_t>(L.meta) + word; }
+  void *cache_plane(int c_layer, int kvsel) const {
+    return (unsigned char *)kv->data + ((int64_t)c_layer * layer_stride + (int64_t)kvsel * plane) * esz;
+  }
+};
+
+int run_plan(Run &r, const int32_t *token_ids) {
+  swiftkv_ctx *c = r.c;
+  HIP_TRY(hipMemcpyAsync(r.ws + r.L.meta, r.hp.meta.data(), r.hp.meta.size() * 4, hipMemcpyHostToDevice, r.st));
+  launch_fill_u32(r.at<uint32_t>(r.L.err), 0, 1, r.st);
+  if (r.fp8) launch_fill_u32(r.at<uint32_t>(r.L.amax), 0, (int64_t)c->C * 2 * c->cfg.n_kv_heads, r.st);
+  PlanParams pp{};
+  pp.T = (int32_t)r.L.T; pp.B = r.L.B; pp.head_dim = c->cfg.head_dim; pp.n_blocks = r.kv->n_blocks;
+  pp.max_blocks_per_seq = r.kv->max_blocks_per_seq; pp.vocab = c->cfg.vocab; pp.rope_theta = c->cfg.rope_theta;
+  pp.cu_seqlens = r.meta(r.L.m_cu); pp.context_lens = r.meta(r.L.m_ctx); pp.block_tables = r.kv->block_tables;
+  pp.token_ids = token_ids;
+  pp.positions = r.at<int32_t>(r.L.positions); pp.seq_of = r.at<int32_t>(r.L.seq_of);
+  pp.last_rows = r.at<int32_t>(r.L.last_rows); pp.err_flag = r.at<int32_t>(r.L.err);
+  pp.slots = r.at<int64_t>(r.L.slots); pp.cos_sin = r.at<float2>(r.L.cos_sin);
+  launch_plan(pp, r.st);
+  return check_launch("plan");
+}
+
+// Eq. 2 + AcrossKV: one GEMM over the concatenated leader [W_K;W_V] matrices.
+int run_fused_kv(Run &r, const bf16_t *hidden, Timer &tm) {
+  swiftkv_ctx *c = r.c;
+  const swiftkv_model_cfg &m = c->cfg;
+  const int kvd = m.n_kv_heads * m.head_dim;
+  tm.begin(TC_OTHER);
+  launch_rstd(hidden, r.at<float>(r.L.rstd), (int32_t)r.L.T, m.hidden, m.rms_eps, r.st);
+  tm.end();
+  GemmParams g{};
+  g.A = hidden; g.lda = m.hidden; g.M = (int32_t)r.L.T; g.N = c->P * 2 * kvd; g.K = m.hidden;
+  g.wtab = c->kv_tab; g.ldw = m.hidden; g.gain_tab = c->kv_gain_tab; g.gain_seg = 2 * kvd;
+  g.rstd = r.at<float>(r.L.rstd); g.cos_sin = r.at<float2>(r.L.cos_sin);
+  g.head_dim = m.head_dim; g.q_dim = m.n_q_heads * m.head_dim; g.kv_dim = kvd;
+  g.slots = r.at<int64_t>(r.L.slots); g.cache = (bf16_t *)r.kv->data;
+  g.cache_layer_stride = r.layer_stride; g.cache_kv_stride = r.plane; g.first_cache_layer = c->l;
+  if (r.fp8) {
+    g.stage = r.at<bf16_t>(r.L.stage);
+    g.amax = r.kv->scale_mode == SWIFTKV_SCALE_COMPUTE_ABSMAX ? r.at<uint32_t>(r.L.amax) : nullptr;
+  }
+  tm.begin(TC_KV);
+  if (launch_gemm(g, EPI_KV, 0, r.st) != 0) return fail(SWIFTKV_EHIP, "fused KV GEMM launch failed");
+  tm.end();
+  if (int e = check_launch("fused KV GEMM")) return e;
+  if (r.fp8) {
+    tm.begin(TC_OTHER);
+    for (int p = 0; p < c->P; ++p) {
+      const int cl = c->l + p;
+      CommitParams cp{};
+      cp.tiles = (const KVTile *)r.meta(r.L.m_kvtiles); cp.n_tiles = r.L.n_kvtiles;
+      cp.n_kv_heads = m.n_kv_heads; cp.head_dim = m.head_dim;
+      cp.k_src = r.at<bf16_t>(r.L.stage) + (int64_t)p * 2 * kvd; cp.v_src = cp.k_src + kvd; cp.ld_src = g.N;
+      cp.cache_k = r.cache_plane(cl, 0); cp.cache_v = r.cache_plane(cl, 1);
+      cp.slots = r.at<int64_t>(r.L.slots); cp.fp8 = 1;
+      cp.compute_scale = r.kv->scale_mode == SWIFTKV_SCALE_COMPUTE_ABSMAX;
+      cp.amax = r.at<uint32_t>(r.L.amax) + (int64_t)cl * 2 * m.n_kv_heads;
+      cp.scales = r.kv->scales + (int64_t)cl * 2 * m.n_kv_heads;
+      cp.vt = nullptr; cp.writeback = 0;
+      launch_kv_commit(cp, r.st);
+    }
+    tm.end();
+    if (int e = check_launch("fp8 KV commit")) return e;
+  }
+  return 0;
+}
+
+int tail_gemm(const swiftkv_ctx *c, const bf16_t *A, int M, int N, int K, const bf16_t *W, const bf16_t *W2,
+              const bf16_t *const *gu_tab, void *C, int epi, hipStream_t st) {
+  if (M <= 80) {
+    SkinnyParams s{A, M, N, K, W, W2, C};
+    return launch_skinny(s, epi, st);
+  }
+  GemmParams g{};
+  g.A = A; g.lda = K; g.M = M; g.K = K; g.ldw = K; g.C = C;
+  if (epi == EPI_SWIGLU) { g.wtab = gu_tab; g.N = 2 * N; g.ldc = N; }
+  else { g.W = W; g.N = N; g.ldc = N; }
+  (void)c;
+  return launch_gemm(g, epi, 2, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *swiftkv_last_error(void) { return g_err; }
+const char *swiftkv_version(void) { return "swiftkv-gfx950 0.1"; }
+
+int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftkv_weights *w, int32_t l, int32_t g) {
+  if (!out || !cfg || !w) return fail(SWIFTKV_EINVAL, "null argument");
+  *out = nullptr;
+  const swiftkv_model_cfg &m = *cfg;
+  if (m.n_layers < 1 || m.hidden < 16 || m.n_q_heads < 1 || m.n_kv_heads < 1 || m.ffn < 16 || m.vocab < 16)
+    return fail(SWIFTKV_EINVAL, "bad model shape");
+  if (m.head_dim != 64 && m.head_dim != 128) return fail(SWIFTKV_EINVAL, "head_dim must be 64 or 128, got %d", m.head_dim);
+  if (m.n_q_heads % m.n_kv_heads) return fail(SWIFTKV_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
+  const int R = m.n_q_heads / m.n_kv_heads;
+  if (R != 1 && R != 2 && R != 4 && R != 8) return fail(SWIFTKV_EINVAL, "query heads per KV head must be 1, 2, 4 or 8");
+  const int qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
+  if (qd % 128 || kvd % 128) return fail(SWIFTKV_EINVAL, "n_heads*head_dim must be multiples of 128");
+  if (m.hidden % 16 || m.ffn % 16 || m.vocab % 16) return fail(SWIFTKV_EINVAL, "hidden, ffn and vocab must be multiples of 16");
+  if (l < 1 || l > m.n_layers) return fail(SWIFTKV_EINVAL, "l = %d outside [1, %d]", l, m.n_layers);
+  if (g < 1 || (m.n_layers - l) % g) return fail(SWIFTKV_EINVAL, "(n_layers - l) = %d is not divisible by acrosskv_group = %d", m.n_layers - l, g);
+  if (!w->embed || !w->final_norm || !w->lm_head || !w->norm1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->norm2 ||
+      !w->wgate || !w->wup || !w->wdown)
+    return fail(SWIFTKV_EINVAL, "null weight array");
+  swiftkv_ctx *c = new swiftkv_ctx();
+  c->cfg = m; c->l = l; c->g = g; c->P = (m.n_layers - l) / g; c->C = l + c->P;
+  c->embed = (const bf16_t *)w->embed; c->final_norm = (const bf16_t *)w->final_norm; c->lm_head = (const bf16_t *)w->lm_head;
+  auto grab = [&](std::vector<const bf16_t *> &v, const void *const *src) {
+    v.resize(m.n_layers);
+    for (int j = 0; j < m.n_layers; ++j) v[j] = (const bf16_t *)src[j];
+  };
+  grab(c->norm1, w->norm1); grab(c->wq, w->wq); grab(c->wk, w->wk); grab(c->wv, w->wv); grab(c->wo, w->wo);
+  grab(c->norm2, w->norm2); grab(c->wgate, w->wgate); grab(c->wup, w->wup); grab(c->wdown, w->wdown);
+  for (int j = 0; j < m.n_layers; ++j) {
+    const bool need_kv = j < l || ((j - l) % g == 0);
+    if (!c->norm1[j] || !c->wq[j] || !c->wo[j] || !c->norm2[j] || !c->wgate[j] || !c->wup[j] || !c->wdown[j] ||
+        (need_kv && (!c->wk[j] || !c->wv[j]))) {
+      delete c;
+      return fail(SWIFTKV_EINVAL, "layer %d has a null weight pointer", j);
+    }
+  }
+  // ---- row-block pointer tables (16 rows per entry) ----
+  std::vector<const bf16_t *> tab;
+  std::vector<size_t> off_qkv(m.n_layers), off_gu(m.n_layers), off_n1(m.n_layers), off_n2(m.n_layers);
+  const int64_t d = m.hidden;
+  for (int j = 0; j < m.n_layers; ++j) {
+    off_qkv[j] = tab.size();
+    for (int r = 0; r < qd; r += 16) tab.push_back(c->wq[j] + (int64_t)r * d);
+    for (int r = 0; r < kvd; r += 16) tab.push_back(c->wk[j] ? c->wk[j] + (int64_t)r * d : nullptr);
+    for (int r = 0; r < kvd; r += 16) tab.push_back(c->wv[j] ? c->wv[j] + (int64_t)r * d : nullptr);
+    off_gu[j] = tab.size();
+    for (int r = 0; r < m.ffn; r += 16) {
+      tab.push_back(c->wgate[j] + (int64_t)r * d);
+      tab.push_back(c->wup[j] + (int64_t)r * d);
+    }
+    off_n1[j] = tab.size(); tab.push_back(c->norm1[j]);
+    off_n2[j] = tab.size(); tab.push_back(c->norm2[j]);
+  }
+  const size_t off_kv = tab.size();
+  for (int p = 0; p < c->P; ++p) {
+    const int j = l + p * g;
+    for (int r = 0; r < kvd; r += 16) tab.push_back(c->wk[j] + (int64_t)r * d);
+    for (int r = 0; r < kvd; r += 16) tab.push_back(c->wv[j] + (int64_t)r * d);
+  }
+  const size_t off_kvg = tab.size();
+  for (int p = 0; p < c->P; ++p) tab.push_back(c->norm1[l + p * g]);
+  tab.push_back(nullptr);
+  hipError_t e = hipGetDevice(&c->device);
+  if (e == hipSuccess) e = hipMalloc(&c->dev_tables, tab.size() * sizeof(void *));
+  if (e == hipSuccess) e = hipMemcpy(c->dev_tables, tab.data(), tab.size() * sizeof(void *), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    if (c->dev_tables) (void)hipFree(c->dev_tables);
+    delete c;
+    return fail(SWIFTKV_EHIP, "building weight tables: %s", hipGetErrorString(e));
+  }
+  const bf16_t *const *base = (const bf16_t *const *)c->dev_tables;
+  c->qkv_tab.resize(m.n_layers); c->gu_tab.resize(m.n_layers); c->norm1_tab.resize(m.n_layers); c->norm2_tab.resize(m.n_layers);
+  for (int j = 0; j < m.n_layers; ++j) {
+    c->qkv_tab[j] = base + off_qkv[j]; c->gu_tab[j] = base + off_gu[j];
+    c->norm1_tab[j] = base + off_n1[j]; c->norm2_tab[j] = base + off_n2[j];
+  }
+  c->kv_tab = base + off_kv;
+  c->kv_gain_tab = base + off_kvg;
+  *out = c;
+  return SWIFTKV_OK;
+}
+
+void swiftkv_destroy(swiftkv_ctx *c) {
+  if (!c) return;
+  if (c->dev_tables) (void)hipFree(c->dev_tables);
+  for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+  delete c;
+}
+
+size_t swiftkv_workspace_bytes(const swiftkv_ctx *c, int64_t max_tokens, int32_t max_seqs, int32_t kv_dtype) {
+  if (!c || max_tokens < 1 || max_seqs < 1) return 0;
+  const int64_t vt_ld = max_tokens + 64LL * max_seqs;
+  const int32_t nqb = (int32_t)(max_tokens / 128 + max_seqs), nkt = (int32_t)(max_tokens / 64 + max_seqs);
+  Layout L = make_layout(c, max_tokens, max_seqs, vt_ld, nqb, nkt, max_seqs, kv_dtype == SWIFTKV_KV_FP8_E4M3);
+  return L.total + 4096;
+}
+
+int swiftkv_set_timing(swiftkv_ctx *c, int32_t enable) {
+  if (!c) return fail(SWIFTKV_EINVAL, "null ctx");
+  c->timing = enable != 0;
+  c->ev_used = 0;          // (re)start accumulating
+  c->ev_class.clear();
+  return SWIFTKV_OK;
+}
+
+int swiftkv_get_timing(swiftkv_ctx *c, double ms_out[8], int32_t launches_out[8]) {
+  if (!c || !ms_out || !launches_out) return fail(SWIFTKV_EINVAL, "null argument");
+  for (int i = 0; i < TC_COUNT; ++i) { ms_out[i] = 0; launches_out[i] = 0; }
+  if (c->ev_used == 0) return SWIFTKV_OK;
+  HIP_TRY(hipEventSynchronize(c->ev[c->ev_used - 1]));
+  for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, c->ev[i], c->ev[i + 1]));
+    ms_out[c->ev_class[i / 2]] += ms;
+    launches_out[c->ev_class[i / 2]] += 1;
+  }
+  return SWIFTKV_OK;
+}
+
+int swiftkv_flops(const swiftkv_ctx *c, const int32_t *seq_lens, const int32_t *ctx_lens, int32_t B, double *gemm, double *attn) {
+  if (!c || !seq_lens || !gemm || !attn) return fail(SWIFTKV_EINVAL, "null argument");
+  const swiftkv_model_cfg &m = c->cfg;
+  const double d = m.hidden, qd = (double)m.n_q_heads * m.head_dim, kvd = (double)m.n_kv_heads * m.head_dim;
+  const double layer = 2 * d * (qd + 2 * kvd) + 2 * d * qd + 6 * d * m.ffn;
+  double T = 0, a = 0;
+  for (int b = 0; b < B; ++b) {
+    const double n = seq_lens[b], ctx = ctx_lens ? ctx_lens[b] : 0;
+    T += n;
+    a += c->l * 4 * qd * (n * ctx + n * (n + 1) / 2);
+    a += (m.n_layers - c->l) * 4 * qd * (ctx + n);
+  }
+  *gemm = T * (c->l * layer + c->P * 2 * d * 2 * kvd) + B * ((m.n_layers - c->l) * (4 * d * qd + 6 * d * m.ffn) + 2 * d * m.vocab);
+  *attn = a;
+  return SWIFTKV_OK;
+}
+
+static int setup_run(Run &r, swiftkv_ctx *c, const int32_t *seq_lens, int32_t B, const swiftkv_kv_cache *kv,
+                     void *workspace, size_t workspace_bytes, void *stream) {
+  if (!c || !seq_lens || !workspace) return fail(SWIFTKV_EINVAL, "null argument");
+  if (B < 1) return fail(SWIFTKV_EINVAL, "n_seqs must be >= 1");
+  if (int e = validate_cache(c, kv)) return e;
+  r.c = c; r.kv = kv; r.ws = (unsigned char *)workspace; r.st = (hipStream_t)stream;
+  r.fp8 = kv->dtype == SWIFTKV_KV_FP8_E4M3;
+  r.esz = r.fp8 ? 1 : 2;
+  r.plane = (int64_t)kv->n_blocks * SKV_BLOCK * c->cfg.n_kv_heads * c->cfg.head_dim;
+  r.layer_stride = 2 * r.plane;
+  if (int e = build_host_plan(c, seq_lens, kv->context_lens, B, kv->max_blocks_per_seq, r.hp, r.L, r.fp8)) return e;
+  if (r.L.total > workspace_bytes)
+    return fail(SWIFTKV_ENOSPC, "workspace has %zu bytes, %zu needed", workspace_bytes, r.L.total);
+  if (((uintptr_t)workspace & 255) != 0) return fail(SWIFTKV_EINVAL, "workspace must be 256-byte aligned");
+  return 0;
+}
+
+int swiftkv_kv_from_hidden(swiftkv_ctx *c, const void *hidden_l, const int32_t *seq_lens, int32_t B,
+                           const swiftkv_kv_cache *kv, void *workspace, size_t workspace_bytes, void *stream) {
+  Run r;
+  if (int e = setup_run(r, c, seq_lens, B, kv, workspace, workspace_bytes, stream)) return e;
+  if (!hidden_l) return fail(SWIFTKV_EINVAL, "null hidden_l");
+  if (c->P == 0) return fail(SWIFTKV_EINVAL, "l == n_layers: there are no later layers to project for");
+  if (int e = run_plan(r, nullptr)) return e;
+  Timer tm{c, r.st};
+  if (int e = run_fused_kv(r, (const bf16_t *)hidden_l, tm)) return e;
+  c->last = r.L; c->have_last = true;
+  return SWIFTKV_OK;
+}
+
+int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq_lens, int32_t B,
+                    const swiftkv_kv_cache *kv, float *logits_out, void *workspace, size_t workspace_bytes, void *stream) {
+  Run r;
+  if (int e = setup_run(r, c, seq_lens, B, kv, workspace, workspace_bytes, stream)) return e;
+  if (!token_ids || !logits_out) return fail(SWIFTKV_EINVAL, "null token_ids or logits_out");
+  const swiftkv_model_cfg &m = c->cfg;
+  const int T = (int)r.L.T, d = m.hidden, qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
+  hipStream_t st = r.st;
+  Timer tm{c, st};
+  tm.begin(TC_OTHER);
+  if (int e = run_plan(r, token_ids)) return e;
+  bf16_t *h = r.at<bf16_t>(r.L.h);
+  launch_embed(token_ids, c->embed, h, T, d, m.vocab, st);
+  tm.end();
+  float *rstd = r.at<float>(r.L.rstd);
+  bf16_t *qb = r.at<bf16_t>(r.L.q), *kb = r.at<bf16_t>(r.L.k), *vb = r.at<bf16_t>(r.L.v), *ob = r.at<bf16_t>(r.L.o);
+  bf16_t *vt = r.at<bf16_t>(r.L.vt), *zb = r.at<bf16_t>(r.L.z);
+  const bool compute_scale = r.fp8 && kv->scale_mode == SWIFTKV_SCALE_COMPUTE_ABSMAX;
+
+  // ------------------------------------------ layers 1..l on every new token ----
+  for (int j = 0; j < c->l; ++j) {
+    tm.begin(TC_OTHER);
+    launch_rstd(h, rstd, T, d, m.rms_eps, st);
+    tm.end();
+    {
+      GemmParams g{};
+      g.A = h; g.lda = d; g.M = T; g.N = qd + 2 * kvd; g.K = d;
+      g.wtab = c->qkv_tab[j]; g.ldw = d; g.gain_tab = c->norm1_tab[j]; g.gain_seg = 1 << 30;
+      g.rstd = rstd; g.cos_sin = r.at<float2>(r.L.cos_sin);
+      g.head_dim = m.head_dim; g.q_dim = qd; g.kv_dim = kvd;
+      g.q_out = qb; g.k_out = kb; g.v_out = vb;
+      g.first_cache_layer = j;
+      g.amax = compute_scale ? r.at<uint32_t>(r.L.amax) : nullptr;
+      tm.begin(TC_QKV);
+      if (launch_gemm(g, EPI_QKV, 0, st) != 0) return fail(SWIFTKV_EHIP, "QKV GEMM launch failed");
+      tm.end();
+    }
+    {
+      CommitParams cp{};
+      cp.tiles = (const KVTile *)r.meta(r.L.m_kvtiles); cp.n_tiles = r.L.n_kvtiles;
+      cp.n_kv_heads = m.n_kv_heads; cp.head_dim = m.head_dim;
+      cp.k_src = kb; cp.v_src = vb; cp.ld_src = kvd;
+      cp.cache_k = r.cache_plane(j, 0); cp.cache_v = r.cache_plane(j, 1);
+      cp.slots = r.at<int64_t>(r.L.slots);
+      cp.fp8 = r.fp8; cp.compute_scale = compute_scale; cp.writeback = r.fp8;
+      if (r.fp8) {
+        cp.amax = r.at<uint32_t>(r.L.amax) + (int64_t)j * 2 * m.n_kv_heads;
+        cp.scales = kv->scales + (int64_t)j * 2 * m.n_kv_heads;
+      }
+      cp.vt = vt; cp.vt_ld = r.L.vt_ld;
+      tm.begin(TC_OTHER);
+      launch_kv_commit(cp, st);
+      tm.end();
+    }
+    {
+      AttnPrefillParams ap{};
+      ap.q = qb; ap.k = kb; ap.vt = vt; ap.vt_ld = r.L.vt_ld; ap.out = ob;
+      ap.qblocks = (const QBlock *)r.meta(r.L.m_qblocks); ap.n_qblocks = r.L.n_qblocks;
+      ap.n_q_heads = m.n_q_heads; ap.n_kv_heads = m.n_kv_heads; ap.head_dim = m.head_dim;
+      tm.begin(TC_ATTN);
+      if (launch_attention_prefill(ap, st) != 0) return fail(SWIFTKV_EHIP, "attention launch failed");
+      tm.end();
+    }
+    if (r.L.n_dec > 0) {  // decode tokens: one query against the paged cache of this layer
+      AttnDecodeParams dp{};
+      dp.q = qb; dp.out = ob; dp.rows = (const DecodeRow *)r.meta(r.L.m_dec); dp.n_rows = r.L.n_dec;
+      dp.n_q_heads = m.n_q_heads; dp.n_kv_heads = m.n_kv_heads; dp.head_dim = m.head_dim;
+      dp.cache_k = r.cache_plane(j, 0); dp.cache_v = r.cache_plane(j, 1); dp.fp8 = r.fp8;
+      if (r.fp8) { dp.scale_k = kv->scales + (int64_t)j * 2 * m.n_kv_heads; dp.scale_v = dp.scale_k + m.n_kv_heads; }
+      dp.block_tables = kv->block_tables; dp.max_blocks_per_seq = kv->max_blocks_per_seq; dp.n_blocks = kv->n_blocks;
+      dp.cos_sin = r.at<float2>(r.L.cos_sin); dp.partial = r.at<float>(r.L.partial);
+      dp.n_split = pick_split(r.L.n_dec, m.n_kv_heads, r.hp.max_keys_dec);
+      tm.begin(TC_OTHER);
+      if (launch_attention_decode(dp, st) != 0) return fail(SWIFTKV_EHIP, "decode attention launch failed");
+      launch_decode_combine(dp.partial, ob, dp.rows, dp.n_rows, m.n_q_heads, m.head_dim, dp.n_split, st);
+      tm.end();
+    }
+    {
+      GemmParams g{};
+      g.A = ob; g.lda = qd; g.M = T; g.N = d; g.K = qd; g.W = c->wo[j]; g.ldw = qd; g.C = h; g.ldc = d;
+      tm.begin(TC_O);
+      if (launch_gemm(g, EPI_RESID, 0, st) != 0) return fail(SWIFTKV_EHIP, "O GEMM launch failed");
+      tm.end();
+    }
+    tm.begin(TC_OTHER);
+    launch_rstd(h, rstd, T, d, m.rms_eps, st);
+    tm.end();
+    {
+      GemmParams g{};
+      g.A = h; g.lda = d; g.M = T; g.N = 2 * m.ffn; g.K = d; g.wtab = c->gu_tab[j]; g.ldw = d;
+      g.gain_tab = c->norm2_tab[j]; g.gain_seg = 1 << 30; g.rstd = rstd; g.C = zb; g.ldc = m.ffn;
+      tm.begin(TC_GATEUP);
+      if (launch_gemm(g, EPI_SWIGLU, 0, st) != 0) return fail(SWIFTKV_EHIP, "gate/up GEMM launch failed");
+      tm.end();
+    }
+    {
+      GemmParams g{};
+      g.A = zb; g.lda = m.ffn; g.M = T; g.N = d; g.K = m.ffn; g.W = c->wdown[j]; g.ldw = m.ffn; g.C = h; g.ldc = d;
+      tm.begin(TC_DOWN);
+      if (launch_gemm(g, EPI_RESID, 0, st) != 0) return fail(SWIFTKV_EHIP, "down GEMM launch failed");
+      tm.end();
+    }
+    if (int e = check_launch("decoder layer")) return e;
+  }
+
+  // -------------------------- later layers' K/V from the layer-l output ----
+  if (c->P > 0)
+    if (int e = run_fused_kv(r, h, tm)) return e;
+
+  // ----------------------------- last token of every sequence: layers l+1..L ----
+  tm.begin(TC_TAIL);
+  bf16_t *th = r.at<bf16_t>(r.L.th), *ta = r.at<bf16_t>(r.L.ta), *tq = r.at<bf16_t>(r.L.tq), *to = r.at<bf16_t>(r.L.to), *tz = r.at<bf16_t>(r.L.tz);
+  launch_gather_rows(h, r.at<int32_t>(r.L.last_rows), th, B, d, st);
+  for (int j = c->l; j < m.n_layers; ++j) {
+    const int cl = c->l + (j - c->l) / c->g;
+    launch_rmsnorm_rows(th, c->norm1[j], ta, B, d, m.rms_eps, st);
+    if (tail_gemm(c, ta, B, qd, d, c->wq[j], nullptr, nullptr, tq, EPI_STORE_BF16, st)) return fail(SWIFTKV_EHIP, "tail q GEMM failed");
+    AttnDecodeParams dp{};
+    dp.q = tq; dp.out = to; dp.rows = (const DecodeRow *)r.meta(r.L.m_tail); dp.n_rows = B;
+    dp.n_q_heads = m.n_q_heads; dp.n_kv_heads = m.n_kv_heads; dp.head_dim = m.head_dim;
+    dp.cache_k = r.cache_plane(cl, 0); dp.cache_v = r.cache_plane(cl, 1); dp.fp8 = r.fp8;
+    if (r.fp8) { dp.scale_k = kv->scales + (int64_t)cl * 2 * m.n_kv_heads; dp.scale_v = dp.scale_k + m.n_kv_heads; }
+    dp.block_tables = kv->block_tables; dp.max_blocks_per_seq = kv->max_blocks_per_seq; dp.n_blocks = kv->n_blocks;
+    dp.cos_sin = r.at<float2>(r.L.cos_sin); dp.partial = r.at<float>(r.L.partial);
+    dp.n_split = pick_split(B, m.n_kv_heads, r.hp.max_keys_tail);
+    if (launch_attention_decode(dp, st) != 0) return fail(SWIFTKV_EHIP, "tail attention launch failed");
+    launch_decode_combine(dp.partial, to, dp.rows, B, m.n_q_heads, m.head_dim, dp.n_split, st);
+    if (tail_gemm(c, to, B, d, qd, c->wo[j], nullptr, nullptr, th, EPI_RESID, st)) return fail(SWIFTKV_EHIP, "tail o GEMM failed");
+    launch_rmsnorm_rows(th, c->norm2[j], ta, B, d, m.rms_eps, st);
+    if (tail_gemm(c, ta, B, m.ffn, d, c->wgate[j], c->wup[j], c->gu_tab[j], tz, EPI_SWIGLU, st)) return fail(SWIFTKV_EHIP, "tail MLP GEMM failed");
+    if (tail_gemm(c, tz, B, d, m.ffn, c->wdown[j], nullptr, nullptr, th, EPI_RESID, st)) return fail(SWIFTKV_EHIP, "tail down GEMM failed");
+  }
+  launch_rmsnorm_rows(th, c->final_norm, ta, B, d, m.rms_eps, st);
+  if (tail_gemm(c, ta, B, m.vocab, d, c->lm_head, nullptr, nullptr, logits_out, EPI_STORE_F32, st)) return fail(SWIFTKV_EHIP, "LM head GEMM failed");
+  tm.end();
+  if (int e = check_launch("tail")) return e;
+  c->last = r.L; c->have_last = true;
+  return SWIFTKV_OK;
+}
+
+int swiftkv_export_plan(swiftkv_ctx *c, const void *workspace, int64_t *slot_mapping, int32_t *positions,
+                        int32_t *cu_seqlens, int32_t *last_rows, void *stream) {
+  if (!c || !workspace) return fail(SWIFTKV_EINVAL, "null argument");
+  if (!c->have_last) return fail(SWIFTKV_EINVAL, "no prefill has run on this ctx");
+  const Layout &L = c->last;
+  const unsigned char *ws = (const unsigned char *)workspace;
+  hipStream_t st = (hipStream_t)stream;
+  if (slot_mapping) HIP_TRY(hipMemcpyAsync(slot_mapping, ws + L.slots, L.T * 8, hipMemcpyDeviceToDevice, st));
+  if (positions) HIP_TRY(hipMemcpyAsync(positions, ws + L.positions, L.T * 4, hipMemcpyDeviceToDevice, st));
+  if (cu_seqlens) HIP_TRY(hipMemcpyAsync(cu_seqlens, ws + L.meta + L.m_cu * 4, (size_t)(L.B + 1) * 4, hipMemcpyDeviceToDevice, st));
+  if (last_rows) HIP_TRY(hipMemcpyAsync(last_rows, ws + L.last_rows, (size_t)L.B * 4, hipMemcpyDeviceToDevice, st));
+  int32_t flag = 0;
+  HIP_TRY(hipMemcpyAsync(&flag, ws + L.err, 4, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (flag & 1) return fail(SWIFTKV_EDATA, "a block table entry was outside [0, n_blocks)");
+  if (flag & 2) return fail(SWIFTKV_EDATA, "a token id was outside [0, vocab)");
+  return SWIFTKV_OK;
+}
+
+int swiftkv_export_hidden(swiftkv_ctx *c, const void *workspace, void *hidden_out, void *stream) {
+  if (!c || !workspace || !hidden_out) return fail(SWIFTKV_EINVAL, "null argument");
+  if (!c->have_last) return fail(SWIFTKV_EINVAL, "no prefill has run on this ctx");
+  const Layout &L = c->last;
+  HIP_TRY(hipMemcpyAsync(hidden_out, (const unsigned char *)workspace + L.h, (size_t)L.T * c->cfg.hidden * 2, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+  return SWIFTKV_OK;
+}
+
+// ------------------------------------------------------- single operations ----
+int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K, int32_t out_f32,
+                    int32_t variant, void *stream) {
+  if (!A || !W || !C) return fail(SWIFTKV_EINVAL, "null argument");
+  if (M < 1 || N < 16 || K < 8 || (N % 16) || (K % 8)) return fail(SWIFTKV_EINVAL, "need M >= 1, N %% 16 == 0, K %% 8 == 0");
+  if (variant < 0 || variant > 3) return fail(SWIFTKV_EINVAL, "variant must be 0..3");
+  hipStream_t st = (hipStream_t)stream;
+  if (variant == 3) {
+    if (M > 80) return fail(SWIFTKV_EINVAL, "weight-streaming kernel handles M <= 80");
+    SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C};
+    if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, st)) return fail(SWIFTKV_EHIP, "skinny launch failed");
+    return check_launch("skinny gemm");
+  }
+  GemmParams g{};
+  g.A = (const bf16_t *)A; g.lda = K; g.M = M; g.N = N; g.K = K; g.W = (const bf16_t *)W; g.ldw = K; g.C = C; g.ldc = N;
+  if (launch_gemm(g, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, variant, st)) return fail(SWIFTKV_EHIP, "gemm launch failed");
+  return check_launch("gemm");
+}
+
+size_t swiftkv_op_attention_workspace(int64_t n_tokens, int32_t n_seqs, int32_t n_kv_heads, int32_t head_dim) {
+  const int64_t vt_ld = n_tokens + 64LL * n_seqs;
+  return align_up((size_t)n_kv_heads * head_dim * vt_ld * 2) + align_up((size_t)(n_tokens / 128 + n_seqs) * 32) +
+         align_up((size_t)(n_tokens / 64 + n_seqs) * 16) + 4096;
+}
+
+int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, void *out, const int32_t *seq_lens,
+                                 int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, void *workspace,
+                                 size_t workspace_bytes, void *stream) {
+  if (!q || !k || !v || !out || !seq_lens || !workspace) return fail(SWIFTKV_EINVAL, "null argument");
+  if ((hd != 64 && hd != 128) || Hq % Hkv || (Hkv * hd) % 128 || (Hq * hd) % 128) return fail(SWIFTKV_EINVAL, "bad head shape");
+  hipStream_t st = (hipStream_t)stream;
+  std::vector<int32_t> qbs, kvt;
+  int64_t row = 0, col = 0;
+  for (int b = 0; b < B; ++b) {
+    const int n = seq_lens[b];
+    if (n < 1) return fail(SWIFTKV_EINVAL, "seq_lens must be >= 1");
+    for (int q0 = 0; q0 < n; q0 += 128) qbs.insert(qbs.end(), {(int32_t)(row + q0), q0, n, (int32_t)row, (int32_t)col, 0, 0, 0});
+    for (int p0 = 0; p0 < n; p0 += 64) kvt.insert(kvt.end(), {(int32_t)(row + p0), std::min(64, n - p0), (int32_t)(col + p0), 0});
+    row += n;
+    col += (n + 63) / 64 * 64;
+  }
+  const int64_t vt_ld = col;
+  size_t o_vt = 0, o_qb = align_up((size_t)Hkv * hd * vt_ld * 2), o_kt = o_qb + align_up(qbs.size() * 4), total = o_kt + align_up(kvt.size() * 4);
+  if (total > workspace_bytes) return fail(SWIFTKV_ENOSPC, "workspace has %zu bytes, %zu needed", workspace_bytes, total);
+  unsigned char *ws = (unsigned char *)workspace;
+  HIP_TRY(hipMemcpyAsync(ws + o_qb, qbs.data(), qbs.size() * 4, hipMemcpyHostToDevice, st));
+  HIP_TRY(hipMemcpyAsync(ws + o_kt, kvt.data(), kvt.size() * 4, hipMemcpyHostToDevice, st));
+  CommitParams cp{};
+  cp.tiles = (const KVTile *)(ws + o_kt); cp.n_tiles = (int32_t)(kvt.size() / 4); cp.n_kv_heads = Hkv; cp.head_dim = hd;
+  cp.k_src = (bf16_t *)k; cp.v_src = (bf16_t *)v; cp.ld_src = (int64_t)Hkv * hd;
+  cp.vt = (bf16_t *)(ws + o_vt); cp.vt_ld = vt_ld;
+  launch_kv_commit(cp, st);
+  AttnPrefillParams ap{};
+  ap.q = (const bf16_t *)q; ap.k = (const bf16_t *)k; ap.vt = (const bf16_t *)(ws + o_vt); ap.vt_ld = vt_ld; ap.out = (bf16_t *)out;
+  ap.qblocks = (const QBlock *)(ws + o_qb); ap.n_qblocks = (int32_t)(qbs.size() / 8);
+  ap.n_q_heads = Hq; ap.n_kv_heads = Hkv; ap.head_dim = hd;
+  if (launch_attention_prefill(ap, st)) return fail(SWIFTKV_EHIP, "attention launch failed");
+  return check_launch("attention");
+}
+
+int swiftkv_op_fp8_quantize(const float *x, float scale, uint8_t *codes, int64_t n, void *stream) {
+  if (!x || !codes || n < 0) return fail(SWIFTKV_EINVAL, "bad argument");
+  launch_fp8_quantize(x, scale, codes, n, (hipStream_t)stream);
+  return check_launch("fp8 quantize");
+}
+
+}  // extern "C"

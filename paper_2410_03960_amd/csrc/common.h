@@ -1,0 +1,203 @@
+// Shared device helpers and launch declarations for libswiftkv (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef unsigned short bf16_t;  // raw bf16 storage
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+#define SKV_BLOCK 16
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+
+// round-to-nearest-even fp32 -> bf16 (hardware v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ bf16_t f32_to_bf16(float x) {
+  __bf16 b = (__bf16)x;
+  return __builtin_bit_cast(bf16_t, b);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+__device__ __forceinline__ float bf16lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// Saturating RNE fp32 -> OCP e4m3fn (1-4-3, bias 7, max 448, no inf).
+__device__ __forceinline__ uint8_t f32_to_e4m3fn(float x) {
+  uint32_t u = __float_as_uint(x);
+  uint32_t sign = (u >> 24) & 0x80u;
+  float a = fabsf(x);
+  if (!(a < 448.0f)) return (uint8_t)(sign | 0x7E);  // saturate (also NaN -> max; inputs are finite)
+  uint32_t code;
+  if (a < 0.015625f) {  // below 2^-6: subnormal grid of 2^-9; exact RNE via float add trick
+    float r = a * 512.0f;                 // exact scaling
+    float q = rintf(r);                   // RNE to integer 0..8
+    code = (uint32_t)q;                   // 8 == smallest normal (0x08)
+  } else {
+    uint32_t au = __float_as_uint(a);
+    uint32_t lsb = (au >> 20) & 1u;
+    au += 0x7FFFFu + lsb;                 // RNE to 3 mantissa bits
+    uint32_t e = (au >> 23) - 120u;       // rebias 127 -> 7
+    uint32_t m = (au >> 20) & 7u;
+    code = (e << 3) | m;
+    if (code > 0x7E) code = 0x7E;
+  }
+  return (uint8_t)(sign | code);
+}
+__device__ __forceinline__ float e4m3fn_to_f32(uint8_t c) {
+  uint32_t s = ((uint32_t)c & 0x80u) << 24;
+  uint32_t e = (c >> 3) & 0xF, m = c & 7;
+  float v = (e == 0) ? (float)m * 0.001953125f : __uint_as_float(((e + 120u) << 23) | (m << 20));
+  return __uint_as_float(__float_as_uint(v) | s);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// ------------------------------------------------------------------ GEMM ----
+enum GemmEpi {
+  EPI_STORE_BF16 = 0,  // C bf16 [M, ldc]
+  EPI_STORE_F32 = 1,   // C fp32 [M, ldc]
+  EPI_RESID = 2,       // C bf16 [M, ldc] += acc  (in place on the residual stream)
+  EPI_SWIGLU = 3,      // virtual N = 2*ffn in 16-row gate/up interleave; C bf16 [M, ffn]
+  EPI_QKV = 4,         // rstd row scale, RoPE on q/k columns, q/k/v to separate row-major buffers
+  EPI_KV = 5           // rstd row scale, RoPE on K columns, paged scatter (bf16) or staging (+absmax)
+};
+
+struct GemmParams {
+  // activations: A [M, K] bf16 row-major, leading dimension lda
+  const bf16_t *A;
+  int64_t lda;
+  int32_t M, N, K;  // N = (virtual) output columns
+  // weights: table of device pointers, one per block of 16 (virtual) output rows,
+  // each pointing at 16 rows of K contiguous bf16 with row stride ldw.
+  // With wtab == nullptr the rows are simply W + n * ldw.
+  const bf16_t *const *wtab;
+  const bf16_t *W;
+  int64_t ldw;
+  // optional A prologue: A[m,k] *= gain[k]; gain vector chosen per block of gain_seg output columns
+  const bf16_t *const *gain_tab;  // device table of gain pointers (nullptr = no gain)
+  int32_t gain_seg;
+  // epilogue
+  void *C;
+  int64_t ldc;
+  const float *rstd;      // [M] row scale (QKV / KV / SWIGLU with gain), may be null
+  const float2 *cos_sin;  // [M][hd/2] (QKV / KV)
+  int32_t head_dim, q_dim, kv_dim;
+  bf16_t *q_out, *k_out, *v_out;  // QKV: [M,q_dim], [M,kv_dim], [M,kv_dim]
+  // KV scatter
+  bf16_t *cache;               // base of the bf16 cache
+  const int64_t *slots;        // [M]
+  int64_t cache_layer_stride;  // elements between cache layers (2 * n_blocks*16 * kv_dim)
+  int64_t cache_kv_stride;     // elements between the K and V planes of a layer
+  int32_t first_cache_layer;   // KV: cache layer of projection 0
+  bf16_t *stage;               // KV FP8 mode: staging [M, N] bf16 instead of the cache
+  uint32_t *amax;              // FP8: [n_cache_layers][2][Hkv] absmax bit patterns (atomicMax), or null
+};
+
+int launch_gemm(const GemmParams &p, int epi, int variant, hipStream_t st);
+
+// skinny (weight-streaming) GEMM for M <= 80 rows
+struct SkinnyParams {
+  const bf16_t *A;  // [M, K] bf16 (already normalised where needed)
+  int32_t M, N, K;
+  const bf16_t *W;   // [N, K]
+  const bf16_t *W2;  // SWIGLU: up-projection [N, K]
+  void *C;           // bf16 [M,N] (STORE_BF16, RESID in place, SWIGLU) or fp32 (STORE_F32)
+};
+int launch_skinny(const SkinnyParams &p, int epi, hipStream_t st);
+
+// ------------------------------------------------------------- attention ----
+struct QBlock {  // one 128-row query block of a fresh sequence
+  int32_t row0;   // packed row of the block's first query
+  int32_t q0;     // position of that query inside the sequence
+  int32_t n;      // sequence length (keys available)
+  int32_t seq_row0;  // packed row of the sequence's first token
+  int32_t vt_col0;   // column of the sequence's first token in the V^T buffer
+  int32_t pad[3];
+};
+struct AttnPrefillParams {
+  const bf16_t *q, *k;  // [T, q_dim], [T, kv_dim]
+  const bf16_t *vt;     // [kv_dim, vt_ld]  V transposed, sequences at 64-aligned columns
+  int64_t vt_ld;
+  bf16_t *out;          // [T, q_dim]
+  const QBlock *qblocks;
+  int32_t n_qblocks, n_q_heads, n_kv_heads, head_dim;
+};
+int launch_attention_prefill(const AttnPrefillParams &p, hipStream_t st);
+
+struct DecodeRow {  // one single-query attention problem
+  int32_t q_row;    // row in q buffer
+  int32_t out_row;  // row in out buffer
+  int32_t seq;      // sequence (block-table row)
+  int32_t n_keys;   // keys 0..n_keys-1 are visible
+  int32_t cs_row;   // row of cos/sin table to rotate q with, or -1
+  int32_t pad[3];
+};
+struct AttnDecodeParams {
+  const bf16_t *q;  // [*, q_dim]
+  bf16_t *out;      // [*, q_dim]
+  const DecodeRow *rows;
+  int32_t n_rows, n_q_heads, n_kv_heads, head_dim;
+  const void *cache_k, *cache_v;  // this cache layer's K and V planes [n_blocks*16][Hkv][hd]
+  int32_t fp8;
+  const float *scale_k, *scale_v;  // [Hkv] (fp8)
+  const int32_t *block_tables;
+  int32_t max_blocks_per_seq, n_blocks;
+  const float2 *cos_sin;  // [T][hd/2]
+  float *partial;         // [n_rows][Hq][n_split][hd + 2]
+  int32_t n_split;
+};
+int launch_attention_decode(const AttnDecodeParams &p, hipStream_t st);
+
+// ----------------------------------------------------------- elementwise ----
+struct PlanParams {
+  int32_t T, B, head_dim, n_blocks, max_blocks_per_seq, vocab;
+  float rope_theta;
+  const int32_t *cu_seqlens;    // dev [B+1]
+  const int32_t *context_lens;  // dev [B]
+  const int32_t *block_tables;  // dev
+  const int32_t *token_ids;     // dev [T] (may be null)
+  int32_t *positions, *seq_of, *last_rows, *err_flag;
+  int64_t *slots;
+  float2 *cos_sin;
+};
+int launch_plan(const PlanParams &p, hipStream_t st);
+int launch_embed(const int32_t *ids, const bf16_t *E, bf16_t *h, int32_t T, int32_t d, int32_t vocab, hipStream_t st);
+int launch_rstd(const bf16_t *h, float *rstd, int32_t T, int32_t d, float eps, hipStream_t st);
+int launch_rmsnorm_rows(const bf16_t *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, hipStream_t st);
+int launch_gather_rows(const bf16_t *h, const int32_t *rows, bf16_t *out, int32_t n_rows, int32_t d, hipStream_t st);
+int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t st);
+
+struct KVTile {  // 64 consecutive new tokens of one sequence
+  int32_t row0;     // packed row of first token
+  int32_t n_valid;  // tokens present (1..64)
+  int32_t vt_col0;  // V^T column of first token (64-aligned), or -1 when no V^T is wanted
+  int32_t pad;
+};
+struct CommitParams {
+  const KVTile *tiles;
+  int32_t n_tiles, n_kv_heads, head_dim;
+  bf16_t *k_src, *v_src;  // row-major [T, ld_src] (+ column offset applied by caller); fp8 writes dequantised values back
+  int64_t ld_src;
+  void *cache_k, *cache_v;  // planes of the destination cache layer
+  const int64_t *slots;
+  int32_t fp8, compute_scale, writeback;
+  const uint32_t *amax;  // [2][Hkv] absmax bits of this cache layer (fp8 compute mode)
+  float *scales;         // [2][Hkv] of this cache layer (fp8)
+  bf16_t *vt;            // [kv_dim, vt_ld] or null
+  int64_t vt_ld;
+};
+int launch_kv_commit(const CommitParams &p, hipStream_t st);
+int launch_fp8_quantize(const float *x, float scale, uint8_t *codes, int64_t n, hipStream_t st);
+int launch_decode_combine(const float *partial, bf16_t *out, const DecodeRow *rows, int32_t n_rows,
+                          int32_t n_q_heads, int32_t head_dim, int32_t n_split, hipStream_t st);

@@ -1,0 +1,272 @@
+// HBM-bound kernels of the SwiftKV prefill path: integer plan + RoPE table,
+// embedding gather, row rstd, RMSNorm of a few rows, row gather, KV commit
+// (paged scatter, FP8 quantise, V transpose), split-KV combine.
+#include "common.h"
+
+// ---------------------------------------------------------------- plan -----
+// One thread per new token: sequence by binary search in cu_seqlens, absolute
+// position, paged slot = block_table[b][p/16]*16 + p%16, and the RoPE angle
+// table cos/sin(p * theta^(-2i/hd)) formed in double precision.
+__global__ void plan_kernel(PlanParams p) {
+  int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < p.B) p.last_rows[t] = p.cu_seqlens[t + 1] - 1;
+  if (t >= p.T) return;
+  int lo = 0, hi = p.B - 1;
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (p.cu_seqlens[mid] <= t) lo = mid; else hi = mid - 1;
+  }
+  int b = lo;
+  int pos = p.context_lens[b] + (t - p.cu_seqlens[b]);
+  int blk = p.block_tables[(int64_t)b * p.max_blocks_per_seq + pos / SKV_BLOCK];
+  if (blk < 0 || blk >= p.n_blocks) {  // never let a bad table turn into a wild store
+    atomicOr(p.err_flag, 1);
+    blk = 0;
+  }
+  if (p.token_ids) {
+    int id = p.token_ids[t];
+    if (id < 0 || id >= p.vocab) atomicOr(p.err_flag, 2);
+  }
+  p.positions[t] = pos;
+  p.seq_of[t] = b;
+  p.slots[t] = (int64_t)blk * SKV_BLOCK + pos % SKV_BLOCK;
+  int half = p.head_dim / 2;
+  for (int i = 0; i < half; ++i) {
+    double inv_freq = pow((double)p.rope_theta, -2.0 * (double)i / (double)p.head_dim);
+    double ang = (double)pos * inv_freq;
+    p.cos_sin[(int64_t)t * half + i] = make_float2((float)cos(ang), (float)sin(ang));
+  }
+}
+int launch_plan(const PlanParams &p, hipStream_t st) {
+  int n = p.T > p.B ? p.T : p.B;
+  hipLaunchKernelGGL(plan_kernel, dim3((n + 127) / 128), dim3(128), 0, st, p);
+  return 0;
+}
+
+// --------------------------------------------------------------- embed -----
+__global__ void embed_kernel(const int32_t *ids, const uint4 *E, uint4 *h, int T, int chunks, int vocab) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)T * chunks) return;
+  int t = (int)(i / chunks), c = (int)(i % chunks);
+  int id = ids[t];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+  h[i] = E[(int64_t)id * chunks + c];
+}
+int launch_embed(const int32_t *ids, const bf16_t *E, bf16_t *h, int32_t T, int32_t d, int32_t vocab, hipStream_t st) {
+  int chunks = d / 8;
+  int64_t n = (int64_t)T * chunks;
+  hipLaunchKernelGGL(embed_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, ids, (const uint4 *)E, (uint4 *)h, T, chunks, vocab);
+  return 0;
+}
+
+// ---------------------------------------------------------------- rstd -----
+// rstd[t] = rsqrt(mean(h[t,:]^2) + eps); one wave per row.
+__global__ void rstd_kernel(const uint4 *h, float *rstd, int T, int chunks, float eps, float inv_d) {
+  int row = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
+  int lane = threadIdx.x & 63;
+  if (row >= T) return;
+  const uint4 *r = h + (int64_t)row * chunks;
+  float s = 0.f;
+  for (int c = lane; c < chunks; c += 64) {
+    uint4 u = r[c];
+    float a;
+    a = bf16lo(u.x); s += a * a; a = bf16hi(u.x); s += a * a;
+    a = bf16lo(u.y); s += a * a; a = bf16hi(u.y); s += a * a;
+    a = bf16lo(u.z); s += a * a; a = bf16hi(u.z); s += a * a;
+    a = bf16lo(u.w); s += a * a; a = bf16hi(u.w); s += a * a;
+  }
+  s = wave_sum(s);
+  if (lane == 0) rstd[row] = rsqrtf(s * inv_d + eps);
+}
+int launch_rstd(const bf16_t *h, float *rstd, int32_t T, int32_t d, float eps, hipStream_t st) {
+  hipLaunchKernelGGL(rstd_kernel, dim3((T + 3) / 4), dim3(256), 0, st, (const uint4 *)h, rstd, T, d / 8, eps, 1.0f / (float)d);
+  return 0;
+}
+
+// ------------------------------------------------- RMSNorm of a few rows ----
+__global__ void rmsnorm_rows_kernel(const uint4 *h, const uint4 *gain, uint4 *out, int rows, int chunks, float eps, float inv_d) {
+  int row = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
+  int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const uint4 *r = h + (int64_t)row * chunks;
+  float s = 0.f;
+  for (int c = lane; c < chunks; c += 64) {
+    uint4 u = r[c];
+    float a;
+    a = bf16lo(u.x); s += a * a; a = bf16hi(u.x); s += a * a;
+    a = bf16lo(u.y); s += a * a; a = bf16hi(u.y); s += a * a;
+    a = bf16lo(u.z); s += a * a; a = bf16hi(u.z); s += a * a;
+    a = bf16lo(u.w); s += a * a; a = bf16hi(u.w); s += a * a;
+  }
+  s = wave_sum(s);
+  float rs = rsqrtf(s * inv_d + eps);
+  for (int c = lane; c < chunks; c += 64) {
+    uint4 u = r[c], g = gain[c], o;
+    o.x = pack_bf16x2(bf16lo(u.x) * rs * bf16lo(g.x), bf16hi(u.x) * rs * bf16hi(g.x));
+    o.y = pack_bf16x2(bf16lo(u.y) * rs * bf16lo(g.y), bf16hi(u.y) * rs * bf16hi(g.y));
+    o.z = pack_bf16x2(bf16lo(u.z) * rs * bf16lo(g.z), bf16hi(u.z) * rs * bf16hi(g.z));
+    o.w = pack_bf16x2(bf16lo(u.w) * rs * bf16lo(g.w), bf16hi(u.w) * rs * bf16hi(g.w));
+    out[(int64_t)row * chunks + c] = o;
+  }
+}
+int launch_rmsnorm_rows(const bf16_t *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, hipStream_t st) {
+  hipLaunchKernelGGL(rmsnorm_rows_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, (const uint4 *)h, (const uint4 *)gain, (uint4 *)out, rows, d / 8, eps, 1.0f / (float)d);
+  return 0;
+}
+
+// -------------------------------------------------------------- gather -----
+__global__ void gather_rows_kernel(const uint4 *h, const int32_t *rows, uint4 *out, int n_rows, int chunks) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)n_rows * chunks) return;
+  int r = (int)(i / chunks), c = (int)(i % chunks);
+  out[i] = h[(int64_t)rows[r] * chunks + c];
+}
+int launch_gather_rows(const bf16_t *h, const int32_t *rows, bf16_t *out, int32_t n_rows, int32_t d, hipStream_t st) {
+  int chunks = d / 8;
+  int64_t n = (int64_t)n_rows * chunks;
+  hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const uint4 *)h, rows, (uint4 *)out, n_rows, chunks);
+  return 0;
+}
+
+__global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t st) {
+  if (n <= 0) return 0;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);
+  return 0;
+}
+
+// ----------------------------------------------------------- KV commit -----
+// One workgroup per (64-token tile, KV head).  Reads the tile's K and V rows
+// (row-major, already rotated), stores them at their paged slots as bf16 or as
+// e4m3 codes of x/scale, optionally writes the dequantised values back (so that
+// attention sees exactly what the cache holds) and writes V transposed
+// ([dim][token], 64-aligned columns, zero padded) for the prefill attention.
+template <int HD>
+__global__ __launch_bounds__(256) void kv_commit_kernel(CommitParams p) {
+  constexpr int CH = HD / 8;  // 16-byte chunks per row
+  __shared__ bf16_t sv[64][HD + 8];
+  const KVTile tile = p.tiles[blockIdx.x];
+  const int head = blockIdx.y;
+  const int tid = threadIdx.x;
+  float sk = 1.f, svs = 1.f, isk = 1.f, isv = 1.f;
+  if (p.fp8) {
+    if (p.compute_scale) {
+      sk = fmaxf(__uint_as_float(p.amax[head]), 1e-12f) / 448.0f;
+      svs = fmaxf(__uint_as_float(p.amax[p.n_kv_heads + head]), 1e-12f) / 448.0f;
+      if (blockIdx.x == 0 && tid == 0) {
+        p.scales[head] = sk;
+        p.scales[p.n_kv_heads + head] = svs;
+      }
+    } else {
+      sk = p.scales[head];
+      svs = p.scales[p.n_kv_heads + head];
+    }
+  }
+  (void)isk; (void)isv;
+  const int kv_dim = p.n_kv_heads * HD;
+  for (int i = tid; i < 64 * CH; i += 256) {
+    int r = i / CH, c = i % CH;
+    uint4 kq = make_uint4(0, 0, 0, 0), vq = make_uint4(0, 0, 0, 0);
+    if (r < tile.n_valid) {
+      int64_t row = tile.row0 + r;
+      bf16_t *kp = p.k_src + row * p.ld_src + head * HD + c * 8;
+      bf16_t *vp = p.v_src + row * p.ld_src + head * HD + c * 8;
+      kq = *(const uint4 *)kp;
+      vq = *(const uint4 *)vp;
+      int64_t dst = p.cache_k ? (p.slots[row] * p.n_kv_heads + head) * HD + c * 8 : 0;
+      if (!p.cache_k) {
+        // no cache wanted (stand-alone attention): only V^T is produced
+      } else if (!p.fp8) {
+        *(uint4 *)((bf16_t *)p.cache_k + dst) = kq;
+        *(uint4 *)((bf16_t *)p.cache_v + dst) = vq;
+      } else {
+        uint32_t kw[4] = {kq.x, kq.y, kq.z, kq.w}, vw[4] = {vq.x, vq.y, vq.z, vq.w};
+        uint32_t kc[2] = {0, 0}, vc[2] = {0, 0};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          uint8_t k0 = f32_to_e4m3fn(bf16lo(kw[e]) / sk), k1 = f32_to_e4m3fn(bf16hi(kw[e]) / sk);
+          uint8_t v0 = f32_to_e4m3fn(bf16lo(vw[e]) / svs), v1 = f32_to_e4m3fn(bf16hi(vw[e]) / svs);
+          kc[e / 2] |= ((uint32_t)k0 | ((uint32_t)k1 << 8)) << ((e & 1) * 16);
+          vc[e / 2] |= ((uint32_t)v0 | ((uint32_t)v1 << 8)) << ((e & 1) * 16);
+          kw[e] = pack_bf16x2(e4m3fn_to_f32(k0) * sk, e4m3fn_to_f32(k1) * sk);
+          vw[e] = pack_bf16x2(e4m3fn_to_f32(v0) * svs, e4m3fn_to_f32(v1) * svs);
+        }
+        *(uint2 *)((uint8_t *)p.cache_k + dst) = make_uint2(kc[0], kc[1]);
+        *(uint2 *)((uint8_t *)p.cache_v + dst) = make_uint2(vc[0], vc[1]);
+        kq = make_uint4(kw[0], kw[1], kw[2], kw[3]);
+        vq = make_uint4(vw[0], vw[1], vw[2], vw[3]);
+        if (p.writeback) {
+          *(uint4 *)kp = kq;
+          *(uint4 *)vp = vq;
+        }
+      }
+    }
+    if (p.vt) {
+      uint32_t w[4] = {vq.x, vq.y, vq.z, vq.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        sv[r][c * 8 + 2 * e] = (bf16_t)(w[e] & 0xffff);
+        sv[r][c * 8 + 2 * e + 1] = (bf16_t)(w[e] >> 16);
+      }
+    }
+  }
+  if (!p.vt || tile.vt_col0 < 0) return;
+  __syncthreads();
+  // V^T: thread writes 8 consecutive tokens of one dim (16 bytes)
+  for (int i = tid; i < HD * 8; i += 256) {
+    int d = i / 8, tc = i % 8;
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = (uint32_t)sv[tc * 8 + 2 * e][d] | ((uint32_t)sv[tc * 8 + 2 * e + 1][d] << 16);
+    *(uint4 *)(p.vt + (int64_t)(head * HD + d) * p.vt_ld + tile.vt_col0 + tc * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  (void)kv_dim;
+}
+int launch_kv_commit(const CommitParams &p, hipStream_t st) {
+  if (p.n_tiles <= 0) return 0;
+  dim3 grid(p.n_tiles, p.n_kv_heads);
+  if (p.head_dim == 128) hipLaunchKernelGGL(kv_commit_kernel<128>, grid, dim3(256), 0, st, p);
+  else hipLaunchKernelGGL(kv_commit_kernel<64>, grid, dim3(256), 0, st, p);
+  return 0;
+}
+
+__global__ void fp8_quantize_kernel(const float *x, float scale, uint8_t *codes, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    float y = x[i] / scale;
+    codes[i] = f32_to_e4m3fn(y);
+  }
+}
+int launch_fp8_quantize(const float *x, float scale, uint8_t *codes, int64_t n, hipStream_t st) {
+  if (n <= 0) return 0;
+  hipLaunchKernelGGL(fp8_quantize_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, x, scale, codes, n);
+  return 0;
+}
+
+// ------------------------------------------------- split-KV combine --------
+// partial layout: [row][head][split][hd + 2] = (o[hd] unnormalised, m, l), m in log2 units.
+__global__ void decode_combine_kernel(const float *partial, bf16_t *out, const DecodeRow *rows, int n_q_heads, int hd, int n_split) {
+  int row = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
+  if (d >= hd) return;
+  const float *base = partial + ((int64_t)(row * n_q_heads + head) * n_split) * (hd + 2);
+  float m = -INFINITY;
+  for (int s = 0; s < n_split; ++s) m = fmaxf(m, base[s * (hd + 2) + hd]);
+  float acc = 0.f, l = 0.f;
+  for (int s = 0; s < n_split; ++s) {
+    float ms = base[s * (hd + 2) + hd];
+    if (ms == -INFINITY) continue;
+    float w = exp2f(ms - m);
+    acc += w * base[s * (hd + 2) + d];
+    l += w * base[s * (hd + 2) + hd + 1];
+  }
+  out[(int64_t)rows[row].out_row * n_q_heads * hd + head * hd + d] = f32_to_bf16(acc / l);
+}
+int launch_decode_combine(const float *partial, bf16_t *out, const DecodeRow *rows, int32_t n_rows,
+                          int32_t n_q_heads, int32_t head_dim, int32_t n_split, hipStream_t st) {
+  if (n_rows <= 0) return 0;
+  hipLaunchKernelGGL(decode_combine_kernel, dim3(n_rows, n_q_heads), dim3(head_dim), 0, st, partial, out, rows, n_q_heads, head_dim, n_split);
+  return 0;
+}

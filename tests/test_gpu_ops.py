@@ -1,0 +1,80 @@
+"""Kernel-level parity (through the C ABI) against the oracle's definitions."""
+import sys
+
+import pytest
+import torch
+
+import workloads as WL
+from oracle import swiftkv_oracle as O
+from tests.helpers import cosine, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _rand_bf16(seed, name, shape, std=1.0):
+    return WL.seeded_normal_bf16(seed, name, shape, 0.0, std)
+
+
+@pytest.mark.parametrize("variant,M,N,K", [
+    (2, 128, 128, 64), (2, 300, 272, 200), (2, 1, 16, 8), (2, 517, 1040, 688),
+    (1, 256, 256, 64), (1, 700, 528, 456), (1, 2304, 768, 1024),
+    (3, 1, 16, 8), (3, 8, 1024, 256), (3, 16, 272, 688), (3, 17, 64, 96), (3, 65, 160, 1000),
+    (0, 2500, 512, 256),
+])
+def test_gemm_matches_definition(variant, M, N, K):
+    """C = A W^T (Sec. 3.1 projections); fp32 accumulation of bf16 inputs."""
+    from paper_2410_03960_amd import binding as B
+    _say(f"gemm variant={variant} M={M} N={N} K={K}")
+    A = _rand_bf16(1, f"A{M}{K}", (M, K))
+    W = _rand_bf16(2, f"W{N}{K}", (N, K), 0.05)
+    ref = A.double() @ W.double().T
+    for out_f32 in (True, False):
+        got = B.op_gemm(A.cuda(), W.cuda(), out_f32=out_f32, variant=variant)
+        torch.cuda.synchronize()
+        tol = 1e-5 if out_f32 else 4e-3          # fp32 sum of exact products / one bf16 rounding
+        assert rel_err(got.cpu(), ref) <= tol, (out_f32, rel_err(got.cpu(), ref))
+
+
+@pytest.mark.parametrize("hd,Hq,Hkv,lens", [
+    (64, 4, 2, [128]), (64, 4, 2, [1, 63, 64, 65, 200, 129]),
+    (128, 8, 2, [300, 1, 127, 128, 513]), (128, 4, 4, [77]), (128, 8, 1, [1000]),
+])
+def test_prefill_attention_matches_bruteforce_softmax(hd, Hq, Hkv, lens):
+    from paper_2410_03960_amd import binding as B
+    _say(f"attention hd={hd} Hq={Hq} Hkv={Hkv} lens={lens}")
+    T = sum(lens)
+    q = _rand_bf16(3, "q", (T, Hq * hd))
+    k = _rand_bf16(4, "k", (T, Hkv * hd))
+    v = _rand_bf16(5, "v", (T, Hkv * hd))
+    got = B.op_attention_prefill(q.cuda(), k.cuda(), v.cuda(), lens, Hq, Hkv, hd)
+    torch.cuda.synchronize()
+    got = got.cpu()
+    off = 0
+    for n in lens:
+        ref = O.gqa_attention(q[off:off + n].double().view(n, Hq, hd), torch.arange(n),
+                              k[off:off + n].double().view(n, Hkv, hd), v[off:off + n].double().view(n, Hkv, hd))
+        g = got[off:off + n].view(n, Hq, hd)
+        assert rel_err(g, ref) <= 1e-2 and cosine(g, ref) >= 0.9995, (n, rel_err(g, ref), cosine(g, ref))
+        off += n
+
+
+def test_fp8_quantiser_is_bit_exact():
+    """Same fp32 inputs, same fp32 division: codes must agree bit for bit."""
+    from paper_2410_03960_amd import binding as B
+    _say("fp8 quantiser")
+    g = torch.Generator().manual_seed(9)
+    x = torch.cat([torch.randn(200000, generator=g) * 5, torch.randn(20000, generator=g) * 1e-3,
+                   torch.tensor([0.0, -0.0, 1e9, -1e9, 448.0, 464.0, 2.0 ** -9, 2.0 ** -10, 1.5 * 2.0 ** -9])])
+    tab = O.fp8_e4m3fn_decode_table()[:127].float()
+    mids = (tab[:-1] + tab[1:]) / 2
+    x = torch.cat([x, mids, -mids, torch.nextafter(mids, torch.tensor(0.0)), torch.nextafter(mids, torch.tensor(1e9))])
+    for scale in (1.0, 0.0371, 3.3):
+        want = O.fp8_quantize(x * scale, torch.tensor(scale))
+        got = B.op_fp8_quantize((x * scale).cuda(), scale)
+        torch.cuda.synchronize()
+        assert torch.equal(got.cpu(), want), scale

@@ -1,0 +1,208 @@
+"""End-to-end parity of swiftkv_prefill / swiftkv_kv_from_hidden with the CPU
+oracle on the tiny decoder (all cache layers, logits, integer plan)."""
+import sys
+
+import pytest
+import torch
+
+import workloads as WL
+from oracle import swiftkv_oracle as O
+from tests import gpu_helpers as G
+
+pytestmark = pytest.mark.gpu
+TINY = WL.configs.TINY
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    wl = WL.get_workload("tiny")
+    store = WL.make_weights(wl, "cpu", keep=True)
+    return wl, store, G.device_weights(store)
+
+
+def _ctx(dev_w, l, g):
+    from paper_2410_03960_amd import binding as B
+    return B.Context(TINY, dev_w, l, g)
+
+
+def test_config1_tiny_prompt(tiny):
+    """Config 1: L=4, l=2, one 128-token prompt; every cache layer + logits."""
+    wl, store, dev_w = tiny
+    _say("config 1 (tiny)")
+    batch = WL.build_batch(wl)
+    ctx = _ctx(dev_w, wl.l, wl.g)
+    logits, cache, ws = G.run_gpu(ctx, batch)
+    G.check_plan(ctx, ws, batch)
+    ologits, ocache, _ = G.run_oracle(TINY, store, batch, wl.l, wl.g)
+    wc = G.compare_caches(cache, ocache, batch, label="cfg1")
+    wlg = G.compare_logits(logits, ologits, label="cfg1")
+    _say(f"  worst cache rel/cos {wc}, logits {wlg}")
+    assert int(logits[0].argmax()) == int(ologits[0].argmax())
+
+
+@pytest.mark.parametrize("l,g,lens,shuffled", [
+    (4, 1, [50, 3], False),              # l = L: ordinary prefill, no later layers
+    (2, 2, [1, 17, 130, 64], True),      # AcrossKV pair, ragged batch, shuffled blocks
+    (1, 3, [200], True),                 # one group of three later layers
+    (3, 1, [129, 255, 16, 15], True),
+])
+def test_tiny_variants(tiny, l, g, lens, shuffled):
+    wl, store, dev_w = tiny
+    _say(f"tiny l={l} g={g} lens={lens} shuffled={shuffled}")
+    batch = WL.build_batch(wl, lens=lens, shuffled=shuffled)
+    ctx = _ctx(dev_w, l, g)
+    logits, cache, ws = G.run_gpu(ctx, batch)
+    G.check_plan(ctx, ws, batch)
+    ologits, ocache, _ = G.run_oracle(TINY, store, batch, l, g)
+    wc = G.compare_caches(cache, ocache, batch, label=f"l{l}g{g}")
+    wlg = G.compare_logits(logits, ologits, label=f"l{l}g{g}")
+    _say(f"  worst cache rel/cos {wc}, logits {wlg}")
+    # blocks no sequence owns stay untouched (zero)
+    used = torch.zeros(batch.n_blocks, dtype=torch.bool)
+    for b in range(batch.n_seqs):
+        nb = (int(batch.seq_lens[b]) + 15) // 16
+        used[batch.block_tables[b, :nb].long()] = True
+    untouched = cache.data.view(cache.n_cache_layers, 2, batch.n_blocks, -1)[:, :, (~used).cuda()]
+    assert untouched.abs().sum().item() == 0
+
+
+def test_fused_kv_from_oracle_hidden(tiny):
+    """The signature step alone: hidden state after layer l from the oracle ->
+    RMSNorm_j, fused K/V GEMM, RoPE, paged scatter (Eq. 2 + AcrossKV)."""
+    from paper_2410_03960_amd import binding as B
+    wl, store, dev_w = tiny
+    l, g, lens = 2, 2, [33, 150]
+    _say("fused KV from oracle hidden")
+    batch = WL.build_batch(wl, lens=lens, shuffled=True)
+    _, ocache, hl = G.run_oracle(TINY, store, batch, l, g)
+    hidden = torch.cat([hl[0], hl[1]]).to(torch.bfloat16)
+    # oracle K/V for exactly these bf16 hidden values
+    oc2 = O.PagedKVCache(ocache.C, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables)
+    sh = G.oracle_shape(TINY)
+    off = 0
+    for b, n in enumerate(lens):
+        hb = hidden[off:off + n].double()
+        for p, j in enumerate(O.leader_layers(TINY.n_layers, l, g)):
+            a = O.rmsnorm(hb, store.get("norm1", j - 1).double(), TINY.rms_eps)
+            k = O.rope((a @ store.get("wk", j - 1).double().T).view(n, TINY.n_kv_heads, TINY.head_dim), torch.arange(n), TINY.rope_theta)
+            v = (a @ store.get("wv", j - 1).double().T).view(n, TINY.n_kv_heads, TINY.head_dim)
+            oc2.write(l + p, b, torch.arange(n), k, v)
+        off += n
+    ctx = _ctx(dev_w, l, g)
+    cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables, [0, 0])
+    ws = torch.empty(ctx.workspace_bytes(batch.n_tokens, 2), dtype=torch.uint8, device="cuda")
+    ctx.kv_from_hidden(hidden.cuda(), lens, cache, ws)
+    torch.cuda.synchronize()
+    G.check_plan(ctx, ws, batch)
+    for c in range(l, ocache.C):
+        for kvsel in (0, 1):
+            for b, n in enumerate(lens):
+                s = oc2.slots(b, torch.arange(n))
+                got = cache.data[c, kvsel][s.cuda()].float().cpu()
+                want = oc2.read(c, b, n)[kvsel]
+                assert G.rel_err(got, want) <= 6e-3 and G.cosine(got, want) >= 0.9999, (c, kvsel, b, G.rel_err(got, want))
+    assert cache.data[:l].abs().sum().item() == 0       # layers <= l are not this call's business
+
+
+def test_decode_tokens_with_context(tiny):
+    """Prompt + decode tokens in one batch (Sec. 3.5): sequences with cached
+    context bring one new token that runs all layers over the paged cache."""
+    from paper_2410_03960_amd import binding as B
+    wl, store, dev_w = tiny
+    l, g = 2, 2
+    _say("decode tokens with context")
+    ctx_lens = [0, 40, 0, 17]
+    lens = [70, 1, 5, 1]
+    batch = WL.build_batch(wl, lens=lens, ctx=ctx_lens, shuffled=True)
+    # contexts: oracle prefill of seeded prompts into the oracle cache, copied to the GPU cache
+    ocache = O.PagedKVCache(O.n_cache_layers(TINY.n_layers, l, g), batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables)
+    for b, cl in enumerate(ctx_lens):
+        if cl:
+            ids = WL.seeded_token_ids(7, f"ctx{b}", cl, TINY.vocab)
+            sub = O.PagedKVCache(ocache.C, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables[b:b + 1])
+            O.swiftkv_prefill(G.oracle_shape(TINY), G.weight_fn(store), ids, [cl], [0], l, g, sub)
+            s = sub.slots(0, torch.arange(cl))
+            ocache.data[:, :, s] = sub.data[:, :, s]
+    ctx = _ctx(dev_w, l, g)
+    cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables, ctx_lens)
+    cache.data.copy_(ocache.data.to(torch.bfloat16))
+    ocache.data = ocache.data.to(torch.bfloat16).double()      # both sides start from the same bf16 context
+    logits, cache, ws = G.run_gpu(ctx, batch, cache=cache)
+    G.check_plan(ctx, ws, batch)
+    ologits, ocache, _ = G.run_oracle(TINY, store, batch, l, g, cache=ocache)
+    G.compare_caches(cache, ocache, batch, label="decode")
+    G.compare_logits(logits, ologits, label="decode")
+
+
+@pytest.mark.parametrize("lens,ctx_lens", [([90, 20], None), ([64, 1, 1], [0, 30, 9])])
+def test_fp8_kv_cache(tiny, lens, ctx_lens):
+    """FP8 e4m3 cache with per-(layer, K|V, head) absmax scales (Appendix B.1)."""
+    from paper_2410_03960_amd import binding as B
+    wl, store, dev_w = tiny
+    l, g = 2, 2
+    _say(f"fp8 kv cache lens={lens} ctx={ctx_lens}")
+    batch = WL.build_batch(wl, lens=lens, ctx=ctx_lens, shuffled=True)
+    ctx = _ctx(dev_w, l, g)
+    if ctx_lens is None:
+        logits, cache, ws = G.run_gpu(ctx, batch, fp8=True, scale_mode=B.SWIFTKV_SCALE_COMPUTE_ABSMAX)
+        ologits, ocache, _ = G.run_oracle(TINY, store, batch, l, g, fp8=True, compute_scales=True)
+        assert G.rel_err(cache.scales.cpu(), ocache.scales) <= 2e-2
+    else:
+        # given scales + seeded codes as the existing contexts, identical on both sides
+        C = ctx.n_cache_layers
+        ocache = O.PagedKVCache(C, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables, fp8=True)
+        ocache.scales[:] = 0.02 + 0.01 * torch.rand(ocache.scales.shape, generator=torch.Generator().manual_seed(3))
+        codes = WL.seeded_token_ids(11, "codes", ocache.data.numel(), 256).to(torch.uint8).view(ocache.data.shape)
+        codes[(codes & 0x7F) == 0x7F] = 0x3C                     # no NaN codes
+        ocache.data.copy_(codes)
+        cache = B.KVCache(C, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables, ctx_lens,
+                          fp8=True, scale_mode=B.SWIFTKV_SCALE_USE_GIVEN)
+        cache.data.copy_(ocache.data)
+        cache.scales.copy_(ocache.scales)
+        logits, cache, ws = G.run_gpu(ctx, batch, fp8=True, cache=cache)
+        ologits, ocache, _ = G.run_oracle(TINY, store, batch, l, g, fp8=True, compute_scales=False, cache=ocache)
+    G.check_plan(ctx, ws, batch)
+    G.compare_caches(cache, ocache, batch, rel=G.FP8_REL, cos=G.FP8_COS, label="fp8")
+    G.compare_logits(logits, ologits, rel=G.FP8_REL, cos=G.FP8_COS, label="fp8")
+
+
+def test_error_paths(tiny):
+    """Host-side validation returns error codes, nothing is launched."""
+    from paper_2410_03960_amd import binding as B
+    wl, store, dev_w = tiny
+    _say("error paths")
+    with pytest.raises(B.SwiftKVError) as e:
+        B.Context(TINY, dev_w, 2, 3)                 # (L - l) % g != 0
+    assert e.value.code == B.SWIFTKV_EINVAL
+    with pytest.raises(B.SwiftKVError):
+        B.Context(TINY, dev_w, 0, 1)
+    ctx = _ctx(dev_w, 2, 1)
+    batch = WL.build_batch(wl, lens=[40])
+    cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables, [0])
+    logits = torch.empty((1, TINY.vocab), dtype=torch.float32, device="cuda")
+    ids = batch.token_ids.cuda()
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.SwiftKVError) as e:
+        ctx.prefill(ids, [40], cache, logits, small)
+    assert e.value.code == B.SWIFTKV_ENOSPC
+    ws = torch.empty(ctx.workspace_bytes(64, 1), dtype=torch.uint8, device="cuda")
+    short = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables[:, :2], [0])
+    with pytest.raises(B.SwiftKVError) as e:
+        ctx.prefill(ids, [40], short, logits, ws)    # 40 tokens need 3 blocks
+    assert e.value.code == B.SWIFTKV_ENOSPC
+    ctxd = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables, [5])
+    with pytest.raises(B.SwiftKVError) as e:
+        ctx.prefill(ids, [3], ctxd, logits, ws)      # context with several new tokens
+    assert e.value.code == B.SWIFTKV_EINVAL
+    # a block id outside the pool is caught on the device and reported, not dereferenced
+    bad = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim,
+                    torch.full_like(batch.block_tables, 10 ** 6), [0])
+    ctx.prefill(ids, [40], bad, logits, ws)
+    with pytest.raises(B.SwiftKVError) as e:
+        ctx.export_plan(ws, 40, 1)
+    assert e.value.code == B.SWIFTKV_EDATA
