@@ -77,12 +77,14 @@ def rope(x: torch.Tensor, pos: torch.Tensor, theta: float) -> torch.Tensor:
     return torch.cat([x1 * cos - x2 * sin, x2 * cos + x1 * sin], dim=-1)
 
 
-def gqa_attention(q: torch.Tensor, q_pos: torch.Tensor, k: torch.Tensor, v: torch.Tensor) -> torch.Tensor:
+def gqa_attention(q: torch.Tensor, q_pos: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                  act_round=None) -> torch.Tensor:
     """Causal grouped-query attention of queries at absolute positions q_pos
     over keys/values at positions 0..n_k-1.
 
     q: [n_q, Hq, hd]; k, v: [n_k, Hkv, hd].  Query head h uses KV head
     h // (Hq / Hkv).  Key s is visible to a query at position p iff s <= p.
+    act_round: see swiftkv_prefill (applied to the softmax weights).
     """
     n_q, Hq, hd = q.shape
     n_k, Hkv, _ = k.shape
@@ -93,7 +95,8 @@ def gqa_attention(q: torch.Tensor, q_pos: torch.Tensor, k: torch.Tensor, v: torc
         kh, vh = k[:, h // rep, :], v[:, h // rep, :]
         s = (q[:, h, :] @ kh.T) / math.sqrt(hd)
         s = s.masked_fill(~visible, float("-inf"))
-        out[:, h, :] = torch.softmax(s, dim=-1) @ vh
+        w = torch.softmax(s, dim=-1)
+        out[:, h, :] = (w if act_round is None else act_round(w)) @ vh
     return out
 
 
@@ -263,18 +266,18 @@ norm gains); layer0 is the 0-based layer or None for embed/final_norm/lm_head.""
 
 
 def _attn_and_mlp(sh: Shape, W, j0: int, h: torch.Tensor, q_pos: torch.Tensor,
-                  k: torch.Tensor, v: torch.Tensor, a: torch.Tensor) -> torch.Tensor:
+                  k: torch.Tensor, v: torch.Tensor, a: torch.Tensor, R=lambda x: x, act_round=None) -> torch.Tensor:
     """Rest of decoder layer j0 (0-based) after its K/V are known: queries from
     the normed input `a`, attention over (k, v), O-projection, residual,
     second norm, SwiGLU MLP, residual."""
     n = h.shape[0]
     q = (a @ W("wq", j0).T).view(n, sh.n_q_heads, sh.head_dim)
-    q = rope(q, q_pos, sh.rope_theta)
-    o = gqa_attention(q, q_pos, k, v).reshape(n, sh.n_q_heads * sh.head_dim)
-    u = h + o @ W("wo", j0).T
-    m = rmsnorm(u, W("norm2", j0), sh.rms_eps)
-    z = silu(m @ W("wgate", j0).T) * (m @ W("wup", j0).T)
-    return u + z @ W("wdown", j0).T
+    q = R(rope(q, q_pos, sh.rope_theta))
+    o = R(gqa_attention(q, q_pos, k, v, act_round).reshape(n, sh.n_q_heads * sh.head_dim))
+    u = R(h + o @ W("wo", j0).T)
+    m = R(rmsnorm(u, W("norm2", j0), sh.rms_eps))
+    z = R(silu(m @ W("wgate", j0).T) * (m @ W("wup", j0).T))
+    return R(u + z @ W("wdown", j0).T)
 
 
 def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
@@ -282,7 +285,7 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
                     l: int, g: int, cache: PagedKVCache,
                     dtype=torch.float64, fp8_compute_scales: bool = True,
                     seq_subset: Optional[Sequence[int]] = None,
-                    all_token_tail: bool = False):
+                    all_token_tail: bool = False, act_round=None):
     """SwiftKV prefill of a packed batch.  Returns logits [B, vocab] (rows of
     sequences outside `seq_subset` are NaN) and leaves K/V in `cache`.
 
@@ -294,7 +297,14 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
     sequences); otherwise use the scales already in `cache`.
     all_token_tail: run layers l+1..L on every new token instead of only the
     last (checking aid); logits are still those of the last token.
+    act_round: None gives the plain definition.  A function (e.g. round to
+    bfloat16 and back) is applied to every activation a reduced-precision
+    pipeline would store between matrix products (normed inputs, q/k/v,
+    softmax weights, attention output, residual stream, MLP product); the tests
+    use it to measure how far such storage alone moves the result on a given
+    model, which bounds what any bf16 implementation can achieve.
     """
+    R = (lambda x: x) if act_round is None else act_round
     L = sh.n_layers
     C = n_cache_layers(L, l, g)
     assert cache.C == C
@@ -328,15 +338,15 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
         a, kv = {}, {}
         for b in seqs:
             n = h[b].shape[0]
-            a[b] = rmsnorm(h[b], W("norm1", j0), sh.rms_eps)
+            a[b] = R(rmsnorm(h[b], W("norm1", j0), sh.rms_eps))
             k = rope((a[b] @ W("wk", j0).T).view(n, sh.n_kv_heads, sh.head_dim), pos[b], sh.rope_theta)
             v = (a[b] @ W("wv", j0).T).view(n, sh.n_kv_heads, sh.head_dim)
-            kv[b] = (k, v)
+            kv[b] = (R(k), R(v))
         store(j0, kv)
         for b in seqs:
             n_ctx = int(context_lens[b]) + int(seq_lens[b])
             k_all, v_all = cache.read(j0, b, n_ctx)          # as stored (FP8: dequantised)
-            h[b] = _attn_and_mlp(sh, W, j0, h[b], pos[b], k_all, v_all, a[b])
+            h[b] = _attn_and_mlp(sh, W, j0, h[b], pos[b], k_all, v_all, a[b], R, act_round)
 
     # ---- Eq. 2 + AcrossKV: K/V of every later layer from x_{l+1} -----------
     for p, j in enumerate(leader_layers(L, l, g)):
@@ -344,10 +354,10 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
         kv = {}
         for b in seqs:
             n = h[b].shape[0]
-            a_p = rmsnorm(h[b], W("norm1", j0), sh.rms_eps)
+            a_p = R(rmsnorm(h[b], W("norm1", j0), sh.rms_eps))
             k = rope((a_p @ W("wk", j0).T).view(n, sh.n_kv_heads, sh.head_dim), pos[b], sh.rope_theta)
             v = (a_p @ W("wv", j0).T).view(n, sh.n_kv_heads, sh.head_dim)
-            kv[b] = (k, v)
+            kv[b] = (R(k), R(v))
         store(l + p, kv)
 
     # ---- only the last new token continues (footnote of Sec. 3.2, Sec. 3.5) -
@@ -362,13 +372,13 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
         for b in seqs:
             n_ctx = int(context_lens[b]) + int(seq_lens[b])
             k_all, v_all = cache.read(c, b, n_ctx)
-            a = rmsnorm(t[b], W("norm1", j0), sh.rms_eps)
-            t[b] = _attn_and_mlp(sh, W, j0, t[b], tpos[b], k_all, v_all, a)
+            a = R(rmsnorm(t[b], W("norm1", j0), sh.rms_eps))
+            t[b] = _attn_and_mlp(sh, W, j0, t[b], tpos[b], k_all, v_all, a, R, act_round)
 
     logits = torch.full((B, sh.vocab), float("nan"), dtype=dtype)
     gf, Wlm = W("final_norm"), W("lm_head")
     for b in seqs:
-        logits[b] = rmsnorm(t[b][-1], gf, sh.rms_eps) @ Wlm.T
+        logits[b] = R(rmsnorm(t[b][-1], gf, sh.rms_eps)) @ Wlm.T
     hidden_l = {b: h[b] for b in seqs}
     return logits, hidden_l
 

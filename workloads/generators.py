@@ -96,3 +96,16 @@ def seeded_permutation(seed: int, name: str, n: int) -> np.ndarray:
     """A permutation of [0, n): stable argsort of n hashed keys (host)."""
     bits = counter_hash(stream_key(seed, name), 0, n)
     return np.argsort(_lsr(bits, 1).numpy(), kind="stable").astype(np.int64)
+
+
+def seeded_fp8_codes(seed: int, name: str, shape, device="cpu", mag_lo: int = 0x48,
+                     mag_hi: int = 0x77) -> torch.Tensor:
+    """uint8 e4m3fn codes with a random sign and a magnitude field uniform in
+    [mag_lo, mag_hi] (default: values 4 .. 240 times the scale, i.e. spread over
+    six binades; never the NaN patterns).  Used to synthesise pre-existing FP8
+    cache contents."""
+    n = int(np.prod(shape))
+    bits = counter_hash(stream_key(seed, name), 0, n, device)
+    b = _lsr(bits, 40)
+    mag = mag_lo + (b & 0xFFFF) % (mag_hi - mag_lo + 1)
+    return ((_lsr(bits, 63) << 7) | mag).to(torch.uint8).view(*shape)
