@@ -97,9 +97,11 @@ typedef struct swiftkv_ctx swiftkv_ctx;
 /* Bind a model, the SwiftKV split l (1 <= l <= n_layers: number of layers the
  * prompt runs in full, Sec. 3.2) and the AcrossKV group size g >= 1 with
  * (n_layers - l) % g == 0 (Sec. 3.3; 1 = off).  Builds the row-pointer tables
- * that present [W_Q;W_K;W_V], [W_gate;W_up] and the concatenation of the group
- * leaders' [W_K;W_V] (the single fused KV GEMM of Eq. 2) as one operand each,
- * without copying weights.  Allocates a few MB on the current device. */
+ * that present [W_Q;W_K;W_V] and [W_gate;W_up] as one operand each without
+ * copying weights, and packs the operand of the single fused KV GEMM of Eq. 2:
+ * the group leaders' [W_K;W_V] with their input-norm gain folded in (a device
+ * allocation of (L-l)/g * 2*n_kv_heads*head_dim * hidden bf16 elements, plus a
+ * few MB of tables).  Synchronises the device once. */
 int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftkv_weights *w,
                    int32_t l, int32_t acrosskv_group);
 void swiftkv_destroy(swiftkv_ctx *ctx);
@@ -146,8 +148,11 @@ int swiftkv_export_hidden(swiftkv_ctx *ctx, const void *workspace, void *hidden_
 /* ---- single operations, exposed for kernel-level checks and timing -------- */
 
 /* C[M,N] = A[M,K] * W[N,K]^T, bf16 inputs, fp32 accumulation.  out_f32 != 0
- * stores fp32, else bf16.  variant: 0 = pick by shape, 1 = 256x256 tile, 2 =
- * 128x128 tile, 3 = weight-streaming kernel for M <= 80 rows.  All dev. */
+ * stores fp32, else bf16.  variant: 0 = pick by shape, 1 = 256x256 tile with
+ * register-staged loads, 2 = 128x128 tile, 3 = weight-streaming kernel for
+ * M <= 80 rows, 4 / 5 = 256x256 tile with direct-to-LDS loads and 8 / 4 waves
+ * (K % 64 == 0, else they fall back to 1); 6..9 are timing experiments whose
+ * results are not meaningful.  All dev. */
 int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K,
                     int32_t out_f32, int32_t variant, void *stream);
 

@@ -39,7 +39,7 @@ struct Layout {  // byte offsets into the workspace
   int32_t B = 0;
   int64_t vt_ld = 0;
   int32_t n_qblocks = 0, n_kvtiles = 0, n_dec = 0;
-  size_t err, meta, positions, seq_of, last_rows, slots, cos_sin, h, rstd, q, k, v, o, vt, z, stage, amax;
+  size_t err, meta, positions, seq_of, last_rows, slots, cos_sin, h, a, rstd, q, k, v, o, vt, z, stage, amax;
   size_t th, ta, tq, to, tz, partial, total;
   // offsets (in int32 units) inside the meta block copied from the host
   size_t m_cu, m_ctx, m_qblocks, m_kvtiles, m_dec, m_tail, m_words;
@@ -56,8 +56,7 @@ struct swiftkv_ctx {
   // device tables
   void *dev_tables = nullptr;
   std::vector<const bf16_t *const *> qkv_tab, gu_tab, norm1_tab, norm2_tab;
-  const bf16_t *const *kv_tab = nullptr;
-  const bf16_t *const *kv_gain_tab = nullptr;
+  bf16_t *kv_pack = nullptr;   // [P * 2 * kv_dim, hidden]: leaders' [W_K; W_V] with their norm gain folded in
   Layout last;
   bool have_last = false;
   // timing
@@ -97,6 +96,7 @@ Layout make_layout(const swiftkv_ctx *c, int64_t T, int32_t B, int64_t vt_ld, in
   L.slots = take(T * 8);
   L.cos_sin = take(T * (m.head_dim / 2) * 8);
   L.h = take(T * d * 2);
+  L.a = take(T * d * 2);
   L.rstd = take(T * 4);
   L.q = take(T * qd * 2);
   L.k = take(T * kvd * 2);
@@ -273,7 +273,7 @@ int run_fused_kv(Run &r, const bf16_t *hidden, Timer &tm) {
   tm.end();
   GemmParams g{};
   g.A = hidden; g.lda = m.hidden; g.M = (int32_t)r.L.T; g.N = c->P * 2 * kvd; g.K = m.hidden;
-  g.wtab = c->kv_tab; g.ldw = m.hidden; g.gain_tab = c->kv_gain_tab; g.gain_seg = 2 * kvd;
+  g.W = c->kv_pack; g.ldw = m.hidden;   // gains are folded into kv_pack; rstd is applied in the epilogue
   g.rstd = r.at<float>(r.L.rstd); g.cos_sin = r.at<float2>(r.L.cos_sin);
   g.head_dim = m.head_dim; g.q_dim = m.n_q_heads * m.head_dim; g.kv_dim = kvd;
   g.slots = r.at<int64_t>(r.L.slots); g.cache = (bf16_t *)r.kv->data;
@@ -381,14 +381,6 @@ int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftk
     off_n1[j] = tab.size(); tab.push_back(c->norm1[j]);
     off_n2[j] = tab.size(); tab.push_back(c->norm2[j]);
   }
-  const size_t off_kv = tab.size();
-  for (int p = 0; p < c->P; ++p) {
-    const int j = l + p * g;
-    for (int r = 0; r < kvd; r += 16) tab.push_back(c->wk[j] + (int64_t)r * d);
-    for (int r = 0; r < kvd; r += 16) tab.push_back(c->wv[j] + (int64_t)r * d);
-  }
-  const size_t off_kvg = tab.size();
-  for (int p = 0; p < c->P; ++p) tab.push_back(c->norm1[l + p * g]);
   tab.push_back(nullptr);
   hipError_t e = hipGetDevice(&c->device);
   if (e == hipSuccess) e = hipMalloc(&c->dev_tables, tab.size() * sizeof(void *));
@@ -404,8 +396,28 @@ int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftk
     c->qkv_tab[j] = base + off_qkv[j]; c->gu_tab[j] = base + off_gu[j];
     c->norm1_tab[j] = base + off_n1[j]; c->norm2_tab[j] = base + off_n2[j];
   }
-  c->kv_tab = base + off_kv;
-  c->kv_gain_tab = base + off_kvg;
+  if (c->P > 0) {
+    // one operand for the single KV GEMM of Eq. 2: [W_K^j; W_V^j] diag(g1_j) of every group leader j
+    const size_t pack_elems = (size_t)c->P * 2 * kvd * d;
+    e = hipMalloc((void **)&c->kv_pack, pack_elems * 2);
+    if (e != hipSuccess) {
+      (void)hipFree(c->dev_tables);
+      delete c;
+      return fail(SWIFTKV_EHIP, "allocating the fused KV weight (%zu bytes): %s", pack_elems * 2, hipGetErrorString(e));
+    }
+    for (int p = 0; p < c->P; ++p) {
+      const int j = l + p * g;
+      bf16_t *dst = c->kv_pack + (size_t)p * 2 * kvd * d;
+      launch_fold_gain(c->wk[j], c->norm1[j], dst, kvd, m.hidden, nullptr);
+      launch_fold_gain(c->wv[j], c->norm1[j], dst + (size_t)kvd * d, kvd, m.hidden, nullptr);
+    }
+    e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+      (void)hipFree(c->kv_pack); (void)hipFree(c->dev_tables);
+      delete c;
+      return fail(SWIFTKV_EHIP, "folding gains into the fused KV weight: %s", hipGetErrorString(e));
+    }
+  }
   *out = c;
   return SWIFTKV_OK;
 }
@@ -413,6 +425,7 @@ int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftk
 void swiftkv_destroy(swiftkv_ctx *c) {
   if (!c) return;
   if (c->dev_tables) (void)hipFree(c->dev_tables);
+  if (c->kv_pack) (void)hipFree(c->kv_pack);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
   delete c;
 }
@@ -508,7 +521,7 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   bf16_t *h = r.at<bf16_t>(r.L.h);
   launch_embed(token_ids, c->embed, h, T, d, m.vocab, st);
   tm.end();
-  float *rstd = r.at<float>(r.L.rstd);
+  bf16_t *ab = r.at<bf16_t>(r.L.a);
   bf16_t *qb = r.at<bf16_t>(r.L.q), *kb = r.at<bf16_t>(r.L.k), *vb = r.at<bf16_t>(r.L.v), *ob = r.at<bf16_t>(r.L.o);
   bf16_t *vt = r.at<bf16_t>(r.L.vt), *zb = r.at<bf16_t>(r.L.z);
   const bool compute_scale = r.fp8 && kv->scale_mode == SWIFTKV_SCALE_COMPUTE_ABSMAX;
@@ -516,13 +529,13 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   // ------------------------------------------ layers 1..l on every new token ----
   for (int j = 0; j < c->l; ++j) {
     tm.begin(TC_OTHER);
-    launch_rstd(h, rstd, T, d, m.rms_eps, st);
+    launch_rmsnorm_rows(h, c->norm1[j], ab, T, d, m.rms_eps, st);
     tm.end();
     {
       GemmParams g{};
-      g.A = h; g.lda = d; g.M = T; g.N = qd + 2 * kvd; g.K = d;
-      g.wtab = c->qkv_tab[j]; g.ldw = d; g.gain_tab = c->norm1_tab[j]; g.gain_seg = 1 << 30;
-      g.rstd = rstd; g.cos_sin = r.at<float2>(r.L.cos_sin);
+      g.A = ab; g.lda = d; g.M = T; g.N = qd + 2 * kvd; g.K = d;
+      g.wtab = c->qkv_tab[j]; g.ldw = d;
+      g.cos_sin = r.at<float2>(r.L.cos_sin);
       g.head_dim = m.head_dim; g.q_dim = qd; g.kv_dim = kvd;
       g.q_out = qb; g.k_out = kb; g.v_out = vb;
       g.first_cache_layer = j;
@@ -579,12 +592,12 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
       tm.end();
     }
     tm.begin(TC_OTHER);
-    launch_rstd(h, rstd, T, d, m.rms_eps, st);
+    launch_rmsnorm_rows(h, c->norm2[j], ab, T, d, m.rms_eps, st);
     tm.end();
     {
       GemmParams g{};
-      g.A = h; g.lda = d; g.M = T; g.N = 2 * m.ffn; g.K = d; g.wtab = c->gu_tab[j]; g.ldw = d;
-      g.gain_tab = c->norm2_tab[j]; g.gain_seg = 1 << 30; g.rstd = rstd; g.C = zb; g.ldc = m.ffn;
+      g.A = ab; g.lda = d; g.M = T; g.N = 2 * m.ffn; g.K = d; g.wtab = c->gu_tab[j]; g.ldw = d;
+      g.C = zb; g.ldc = m.ffn;
       tm.begin(TC_GATEUP);
       if (launch_gemm(g, EPI_SWIGLU, 0, st) != 0) return fail(SWIFTKV_EHIP, "gate/up GEMM launch failed");
       tm.end();
@@ -666,7 +679,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
                     int32_t variant, void *stream) {
   if (!A || !W || !C) return fail(SWIFTKV_EINVAL, "null argument");
   if (M < 1 || N < 16 || K < 8 || (N % 16) || (K % 8)) return fail(SWIFTKV_EINVAL, "need M >= 1, N %% 16 == 0, K %% 8 == 0");
-  if (variant < 0 || variant > 3) return fail(SWIFTKV_EINVAL, "variant must be 0..3");
+  if (variant < 0 || variant > 9) return fail(SWIFTKV_EINVAL, "variant must be 0..9");
   hipStream_t st = (hipStream_t)stream;
   if (variant == 3) {
     if (M > 80) return fail(SWIFTKV_EINVAL, "weight-streaming kernel handles M <= 80");
@@ -676,6 +689,9 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
   }
   GemmParams g{};
   g.A = (const bf16_t *)A; g.lda = K; g.M = M; g.N = N; g.K = K; g.W = (const bf16_t *)W; g.ldw = K; g.C = C; g.ldc = N;
+  if (variant == 6 || variant == 7) { g.dbg = variant - 5; variant = 4; }
+  if (variant == 8) { g.dbg = 4; variant = 4; }
+  if (variant == 9) { g.dbg = 4; variant = 5; }
   if (launch_gemm(g, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, variant, st)) return fail(SWIFTKV_EHIP, "gemm launch failed");
   return check_launch("gemm");
 }

@@ -102,6 +102,7 @@ struct GemmParams {
   int32_t first_cache_layer;   // KV: cache layer of projection 0
   bf16_t *stage;               // KV FP8 mode: staging [M, N] bf16 instead of the cache
   uint32_t *amax;              // FP8: [n_cache_layers][2][Hkv] absmax bit patterns (atomicMax), or null
+  int32_t dbg;                 // timing experiments only: 1 = no global loads in the k loop, 2 = always k-tile 0
 };
 
 int launch_gemm(const GemmParams &p, int epi, int variant, hipStream_t st);
@@ -177,6 +178,7 @@ int launch_rstd(const bf16_t *h, float *rstd, int32_t T, int32_t d, float eps, h
 int launch_rmsnorm_rows(const bf16_t *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, hipStream_t st);
 int launch_gather_rows(const bf16_t *h, const int32_t *rows, bf16_t *out, int32_t n_rows, int32_t d, hipStream_t st);
 int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t st);
+int launch_fold_gain(const bf16_t *W, const bf16_t *gain, bf16_t *out, int64_t rows, int32_t K, hipStream_t st);
 
 struct KVTile {  // 64 consecutive new tokens of one sequence
   int32_t row0;     // packed row of first token

@@ -114,6 +114,25 @@ int launch_rmsnorm_rows(const bf16_t *h, const bf16_t *gain, bf16_t *out, int32_
   return 0;
 }
 
+// ------------------------------------------- fold a norm gain into weights ----
+// out[n, k] = bf16(W[n, k] * gain[k]): RMSNorm_j(x) W^T = rstd(x) * (x (W diag(g_j))^T), so the
+// per-layer gain can live in the weights and only the row scale rstd is left for the GEMM epilogue.
+__global__ void fold_gain_kernel(const uint4 *W, const uint4 *gain, uint4 *out, int64_t n_chunks, int chunks_per_row) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_chunks) return;
+  uint4 u = W[i], g = gain[i % chunks_per_row], o;
+  o.x = pack_bf16x2(bf16lo(u.x) * bf16lo(g.x), bf16hi(u.x) * bf16hi(g.x));
+  o.y = pack_bf16x2(bf16lo(u.y) * bf16lo(g.y), bf16hi(u.y) * bf16hi(g.y));
+  o.z = pack_bf16x2(bf16lo(u.z) * bf16lo(g.z), bf16hi(u.z) * bf16hi(g.z));
+  o.w = pack_bf16x2(bf16lo(u.w) * bf16lo(g.w), bf16hi(u.w) * bf16hi(g.w));
+  out[i] = o;
+}
+int launch_fold_gain(const bf16_t *W, const bf16_t *gain, bf16_t *out, int64_t rows, int32_t K, hipStream_t st) {
+  int64_t n = rows * (K / 8);
+  hipLaunchKernelGGL(fold_gain_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const uint4 *)W, (const uint4 *)gain, (uint4 *)out, n, K / 8);
+  return 0;
+}
+
 // -------------------------------------------------------------- gather -----
 __global__ void gather_rows_kernel(const uint4 *h, const int32_t *rows, uint4 *out, int n_rows, int chunks) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
