@@ -679,7 +679,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
                     int32_t variant, void *stream) {
   if (!A || !W || !C) return fail(SWIFTKV_EINVAL, "null argument");
   if (M < 1 || N < 16 || K < 8 || (N % 16) || (K % 8)) return fail(SWIFTKV_EINVAL, "need M >= 1, N %% 16 == 0, K %% 8 == 0");
-  if (variant < 0 || variant > 9) return fail(SWIFTKV_EINVAL, "variant must be 0..9");
+  if (variant < 0 || variant > 15) return fail(SWIFTKV_EINVAL, "variant must be 0..15");
   hipStream_t st = (hipStream_t)stream;
   if (variant == 3) {
     if (M > 80) return fail(SWIFTKV_EINVAL, "weight-streaming kernel handles M <= 80");
@@ -689,9 +689,16 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
   }
   GemmParams g{};
   g.A = (const bf16_t *)A; g.lda = K; g.M = M; g.N = N; g.K = K; g.W = (const bf16_t *)W; g.ldw = K; g.C = C; g.ldc = N;
-  if (variant == 6 || variant == 7) { g.dbg = variant - 5; variant = 4; }
-  if (variant == 8) { g.dbg = 4; variant = 4; }
-  if (variant == 9) { g.dbg = 4; variant = 5; }
+  if (variant == 6) { g.dbg = 2; variant = 5; }
+  if (variant == 7) { g.dbg = 2; variant = 4; }
+  if (variant == 8) { g.dbg = 6; variant = 5; }
+  if (variant == 9) { g.dbg = 7; variant = 5; }
+  if (variant >= 10 && variant <= 13) {  // 10/11: cycle breakdown of variant 5/4; C must have room for 5*8*n_waves*n_workgroups bytes of int64 counters after the M x N result
+    g.dbg = 8; g.stage = (bf16_t *)C + (int64_t)M * N;
+    if (variant >= 12) { g.head_dim = 1; variant -= 2; }   // 12/13: same without the global loads
+    variant = variant == 10 ? 5 : 4;   // counters go after the M x N result
+    if (out_f32) return fail(SWIFTKV_EINVAL, "profiling variants need bf16 output");
+  }
   if (launch_gemm(g, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, variant, st)) return fail(SWIFTKV_EHIP, "gemm launch failed");
   return check_launch("gemm");
 }

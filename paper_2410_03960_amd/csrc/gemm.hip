@@ -20,9 +20,12 @@
 // the concatenated [W_K;W_V] of all AcrossKV group leaders be consumed in place.
 #include "common.h"
 
+#include <cstdlib>
+
 namespace {
 
 constexpr int BK = 64;
+int g_big_variant = 14;   // main loop used for large plain GEMMs: 14 = five-stage direct-to-LDS, 5 = two-stage
 
 // Shared epilogue.  acc[bn][bm][4*jg + e] is C[m][n + e] with
 // m = m_base + bm*32 + (lane & 31), n = n_base + bn*32 + 8*jg + 4*(lane >> 5).
@@ -315,7 +318,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(GemmParams p) {
 // MFMA operand reads expect.
 // No staging registers and no LDS store instructions; needs K % 64 == 0 and no
 // gain prologue.
-template <int BM, int BN, int WGM, int WGN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int EPI, bool PROF = false>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds_kernel(GemmParams p) {
   constexpr int NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -375,32 +378,6 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds_kernel(GemmParams p) 
       __builtin_amdgcn_global_load_lds((glb_ptr_t)(w_ptr[i] + k0), (lds_ptr_t)(sb + (wave + i * NW) * 1024), 16, 0, 0);
   };
 
-  // L2 prefetch two k-tiles ahead: a 4-byte LDS-DMA read of the first word of
-  // every 128-byte row segment of that tile, dumped into a scratch corner of LDS.
-  // It costs no registers, pulls the lines into L2 early, and - because vector
-  // loads retire in order - the end-of-tile wait can leave exactly these
-  // youngest requests outstanding (vmcnt(PF)).
-  constexpr int PF = (BM + BN) / (NW * 64);   // prefetch instructions per wave per tile
-  const bf16_t *pf_ptr[PF];
-#pragma unroll
-  for (int i = 0; i < PF; ++i) {
-    const int row = tid + i * NW * 64;        // 0..BM-1: A rows, BM..BM+BN-1: W rows
-    if (row < BM) {
-      int m = m0 + row;
-      m = m < p.M ? m : p.M - 1;
-      pf_ptr[i] = p.A + (int64_t)m * p.lda;
-    } else {
-      int n = n0 + row - BM;
-      n = n < p.N ? n : p.N - 1;
-      pf_ptr[i] = p.wtab ? p.wtab[n >> 4] + (int64_t)(n & 15) * p.ldw : p.W + (int64_t)n * p.ldw;
-    }
-  }
-  unsigned char *pf_lds = smem + 2 * STAGE_BYTES + wave * 256;
-  auto prefetch = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < PF; ++i) __builtin_amdgcn_global_load_lds((glb_ptr_t)(pf_ptr[i] + k0), (lds_ptr_t)pf_lds, 4, 0, 0);
-  };
-
   floatx16 acc[FN][FM];
 #pragma unroll
   for (int bn = 0; bn < FN; ++bn)
@@ -426,48 +403,337 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds_kernel(GemmParams p) 
   };
 
   const int nk = p.K / BK;
-  const bool use_pf = p.dbg != 4;
+  long long t_vm = 0, t_bar = 0, t_frag = 0, t_begin = 0;
+  if constexpr (PROF) t_begin = clock64();
   issue_loads(0, 0);
-  if (nk > 1 && use_pf) prefetch(BK);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk && p.dbg != 1) issue_loads((kt + 1) & 1, p.dbg == 2 ? 0 : (kt + 1) * BK);
-    // always issued (clamped to the last tile) so that the vmcnt below is a constant
-    if (use_pf) prefetch((kt + 2 < nk ? kt + 2 : nk - 1) * BK);
     const unsigned char *st = smem + (kt & 1) * STAGE_BYTES;
+    long long tf0 = 0;
+    if constexpr (PROF) tf0 = clock64();
     load_frags(0, st, 0);
+    if constexpr (PROF) { __builtin_amdgcn_s_waitcnt(0xC07F); t_frag += clock64() - tf0; }
     __builtin_amdgcn_sched_barrier(0);
+    // Step 0: its MFMAs are interleaved one-to-one with the LDS-DMA loads of the
+    // next tile and with the operand reads of step 1, so that every non-MFMA
+    // instruction issues in the shadow of an MFMA that is executing.  The loads
+    // are unconditional (after the last tile they re-read it into the idle stage).
+    {
+      const int nstage = (kt + 1) & 1;
+      const int nk0 = p.dbg == 2 ? 0 : (kt + 1 < nk ? kt + 1 : kt) * BK;
+      unsigned char *nsa = smem + nstage * STAGE_BYTES;
+      unsigned char *nsb = nsa + BM * 128;
+      const int cc1 = 2 + g;
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      // Operands of step kk+1 are requested right after the first MFMAs of step
-      // kk were issued, so at the top of every step the only outstanding LDS
-      // reads are the ones it needs, and they have had most of a step to arrive.
+      for (int i = 0; i < FN * FM; ++i) {
+        const int bn = i / FM, bm = i % FM;
+        acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0][bn], af[0][bm], acc[bn][bm], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!PROF || p.head_dim == 0) {   // (the profiling build can drop the loads: head_dim = 1 there means "no loads")
+          if (i < A_CH)
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(a_ptr[i] + nk0), (lds_ptr_t)(nsa + (wave + i * NW) * 1024), 16, 0, 0);
+          else if (i < A_CH + B_CH)
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(w_ptr[i - A_CH] + nk0), (lds_ptr_t)(nsb + (wave + (i - A_CH) * NW) * 1024), 16, 0, 0);
+        }
+        if (i < FN) wf[1][i] = *(const bf16x8 *)(st + w_off[i] + ((cc1 ^ w_sw[i]) << 4));
+        else if (i < FN + FM) af[1][i - FN] = *(const bf16x8 *)(st + a_off[i - FN] + ((cc1 ^ a_sw[i - FN]) << 4));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
 #pragma unroll
-      for (int bm = 0; bm < FM; ++bm)
-        acc[0][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk & 1][0], af[kk & 1][bm], acc[0][bm], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
+    for (int kk = 1; kk < BK / 16; ++kk) {
       if (kk + 1 < BK / 16) load_frags((kk + 1) & 1, st, kk + 1);
-      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int bn = 1; bn < FN; ++bn)
+      for (int bn = 0; bn < FN; ++bn)
 #pragma unroll
         for (int bm = 0; bm < FM; ++bm)
           acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk & 1][bn], af[kk & 1][bm], acc[bn][bm], 0, 0, 0);
+      if (kk + 1 < BK / 16) {
+#pragma unroll
+        for (int i = 0; i < FN + FM; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
-    // this wave's loads of the next tile have landed in LDS; the PF prefetches issued after them may still fly
-    if (use_pf) __builtin_amdgcn_s_waitcnt(0x0F70 | PF); else __builtin_amdgcn_s_waitcnt(0x0F70);
+    long long t0 = 0, t1 = 0;
+    if constexpr (PROF) t0 = clock64();
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // this wave's loads of the next tile have landed in LDS
+    if constexpr (PROF) t1 = clock64();
     __syncthreads();
+    if constexpr (PROF) { t_vm += t1 - t0; t_bar += clock64() - t1; }
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the last prefetches before LDS is released
+  if constexpr (PROF) {
+    long long t_loop = clock64() - t_begin;
+    gemm_epilogue<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
+    if (lane == 0 && p.stage) {   // experiment only: `stage` doubles as the int64 output [wg][wave][5]
+      long long *o = (long long *)p.stage + ((long long)blockIdx.x * (WGM * WGN) + wave) * 5;
+      o[0] = t_loop; o[1] = t_vm; o[2] = t_bar; o[3] = t_frag; o[4] = clock64() - t_begin;
+    }
+    return;
+  }
+  gemm_epilogue<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
+}
+
+// ---------------------------------------------------------------------------
+// Five-stage variant of the direct-to-LDS main loop with 32-wide k steps.
+// LDS holds five (BM+BN) x 64-byte stages (160 KB for 256x256): while step t is
+// multiplied, the loads of steps t+3 and t+4 are in flight and step t+1/t+2 are
+// resident.  The LDS-DMA instructions of a step are spread one by one between
+// its MFMAs (the address unit accepts about one 1 KB request per 16 cycles per
+// CU, so a burst of them stalls the issuing waves), operand fragments of the
+// next k sub-step are fetched between the MFMAs of the current one, including
+// across the step boundary, and the only synchronisation is one barrier per
+// step, which (a) publishes the step that landed two steps ahead and (b) frees
+// the stage that the next step's loads overwrite.
+// A stage row is 64 bytes = four 16-byte chunks; chunk c of row r sits at
+// physical chunk c ^ ((r >> 2) & 3), which makes any 16 consecutive rows of one
+// logical chunk hit 16 different bank groups.
+// One LDS-DMA request: 64 lanes x 16 bytes from per-lane global addresses into the 1 KB of LDS
+// starting at byte offset lds_addr (wave-uniform).  Written as inline assembly because the
+// compiler, not knowing which LDS bytes a DMA targets, would otherwise wait for *all* outstanding
+// loads before the next LDS read; here the waits are placed by hand (s_waitcnt vmcnt).
+__device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+}
+
+template <int BM, int BN, int WGM, int WGN, int EPI>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p) {
+  constexpr int NW = WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  static_assert(WTN == 128 && WTM % 32 == 0, "wave tile");
+  constexpr int FM = WTM / 32, FN = WTN / 32;
+  constexpr int NS = 5, BKS = 32;
+  constexpr int A_CH = BM / 16 / NW, B_CH = BN / 16 / NW;   // 1 KB chunks (16 rows) per wave per stage
+  constexpr int LPW = A_CH + B_CH;                           // LDS-DMA loads per wave per step
+  constexpr int STAGE_BYTES = (BM + BN) * 64;
+  constexpr int NMF = FN * FM;                               // MFMAs per 16-wide sub-step
+  static_assert(LPW % 2 == 0 && LPW / 2 <= NMF && FN + FM <= NMF, "interleave slots");
+
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int l32 = lane & 31, g = lane >> 5;
+
+  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+  const int total = tiles_m * tiles_n;
+  const int per_xcd = (total + 7) / 8;
+  const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (logical >= total) return;
+  constexpr int GM = 8;
+  const int group = logical / (GM * tiles_n);
+  const int first_m = group * GM;
+  const int gsz = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+  const int in_group = logical % (GM * tiles_n);
+  const int tm = first_m + in_group % gsz, tn = in_group / gsz;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  // LDS-DMA source: lane i of a 16-row chunk -> row i/4, logical chunk (i%4) ^ ((i/16)&3)
+  const int cr = lane >> 2;
+  const int cl = (lane & 3) ^ ((lane >> 4) & 3);
+  const bf16_t *a_ptr[A_CH];
+  const bf16_t *w_ptr[B_CH];
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) {
+    int m = m0 + (wave + i * NW) * 16 + cr;
+    m = m < p.M ? m : p.M - 1;
+    a_ptr[i] = p.A + (int64_t)m * p.lda + cl * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) {
+    int n = n0 + (wave + i * NW) * 16 + cr;
+    n = n < p.N ? n : p.N - 1;
+    w_ptr[i] = (p.wtab ? p.wtab[n >> 4] + (int64_t)(n & 15) * p.ldw : p.W + (int64_t)n * p.ldw) + cl * 8;
+  }
+  typedef __attribute__((address_space(3))) void *lds_ptr_t;
+  const unsigned lds_base = (unsigned)(size_t)(lds_ptr_t)smem;
+  // one of the LPW loads of a step: idx < A_CH -> A chunk, else W chunk; `stage` = byte offset of the stage
+  auto issue_one = [&](int idx, unsigned stage, int k0) {
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i)
+      if (idx == i) lds_dma16(a_ptr[i] + k0, lds_base + stage + (wave + i * NW) * 1024);
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i)
+      if (idx == A_CH + i) lds_dma16(w_ptr[i] + k0, lds_base + stage + BM * 64 + (wave + i * NW) * 1024);
+  };
+
+  floatx16 acc[FN][FM];
+#pragma unroll
+  for (int bn = 0; bn < FN; ++bn)
+#pragma unroll
+    for (int bm = 0; bm < FM; ++bm)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[bn][bm][v] = 0.f;
+
+  int w_off[FN], a_off[FM], w_sw[FN], a_sw[FM];
+#pragma unroll
+  for (int bn = 0; bn < FN; ++bn) { int r = wn * WTN + bn * 32 + l32; w_off[bn] = BM * 64 + r * 64; w_sw[bn] = (r >> 2) & 3; }
+#pragma unroll
+  for (int bm = 0; bm < FM; ++bm) { int r = wm * WTM + bm * 32 + l32; a_off[bm] = r * 64; a_sw[bm] = (r >> 2) & 3; }
+
+  bf16x8 wf[2][FN], af[2][FM];
+  // fragment idx (0..FN+FM-1) of sub-step kk from stage st into buffer buf
+  auto load_frag = [&](int idx, int buf, const unsigned char *st, int kk) {
+    const int cc = kk * 2 + g;
+#pragma unroll
+    for (int bn = 0; bn < FN; ++bn)
+      if (idx == bn) wf[buf][bn] = *(const bf16x8 *)(st + w_off[bn] + ((cc ^ w_sw[bn]) << 4));
+#pragma unroll
+    for (int bm = 0; bm < FM; ++bm)
+      if (idx == FN + bm) af[buf][bm] = *(const bf16x8 *)(st + a_off[bm] + ((cc ^ a_sw[bm]) << 4));
+  };
+
+  const int nk = p.K / BKS;
+  // prologue: steps 0..3 in flight, steps 0 and 1 resident
+#pragma unroll
+  for (int s0 = 0; s0 < NS - 1; ++s0) {
+    const int k0 = (s0 < nk ? s0 : nk - 1) * BKS;
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) issue_one(i, s0 * STAGE_BYTES, k0);
+  }
+  constexpr int VMCNT2 = 2 * LPW;   // two youngest groups may stay in flight
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (VMCNT2 & 15) | ((VMCNT2 >> 4) << 14));
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < FN + FM; ++i) load_frag(i, 0, smem, 0);
+
+  int s_cur = 0;                 // stage of step t
+  for (int t = 0; t < nk; ++t) {
+    const int s_nxt = s_cur + 1 < NS ? s_cur + 1 : 0;           // stage of step t+1 (resident)
+    const int s_ld = s_cur == 0 ? NS - 1 : s_cur - 1;           // stage of step t+4 = stage of step t-1 (free)
+    const unsigned char *st = smem + s_cur * STAGE_BYTES;
+    const unsigned char *stn = smem + s_nxt * STAGE_BYTES;
+    const unsigned stl = s_ld * STAGE_BYTES;
+    const int kl = (t + NS - 1 < nk ? t + NS - 1 : nk - 1) * BKS;   // clamped: the request count per step stays constant
+    __builtin_amdgcn_sched_barrier(0);
+    // sub-step 0: MFMAs on fragment buffer 0; fetch buffer 1 (sub-step 1 of this stage); first half of the loads
+#pragma unroll
+    for (int i = 0; i < NMF; ++i) {
+      const int bn = i / FM, bm = i % FM;
+      acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0][bn], af[0][bm], acc[bn][bm], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (i < FN + FM) load_frag(i, 1, st, 1);
+      if (i >= NMF - LPW / 2) issue_one(i - (NMF - LPW / 2), stl, kl);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // sub-step 1: MFMAs on buffer 1; fetch buffer 0 from the next stage (resident since the previous barrier); second half of the loads
+#pragma unroll
+    for (int i = 0; i < NMF; ++i) {
+      const int bn = i / FM, bm = i % FM;
+      acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1][bn], af[1][bm], acc[bn][bm], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (i < FN + FM) load_frag(i, 0, stn, 0);
+      if (i >= NMF - LPW / 2) issue_one(LPW / 2 + i - (NMF - LPW / 2), stl, kl);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (VMCNT2 & 15) | ((VMCNT2 >> 4) << 14));   // step t+2 has landed (this wave's part)
+    __syncthreads();
+    s_cur = s_nxt;
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped extra loads before LDS is released
   gemm_epilogue<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI>
-int launch_dlds(const GemmParams &p, hipStream_t st) {
+int launch_dlds5(const GemmParams &p, hipStream_t st) {
   constexpr int NT = WGM * WGN * 64;
-  constexpr int SMEM = 2 * (BM + BN) * 128 + WGM * WGN * 256;   // two stages + prefetch scratch
+  constexpr int SMEM = 5 * (BM + BN) * 64;
+  auto kern = gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+    if (e != hipSuccess) return (int)e;
+    attr_set = true;
+  }
+  const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+  const int grid = ((tiles + 7) / 8) * 8;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), SMEM, st, p);
+  return 0;
+}
+
+// Timing experiment: the memory side of gemm_dlds_kernel alone (same addresses,
+// same LDS-DMA instructions, same wait + barrier per k tile, no MFMA work).
+template <int BM, int BN, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_loadonly_kernel(GemmParams p) {
+  constexpr int A_CH = BM / 8 / NW, B_CH = BN / 8 / NW;
+  constexpr int STAGE_BYTES = (BM + BN) * 128;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+  const int total = tiles_m * tiles_n;
+  const int per_xcd = (total + 7) / 8;
+  const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (logical >= total) return;
+  constexpr int GM = 8;
+  const int group = logical / (GM * tiles_n);
+  const int first_m = group * GM;
+  const int gsz = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+  const int in_group = logical % (GM * tiles_n);
+  const int m0 = (first_m + in_group % gsz) * BM, n0 = (in_group / gsz) * BN;
+  const int cr = lane >> 3;
+  const int cl = (lane & 7) ^ (((wave & 1) << 2) | (cr >> 1));
+  const bf16_t *a_ptr[A_CH];
+  const bf16_t *w_ptr[B_CH];
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) {
+    int m = m0 + (wave + i * NW) * 8 + cr;
+    m = m < p.M ? m : p.M - 1;
+    a_ptr[i] = p.A + (int64_t)m * p.lda + cl * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) {
+    int n = n0 + (wave + i * NW) * 8 + cr;
+    n = n < p.N ? n : p.N - 1;
+    w_ptr[i] = p.W + (int64_t)n * p.ldw + cl * 8;
+  }
+  typedef __attribute__((address_space(3))) void *lds_ptr_t;
+  typedef const __attribute__((address_space(1))) void *glb_ptr_t;
+  const int nk = p.K / BK;
+  for (int kt = 0; kt < nk; ++kt) {
+    unsigned char *sa = smem + (kt & 1) * STAGE_BYTES;
+    unsigned char *sb = sa + BM * 128;
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i)
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(a_ptr[i] + kt * BK), (lds_ptr_t)(sa + (wave + i * NW) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i)
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(w_ptr[i] + kt * BK), (lds_ptr_t)(sb + (wave + i * NW) * 1024), 16, 0, 0);
+    if (p.dbg == 6 || (kt & 1)) {   // dbg 6: wait every tile; dbg 7: every second tile (two tiles in flight)
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
+  if (p.dbg == 12345) ((float *)p.C)[tid] = smem[tid];
+}
+
+template <int BM, int BN, int WGM, int WGN, int EPI>
+int launch_dlds(const GemmParams &p, hipStream_t st) {
+  if (p.dbg == 6 || p.dbg == 7) {
+    constexpr int NWV = WGM * WGN;
+    constexpr int SMEMX = 2 * (BM + BN) * 128;
+    auto kx = gemm_loadonly_kernel<BM, BN, NWV>;
+    (void)hipFuncSetAttribute((const void *)kx, hipFuncAttributeMaxDynamicSharedMemorySize, SMEMX);
+    const int tilesx = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+    hipLaunchKernelGGL(kx, dim3(((tilesx + 7) / 8) * 8), dim3(NWV * 64), SMEMX, st, p);
+    return 0;
+  }
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int SMEM = 2 * (BM + BN) * 128;
+  if constexpr (EPI == EPI_STORE_BF16) {
+    if (p.dbg == 8) {   // timing experiment: per-wave cycle breakdown written through p.stage
+      auto kp = gemm_dlds_kernel<BM, BN, WGM, WGN, EPI, true>;
+      (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+      const int tl = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+      hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(NT), SMEM, st, p);
+      return 0;
+    }
+  }
   auto kern = gemm_dlds_kernel<BM, BN, WGM, WGN, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -500,13 +766,16 @@ int launch_one(const GemmParams &p, hipStream_t st) {
 
 template <int EPI, bool GAIN>
 int launch_epi(const GemmParams &p, int variant, hipStream_t st) {
-  if (variant == 0) variant = (p.M >= 1024) ? ((!GAIN && (p.K % BK) == 0) ? 5 : 1) : 2;
+  if (variant == 0) variant = (p.M >= 1024) ? ((!GAIN && (p.K % BK) == 0) ? g_big_variant : 1) : 2;
   if constexpr (!GAIN) {
     if ((variant == 4 || variant == 5) && (p.K % BK) != 0) variant = 1;
+    if ((variant == 14 || variant == 15) && (p.K % BK) != 0) variant = 1;
+    if (variant == 14) return launch_dlds5<256, 256, 2, 2, EPI>(p, st);
+    if (variant == 15) return launch_dlds5<256, 256, 4, 2, EPI>(p, st);
     if (variant == 4) return launch_dlds<256, 256, 4, 2, EPI>(p, st);
     if (variant == 5) return launch_dlds<256, 256, 2, 2, EPI>(p, st);
   }
-  if (variant == 1 || variant == 4 || variant == 5) return launch_one<256, 256, 2, 2, EPI, GAIN>(p, st);
+  if (variant == 1 || variant == 4 || variant == 5 || variant == 14 || variant == 15) return launch_one<256, 256, 2, 2, EPI, GAIN>(p, st);
   return launch_one<128, 128, 4, 1, EPI, GAIN>(p, st);
 }
 
@@ -514,6 +783,12 @@ int launch_epi(const GemmParams &p, int variant, hipStream_t st) {
 
 int launch_gemm(const GemmParams &p, int epi, int variant, hipStream_t st) {
   if (p.M <= 0 || p.N <= 0 || p.K <= 0) return 0;
+  static bool env_read = false;
+  if (!env_read) {   // SWIFTKV_GEMM_MAINLOOP=5|14|15 picks the main loop of large GEMMs (tuning aid)
+    const char *e = getenv("SWIFTKV_GEMM_MAINLOOP");
+    if (e && (atoi(e) == 5 || atoi(e) == 14 || atoi(e) == 15 || atoi(e) == 4 || atoi(e) == 1)) g_big_variant = atoi(e);
+    env_read = true;
+  }
   const bool gain = p.gain_tab != nullptr;
   switch (epi) {
     case EPI_STORE_BF16: return launch_epi<EPI_STORE_BF16, false>(p, variant, st);
