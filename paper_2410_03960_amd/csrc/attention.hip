@@ -18,7 +18,7 @@ constexpr int BQ = 128;   // queries per workgroup
 constexpr int BKV = 64;   // keys per tile
 
 template <int HD>
-__global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillParams p) {
+__global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams p) {
   constexpr int KROW = HD * 2 + 16;        // padded K row bytes (conflict-free 16-byte reads)
   constexpr int VROW = BKV * 2 + 8;        // padded V^T row bytes (conflict-free 8-byte reads)
   constexpr int K_BYTES = BKV * KROW, V_BYTES = HD * VROW;
@@ -66,7 +66,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillParams p) 
       int idx = tid + i * 256;
       int r = idx / KCH, c = idx % KCH;
       int key = key0 + r;
-      rk[i] = key < qb.n ? *(const uint4 *)(kbase + (int64_t)key * kv_dim + c * 8) : make_uint4(0, 0, 0, 0);
+      key = key < qb.n ? key : qb.n - 1;   // rows past the end are masked later; any finite data will do
+      rk[i] = *(const uint4 *)(kbase + (int64_t)key * kv_dim + c * 8);
     }
 #pragma unroll
     for (int i = 0; i < V_IT; ++i) {
@@ -100,6 +101,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillParams p) 
     for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = 1.4426950408889634f * rsqrtf((float)HD);   // log2(e) / sqrt(hd)
+  const float inv_sc = 1.0f / sc;
 
   load_tile(0);
   store_tile(0);
@@ -112,62 +114,95 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillParams p) 
       const unsigned char *sv = sk + K_BYTES;
       floatx16 s[2];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
+      // K operand fragments are fetched one group (GK MFMAs' worth) ahead of their use, and the
+      // first V^T fragments are requested before the softmax arithmetic starts.
+      constexpr int NG = DS / 2;              // groups per tile: two d steps x two key blocks = 4 independent-ish MFMAs
+      bf16x8 kfr[2][4];
+      uint4 vfr[2][DB];
+      auto load_k = [&](int buf, int gi) {
 #pragma unroll
-        for (int ds = 0; ds < DS; ++ds) {
-          bf16x8 kf = *(const bf16x8 *)(sk + (kb * 32 + l32) * KROW + (ds * 2 + g) * 16);
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ds], s[kb], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) {
+          const int kb = i & 1, ds = gi * 2 + (i >> 1);
+          kfr[buf][i] = *(const bf16x8 *)(sk + (kb * 32 + l32) * KROW + (ds * 2 + g) * 16);
         }
+      };
+      auto load_v = [&](int buf, int st) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const unsigned char *vp = sv + (db * 32 + l32) * VROW + (st * 16 + 4 * g) * 2;
+          uint2 lo = *(const uint2 *)vp, hi = *(const uint2 *)(vp + 16);
+          vfr[buf][db] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        }
+      };
+      load_k(0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int gi = 0; gi < NG; ++gi) {
+        if (gi + 1 < NG) load_k((gi + 1) & 1, gi + 1); else load_v(0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {   // alternate the two accumulators so consecutive MFMAs are independent
+          const int kb = i & 1, ds = gi * 2 + (i >> 1);
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[gi & 1][i], qf[ds], s[kb], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      // s[kb][4*jg+e] = score(key = key0 + kb*32 + 8*jg + 4*g + e, this lane's query)
+      // s[kb][4*jg+e] = raw score(key = key0 + kb*32 + 8*jg + 4*g + e, this lane's query)
       const bool need_mask = (key0 + BKV - 1 > qb.q0 + wave * 32) || (key0 + BKV > qb.n);
-      float mx = m_run;
+      if (need_mask) {   // wave-uniform: only tiles on the diagonal or at the end of the sequence
+        // element (kb, v) is key key0 + 4*g + kb*32 + 8*(v>>2) + (v&3); visible iff key <= min(qpos, n-1)
+        const int lim = (qpos < qb.n - 1 ? qpos : qb.n - 1) - key0 - 4 * g;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) s[kb][v] = (kb * 32 + 8 * (v >> 2) + (v & 3) > lim) ? -INFINITY : s[kb][v];
+      }
+      float mx = -INFINITY;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float x = s[kb][v] * sc;
-          if (need_mask) {
-            int key = key0 + kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-            if (key > qpos || key >= qb.n) x = -INFINITY;
-          }
-          s[kb][v] = x;
-          mx = fmaxf(mx, x);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      // every query sees key 0 <= qpos, and tile 0 is never skipped, so mx is finite from the first tile on
-      const float alpha = exp2f(m_run - mx);
-      m_run = mx;
+        for (int v = 0; v < 16; ++v) mx = __builtin_fmaxf(mx, s[kb][v]);
+      mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
+      // Lazy rescaling: the reference maximum m_run (raw score units) only moves when some query's
+      // tile maximum exceeds it by more than 8/sc, i.e. when an exponential would exceed 2^8.  The
+      // result is unchanged (numerator and denominator share m_run); the 64-register rescale of O
+      // is skipped on most tiles.  Every query sees key 0 in tile 0, so m_run is finite from then on.
+      if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.0f * inv_sc) != 0) {
+        const float m_new = __builtin_fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+      }
+      const float msc = m_run * sc;
       float rs = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          float e = exp2f(s[kb][v] - mx);
+          float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], sc, -msc));   // exp2 of (-inf) is 0
           s[kb][v] = e;
           rs += e;
         }
-      l_run = l_run * alpha + rs;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+      l_run += rs;
       // O^T += V^T P^T, 16 keys per MFMA: step st uses s[st/2][(st%2)*8 .. +8]
 #pragma unroll
       for (int st = 0; st < 4; ++st) {
         bf16x8 pf;
 #pragma unroll
         for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s[st >> 1][(st & 1) * 8 + e];
+        if (st + 1 < 4) load_v((st + 1) & 1, st + 1);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const unsigned char *vp = sv + (db * 32 + l32) * VROW + (st * 16 + 4 * g) * 2;
-          uint2 lo = *(const uint2 *)vp, hi = *(const uint2 *)(vp + 16);
-          uint4 vv = make_uint4(lo.x, lo.y, hi.x, hi.y);
-          bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[db], 0, 0, 0);
-        }
+        for (int db = 0; db < DB; ++db)
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vfr[st & 1][db]), pf, o[db], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     if (t + 1 < n_tiles) store_tile((t + 1) & 1);
