@@ -16,6 +16,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+# HBM-side bytes per launch of the dominant kernel (gate/up GEMM), from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# scaled on a 1 GiB copy: see profiles/bench_8b_l16_b8x2048_hbm_traffic.txt (rocprofv3 cannot run inside the bench)
+MEASURED_TRAFFIC_BYTES = {("8b_l16_b8x2048", "gateup_gemm"): 5826.5 * 2 ** 20}
 
 
 def main():
@@ -28,6 +31,9 @@ def main():
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-launch HIP events (roofline is then null)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=256)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first copy 1 GiB device-to-device (a plain copy of known size, to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
@@ -39,6 +45,13 @@ def main():
     from paper_2410_03960_amd import binding as B
 
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 29, dtype=torch.bfloat16, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     wl = WL.get_workload(args.workload)
     sh = wl.shape
     t0 = time.time()
@@ -123,7 +136,8 @@ def main():
             roof = {"bound": "mfma", "kernel": f"gemm_kernel ({dom})", "achieved": classes[dom]["tflops"],
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": classes[dom]["tflops"] / PEAK_BF16_TFLOPS,
                     "avg_launch_ms": classes[dom]["avg_launch_ms"],
-                    "flops_per_launch": per_launch_flops[dom], "traffic": None}
+                    "flops_per_launch": per_launch_flops[dom],
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom))}
     out["roofline"] = roof
 
     if not args.no_cpu_baseline:
