@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -695,8 +696,8 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
   if (variant == 9) { g.dbg = 7; variant = 5; }
   if (variant >= 10 && variant <= 13) {  // 10/11: cycle breakdown of variant 5/4; C must have room for 5*8*n_waves*n_workgroups bytes of int64 counters after the M x N result
     g.dbg = 8; g.stage = (bf16_t *)C + (int64_t)M * N;
-    if (variant >= 12) { g.head_dim = 1; variant -= 2; }   // 12/13: same without the global loads
-    variant = variant == 10 ? 5 : 4;   // counters go after the M x N result
+    if (variant >= 12) { variant = variant == 12 ? 14 : 15; }   // 12/13: the five-stage loop with 4 / 8 waves
+    else variant = variant == 10 ? 5 : 4;   // counters go after the M x N result
     if (out_f32) return fail(SWIFTKV_EINVAL, "profiling variants need bf16 output");
   }
   if (launch_gemm(g, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, variant, st)) return fail(SWIFTKV_EHIP, "gemm launch failed");
@@ -706,7 +707,8 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
 size_t swiftkv_op_attention_workspace(int64_t n_tokens, int32_t n_seqs, int32_t n_kv_heads, int32_t head_dim) {
   const int64_t vt_ld = n_tokens + 64LL * n_seqs;
   return align_up((size_t)n_kv_heads * head_dim * vt_ld * 2) + align_up((size_t)(n_tokens / 128 + n_seqs) * 32) +
-         align_up((size_t)(n_tokens / 64 + n_seqs) * 16) + 4096;
+         align_up((size_t)(n_tokens / 64 + n_seqs) * 16) + 4096 +
+         (size_t)(n_tokens / 128 + n_seqs) * 64 * 16 * 8;   // + room for the optional cycle counters (<= 64 heads)
 }
 
 int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, void *out, const int32_t *seq_lens,
@@ -740,6 +742,10 @@ int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, vo
   ap.q = (const bf16_t *)q; ap.k = (const bf16_t *)k; ap.vt = (const bf16_t *)(ws + o_vt); ap.vt_ld = vt_ld; ap.out = (bf16_t *)out;
   ap.qblocks = (const QBlock *)(ws + o_qb); ap.n_qblocks = (int32_t)(qbs.size() / 8);
   ap.n_q_heads = Hq; ap.n_kv_heads = Hkv; ap.head_dim = hd;
+  if (getenv("SWIFTKV_ATTN_PROF")) {   // timing experiment: per-wave cycle counters after the tables
+    const size_t need = (size_t)ap.n_qblocks * Hq * 16 * 8;
+    if (total + need <= workspace_bytes) ap.prof = (long long *)(ws + total);
+  }
   if (launch_attention_prefill(ap, st)) return fail(SWIFTKV_EHIP, "attention launch failed");
   return check_launch("attention");
 }

@@ -17,7 +17,7 @@ namespace {
 constexpr int BQ = 128;   // queries per workgroup
 constexpr int BKV = 64;   // keys per tile
 
-template <int HD>
+template <int HD, bool PROF = false>
 __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams p) {
   constexpr int KROW = HD * 2 + 16;        // padded K row bytes (conflict-free 16-byte reads)
   constexpr int VROW = BKV * 2 + 8;        // padded V^T row bytes (conflict-free 8-byte reads)
@@ -103,9 +103,12 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
   const float sc = 1.4426950408889634f * rsqrtf((float)HD);   // log2(e) / sqrt(hd)
   const float inv_sc = 1.0f / sc;
 
+  long long t_begin = 0, t_wait = 0, t_pro = 0;
+  if constexpr (PROF) t_begin = clock64();
   load_tile(0);
   store_tile(0);
   __syncthreads();
+  if constexpr (PROF) t_pro = clock64() - t_begin;
   for (int t = 0; t < n_tiles; ++t) {
     if (t + 1 < n_tiles) load_tile(t + 1);
     const int key0 = t * BKV;
@@ -205,8 +208,17 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+    long long tw0 = 0;
+    if constexpr (PROF) tw0 = clock64();
     if (t + 1 < n_tiles) store_tile((t + 1) & 1);
     __syncthreads();
+    if constexpr (PROF) t_wait += clock64() - tw0;
+  }
+  if constexpr (PROF) {
+    if (lane == 0 && p.prof) {
+      long long *o4 = p.prof + ((long long)(blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave) * 4;
+      o4[0] = clock64() - t_begin; o4[1] = t_wait; o4[2] = t_pro; o4[3] = n_tiles;
+    }
   }
 
   // ---- normalise and store: o[db][4*jg+e] = O[query][d = db*32 + 8*jg + 4*g + e] ----
@@ -379,6 +391,11 @@ int launch_attention_prefill(const AttnPrefillParams &p, hipStream_t st) {
       hipError_t e = hipFuncSetAttribute((const void *)attn_prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
       if (e != hipSuccess) return (int)e;
       set = true;
+    }
+    if (p.prof) {
+      (void)hipFuncSetAttribute((const void *)attn_prefill_kernel<128, true>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+      hipLaunchKernelGGL((attn_prefill_kernel<128, true>), grid, dim3(256), SMEM, st, p);
+      return 0;
     }
     hipLaunchKernelGGL(attn_prefill_kernel<128>, grid, dim3(256), SMEM, st, p);
   } else {

@@ -133,6 +133,7 @@ struct AttnPrefillParams {
   bf16_t *out;          // [T, q_dim]
   const QBlock *qblocks;
   int32_t n_qblocks, n_q_heads, n_kv_heads, head_dim;
+  long long *prof;      // timing experiments only: per-wave cycle counters [wg][wave][4], or null
 };
 int launch_attention_prefill(const AttnPrefillParams &p, hipStream_t st);
 

@@ -478,6 +478,170 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds_kernel(GemmParams p) 
 }
 
 // ---------------------------------------------------------------------------
+// Epilogue that leaves through LDS.  The accumulator layout gives a lane 4
+// consecutive columns of 32 different rows, i.e. 8-byte stores into 32 different
+// cache lines per instruction.  Here each wave first applies its epilogue
+// arithmetic in registers, writes the result into a private LDS slab laid out
+// [row][column] (row stride padded by 16 bytes), and then streams it out with
+// 16-byte stores in which 16 (or 8) consecutive lanes cover one contiguous row
+// segment of 256 (128) bytes.  The residual add stages fp32 accumulators, 32 rows
+// at a time, so that h + acc is rounded to bf16 once.
+template <int EPI, int FM, int FN>
+__device__ __forceinline__ void gemm_epilogue_lds(const GemmParams &p, floatx16 (&acc)[FN][FM], const int m_base,
+                                                  const int n_base, const int lane, unsigned char *slab) {
+  static_assert(FN == 4, "wave tile spans 128 output columns");
+  const int l32 = lane & 31, g = lane >> 5;
+  if (n_base >= p.N) return;                       // N is a multiple of 16; a wave tile past it has nothing to do
+  if constexpr (EPI == EPI_RESID) {
+    constexpr int RS = 128 * 4 + 16;               // fp32 row stride in bytes
+    bf16_t *cbase = (bf16_t *)p.C + n_base;
+#pragma unroll
+    for (int bm = 0; bm < FM; ++bm) {
+#pragma unroll
+      for (int bn = 0; bn < FN; ++bn)
+#pragma unroll
+        for (int jg = 0; jg < 4; ++jg)
+          *(float4 *)(slab + l32 * RS + (bn * 32 + 8 * jg + 4 * g) * 4) =
+              make_float4(acc[bn][bm][4 * jg], acc[bn][bm][4 * jg + 1], acc[bn][bm][4 * jg + 2], acc[bn][bm][4 * jg + 3]);
+      // a wave's LDS operations execute in order: the reads below see the writes above
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int row = it * 4 + (lane >> 4), ch = lane & 15;
+        const int m = m_base + bm * 32 + row, n = n_base + ch * 8;
+        const float4 lo = *(const float4 *)(slab + row * RS + ch * 32), hi = *(const float4 *)(slab + row * RS + ch * 32 + 16);
+        if (m < p.M && n < p.N) {
+          bf16_t *dst = cbase + (int64_t)m * p.ldc + ch * 8;
+          const uint4 r = *(const uint4 *)dst;
+          *(uint4 *)dst = make_uint4(pack_bf16x2(lo.x + bf16lo(r.x), lo.y + bf16hi(r.x)), pack_bf16x2(lo.z + bf16lo(r.y), lo.w + bf16hi(r.y)),
+                                     pack_bf16x2(hi.x + bf16lo(r.z), hi.y + bf16hi(r.z)), pack_bf16x2(hi.z + bf16lo(r.w), hi.w + bf16hi(r.w)));
+        }
+      }
+    }
+    return;
+  } else {
+    constexpr int NC = (EPI == EPI_SWIGLU) ? 64 : 128;   // output columns of the wave tile
+    constexpr int RS = NC * 2 + 16;                      // bf16 row stride in bytes
+    constexpr int CPR = NC / 8, RPI = 64 / CPR;          // 16-byte chunks per row, rows per store instruction
+    // ---- epilogue arithmetic in registers, result (bf16) into the slab ----
+    int kind = 0, col0 = n_base, proj = 0;               // QKV/KV: kind 0 = q, 1 = k, 2 = v
+    if constexpr (EPI == EPI_QKV) {
+      if (n_base < p.q_dim) { kind = 0; col0 = n_base; }
+      else if (n_base < p.q_dim + p.kv_dim) { kind = 1; col0 = n_base - p.q_dim; }
+      else { kind = 2; col0 = n_base - p.q_dim - p.kv_dim; }
+    } else if constexpr (EPI == EPI_KV) {
+      proj = n_base / (2 * p.kv_dim);
+      const int within = n_base % (2 * p.kv_dim);
+      kind = within < p.kv_dim ? 1 : 2;
+      col0 = within % p.kv_dim;
+    }
+    const int hd = p.head_dim;
+    float amax_h[2] = {0.f, 0.f};
+#pragma unroll
+    for (int bm = 0; bm < FM; ++bm) {
+      const int m = m_base + bm * 32 + l32;
+      const int mc = m < p.M ? m : p.M - 1;
+      unsigned char *srow = slab + (bm * 32 + l32) * RS;
+      if constexpr (EPI == EPI_SWIGLU) {
+        const float rs = p.rstd ? p.rstd[mc] : 1.f;
+#pragma unroll
+        for (int bn = 0; bn < FN; ++bn)
+#pragma unroll
+          for (int jg = 0; jg < 2; ++jg) {
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float gt = acc[bn][bm][4 * jg + e] * rs, up = acc[bn][bm][4 * (jg + 2) + e] * rs;
+              o[e] = gt / (1.f + __expf(-gt)) * up;
+            }
+            *(uint2 *)(srow + (bn * 16 + 8 * jg + 4 * g) * 2) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+          }
+      } else {
+        if constexpr (EPI == EPI_QKV || EPI == EPI_KV) {
+          const float rs = p.rstd ? p.rstd[mc] : 1.f;
+#pragma unroll
+          for (int bn = 0; bn < FN; ++bn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[bn][bm][v] *= rs;
+          if (kind != 2) {
+            const float2 *cs = p.cos_sin + (int64_t)mc * (hd / 2);
+            const int half_blocks = hd / 64, heads_per_tile = 128 / hd;
+            for (int hh = 0; hh < heads_per_tile; ++hh)
+              for (int hb = 0; hb < half_blocks; ++hb) {
+                const int blo = hh * (hd / 32) + hb, bhi = blo + half_blocks;
+#pragma unroll
+                for (int jg = 0; jg < 4; ++jg) {
+                  const int i0 = hb * 32 + 8 * jg + 4 * g;
+                  const float4 c01 = *(const float4 *)(cs + i0), c23 = *(const float4 *)(cs + i0 + 2);
+                  const float cv[4] = {c01.x, c01.z, c23.x, c23.z}, sv[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+                  for (int e = 0; e < 4; ++e) {
+                    float x1 = 0.f, x2 = 0.f;
+#pragma unroll
+                    for (int b = 0; b < FN; ++b) {
+                      if (b == blo) x1 = acc[b][bm][4 * jg + e];
+                      if (b == bhi) x2 = acc[b][bm][4 * jg + e];
+                    }
+                    const float y1 = x1 * cv[e] - x2 * sv[e], y2 = x2 * cv[e] + x1 * sv[e];
+#pragma unroll
+                    for (int b = 0; b < FN; ++b) {
+                      if (b == blo) acc[b][bm][4 * jg + e] = y1;
+                      if (b == bhi) acc[b][bm][4 * jg + e] = y2;
+                    }
+                  }
+                }
+              }
+          }
+        }
+#pragma unroll
+        for (int bn = 0; bn < FN; ++bn)
+#pragma unroll
+          for (int jg = 0; jg < 4; ++jg) {
+            const uint2 pk = make_uint2(pack_bf16x2(acc[bn][bm][4 * jg], acc[bn][bm][4 * jg + 1]), pack_bf16x2(acc[bn][bm][4 * jg + 2], acc[bn][bm][4 * jg + 3]));
+            *(uint2 *)(srow + (bn * 32 + 8 * jg + 4 * g) * 2) = pk;
+            if constexpr (EPI == EPI_QKV || EPI == EPI_KV) {
+              if (p.amax && kind != 0 && m < p.M) {   // absmax of the values as stored (bf16-rounded)
+                const float a = fmaxf(fmaxf(fabsf(bf16lo(pk.x)), fabsf(bf16hi(pk.x))), fmaxf(fabsf(bf16lo(pk.y)), fabsf(bf16hi(pk.y))));
+                if ((bn * 32) / hd == 0) amax_h[0] = fmaxf(amax_h[0], a); else amax_h[1] = fmaxf(amax_h[1], a);
+              }
+            }
+          }
+      }
+    }
+    if constexpr (EPI == EPI_QKV || EPI == EPI_KV) {
+      if (p.amax && kind != 0) {
+        const int n_kv_heads = p.kv_dim / hd;
+        for (int hh = 0; hh < 128 / hd; ++hh) {
+          const float a = wave_max(amax_h[hh]);
+          if (lane == 0)
+            atomicMax(p.amax + ((int64_t)(p.first_cache_layer + proj) * 2 + (kind == 2 ? 1 : 0)) * n_kv_heads + col0 / hd + hh, __float_as_uint(a));
+        }
+      }
+    }
+    // ---- stream the slab out: lane -> (row it*RPI + lane/CPR, 16-byte chunk lane%CPR) ----
+    const int ch = lane % CPR;
+#pragma unroll
+    for (int it = 0; it < FM * 32 / RPI; ++it) {
+      const int row = it * RPI + lane / CPR;
+      const int m = m_base + row;
+      const uint4 val = *(const uint4 *)(slab + row * RS + ch * 16);
+      if (m >= p.M) continue;
+      bf16_t *dst;
+      if constexpr (EPI == EPI_STORE_BF16) dst = (bf16_t *)p.C + (int64_t)m * p.ldc + n_base;
+      else if constexpr (EPI == EPI_SWIGLU) dst = (bf16_t *)p.C + (int64_t)m * p.ldc + n_base / 2;
+      else if constexpr (EPI == EPI_QKV)
+        dst = kind == 0 ? p.q_out + (int64_t)m * p.q_dim + col0 : (kind == 1 ? p.k_out : p.v_out) + (int64_t)m * p.kv_dim + col0;
+      else
+        dst = p.stage ? p.stage + (int64_t)m * p.N + n_base
+                      : p.cache + (int64_t)(p.first_cache_layer + proj) * p.cache_layer_stride +
+                            (kind == 2 ? p.cache_kv_stride : 0) + p.slots[m] * p.kv_dim + col0;
+      if constexpr (EPI == EPI_STORE_BF16) { if (n_base + ch * 8 >= p.N) continue; }
+      if constexpr (EPI == EPI_SWIGLU) { if (n_base + ch * 16 >= p.N) continue; }
+      *(uint4 *)(dst + ch * 8) = val;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Five-stage variant of the direct-to-LDS main loop with 32-wide k steps.
 // LDS holds five (BM+BN) x 64-byte stages (160 KB for 256x256): while step t is
 // multiplied, the loads of steps t+3 and t+4 are in flight and step t+1/t+2 are
@@ -499,7 +663,7 @@ __device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int EPI, bool PROF = false>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p) {
   constexpr int NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -510,7 +674,8 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
   constexpr int LPW = A_CH + B_CH;                           // LDS-DMA loads per wave per step
   constexpr int STAGE_BYTES = (BM + BN) * 64;
   constexpr int NMF = FN * FM;                               // MFMAs per 16-wide sub-step
-  static_assert(LPW % 2 == 0 && LPW / 2 <= NMF && FN + FM <= NMF, "interleave slots");
+  constexpr int GSP = NMF / (LPW / 2);                       // MFMAs between two LDS-DMA requests of a wave
+  static_assert(LPW % 2 == 0 && NMF % (LPW / 2) == 0 && FN + FM <= NMF, "interleave slots");
 
   extern __shared__ __align__(16) unsigned char smem[];
 
@@ -588,6 +753,8 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
   };
 
   const int nk = p.K / BKS;
+  long long t_vm = 0, t_bar = 0, t_begin = 0;
+  if constexpr (PROF) t_begin = clock64();
   // prologue: steps 0..3 in flight, steps 0 and 1 resident
 #pragma unroll
   for (int s0 = 0; s0 < NS - 1; ++s0) {
@@ -617,7 +784,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
       acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0][bn], af[0][bm], acc[bn][bm], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       if (i < FN + FM) load_frag(i, 1, st, 1);
-      if (i >= NMF - LPW / 2) issue_one(i - (NMF - LPW / 2), stl, kl);
+      if ((i % GSP) == GSP - 1) issue_one(i / GSP, stl, kl);              // one request every GSP MFMAs: keeps the address unit's queue short
       __builtin_amdgcn_sched_barrier(0);
     }
     // sub-step 1: MFMAs on buffer 1; fetch buffer 0 from the next stage (resident since the previous barrier); second half of the loads
@@ -627,21 +794,49 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
       acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1][bn], af[1][bm], acc[bn][bm], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       if (i < FN + FM) load_frag(i, 0, stn, 0);
-      if (i >= NMF - LPW / 2) issue_one(LPW / 2 + i - (NMF - LPW / 2), stl, kl);
+      if ((i % GSP) == GSP - 1) issue_one(LPW / 2 + i / GSP, stl, kl);
       __builtin_amdgcn_sched_barrier(0);
     }
+    long long tp0 = 0, tp1 = 0;
+    if constexpr (PROF) { __builtin_amdgcn_s_waitcnt(0xC07F); tp0 = clock64(); }
     __builtin_amdgcn_s_waitcnt(0x0F70 | (VMCNT2 & 15) | ((VMCNT2 >> 4) << 14));   // step t+2 has landed (this wave's part)
+    if constexpr (PROF) tp1 = clock64();
     __syncthreads();
+    if constexpr (PROF) { t_vm += tp1 - tp0; t_bar += clock64() - tp1; }
     s_cur = s_nxt;
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped extra loads before LDS is released
-  gemm_epilogue<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped extra loads ...
+  __syncthreads();                      // ... of every wave, before LDS is reused by the epilogue
+  constexpr int SLAB = WTM * (128 * 2 + 16) > 32 * (128 * 4 + 16) ? WTM * (128 * 2 + 16) : 32 * (128 * 4 + 16);
+  static_assert(NW * SLAB <= NS * STAGE_BYTES, "epilogue slabs must fit in the stage memory");
+  unsigned char *slab = smem + wave * SLAB;
+  if constexpr (PROF) {
+    const long long t_loop = clock64() - t_begin;
+    if constexpr (EPI == EPI_STORE_F32) gemm_epilogue<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
+    else gemm_epilogue_lds<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane, slab);
+    if (lane == 0 && p.stage) {   // experiment only: `stage` doubles as the int64 output [wg][wave][5]
+      long long *o = (long long *)p.stage + ((long long)blockIdx.x * NW + wave) * 5;
+      o[0] = t_loop; o[1] = t_vm; o[2] = t_bar; o[3] = 0; o[4] = clock64() - t_begin;
+    }
+    return;
+  }
+  if constexpr (EPI == EPI_STORE_F32) gemm_epilogue<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
+  else gemm_epilogue_lds<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane, slab);
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI>
 int launch_dlds5(const GemmParams &p, hipStream_t st) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int SMEM = 5 * (BM + BN) * 64;
+  if constexpr (EPI == EPI_STORE_BF16) {
+    if (p.dbg == 8) {   // timing experiment: per-wave cycle breakdown written through p.stage
+      auto kp = gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, true>;
+      (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+      const int tl = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+      hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(NT), SMEM, st, p);
+      return 0;
+    }
+  }
   auto kern = gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI>;
   static bool attr_set = false;
   if (!attr_set) {

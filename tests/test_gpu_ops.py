@@ -27,6 +27,8 @@ def _rand_bf16(seed, name, shape, std=1.0):
     (0, 2500, 512, 256),
     (4, 256, 256, 64), (4, 700, 528, 448), (4, 2304, 768, 1024), (4, 1, 16, 128),
     (5, 256, 256, 64), (5, 700, 528, 448), (5, 2304, 768, 1024), (5, 300, 272, 200),
+    (14, 256, 256, 64), (14, 700, 528, 448), (14, 2304, 768, 1024), (14, 1, 16, 128), (14, 1031, 1040, 320),
+    (15, 256, 256, 64), (15, 700, 528, 448), (15, 2304, 768, 1024), (15, 517, 272, 192),
 ])
 def test_gemm_matches_definition(variant, M, N, K):
     """C = A W^T (Sec. 3.1 projections); fp32 accumulation of bf16 inputs."""
