@@ -109,8 +109,52 @@ __global__ void rmsnorm_rows_kernel(const uint4 *h, const uint4 *gain, uint4 *ou
     out[(int64_t)row * chunks + c] = o;
   }
 }
+// Single-pass variant: the row (d = 512 * CH elements) stays in registers between the reduction and the scaling.
+template <int CH>
+__global__ void rmsnorm_rows_reg_kernel(const uint4 *h, const uint4 *gain, uint4 *out, int rows, float eps, float inv_d) {
+  const int row = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const uint4 *r = h + (int64_t)row * (CH * 64);
+  uint4 u[CH];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    u[i] = r[i * 64 + lane];
+    float a;
+    a = bf16lo(u[i].x); s += a * a; a = bf16hi(u[i].x); s += a * a;
+    a = bf16lo(u[i].y); s += a * a; a = bf16hi(u[i].y); s += a * a;
+    a = bf16lo(u[i].z); s += a * a; a = bf16hi(u[i].z); s += a * a;
+    a = bf16lo(u[i].w); s += a * a; a = bf16hi(u[i].w); s += a * a;
+  }
+  s = wave_sum(s);
+  const float rs = rsqrtf(s * inv_d + eps);
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const uint4 g = gain[i * 64 + lane];
+    uint4 o;
+    o.x = pack_bf16x2(bf16lo(u[i].x) * rs * bf16lo(g.x), bf16hi(u[i].x) * rs * bf16hi(g.x));
+    o.y = pack_bf16x2(bf16lo(u[i].y) * rs * bf16lo(g.y), bf16hi(u[i].y) * rs * bf16hi(g.y));
+    o.z = pack_bf16x2(bf16lo(u[i].z) * rs * bf16lo(g.z), bf16hi(u[i].z) * rs * bf16hi(g.z));
+    o.w = pack_bf16x2(bf16lo(u[i].w) * rs * bf16lo(g.w), bf16hi(u[i].w) * rs * bf16hi(g.w));
+    out[(int64_t)row * (CH * 64) + i * 64 + lane] = o;
+  }
+}
 int launch_rmsnorm_rows(const bf16_t *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, hipStream_t st) {
-  hipLaunchKernelGGL(rmsnorm_rows_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, (const uint4 *)h, (const uint4 *)gain, (uint4 *)out, rows, d / 8, eps, 1.0f / (float)d);
+  const dim3 grid((rows + 3) / 4), block(256);
+  const float inv_d = 1.0f / (float)d;
+#define SKV_RMS_CASE(CH_)                                                                                          \
+  case CH_:                                                                                                        \
+    hipLaunchKernelGGL(rmsnorm_rows_reg_kernel<CH_>, grid, block, 0, st, (const uint4 *)h, (const uint4 *)gain, (uint4 *)out, rows, eps, inv_d); \
+    return 0;
+  if (d % 512 == 0) {
+    switch (d / 512) {
+      SKV_RMS_CASE(1) SKV_RMS_CASE(2) SKV_RMS_CASE(4) SKV_RMS_CASE(8) SKV_RMS_CASE(10) SKV_RMS_CASE(12) SKV_RMS_CASE(16)
+      default: break;
+    }
+  }
+#undef SKV_RMS_CASE
+  hipLaunchKernelGGL(rmsnorm_rows_kernel, grid, block, 0, st, (const uint4 *)h, (const uint4 *)gain, (uint4 *)out, rows, d / 8, eps, inv_d);
   return 0;
 }
 
