@@ -775,7 +775,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
     const unsigned char *st = smem + s_cur * STAGE_BYTES;
     const unsigned char *stn = smem + s_nxt * STAGE_BYTES;
     const unsigned stl = s_ld * STAGE_BYTES;
-    const int kl = (t + NS - 1 < nk ? t + NS - 1 : nk - 1) * BKS;   // clamped: the request count per step stays constant
+    const int kl = (PROF && p.head_dim == 1) ? 0 : (t + NS - 1 < nk ? t + NS - 1 : nk - 1) * BKS;   // clamped: the request count per step stays constant (profiling build: head_dim 1 = always tile 0)
     __builtin_amdgcn_sched_barrier(0);
     // sub-step 0: MFMAs on fragment buffer 0; fetch buffer 1 (sub-step 1 of this stage); first half of the loads
 #pragma unroll
