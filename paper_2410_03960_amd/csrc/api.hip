@@ -11,6 +11,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <string>
+#include <array>
 #include <vector>
 
 namespace {
@@ -680,7 +681,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
                     int32_t variant, void *stream) {
   if (!A || !W || !C) return fail(SWIFTKV_EINVAL, "null argument");
   if (M < 1 || N < 16 || K < 8 || (N % 16) || (K % 8)) return fail(SWIFTKV_EINVAL, "need M >= 1, N %% 16 == 0, K %% 8 == 0");
-  if (variant < 0 || variant > 16) return fail(SWIFTKV_EINVAL, "variant must be 0..16");
+  if (variant < 0 || variant > 21) return fail(SWIFTKV_EINVAL, "variant must be 0..21");
   hipStream_t st = (hipStream_t)stream;
   if (variant == 3) {
     if (M > 80) return fail(SWIFTKV_EINVAL, "weight-streaming kernel handles M <= 80");
@@ -694,6 +695,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
   if (variant == 7) { g.dbg = 2; variant = 4; }
   if (variant == 8) { g.dbg = 6; variant = 5; }
   if (variant == 9) { g.dbg = 7; variant = 5; }
+  if (variant >= 17) { g.dbg = 20 + (variant - 17); variant = 14; }   // 17/18/19: five-stage loop without LDS reads / DMA / both (timing only); 20/21: the same loop with 4 / 3 stages
   if (variant == 16) { g.head_dim = 1; variant = 12; }   // 16: as 12 but every load re-reads k tile 0 (cache-hot)
   if (variant >= 10 && variant <= 13) {  // 10/11: cycle breakdown of variant 5/4; C must have room for 5*8*n_waves*n_workgroups bytes of int64 counters after the M x N result
     g.dbg = 8; g.stage = (bf16_t *)C + (int64_t)M * N;
@@ -719,15 +721,21 @@ int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, vo
   if ((hd != 64 && hd != 128) || Hq % Hkv || (Hkv * hd) % 128 || (Hq * hd) % 128) return fail(SWIFTKV_EINVAL, "bad head shape");
   hipStream_t st = (hipStream_t)stream;
   std::vector<int32_t> qbs, kvt;
+  std::vector<std::array<int32_t, 8>> qb_list;
   int64_t row = 0, col = 0;
   for (int b = 0; b < B; ++b) {
     const int n = seq_lens[b];
     if (n < 1) return fail(SWIFTKV_EINVAL, "seq_lens must be >= 1");
-    for (int q0 = 0; q0 < n; q0 += 128) qbs.insert(qbs.end(), {(int32_t)(row + q0), q0, n, (int32_t)row, (int32_t)col, 0, 0, 0});
+    for (int q0 = 0; q0 < n; q0 += 128) qb_list.push_back({(int32_t)(row + q0), q0, n, (int32_t)row, (int32_t)col, 0, 0, 0});
     for (int p0 = 0; p0 < n; p0 += 64) kvt.insert(kvt.end(), {(int32_t)(row + p0), std::min(64, n - p0), (int32_t)(col + p0), 0});
     row += n;
     col += (n + 63) / 64 * 64;
   }
+  // longest query blocks first (the attention kernel deals them out in that order)
+  std::stable_sort(qb_list.begin(), qb_list.end(), [](const std::array<int32_t, 8> &a, const std::array<int32_t, 8> &b) {
+    return std::min(a[1] + 128, a[2]) > std::min(b[1] + 128, b[2]);
+  });
+  for (const auto &e : qb_list) qbs.insert(qbs.end(), e.begin(), e.end());
   const int64_t vt_ld = col;
   size_t o_vt = 0, o_qb = align_up((size_t)Hkv * hd * vt_ld * 2), o_kt = o_qb + align_up(qbs.size() * 4), total = o_kt + align_up(kvt.size() * 4);
   if (total > workspace_bytes) return fail(SWIFTKV_ENOSPC, "workspace has %zu bytes, %zu needed", workspace_bytes, total);
@@ -744,7 +752,7 @@ int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, vo
   ap.qblocks = (const QBlock *)(ws + o_qb); ap.n_qblocks = (int32_t)(qbs.size() / 8);
   ap.n_q_heads = Hq; ap.n_kv_heads = Hkv; ap.head_dim = hd;
   if (getenv("SWIFTKV_ATTN_PROF")) {   // timing experiment: per-wave cycle counters after the tables
-    const size_t need = (size_t)ap.n_qblocks * Hq * 16 * 8;
+    const size_t need = (size_t)ap.n_qblocks * Hq * 16 * 8 + 1024 * 4 * 8;   // per (item, wave) records, then per workgroup records
     if (total + need <= workspace_bytes) ap.prof = (long long *)(ws + total);
   }
   if (launch_attention_prefill(ap, st)) return fail(SWIFTKV_EHIP, "attention launch failed");

@@ -17,25 +17,55 @@ namespace {
 constexpr int BQ = 128;   // queries per workgroup
 constexpr int BKV = 64;   // keys per tile
 
+// 16 bytes per lane from global memory straight into LDS: lane i lands at lds_addr + 16*i
+// (M0 carries the LDS base).  The waits are placed by hand (s_waitcnt vmcnt) because the
+// compiler cannot tell which LDS bytes a request targets.
+__device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+}
+
+// LDS tiles are unpadded and filled by LDS-DMA in 1 KB pieces; 16-byte chunks are XOR-swizzled
+// inside a row so that the 16 lanes served per LDS cycle (256 bytes, 64 banks) never collide:
+//   K   tile [64 keys][HD*2 bytes]:  chunk c of row r sits at c ^ swz_k(r)
+//   V^T tile [HD dims][128 bytes]:   chunk c of row d sits at c ^ ((d >> 1) & 7)
+// The 32 MFMA rows of a key block are fed with the keys in the order bit2 <-> bit3 swapped, which
+// makes the 8 exponentials a lane holds per PV step belong to 8 consecutive keys -- one 16-byte
+// V^T chunk instead of two 8-byte halves.
 template <int HD, bool PROF = false>
 __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams p) {
-  constexpr int KROW = HD * 2 + 16;        // padded K row bytes (conflict-free 16-byte reads)
-  constexpr int VROW = BKV * 2 + 8;        // padded V^T row bytes (conflict-free 8-byte reads)
-  constexpr int K_BYTES = BKV * KROW, V_BYTES = HD * VROW;
+  constexpr int KCH = HD / 8;              // 16-byte chunks per K row (16 or 8)
+  constexpr int K_RPI = 64 / KCH;          // K rows per 1 KB DMA request (4 or 8)
+  constexpr int K_BYTES = BKV * HD * 2, V_BYTES = HD * BKV * 2;
   constexpr int STAGE = K_BYTES + V_BYTES;
+  constexpr int K_IT = K_BYTES / 1024 / 4; // DMA requests per wave per K tile
+  constexpr int V_IT = V_BYTES / 1024 / 4; // ... per V^T tile (8 rows of 128 bytes each)
   constexpr int DS = HD / 16;              // d steps of the QK^T contraction
   constexpr int DB = HD / 32;              // 32-wide d blocks of the output
-  constexpr int KCH = HD / 8;              // 16-byte chunks per K row
-  constexpr int K_IT = BKV * KCH / 256;    // K chunks per thread
-  constexpr int V_IT = HD * 8 / 256;       // V^T chunks per thread (rows of 8 chunks)
 
   extern __shared__ __align__(16) unsigned char smem[];
 
-  const QBlock qb = p.qblocks[blockIdx.x];
-  const int head = blockIdx.y;
-  const int kvh = head / (p.n_q_heads / p.n_kv_heads);
+  // Persistent workgroups: item = (query block, head), heads fastest, query blocks sorted longest
+  // first by the plan.  The items are dealt to the workgroups in rounds of gridDim.x, every other
+  // round in reverse order, so each workgroup ends up with nearly the same number of key tiles.
+  const int n_items = p.n_qblocks * p.n_q_heads;
+  long long wg_t0 = 0, wg_in = 0, wg_n = 0;
+  if constexpr (PROF) wg_t0 = wall_clock64();
+  for (int round = 0;; ++round) {
+  const int item = round * gridDim.x + ((round & 1) ? gridDim.x - 1 - blockIdx.x : blockIdx.x);
+  if (item >= n_items) {
+    if ((round + 1) * gridDim.x >= (unsigned)n_items + gridDim.x) break;   // past the last (partial) round
+    continue;
+  }
+  long long it_t0 = 0;
+  if constexpr (PROF) it_t0 = wall_clock64();
+  const QBlock qb = p.qblocks[item / p.n_q_heads];
+  // Consecutive workgroups sit on different XCDs (workgroup id mod 8), each with its own L2: the
+  // query heads that share a KV head are spaced n_kv_heads items apart so that they meet in one L2.
+  const int hslot = item % p.n_q_heads;
+  const int kvh = hslot % p.n_kv_heads;
+  const int head = kvh * (p.n_q_heads / p.n_kv_heads) + hslot / p.n_kv_heads;
   const int q_dim = p.n_q_heads * HD, kv_dim = p.n_kv_heads * HD;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, g = lane >> 5;
 
   // ---- this lane's query: position and Q fragments (second MFMA operand) ----
@@ -58,41 +88,48 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
   const bf16_t *kbase = p.k + (int64_t)qb.seq_row0 * kv_dim + kvh * HD;
   const bf16_t *vbase = p.vt + (int64_t)(kvh * HD) * p.vt_ld + qb.vt_col0;
 
-  uint4 rk[K_IT], rv[V_IT];
-  auto load_tile = [&](int t) {
+  typedef __attribute__((address_space(3))) void *lds_ptr_t;
+  const unsigned lds_base = (unsigned)(size_t)(lds_ptr_t)smem;
+
+  // ---- DMA sources of this lane ----
+  // K request i of this wave covers rows (wave*K_IT + i)*K_RPI ... of the tile; this lane fetches
+  // row k_r0 + i*K_RPI, chunk k_c0 ^ 4i (the swizzle, folded: wave*K_IT*K_RPI is a multiple of 16).
+  // V^T request i covers dims (wave*V_IT + i)*8 ...; chunk v_c0 ^ 4*(i&1).
+  const int k_r0 = wave * K_IT * K_RPI + lane / KCH;
+  const int k_c0 = (lane % KCH) ^ (HD == 128 ? (lane >> 4) : (lane >> 4));
+  const int v_d0 = wave * V_IT * 8 + (lane >> 3);
+  const int v_c0 = (lane & 7) ^ (lane >> 4);
+  const bf16_t *v_src0 = vbase + (int64_t)v_d0 * p.vt_ld + v_c0 * 8;
+  const bf16_t *v_src1 = vbase + (int64_t)v_d0 * p.vt_ld + (v_c0 ^ 4) * 8;
+  // request idx (0 .. K_IT+V_IT-1) of tile t into `stage`: the K rows first, then the V^T rows
+  auto issue_one = [&](int idx, int t, int stage) {
     const int key0 = t * BKV;
+    const unsigned st = lds_base + stage * STAGE;
 #pragma unroll
-    for (int i = 0; i < K_IT; ++i) {
-      int idx = tid + i * 256;
-      int r = idx / KCH, c = idx % KCH;
-      int key = key0 + r;
-      key = key < qb.n ? key : qb.n - 1;   // rows past the end are masked later; any finite data will do
-      rk[i] = *(const uint4 *)(kbase + (int64_t)key * kv_dim + c * 8);
-    }
+    for (int i = 0; i < K_IT; ++i)
+      if (idx == i) {
+        int key = key0 + k_r0 + i * K_RPI;
+        key = key < qb.n ? key : qb.n - 1;   // rows past the end are masked later; any finite data will do
+        lds_dma16(kbase + ((int64_t)key * kv_dim + ((k_c0 ^ (4 * i)) * 8)), st + (wave * K_IT + i) * 1024);
+      }
 #pragma unroll
-    for (int i = 0; i < V_IT; ++i) {
-      int idx = tid + i * 256;
-      int d = idx / 8, c = idx % 8;
-      rv[i] = *(const uint4 *)(vbase + (int64_t)d * p.vt_ld + key0 + c * 8);   // padded columns are zero
-    }
+    for (int i = 0; i < V_IT; ++i)
+      if (idx == K_IT + i)   // padded columns are zero
+        lds_dma16(((i & 1) ? v_src1 : v_src0) + ((int64_t)(8 * i) * p.vt_ld + key0), st + K_BYTES + (wave * V_IT + i) * 1024);
   };
-  auto store_tile = [&](int stage) {
-    unsigned char *sk = smem + stage * STAGE;
-    unsigned char *sv = sk + K_BYTES;
+  auto issue_tile = [&](int t, int stage) {
 #pragma unroll
-    for (int i = 0; i < K_IT; ++i) {
-      int idx = tid + i * 256;
-      int r = idx / KCH, c = idx % KCH;
-      *(uint4 *)(sk + r * KROW + c * 16) = rk[i];
-    }
-#pragma unroll
-    for (int i = 0; i < V_IT; ++i) {
-      int idx = tid + i * 256;
-      int d = idx / 8, c = idx % 8;
-      *(uint2 *)(sv + d * VROW + c * 16) = make_uint2(rv[i].x, rv[i].y);
-      *(uint2 *)(sv + d * VROW + c * 16 + 8) = make_uint2(rv[i].z, rv[i].w);
-    }
+    for (int i = 0; i < K_IT + V_IT; ++i) issue_one(i, t, stage);
   };
+
+  // ---- LDS read addresses of this lane ----
+  // K operand: MFMA row l32 of key block kb is key kb*32 + swap23(l32); both blocks share the swizzle.
+  // Chunk (2*ds + g) ^ swz = (2*ds) ^ (g ^ swz): the d step enters as one XOR of the byte address with
+  // 32*ds (the chunk bits of the row bases are zero), likewise the PV step for V^T.
+  const int krow = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+  const unsigned k_lane = krow * (HD * 2) + ((g ^ (HD == 128 ? (krow & 15) : ((krow >> 1) & 7))) << 4);
+  // V^T operand: dims db*32 + l32; all d blocks share the swizzle
+  const unsigned v_lane = K_BYTES + l32 * 128 + ((g ^ ((l32 >> 1) & 7)) << 4);
 
   floatx16 o[DB];
 #pragma unroll
@@ -103,65 +140,70 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
   const float sc = 1.4426950408889634f * rsqrtf((float)HD);   // log2(e) / sqrt(hd)
   const float inv_sc = 1.0f / sc;
 
-  long long t_begin = 0, t_wait = 0, t_pro = 0;
-  if constexpr (PROF) t_begin = clock64();
-  load_tile(0);
-  store_tile(0);
+  long long t_begin = 0, t_wait = 0, t_qk = 0, t_sm = 0, t_pv = 0, t_iss = 0;
+  long long w_begin = 0;
+  if constexpr (PROF) { t_begin = clock64(); w_begin = wall_clock64(); }
+  issue_tile(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   __syncthreads();
-  if constexpr (PROF) t_pro = clock64() - t_begin;
   for (int t = 0; t < n_tiles; ++t) {
-    if (t + 1 < n_tiles) load_tile(t + 1);
+    long long ti0 = 0;
+    if constexpr (PROF) ti0 = clock64(); else asm volatile("" ::: "memory");
+    // Tile t+1 goes into the stage every wave finished reading before the last barrier.  The requests
+    // are spread over the MFMA phases (a burst would hold the wave at the address unit's queue).
+    // After the last tile the requests simply repeat it into the idle stage (no branches in the phases).
+    const int tn = t + 1 < n_tiles ? t + 1 : t, sn = (t + 1) & 1;
     const int key0 = t * BKV;
+    if (key0 > wave_last) issue_tile(tn, sn);
+    if constexpr (PROF) t_iss += clock64() - ti0; else asm volatile("" ::: "memory");
     if (key0 <= wave_last) {   // wave-uniform: tiles entirely above the diagonal are skipped
-      const unsigned char *sk = smem + (t & 1) * STAGE;
-      const unsigned char *sv = sk + K_BYTES;
+      const unsigned k_addr = (t & 1) * STAGE + k_lane, v_addr = (t & 1) * STAGE + v_lane;
       floatx16 s[2];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
-      // K operand fragments are fetched one group (GK MFMAs' worth) ahead of their use, and the
-      // first V^T fragments are requested before the softmax arithmetic starts.
-      constexpr int NG = DS / 2;              // groups per tile: two d steps x two key blocks = 4 independent-ish MFMAs
-      bf16x8 kfr[2][4];
-      uint4 vfr[2][DB];
-      auto load_k = [&](int buf, int gi) {
+      // K operand fragments are fetched one d step ahead of their use (the SIMD's other wave covers
+      // the rest of the LDS latency), and the first V^T fragments before the softmax arithmetic starts.
+      bf16x8 kfr[2][2];                       // two d steps (both key blocks each)
+      bf16x8 vfr[DB];
+      auto load_k = [&](int ds) {
+        const unsigned char *kp = smem + (k_addr ^ (unsigned)(ds * 32));
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int kb = i & 1, ds = gi * 2 + (i >> 1);
-          kfr[buf][i] = *(const bf16x8 *)(sk + (kb * 32 + l32) * KROW + (ds * 2 + g) * 16);
-        }
+        for (int kb = 0; kb < 2; ++kb) kfr[ds % 2][kb] = *(const bf16x8 *)(kp + kb * (32 * HD * 2));
       };
-      auto load_v = [&](int buf, int st) {
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const unsigned char *vp = sv + (db * 32 + l32) * VROW + (st * 16 + 4 * g) * 2;
-          uint2 lo = *(const uint2 *)vp, hi = *(const uint2 *)(vp + 16);
-          vfr[buf][db] = make_uint4(lo.x, lo.y, hi.x, hi.y);
-        }
+      auto load_v = [&](int st, int db) {   // keys 16*st + 8*g .. +7 of dim db*32 + l32
+        vfr[db] = *(const bf16x8 *)(smem + (v_addr ^ (unsigned)(st * 32)) + db * 4096);
       };
-      load_k(0, 0);
+      long long ta = 0, tb = 0, tc = 0;
+      if constexpr (PROF) ta = clock64(); else asm volatile("" ::: "memory");
+      load_k(0);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int gi = 0; gi < NG; ++gi) {
-        if (gi + 1 < NG) load_k((gi + 1) & 1, gi + 1); else load_v(0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+      for (int ds = 0; ds < DS; ++ds) {
+        if (ds + 1 < DS) load_k(ds + 1);
+        else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {   // alternate the two accumulators so consecutive MFMAs are independent
-          const int kb = i & 1, ds = gi * 2 + (i >> 1);
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[gi & 1][i], qf[ds], s[kb], 0, 0, 0);
+          for (int db = 0; db < DB; ++db) load_v(0, db);
         }
         __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)   // the two accumulators alternate, so consecutive MFMAs are independent
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ds % 2][kb], qf[ds], s[kb], 0, 0, 0);
+        if (ds % (DS / K_IT) == DS / K_IT - 1) issue_one(ds / (DS / K_IT), tn, sn);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      // s[kb][4*jg+e] = raw score(key = key0 + kb*32 + 8*jg + 4*g + e, this lane's query)
+      __builtin_amdgcn_sched_barrier(0);   // phase boundaries keep the scheduler from stretching live ranges across phases
+      if constexpr (PROF) { if (s[1][15] == 12345.f) t_wait = 0; tb = clock64(); t_qk += tb - ta; } else asm volatile("" ::: "memory");
+      // s[kb][v] = raw score(key = key0 + kb*32 + 16*(v>>3) + 8*g + (v&7), this lane's query)
       const bool need_mask = (key0 + BKV - 1 > qb.q0 + wave * 32) || (key0 + BKV > qb.n);
       if (need_mask) {   // wave-uniform: only tiles on the diagonal or at the end of the sequence
-        // element (kb, v) is key key0 + 4*g + kb*32 + 8*(v>>2) + (v&3); visible iff key <= min(qpos, n-1)
-        const int lim = (qpos < qb.n - 1 ? qpos : qb.n - 1) - key0 - 4 * g;
+        // visible iff key <= min(qpos, n-1)
+        const int lim = (qpos < qb.n - 1 ? qpos : qb.n - 1) - key0 - 8 * g;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) s[kb][v] = (kb * 32 + 8 * (v >> 2) + (v & 3) > lim) ? -INFINITY : s[kb][v];
+          for (int v = 0; v < 16; ++v) s[kb][v] = (kb * 32 + 16 * (v >> 3) + (v & 7) > lim) ? -INFINITY : s[kb][v];
       }
       float mx = -INFINITY;
 #pragma unroll
@@ -185,54 +227,74 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
       }
       const float msc = m_run * sc;
       float rs = 0.f;
+      // exponentials of PV step st (keys 16*st + 8*g .. +7), two at a time, straight into the bf16 operand
+      bf16x8 pf[2];
+      auto exp_pair = [&](int st, int j) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], sc, -msc));   // exp2 of (-inf) is 0
-          s[kb][v] = e;
-          rs += e;
+        for (int e = 2 * j; e < 2 * j + 2; ++e) {
+          const float x = __builtin_amdgcn_exp2f(__builtin_fmaf(s[st >> 1][(st & 1) * 8 + e], sc, -msc));   // exp2 of (-inf) is 0
+          rs += x;
+          pf[st & 1][e] = (__bf16)x;
         }
-      l_run += rs;
-      // O^T += V^T P^T, 16 keys per MFMA: step st uses s[st/2][(st%2)*8 .. +8]
+      };
+#pragma unroll
+      for (int j = 0; j < 4; ++j) exp_pair(0, j);
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (PROF) { if (rs == 12345.f) t_wait = 0; tc = clock64(); t_sm += tc - tb; } else asm volatile("" ::: "memory");
+      // O^T += V^T P^T, 16 keys per MFMA.  The exponentials of the next step are computed between
+      // the MFMAs of this one, and each V^T fragment register is refilled right after its use.
 #pragma unroll
       for (int st = 0; st < 4; ++st) {
-        bf16x8 pf;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s[st >> 1][(st & 1) * 8 + e];
-        if (st + 1 < 4) load_v((st + 1) & 1, st + 1);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vfr[st & 1][db]), pf, o[db], 0, 0, 0);
+        for (int db = 0; db < DB; ++db) {
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[db], pf[st & 1], o[db], 0, 0, 0);
+          if (st + 1 < 4) {
+            load_v(st + 1, db);
+            if (DB == 4) exp_pair(st + 1, db);
+            else { exp_pair(st + 1, 2 * db); exp_pair(st + 1, 2 * db + 1); }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (st % (4 / V_IT) == 4 / V_IT - 1) issue_one(K_IT + st / (4 / V_IT), tn, sn);
         __builtin_amdgcn_sched_barrier(0);
       }
+      l_run += rs;
+      if constexpr (PROF) { if (o[0][0] == 12345.f) t_wait = 0; t_pv += clock64() - tc; } else asm volatile("" ::: "memory");
     }
     long long tw0 = 0;
-    if constexpr (PROF) tw0 = clock64();
-    if (t + 1 < n_tiles) store_tile((t + 1) & 1);
-    __syncthreads();
+    if constexpr (PROF) tw0 = clock64(); else asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // this wave's part of tile t+1 has landed ...
+    __syncthreads();                      // ... everyone's has, and everyone is done reading tile t
     if constexpr (PROF) t_wait += clock64() - tw0;
   }
   if constexpr (PROF) {
     if (lane == 0 && p.prof) {
-      long long *o4 = p.prof + ((long long)(blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave) * 4;
-      o4[0] = clock64() - t_begin; o4[1] = t_wait; o4[2] = t_pro; o4[3] = n_tiles;
+      long long *o4 = p.prof + ((long long)(head * p.n_qblocks + item / p.n_q_heads) * 4 + wave) * 4;
+      o4[0] = (clock64() - t_begin) + ((wall_clock64() - w_begin) << 40); o4[1] = t_wait + (t_pv << 32); o4[2] = t_qk + (t_sm << 32); o4[3] = n_tiles + (t_iss << 32);
     }
   }
 
   // ---- normalise and store: o[db][4*jg+e] = O[query][d = db*32 + 8*jg + 4*g + e] ----
-  float l_tot = l_run + __shfl_xor(l_run, 32);
-  if (!qvalid) return;
-  const float inv = 1.f / l_tot;
-  bf16_t *op = p.out + (int64_t)qrow * q_dim + head * HD;
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (qvalid) {
+    const float inv = 1.f / l_tot;
+    bf16_t *op = p.out + (int64_t)qrow * q_dim + head * HD;
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int jg = 0; jg < 4; ++jg) {
-      *(uint2 *)(op + db * 32 + 8 * jg + 4 * g) =
-          make_uint2(pack_bf16x2(o[db][4 * jg] * inv, o[db][4 * jg + 1] * inv), pack_bf16x2(o[db][4 * jg + 2] * inv, o[db][4 * jg + 3] * inv));
+      for (int jg = 0; jg < 4; ++jg) {
+        *(uint2 *)(op + db * 32 + 8 * jg + 4 * g) =
+            make_uint2(pack_bf16x2(o[db][4 * jg] * inv, o[db][4 * jg + 1] * inv), pack_bf16x2(o[db][4 * jg + 2] * inv, o[db][4 * jg + 3] * inv));
+      }
+  }
+  if constexpr (PROF) { wg_in += wall_clock64() - it_t0; ++wg_n; }
+  }   // next item: the last tile's barrier already separates its LDS reads from the next prologue's writes
+  if constexpr (PROF) {
+    if (threadIdx.x == 0 && p.prof) {   // per workgroup, after the per-item records: first start, end, time inside items, items (100 MHz ticks)
+      long long *w4 = p.prof + (long long)n_items * 16 + blockIdx.x * 4;
+      w4[0] = wg_t0; w4[1] = wall_clock64(); w4[2] = wg_in; w4[3] = wg_n;
     }
+  }
 }
 
 // --------------------------------------------------------------- decode ----
@@ -383,9 +445,15 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
 
 int launch_attention_prefill(const AttnPrefillParams &p, hipStream_t st) {
   if (p.n_qblocks <= 0) return 0;
-  dim3 grid(p.n_qblocks, p.n_q_heads);
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) n_cu = 256;
+  }
+  const long long n_items = (long long)p.n_qblocks * p.n_q_heads;
+  dim3 grid((unsigned)(n_items < 2LL * n_cu ? n_items : 2LL * n_cu));   // two resident workgroups per CU
   if (p.head_dim == 128) {
-    constexpr int SMEM = 2 * (BKV * (128 * 2 + 16) + 128 * (BKV * 2 + 8));
+    constexpr int SMEM = 2 * (BKV * 128 * 2 + 128 * BKV * 2);
     static bool set = false;
     if (!set) {
       hipError_t e = hipFuncSetAttribute((const void *)attn_prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
@@ -399,7 +467,7 @@ int launch_attention_prefill(const AttnPrefillParams &p, hipStream_t st) {
     }
     hipLaunchKernelGGL(attn_prefill_kernel<128>, grid, dim3(256), SMEM, st, p);
   } else {
-    constexpr int SMEM = 2 * (BKV * (64 * 2 + 16) + 64 * (BKV * 2 + 8));
+    constexpr int SMEM = 2 * (BKV * 64 * 2 + 64 * BKV * 2);
     hipLaunchKernelGGL(attn_prefill_kernel<64>, grid, dim3(256), SMEM, st, p);
   }
   return 0;

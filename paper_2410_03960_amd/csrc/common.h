@@ -103,6 +103,7 @@ struct GemmParams {
   bf16_t *stage;               // KV FP8 mode: staging [M, N] bf16 instead of the cache
   uint32_t *amax;              // FP8: [n_cache_layers][2][Hkv] absmax bit patterns (atomicMax), or null
   int32_t dbg;                 // timing experiments only: 1 = no global loads in the k loop, 2 = always k-tile 0
+  int32_t raster_gm;           // five-stage kernel: m tiles per rasterisation group (0 = default)
 };
 
 int launch_gemm(const GemmParams &p, int epi, int variant, hipStream_t st);

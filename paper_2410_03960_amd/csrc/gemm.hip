@@ -663,13 +663,15 @@ __device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, bool PROF = false>
+template <int BM, int BN, int WGM, int WGN, int EPI, int XP = 0>   // XP: 0 product; 1 cycle counters; 2/3/4 timing experiments without the in-loop LDS reads / DMA / both (results are meaningless there)
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p) {
+  constexpr bool PROF = XP == 1;
+  constexpr bool DO_RD = XP != 2 && XP != 4, DO_DMA = XP != 3 && XP != 4;
   constexpr int NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   static_assert(WTN == 128 && WTM % 32 == 0, "wave tile");
   constexpr int FM = WTM / 32, FN = WTN / 32;
-  constexpr int NS = 5, BKS = 32;
+  constexpr int NS = XP == 5 ? 4 : XP == 6 ? 3 : 5, BKS = 32;   // stages (XP 5/6: timing experiments with fewer stages in flight)
   constexpr int A_CH = BM / 16 / NW, B_CH = BN / 16 / NW;   // 1 KB chunks (16 rows) per wave per stage
   constexpr int LPW = A_CH + B_CH;                           // LDS-DMA loads per wave per step
   constexpr int STAGE_BYTES = (BM + BN) * 64;
@@ -689,7 +691,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
   const int per_xcd = (total + 7) / 8;
   const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (logical >= total) return;
-  constexpr int GM = 8;
+  const int GM = p.raster_gm > 0 ? p.raster_gm : 8;
   const int group = logical / (GM * tiles_n);
   const int first_m = group * GM;
   const int gsz = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
@@ -762,7 +764,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
 #pragma unroll
     for (int i = 0; i < LPW; ++i) issue_one(i, s0 * STAGE_BYTES, k0);
   }
-  constexpr int VMCNT2 = 2 * LPW;   // two youngest groups may stay in flight
+  constexpr int VMCNT2 = (NS - 3) * LPW;   // the NS-3 youngest groups may stay in flight
   __builtin_amdgcn_s_waitcnt(0x0F70 | (VMCNT2 & 15) | ((VMCNT2 >> 4) << 14));
   __syncthreads();
 #pragma unroll
@@ -783,8 +785,8 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
       const int bn = i / FM, bm = i % FM;
       acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0][bn], af[0][bm], acc[bn][bm], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      if (i < FN + FM) load_frag(i, 1, st, 1);
-      if ((i % GSP) == GSP - 1) issue_one(i / GSP, stl, kl);              // one request every GSP MFMAs: keeps the address unit's queue short
+      if (DO_RD && i < FN + FM) load_frag(i, 1, st, 1);
+      if (DO_DMA && (i % GSP) == GSP - 1) issue_one(i / GSP, stl, kl);              // one request every GSP MFMAs: keeps the address unit's queue short
       __builtin_amdgcn_sched_barrier(0);
     }
     // sub-step 1: MFMAs on buffer 1; fetch buffer 0 from the next stage (resident since the previous barrier); second half of the loads
@@ -793,8 +795,8 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
       const int bn = i / FM, bm = i % FM;
       acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1][bn], af[1][bm], acc[bn][bm], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      if (i < FN + FM) load_frag(i, 0, stn, 0);
-      if ((i % GSP) == GSP - 1) issue_one(LPW / 2 + i / GSP, stl, kl);
+      if (DO_RD && i < FN + FM) load_frag(i, 0, stn, 0);
+      if (DO_DMA && (i % GSP) == GSP - 1) issue_one(LPW / 2 + i / GSP, stl, kl);
       __builtin_amdgcn_sched_barrier(0);
     }
     long long tp0 = 0, tp1 = 0;
@@ -808,7 +810,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
   __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped extra loads ...
   __syncthreads();                      // ... of every wave, before LDS is reused by the epilogue
   constexpr int SLAB = WTM * (128 * 2 + 16) > 32 * (128 * 4 + 16) ? WTM * (128 * 2 + 16) : 32 * (128 * 4 + 16);
-  static_assert(NW * SLAB <= NS * STAGE_BYTES, "epilogue slabs must fit in the stage memory");
+  static_assert(NW * SLAB <= 5 * STAGE_BYTES, "epilogue slabs must fit in the stage memory");
   unsigned char *slab = smem + wave * SLAB;
   if constexpr (PROF) {
     const long long t_loop = clock64() - t_begin;
@@ -830,11 +832,20 @@ int launch_dlds5(const GemmParams &p, hipStream_t st) {
   constexpr int SMEM = 5 * (BM + BN) * 64;
   if constexpr (EPI == EPI_STORE_BF16) {
     if (p.dbg == 8) {   // timing experiment: per-wave cycle breakdown written through p.stage
-      auto kp = gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, true>;
+      auto kp = gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 1>;
       (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
       const int tl = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
       hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(NT), SMEM, st, p);
       return 0;
+    }
+    if constexpr (WGM == 2) {
+      if (p.dbg >= 20 && p.dbg <= 24) {   // timing experiments: loop without LDS reads (20), without DMA (21), without both (22); 4 / 3 stages (23 / 24)
+        auto kp = p.dbg == 20 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 2> : p.dbg == 21 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 3> : p.dbg == 22 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 4> : p.dbg == 23 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 5> : gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 6>;
+        (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+        const int tl = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+        hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(NT), SMEM, st, p);
+        return 0;
+      }
     }
   }
   auto kern = gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI>;
@@ -976,8 +987,12 @@ int launch_epi(const GemmParams &p, int variant, hipStream_t st) {
 
 }  // namespace
 
-int launch_gemm(const GemmParams &p, int epi, int variant, hipStream_t st) {
-  if (p.M <= 0 || p.N <= 0 || p.K <= 0) return 0;
+int launch_gemm(const GemmParams &p_in, int epi, int variant, hipStream_t st) {
+  if (p_in.M <= 0 || p_in.N <= 0 || p_in.K <= 0) return 0;
+  GemmParams p = p_in;
+  static int env_gm = -1;
+  if (env_gm < 0) { const char *e = getenv("SWIFTKV_GEMM_RASTER_GM"); env_gm = e ? atoi(e) : 0; }
+  if (p.raster_gm == 0) p.raster_gm = env_gm;
   static bool env_read = false;
   if (!env_read) {   // SWIFTKV_GEMM_MAINLOOP=5|14|15 picks the main loop of large GEMMs (tuning aid)
     const char *e = getenv("SWIFTKV_GEMM_MAINLOOP");

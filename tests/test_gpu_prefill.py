@@ -171,6 +171,34 @@ def test_fp8_kv_cache(tiny, lens, ctx_lens):
     G.compare_logits(logits, ologits, rel=G.FP8_REL, cos=G.FP8_COS, label="fp8")
 
 
+def test_context_reuse_other_stream_and_determinism(tiny):
+    """One ctx and one workspace serve calls of different batch shapes, on a
+    non-default stream; a repeated call reproduces its bytes exactly."""
+    from paper_2410_03960_amd import binding as B
+    wl, store, dev_w = tiny
+    _say("ctx reuse / stream / determinism")
+    ctx = _ctx(dev_w, 2, 2)
+    ws = torch.empty(ctx.workspace_bytes(600, 6), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.Stream()
+    results = []
+    for lens in ([300, 17, 1, 64], [5], [300, 17, 1, 64]):
+        batch = WL.build_batch(wl, lens=lens, shuffled=True)
+        cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables,
+                          [0] * len(lens))
+        logits = torch.empty((len(lens), TINY.vocab), dtype=torch.float32, device="cuda")
+        ids = batch.token_ids.cuda()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            ctx.prefill(ids, lens, cache, logits, ws, stream)
+        stream.synchronize()
+        G.check_plan(ctx, ws, batch)
+        ologits, ocache, _ = G.run_oracle(TINY, store, batch, 2, 2)
+        G.compare_caches(cache, ocache, batch, label=f"reuse{lens}")
+        G.compare_logits(logits, ologits, label=f"reuse{lens}")
+        results.append((cache.data.clone(), logits.clone()))
+    assert torch.equal(results[0][0], results[2][0]) and torch.equal(results[0][1], results[2][1])
+
+
 def test_error_paths(tiny):
     """Host-side validation returns error codes, nothing is launched."""
     from paper_2410_03960_amd import binding as B
