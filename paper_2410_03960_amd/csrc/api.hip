@@ -251,7 +251,7 @@ struct Run {
 int run_plan(Run &r, const int32_t *token_ids) {
   swiftkv_ctx *c = r.c;
   HIP_TRY(hipMemcpyAsync(r.ws + r.L.meta, r.hp.meta.data(), r.hp.meta.size() * 4, hipMemcpyHostToDevice, r.st));
-  launch_fill_u32(r.at<uint32_t>(r.L.err), 0, 1, r.st);
+  launch_fill_u32(r.at<uint32_t>(r.L.err), 0, 16, r.st);   // error flags, and (words 4..12) the attention kernel's item counters
   if (r.fp8) launch_fill_u32(r.at<uint32_t>(r.L.amax), 0, (int64_t)c->C * 2 * c->cfg.n_kv_heads, r.st);
   PlanParams pp{};
   pp.T = (int32_t)r.L.T; pp.B = r.L.B; pp.head_dim = c->cfg.head_dim; pp.n_blocks = r.kv->n_blocks;
@@ -567,6 +567,7 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
       AttnPrefillParams ap{};
       ap.q = qb; ap.k = kb; ap.vt = vt; ap.vt_ld = r.L.vt_ld; ap.out = ob;
       ap.qblocks = (const QBlock *)r.meta(r.L.m_qblocks); ap.n_qblocks = r.L.n_qblocks;
+      ap.sched = r.at<int32_t>(r.L.err) + 4;
       ap.n_q_heads = m.n_q_heads; ap.n_kv_heads = m.n_kv_heads; ap.head_dim = m.head_dim;
       tm.begin(TC_ATTN);
       if (launch_attention_prefill(ap, st) != 0) return fail(SWIFTKV_EHIP, "attention launch failed");
@@ -737,7 +738,7 @@ int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, vo
   });
   for (const auto &e : qb_list) qbs.insert(qbs.end(), e.begin(), e.end());
   const int64_t vt_ld = col;
-  size_t o_vt = 0, o_qb = align_up((size_t)Hkv * hd * vt_ld * 2), o_kt = o_qb + align_up(qbs.size() * 4), total = o_kt + align_up(kvt.size() * 4);
+  size_t o_vt = 0, o_qb = align_up((size_t)Hkv * hd * vt_ld * 2), o_kt = o_qb + align_up(qbs.size() * 4), o_sched = o_kt + align_up(kvt.size() * 4), total = o_sched + 256;
   if (total > workspace_bytes) return fail(SWIFTKV_ENOSPC, "workspace has %zu bytes, %zu needed", workspace_bytes, total);
   unsigned char *ws = (unsigned char *)workspace;
   HIP_TRY(hipMemcpyAsync(ws + o_qb, qbs.data(), qbs.size() * 4, hipMemcpyHostToDevice, st));
@@ -751,6 +752,8 @@ int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, vo
   ap.q = (const bf16_t *)q; ap.k = (const bf16_t *)k; ap.vt = (const bf16_t *)(ws + o_vt); ap.vt_ld = vt_ld; ap.out = (bf16_t *)out;
   ap.qblocks = (const QBlock *)(ws + o_qb); ap.n_qblocks = (int32_t)(qbs.size() / 8);
   ap.n_q_heads = Hq; ap.n_kv_heads = Hkv; ap.head_dim = hd;
+  ap.sched = (int32_t *)(ws + o_sched);
+  launch_fill_u32((uint32_t *)(ws + o_sched), 0, 9, st);   // the workspace is the caller's and arrives uninitialised
   if (getenv("SWIFTKV_ATTN_PROF")) {   // timing experiment: per-wave cycle counters after the tables
     const size_t need = (size_t)ap.n_qblocks * Hq * 16 * 8 + 1024 * 4 * 8;   // per (item, wave) records, then per workgroup records
     if (total + need <= workspace_bytes) ap.prof = (long long *)(ws + total);

@@ -44,24 +44,30 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
 
   extern __shared__ __align__(16) unsigned char smem[];
 
-  // Persistent workgroups: item = (query block, head), heads fastest, query blocks sorted longest
-  // first by the plan.  The items are dealt to the workgroups in rounds of gridDim.x, every other
-  // round in reverse order, so each workgroup ends up with nearly the same number of key tiles.
-  const int n_items = p.n_qblocks * p.n_q_heads;
+  // Persistent workgroups pull items from device counters.  Item = (query block, head), query
+  // blocks sorted longest first by the plan, so the long items start first and the short ones fill
+  // the end; the next item is requested while the current one is being computed.
+  // Workgroup w runs on XCD w mod 8, each XCD with its own L2.  With a multiple of 8 query heads
+  // there is one queue per XCD holding the head slots == XCD (mod 8), and head slot s stands for
+  // head (s mod Hkv) * (Hq / Hkv) + s / Hkv: the query heads that share a KV head meet in one L2.
+  __shared__ int s_item;
+  const int NQ = (p.n_q_heads % 8 == 0) ? 8 : 1;
+  const int qid = blockIdx.x % NQ, hpq = p.n_q_heads / NQ;
+  const int n_items = p.n_qblocks * hpq;   // per queue
   long long wg_t0 = 0, wg_in = 0, wg_n = 0;
   if constexpr (PROF) wg_t0 = wall_clock64();
-  for (int round = 0;; ++round) {
-  const int item = round * gridDim.x + ((round & 1) ? gridDim.x - 1 - blockIdx.x : blockIdx.x);
-  if (item >= n_items) {
-    if ((round + 1) * gridDim.x >= (unsigned)n_items + gridDim.x) break;   // past the last (partial) round
-    continue;
-  }
+  if (threadIdx.x == 0) s_item = atomicAdd(p.sched + qid, 1);
+  __syncthreads();
+  for (;;) {
+  const int item = s_item;
+  if (item >= n_items) break;
+  int item_next = 0;
+  if (threadIdx.x == 0) item_next = atomicAdd(p.sched + qid, 1);   // consumed after the last tile
   long long it_t0 = 0;
   if constexpr (PROF) it_t0 = wall_clock64();
-  const QBlock qb = p.qblocks[item / p.n_q_heads];
-  // Consecutive workgroups sit on different XCDs (workgroup id mod 8), each with its own L2: the
-  // query heads that share a KV head are spaced n_kv_heads items apart so that they meet in one L2.
-  const int hslot = item % p.n_q_heads;
+  const int qblock = item / hpq;
+  const QBlock qb = p.qblocks[qblock];
+  const int hslot = (item % hpq) * NQ + qid;
   const int kvh = hslot % p.n_kv_heads;
   const int head = kvh * (p.n_q_heads / p.n_kv_heads) + hslot / p.n_kv_heads;
   const int q_dim = p.n_q_heads * HD, kv_dim = p.n_kv_heads * HD;
@@ -269,7 +275,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
   }
   if constexpr (PROF) {
     if (lane == 0 && p.prof) {
-      long long *o4 = p.prof + ((long long)(head * p.n_qblocks + item / p.n_q_heads) * 4 + wave) * 4;
+      long long *o4 = p.prof + ((long long)(head * p.n_qblocks + qblock) * 4 + wave) * 4;
       o4[0] = (clock64() - t_begin) + ((wall_clock64() - w_begin) << 40); o4[1] = t_wait + (t_pv << 32); o4[2] = t_qk + (t_sm << 32); o4[3] = n_tiles + (t_iss << 32);
     }
   }
@@ -288,10 +294,22 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
       }
   }
   if constexpr (PROF) { wg_in += wall_clock64() - it_t0; ++wg_n; }
-  }   // next item: the last tile's barrier already separates its LDS reads from the next prologue's writes
+  // every wave read s_item before the tile loop's barriers; the same barriers separate the last
+  // tile's LDS reads from the next prologue's writes
+  if (threadIdx.x == 0) s_item = item_next;
+  __syncthreads();
+  }
+  // the last workgroup to leave zeroes the counters for the next launch
+  if (threadIdx.x == 0) {
+    __threadfence();
+    if (atomicAdd(p.sched + 8, 1) == (int)gridDim.x - 1) {
+      for (int i = 0; i < 9; ++i) p.sched[i] = 0;
+      __threadfence();
+    }
+  }
   if constexpr (PROF) {
     if (threadIdx.x == 0 && p.prof) {   // per workgroup, after the per-item records: first start, end, time inside items, items (100 MHz ticks)
-      long long *w4 = p.prof + (long long)n_items * 16 + blockIdx.x * 4;
+      long long *w4 = p.prof + (long long)p.n_qblocks * p.n_q_heads * 16 + blockIdx.x * 4;
       w4[0] = wg_t0; w4[1] = wall_clock64(); w4[2] = wg_in; w4[3] = wg_n;
     }
   }
@@ -450,8 +468,8 @@ int launch_attention_prefill(const AttnPrefillParams &p, hipStream_t st) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) n_cu = 256;
   }
-  const long long n_items = (long long)p.n_qblocks * p.n_q_heads;
-  dim3 grid((unsigned)(n_items < 2LL * n_cu ? n_items : 2LL * n_cu));   // two resident workgroups per CU
+  // two resident workgroups per CU (a multiple of 8, so every XCD's queue has its workgroups)
+  dim3 grid((unsigned)(2 * n_cu));
   if (p.head_dim == 128) {
     constexpr int SMEM = 2 * (BKV * 128 * 2 + 128 * BKV * 2);
     static bool set = false;

@@ -134,6 +134,7 @@ struct AttnPrefillParams {
   bf16_t *out;          // [T, q_dim]
   const QBlock *qblocks;
   int32_t n_qblocks, n_q_heads, n_kv_heads, head_dim;
+  int32_t *sched;       // nine device words, zero at launch (the kernel leaves them zero): next item of 8 queues, workgroups done
   long long *prof;      // timing experiments only: per-wave cycle counters [wg][wave][4], or null
 };
 int launch_attention_prefill(const AttnPrefillParams &p, hipStream_t st);
