@@ -145,10 +145,13 @@ int check_launch(const char *what) {
   return 0;
 }
 
+// Key splits of the single-query attention: enough workgroups to fill the chip, and no workgroup
+// walking more than about 1024 keys of the longest row (rows are split evenly, down to 256 keys).
 int pick_split(int rows, int n_kv_heads, int max_keys) {
-  int want = (512 + rows * n_kv_heads - 1) / (rows * n_kv_heads);
-  int cap = std::max(1, max_keys / 64);
-  return std::max(1, std::min({want, cap, MAX_SPLIT}));
+  const int want = (1024 + rows * n_kv_heads - 1) / (rows * n_kv_heads);
+  const int by_len = (max_keys + 1023) / 1024;
+  const int cap = std::max(1, max_keys / 64);
+  return std::max(1, std::min({std::max(want, by_len), cap, MAX_SPLIT}));
 }
 
 struct HostPlan {
