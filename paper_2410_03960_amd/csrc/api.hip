@@ -685,7 +685,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
                     int32_t variant, void *stream) {
   if (!A || !W || !C) return fail(SWIFTKV_EINVAL, "null argument");
   if (M < 1 || N < 16 || K < 8 || (N % 16) || (K % 8)) return fail(SWIFTKV_EINVAL, "need M >= 1, N %% 16 == 0, K %% 8 == 0");
-  if (variant < 0 || variant > 21) return fail(SWIFTKV_EINVAL, "variant must be 0..21");
+  if (variant < 0 || variant > 25) return fail(SWIFTKV_EINVAL, "variant must be 0..25");
   hipStream_t st = (hipStream_t)stream;
   if (variant == 3) {
     if (M > 80) return fail(SWIFTKV_EINVAL, "weight-streaming kernel handles M <= 80");

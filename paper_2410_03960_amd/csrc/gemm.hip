@@ -662,6 +662,14 @@ __device__ __forceinline__ void gemm_epilogue_lds(const GemmParams &p, floatx16 
 __device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
 }
+// 4 bytes per lane (lane i lands at lds_addr + 4*i): used to pull a cache line into L2 ahead of time
+__device__ __forceinline__ void lds_dma4(const void *gptr, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+}
+// the same with the non-temporal hint (streamed once through L2 by this workgroup)
+__device__ __forceinline__ void lds_dma16_nt(const void *gptr, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds_addr), "v"(gptr) : "memory");
+}
 
 template <int BM, int BN, int WGM, int WGN, int EPI, int XP = 0>   // XP: 0 product; 1 cycle counters; 2/3/4 timing experiments without the in-loop LDS reads / DMA / both (results are meaningless there)
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p) {
@@ -671,7 +679,8 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   static_assert(WTN == 128 && WTM % 32 == 0, "wave tile");
   constexpr int FM = WTM / 32, FN = WTN / 32;
-  constexpr int NS = XP == 5 ? 4 : XP == 6 ? 3 : 5, BKS = 32;   // stages (XP 5/6: timing experiments with fewer stages in flight)
+  constexpr bool TOUCH = XP == 10;   // one L2 prefetch request per wave and step (see below)
+  constexpr int NS = (XP == 5 || TOUCH) ? 4 : XP == 6 ? 3 : 5, BKS = 32;   // stages (XP 5/6: timing experiments with fewer stages in flight)
   constexpr int A_CH = BM / 16 / NW, B_CH = BN / 16 / NW;   // 1 KB chunks (16 rows) per wave per stage
   constexpr int LPW = A_CH + B_CH;                           // LDS-DMA loads per wave per step
   constexpr int STAGE_BYTES = (BM + BN) * 64;
@@ -716,16 +725,35 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
     n = n < p.N ? n : p.N - 1;
     w_ptr[i] = (p.wtab ? p.wtab[n >> 4] + (int64_t)(n & 15) * p.ldw : p.W + (int64_t)n * p.ldw) + cl * 8;
   }
+  // L2 prefetch: the 32 workgroups resident on an XCD are 8 m tiles x 4 n tiles; an A row is used by the
+  // 4 workgroups of its m tile, a W row by the 8 of its n tile, at about the same time, so that all of them
+  // wait for the same miss.  Each workgroup therefore touches its share of the rows (a quarter of its A
+  // tile on even steps, an eighth of its W tile on odd steps) several steps ahead of everybody's loads.
+  const bf16_t *t_a = nullptr, *t_w = nullptr;
+  if constexpr (TOUCH) {
+    int m = m0 + (tn & 3) * 64 + wave * 16 + (lane & 15);
+    m = m < p.M ? m : p.M - 1;
+    t_a = p.A + (int64_t)m * p.lda;
+    int n = n0 + ((in_group % gsz) & 7) * 32 + wave * 8 + (lane & 7);
+    n = n < p.N ? n : p.N - 1;
+    t_w = p.wtab ? p.wtab[n >> 4] + (int64_t)(n & 15) * p.ldw : p.W + (int64_t)n * p.ldw;
+  }
   typedef __attribute__((address_space(3))) void *lds_ptr_t;
   const unsigned lds_base = (unsigned)(size_t)(lds_ptr_t)smem;
   // one of the LPW loads of a step: idx < A_CH -> A chunk, else W chunk; `stage` = byte offset of the stage
   auto issue_one = [&](int idx, unsigned stage, int k0) {
 #pragma unroll
     for (int i = 0; i < A_CH; ++i)
-      if (idx == i) lds_dma16(a_ptr[i] + k0, lds_base + stage + (wave + i * NW) * 1024);
+      if (idx == i) {
+        if constexpr (XP == 7 || XP == 8) lds_dma16_nt(a_ptr[i] + k0, lds_base + stage + (wave + i * NW) * 1024);
+        else lds_dma16(a_ptr[i] + k0, lds_base + stage + (wave + i * NW) * 1024);
+      }
 #pragma unroll
     for (int i = 0; i < B_CH; ++i)
-      if (idx == A_CH + i) lds_dma16(w_ptr[i] + k0, lds_base + stage + BM * 64 + (wave + i * NW) * 1024);
+      if (idx == A_CH + i) {
+        if constexpr (XP == 7 || XP == 9) lds_dma16_nt(w_ptr[i] + k0, lds_base + stage + BM * 64 + (wave + i * NW) * 1024);
+        else lds_dma16(w_ptr[i] + k0, lds_base + stage + BM * 64 + (wave + i * NW) * 1024);
+      }
   };
 
   floatx16 acc[FN][FM];
@@ -764,8 +792,9 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
 #pragma unroll
     for (int i = 0; i < LPW; ++i) issue_one(i, s0 * STAGE_BYTES, k0);
   }
-  constexpr int VMCNT2 = (NS - 3) * LPW;   // the NS-3 youngest groups may stay in flight
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (VMCNT2 & 15) | ((VMCNT2 >> 4) << 14));
+  constexpr int VMCNT0 = (NS - 3) * LPW;                              // prologue: the NS-3 youngest groups may stay in flight
+  constexpr int VMCNT2 = TOUCH ? (NS - 3) * (LPW + 1) + 1 : VMCNT0;   // loop: those, plus the prefetch requests issued since (one per step, after the step's loads)
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (VMCNT0 & 15) | ((VMCNT0 >> 4) << 14));
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < FN + FM; ++i) load_frag(i, 0, smem, 0);
@@ -798,6 +827,11 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
       if (DO_RD && i < FN + FM) load_frag(i, 0, stn, 0);
       if (DO_DMA && (i % GSP) == GSP - 1) issue_one(LPW / 2 + i / GSP, stl, kl);
       __builtin_amdgcn_sched_barrier(0);
+    }
+    if constexpr (TOUCH) {   // the 64-wide k chunk 4 steps beyond the one being requested now
+      int c = (t + NS - 1 + 5) >> 1;
+      c = c < (nk >> 1) ? c : (nk >> 1) - 1;
+      lds_dma4(((t & 1) ? t_w : t_a) + c * 64, lds_base + NS * STAGE_BYTES + wave * 256);
     }
     long long tp0 = 0, tp1 = 0;
     if constexpr (PROF) { __builtin_amdgcn_s_waitcnt(0xC07F); tp0 = clock64(); }
@@ -839,6 +873,13 @@ int launch_dlds5(const GemmParams &p, hipStream_t st) {
       return 0;
     }
     if constexpr (WGM == 2) {
+      if (p.dbg >= 25 && p.dbg <= 28) {   // non-temporal loads: both operands (25), A only (26), W only (27); shared L2 prefetch (28)
+        auto kp = p.dbg == 25 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 7> : p.dbg == 26 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 8> : p.dbg == 27 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 9> : gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 10>;
+        (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+        const int tl = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+        hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(NT), SMEM, st, p);
+        return 0;
+      }
       if (p.dbg >= 20 && p.dbg <= 24) {   // timing experiments: loop without LDS reads (20), without DMA (21), without both (22); 4 / 3 stages (23 / 24)
         auto kp = p.dbg == 20 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 2> : p.dbg == 21 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 3> : p.dbg == 22 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 4> : p.dbg == 23 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 5> : gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 6>;
         (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);

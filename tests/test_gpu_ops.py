@@ -29,6 +29,8 @@ def _rand_bf16(seed, name, shape, std=1.0):
     (5, 256, 256, 64), (5, 700, 528, 448), (5, 2304, 768, 1024), (5, 300, 272, 200),
     (14, 256, 256, 64), (14, 700, 528, 448), (14, 2304, 768, 1024), (14, 1, 16, 128), (14, 1031, 1040, 320),
     (15, 256, 256, 64), (15, 700, 528, 448), (15, 2304, 768, 1024), (15, 517, 272, 192),
+    (20, 700, 528, 448), (21, 700, 528, 448), (22, 700, 528, 448), (23, 2304, 768, 1024), (24, 1, 16, 128),
+    (25, 256, 256, 64), (25, 700, 528, 448), (25, 2304, 768, 1024), (25, 1031, 1040, 320),
 ])
 def test_gemm_matches_definition(variant, M, N, K):
     """C = A W^T (Sec. 3.1 projections); fp32 accumulation of bf16 inputs."""
