@@ -685,7 +685,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
                     int32_t variant, void *stream) {
   if (!A || !W || !C) return fail(SWIFTKV_EINVAL, "null argument");
   if (M < 1 || N < 16 || K < 8 || (N % 16) || (K % 8)) return fail(SWIFTKV_EINVAL, "need M >= 1, N %% 16 == 0, K %% 8 == 0");
-  if (variant < 0 || variant > 25) return fail(SWIFTKV_EINVAL, "variant must be 0..25");
+  if (variant < 0 || variant > 26) return fail(SWIFTKV_EINVAL, "variant must be 0..26");
   hipStream_t st = (hipStream_t)stream;
   if (variant == 3) {
     if (M > 80) return fail(SWIFTKV_EINVAL, "weight-streaming kernel handles M <= 80");
@@ -699,6 +699,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
   if (variant == 7) { g.dbg = 2; variant = 4; }
   if (variant == 8) { g.dbg = 6; variant = 5; }
   if (variant == 9) { g.dbg = 7; variant = 5; }
+  if (variant == 26) { g.dbg = 9; g.stage = (bf16_t *)C + (int64_t)M * N; variant = 14; }   // 26: as 12 without the timers inside the k loop
   if (variant >= 17) { g.dbg = 20 + (variant - 17); variant = 14; }   // 17/18/19: five-stage loop without LDS reads / DMA / both (timing only); 20/21: the same loop with 4 / 3 stages
   if (variant == 16) { g.head_dim = 1; variant = 12; }   // 16: as 12 but every load re-reads k tile 0 (cache-hot)
   if (variant >= 10 && variant <= 13) {  // 10/11: cycle breakdown of variant 5/4; C must have room for 5*8*n_waves*n_workgroups bytes of int64 counters after the M x N result

@@ -673,7 +673,8 @@ __device__ __forceinline__ void lds_dma16_nt(const void *gptr, unsigned lds_addr
 
 template <int BM, int BN, int WGM, int WGN, int EPI, int XP = 0>   // XP: 0 product; 1 cycle counters; 2/3/4 timing experiments without the in-loop LDS reads / DMA / both (results are meaningless there)
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p) {
-  constexpr bool PROF = XP == 1;
+  constexpr bool PROF = XP == 1 || XP == 11;   // 11: only the per-tile totals (no timers inside the loop)
+  constexpr bool PROF_STEP = XP == 1;
   constexpr bool DO_RD = XP != 2 && XP != 4, DO_DMA = XP != 3 && XP != 4;
   constexpr int NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -834,11 +835,11 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
       lds_dma4(((t & 1) ? t_w : t_a) + c * 64, lds_base + NS * STAGE_BYTES + wave * 256);
     }
     long long tp0 = 0, tp1 = 0;
-    if constexpr (PROF) { __builtin_amdgcn_s_waitcnt(0xC07F); tp0 = clock64(); }
+    if constexpr (PROF_STEP) { __builtin_amdgcn_s_waitcnt(0xC07F); tp0 = clock64(); }
     __builtin_amdgcn_s_waitcnt(0x0F70 | (VMCNT2 & 15) | ((VMCNT2 >> 4) << 14));   // step t+2 has landed (this wave's part)
-    if constexpr (PROF) tp1 = clock64();
+    if constexpr (PROF_STEP) tp1 = clock64();
     __syncthreads();
-    if constexpr (PROF) { t_vm += tp1 - tp0; t_bar += clock64() - tp1; }
+    if constexpr (PROF_STEP) { t_vm += tp1 - tp0; t_bar += clock64() - tp1; }
     s_cur = s_nxt;
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped extra loads ...
@@ -865,8 +866,8 @@ int launch_dlds5(const GemmParams &p, hipStream_t st) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int SMEM = 5 * (BM + BN) * 64;
   if constexpr (EPI == EPI_STORE_BF16) {
-    if (p.dbg == 8) {   // timing experiment: per-wave cycle breakdown written through p.stage
-      auto kp = gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 1>;
+    if (p.dbg == 8 || p.dbg == 9) {   // timing experiment: per-wave cycle breakdown written through p.stage (9: totals only)
+      auto kp = p.dbg == 8 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 1> : gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 11>;
       (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
       const int tl = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
       hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(NT), SMEM, st, p);
