@@ -24,6 +24,16 @@ __device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
 }
 
+// max(x[lane], x[lane ^ 32]) without going through LDS: v_permlane32_swap exchanges the upper half
+// of its first operand with the lower half of its second, leaving (lo, lo) and (hi, hi).
+__device__ __forceinline__ float cross_half_max(float x) {
+  unsigned a = __builtin_bit_cast(unsigned, x), b = a;
+  asm volatile("" : "+v"(b));   // two distinct registers
+  auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+  const unsigned r0 = r[0], r1 = r[1];
+  return __builtin_fmaxf(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
+}
+
 // LDS tiles are unpadded and filled by LDS-DMA in 1 KB pieces; 16-byte chunks are XOR-swizzled
 // inside a row so that the 16 lanes served per LDS cycle (256 bytes, 64 banks) never collide:
 //   K   tile [64 keys][HD*2 bytes]:  chunk c of row r sits at c ^ swz_k(r)
@@ -183,6 +193,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
       };
       long long ta = 0, tb = 0, tc = 0;
       if constexpr (PROF) ta = clock64(); else asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_setprio(2);   // the MFMA phases win the issue arbitration against the other wave's softmax arithmetic
       load_k(0);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -199,6 +210,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
         if (ds % (DS / K_IT) == DS / K_IT - 1) issue_one(ds / (DS / K_IT), tn, sn);
         __builtin_amdgcn_sched_barrier(0);
       }
+      __builtin_amdgcn_s_setprio(0);
       __builtin_amdgcn_sched_barrier(0);   // phase boundaries keep the scheduler from stretching live ranges across phases
       if constexpr (PROF) { if (s[1][15] == 12345.f) t_wait = 0; tb = clock64(); t_qk += tb - ta; } else asm volatile("" ::: "memory");
       // s[kb][v] = raw score(key = key0 + kb*32 + 16*(v>>3) + 8*g + (v&7), this lane's query)
@@ -216,7 +228,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) mx = __builtin_fmaxf(mx, s[kb][v]);
-      mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32));
+      mx = cross_half_max(mx);   // (a shuffle through LDS would also wait for the V^T fragments just requested)
       // Lazy rescaling: the reference maximum m_run (raw score units) only moves when some query's
       // tile maximum exceeds it by more than 8/sc, i.e. when an exponential would exceed 2^8.  The
       // result is unchanged (numerator and denominator share m_run); the 64-register rescale of O
@@ -247,6 +259,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
       for (int j = 0; j < 4; ++j) exp_pair(0, j);
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (PROF) { if (rs == 12345.f) t_wait = 0; tc = clock64(); t_sm += tc - tb; } else asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_setprio(1);
       // O^T += V^T P^T, 16 keys per MFMA.  The exponentials of the next step are computed between
       // the MFMAs of this one, and each V^T fragment register is refilled right after its use.
 #pragma unroll
@@ -265,6 +278,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
         __builtin_amdgcn_sched_barrier(0);
       }
       l_run += rs;
+      __builtin_amdgcn_s_setprio(0);
       if constexpr (PROF) { if (o[0][0] == 12345.f) t_wait = 0; t_pv += clock64() - tc; } else asm volatile("" ::: "memory");
     }
     long long tw0 = 0;
