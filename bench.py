@@ -18,7 +18,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 # HBM-side bytes per launch of the dominant kernel (gate/up GEMM), from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # scaled on a 1 GiB copy: see profiles/bench_8b_l16_b8x2048_hbm_traffic.txt (rocprofv3 cannot run inside the bench)
-MEASURED_TRAFFIC_BYTES = {("8b_l16_b8x2048", "gateup_gemm"): 5826.5 * 2 ** 20}
+MEASURED_TRAFFIC_BYTES = {("8b_l16_b8x2048", "gateup_gemm"): 5826.9 * 2 ** 20}
 
 
 def main():
