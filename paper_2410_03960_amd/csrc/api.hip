@@ -59,6 +59,9 @@ struct swiftkv_ctx {
   void *dev_tables = nullptr;
   std::vector<const bf16_t *const *> qkv_tab, gu_tab, norm1_tab, norm2_tab;
   bf16_t *kv_pack = nullptr;   // [P * 2 * kv_dim, hidden]: leaders' [W_K; W_V] with their norm gain folded in
+  // O, gate/up (interleaved) and down weights of the full layers (< l) in MFMA fragment order, or empty
+  bf16_t *w_pack = nullptr;
+  std::vector<const bf16_t *> wo_pack, gu_pack, down_pack;
   Layout last;
   bool have_last = false;
   // timing
@@ -423,6 +426,38 @@ int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftk
       return fail(SWIFTKV_EHIP, "folding gains into the fused KV weight: %s", hipGetErrorString(e));
     }
   }
+  // Fragment-order copies of the large GEMM weights of the layers every token runs (library-owned,
+  // about 0.75 x the size of those layers' weights).  SWIFTKV_PACKED_W=0 keeps the LDS-staged loop.
+  c->wo_pack.assign(m.n_layers, nullptr); c->gu_pack.assign(m.n_layers, nullptr); c->down_pack.assign(m.n_layers, nullptr);
+  const char *pw = getenv("SWIFTKV_PACKED_W");
+  const bool shapes_ok = (d % 256) == 0 && (qd % 256) == 0 && (m.ffn % 256) == 0;
+  if (shapes_ok && !(pw && atoi(pw) == 0)) {
+    const size_t e_o = (size_t)d * qd, e_gu = (size_t)2 * m.ffn * d, e_dn = (size_t)d * m.ffn;
+    const size_t per_layer = e_o + e_gu + e_dn;
+    e = hipMalloc((void **)&c->w_pack, per_layer * l * 2);
+    if (e != hipSuccess) {
+      if (c->kv_pack) (void)hipFree(c->kv_pack);
+      (void)hipFree(c->dev_tables);
+      delete c;
+      return fail(SWIFTKV_EHIP, "allocating the fragment-order weight copies (%zu bytes; SWIFTKV_PACKED_W=0 does without): %s",
+                  per_layer * l * 2, hipGetErrorString(e));
+    }
+    for (int j = 0; j < l; ++j) {
+      bf16_t *po = c->w_pack + (size_t)j * per_layer, *pgu = po + e_o, *pdn = pgu + e_gu;
+      launch_pack_w(nullptr, c->wo[j], qd, (int32_t)d, qd, po, nullptr);
+      launch_pack_w(c->gu_tab[j], nullptr, d, 2 * m.ffn, (int32_t)d, pgu, nullptr);
+      launch_pack_w(nullptr, c->wdown[j], m.ffn, (int32_t)d, m.ffn, pdn, nullptr);
+      c->wo_pack[j] = po; c->gu_pack[j] = pgu; c->down_pack[j] = pdn;
+    }
+    e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+      (void)hipFree(c->w_pack);
+      if (c->kv_pack) (void)hipFree(c->kv_pack);
+      (void)hipFree(c->dev_tables);
+      delete c;
+      return fail(SWIFTKV_EHIP, "packing weights: %s", hipGetErrorString(e));
+    }
+  }
   *out = c;
   return SWIFTKV_OK;
 }
@@ -431,6 +466,7 @@ void swiftkv_destroy(swiftkv_ctx *c) {
   if (!c) return;
   if (c->dev_tables) (void)hipFree(c->dev_tables);
   if (c->kv_pack) (void)hipFree(c->kv_pack);
+  if (c->w_pack) (void)hipFree(c->w_pack);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
   delete c;
 }
@@ -592,7 +628,7 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     }
     {
       GemmParams g{};
-      g.A = ob; g.lda = qd; g.M = T; g.N = d; g.K = qd; g.W = c->wo[j]; g.ldw = qd; g.C = h; g.ldc = d;
+      g.A = ob; g.lda = qd; g.M = T; g.N = d; g.K = qd; g.W = c->wo[j]; g.ldw = qd; g.wpack = c->wo_pack[j]; g.C = h; g.ldc = d;
       tm.begin(TC_O);
       if (launch_gemm(g, EPI_RESID, 0, st) != 0) return fail(SWIFTKV_EHIP, "O GEMM launch failed");
       tm.end();
@@ -602,7 +638,7 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     tm.end();
     {
       GemmParams g{};
-      g.A = ab; g.lda = d; g.M = T; g.N = 2 * m.ffn; g.K = d; g.wtab = c->gu_tab[j]; g.ldw = d;
+      g.A = ab; g.lda = d; g.M = T; g.N = 2 * m.ffn; g.K = d; g.wtab = c->gu_tab[j]; g.ldw = d; g.wpack = c->gu_pack[j];
       g.C = zb; g.ldc = m.ffn;
       tm.begin(TC_GATEUP);
       if (launch_gemm(g, EPI_SWIGLU, 0, st) != 0) return fail(SWIFTKV_EHIP, "gate/up GEMM launch failed");
@@ -610,7 +646,7 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     }
     {
       GemmParams g{};
-      g.A = zb; g.lda = m.ffn; g.M = T; g.N = d; g.K = m.ffn; g.W = c->wdown[j]; g.ldw = m.ffn; g.C = h; g.ldc = d;
+      g.A = zb; g.lda = m.ffn; g.M = T; g.N = d; g.K = m.ffn; g.W = c->wdown[j]; g.ldw = m.ffn; g.wpack = c->down_pack[j]; g.C = h; g.ldc = d;
       tm.begin(TC_DOWN);
       if (launch_gemm(g, EPI_RESID, 0, st) != 0) return fail(SWIFTKV_EHIP, "down GEMM launch failed");
       tm.end();
@@ -685,7 +721,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
                     int32_t variant, void *stream) {
   if (!A || !W || !C) return fail(SWIFTKV_EINVAL, "null argument");
   if (M < 1 || N < 16 || K < 8 || (N % 16) || (K % 8)) return fail(SWIFTKV_EINVAL, "need M >= 1, N %% 16 == 0, K %% 8 == 0");
-  if (variant < 0 || variant > 26) return fail(SWIFTKV_EINVAL, "variant must be 0..26");
+  if (variant < 0 || variant > 27) return fail(SWIFTKV_EINVAL, "variant must be 0..27");
   hipStream_t st = (hipStream_t)stream;
   if (variant == 3) {
     if (M > 80) return fail(SWIFTKV_EINVAL, "weight-streaming kernel handles M <= 80");
@@ -699,8 +735,24 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
   if (variant == 7) { g.dbg = 2; variant = 4; }
   if (variant == 8) { g.dbg = 6; variant = 5; }
   if (variant == 9) { g.dbg = 7; variant = 5; }
+  if (variant == 27) {   // weights repacked into fragment order (library-owned buffer), then the loop that keeps them out of LDS
+    if (M < 1024 || (N % 256) || (K % 256) || out_f32) return fail(SWIFTKV_EINVAL, "variant 27 needs M >= 1024, N %% 256 == 0, K %% 256 == 0, bf16 output");
+    static bf16_t *pack = nullptr;
+    static size_t pack_elems = 0;
+    static const void *pack_src = nullptr;
+    const size_t need = (size_t)N * K;
+    if (need > pack_elems) {
+      if (pack) (void)hipFree(pack);
+      pack = nullptr; pack_elems = 0; pack_src = nullptr;
+      HIP_TRY(hipMalloc((void **)&pack, need * 2));
+      pack_elems = need;
+    }
+    if (pack_src != W || !getenv("SWIFTKV_XP_KEEP_PACK")) launch_pack_w(nullptr, (const bf16_t *)W, K, N, K, pack, st);   // (the variable skips repacking an unchanged pointer, for timing)
+    pack_src = W;
+    g.wpack = pack;
+  }
   if (variant == 26) { g.dbg = 9; g.stage = (bf16_t *)C + (int64_t)M * N; variant = 14; }   // 26: as 12 without the timers inside the k loop
-  if (variant >= 17) { g.dbg = 20 + (variant - 17); variant = 14; }   // 17/18/19: five-stage loop without LDS reads / DMA / both (timing only); 20/21: the same loop with 4 / 3 stages
+  if (variant >= 17 && variant <= 25) { g.dbg = 20 + (variant - 17); variant = 14; }   // 17/18/19: five-stage loop without LDS reads / DMA / both (timing only); 20/21: the same loop with 4 / 3 stages
   if (variant == 16) { g.head_dim = 1; variant = 12; }   // 16: as 12 but every load re-reads k tile 0 (cache-hot)
   if (variant >= 10 && variant <= 13) {  // 10/11: cycle breakdown of variant 5/4; C must have room for 5*8*n_waves*n_workgroups bytes of int64 counters after the M x N result
     g.dbg = 8; g.stage = (bf16_t *)C + (int64_t)M * N;

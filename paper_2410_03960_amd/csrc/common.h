@@ -84,6 +84,8 @@ struct GemmParams {
   const bf16_t *const *wtab;
   const bf16_t *W;
   int64_t ldw;
+  // the same weights in MFMA fragment order (see launch_pack_w), or null: [N/32][K/16][64 lanes][8] bf16
+  const bf16_t *wpack;
   // optional A prologue: A[m,k] *= gain[k]; gain vector chosen per block of gain_seg output columns
   const bf16_t *const *gain_tab;  // device table of gain pointers (nullptr = no gain)
   int32_t gain_seg;
@@ -181,6 +183,9 @@ int launch_rstd(const bf16_t *h, float *rstd, int32_t T, int32_t d, float eps, h
 int launch_rmsnorm_rows(const bf16_t *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, hipStream_t st);
 int launch_gather_rows(const bf16_t *h, const int32_t *rows, bf16_t *out, int32_t n_rows, int32_t d, hipStream_t st);
 int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t st);
+// out[((n/32) * (K/16) + k/16) * 512 + ((k%16)/8 * 32 + n%32) * 8 + k%8] = W row n (through the optional
+// 16-row block pointer table), element k.  N % 32 == 0, K % 16 == 0.
+int launch_pack_w(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, bf16_t *out, hipStream_t st);
 int launch_fold_gain(const bf16_t *W, const bf16_t *gain, bf16_t *out, int64_t rows, int32_t K, hipStream_t st);
 
 struct KVTile {  // 64 consecutive new tokens of one sequence

@@ -19,6 +19,7 @@
 // rows each), which lets [W_Q;W_K;W_V], the 16-row interleave of W_gate/W_up and
 // the concatenated [W_K;W_V] of all AcrossKV group leaders be consumed in place.
 #include "common.h"
+#include <type_traits>
 
 #include <cstdlib>
 
@@ -1012,9 +1013,243 @@ int launch_one(const GemmParams &p, hipStream_t st) {
   return 0;
 }
 
+// ---------------------------------------------------------------------------
+// Main loop that keeps the weight operand out of LDS.  The weights are static, so
+// they can be stored once in MFMA fragment order (`wpack`: for every block of 32
+// output rows and 16 k values, the 1 KB that the 64 lanes hold as first operand,
+// lane i at byte 16*i).  A wave then fetches its weight fragments with fully
+// coalesced 16-byte-per-lane loads straight into registers, four 64-wide k steps
+// ahead, and LDS carries the activations only: five stages of 256 rows x 128
+// bytes, filled by LDS-DMA in whole 128-byte row pieces, three steps ahead.
+// The four waves sit side by side along N (wave tile 256 x 64), so no weight byte
+// is loaded twice; every wave reads all of the activation tile from LDS (the same
+// LDS read volume as a 2 x 2 arrangement of 128 x 128 wave tiles, half the LDS
+// writes, half the LDS-DMA requests).  One barrier per 64-wide step, placed
+// before the last 16-wide sub-step, where the next step's activations are first
+// read.  Needs K % 256 == 0 (four register slots, statically indexed) and
+// N % 256 == 0.
+template <int EPI, int FM>
+__device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 (&acc)[2][FM], const int m_base,
+                                                  const int n_base, const int lane, unsigned char *slab) {
+  // acc[bn][bm][4*jg + e] is C[m_base + bm*32 + l32][n_base + bn*32 + 8*jg + 4*g + e].  32 rows at a
+  // time go through a per-wave LDS slab (row stride padded by 16 bytes) and leave as 16-byte stores
+  // in which consecutive lanes cover a contiguous row segment.
+  const int l32 = lane & 31, g = lane >> 5;
+  if constexpr (EPI == EPI_RESID) {
+    constexpr int RS = 64 * 4 + 16;                // fp32 row stride in bytes
+    bf16_t *cbase = (bf16_t *)p.C + n_base;
+#pragma unroll
+    for (int bm = 0; bm < FM; ++bm) {
+#pragma unroll
+      for (int bn = 0; bn < 2; ++bn)
+#pragma unroll
+        for (int jg = 0; jg < 4; ++jg)
+          *(float4 *)(slab + l32 * RS + (bn * 32 + 8 * jg + 4 * g) * 4) =
+              make_float4(acc[bn][bm][4 * jg], acc[bn][bm][4 * jg + 1], acc[bn][bm][4 * jg + 2], acc[bn][bm][4 * jg + 3]);
+      // a wave's LDS operations execute in order: the reads below see the writes above
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int row = it * 8 + (lane >> 3), ch = lane & 7;
+        const int m = m_base + bm * 32 + row;
+        const float4 lo = *(const float4 *)(slab + row * RS + ch * 32), hi = *(const float4 *)(slab + row * RS + ch * 32 + 16);
+        if (m < p.M) {
+          bf16_t *dst = cbase + (int64_t)m * p.ldc + ch * 8;
+          const uint4 r = *(const uint4 *)dst;
+          *(uint4 *)dst = make_uint4(pack_bf16x2(lo.x + bf16lo(r.x), lo.y + bf16hi(r.x)), pack_bf16x2(lo.z + bf16lo(r.y), lo.w + bf16hi(r.y)),
+                                     pack_bf16x2(hi.x + bf16lo(r.z), hi.y + bf16hi(r.z)), pack_bf16x2(hi.z + bf16lo(r.w), hi.w + bf16hi(r.w)));
+        }
+      }
+    }
+  } else {
+    static_assert(EPI == EPI_STORE_BF16 || EPI == EPI_SWIGLU, "epilogues of the 64-column wave tile");
+    constexpr int NC = (EPI == EPI_SWIGLU) ? 32 : 64;   // output columns of the wave tile
+    constexpr int RS = NC * 2 + 16;                      // bf16 row stride in bytes
+    constexpr int CPR = NC / 8, RPI = 64 / CPR;          // 16-byte chunks per row, rows per store instruction
+#pragma unroll
+    for (int bm = 0; bm < FM; ++bm) {
+      unsigned char *srow = slab + l32 * RS;
+      if constexpr (EPI == EPI_SWIGLU) {
+        const int m = m_base + bm * 32 + l32;
+        const float rs = p.rstd ? p.rstd[m < p.M ? m : p.M - 1] : 1.f;
+#pragma unroll
+        for (int bn = 0; bn < 2; ++bn)
+#pragma unroll
+          for (int jg = 0; jg < 2; ++jg) {
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float gt = acc[bn][bm][4 * jg + e] * rs, up = acc[bn][bm][4 * (jg + 2) + e] * rs;
+              o[e] = gt / (1.f + __expf(-gt)) * up;
+            }
+            *(uint2 *)(srow + (bn * 16 + 8 * jg + 4 * g) * 2) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+          }
+      } else {
+#pragma unroll
+        for (int bn = 0; bn < 2; ++bn)
+#pragma unroll
+          for (int jg = 0; jg < 4; ++jg)
+            *(uint2 *)(srow + (bn * 32 + 8 * jg + 4 * g) * 2) =
+                make_uint2(pack_bf16x2(acc[bn][bm][4 * jg], acc[bn][bm][4 * jg + 1]), pack_bf16x2(acc[bn][bm][4 * jg + 2], acc[bn][bm][4 * jg + 3]));
+      }
+      const int ch = lane % CPR;
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; ++it) {
+        const int row = it * RPI + lane / CPR;
+        const int m = m_base + bm * 32 + row;
+        const uint4 val = *(const uint4 *)(slab + row * RS + ch * 16);
+        if (m >= p.M) continue;
+        bf16_t *dst = (bf16_t *)p.C + (int64_t)m * p.ldc + (EPI == EPI_SWIGLU ? n_base / 2 : n_base);
+        *(uint4 *)(dst + ch * 8) = val;
+      }
+    }
+  }
+}
+
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
+  constexpr int BM = 256, BN = 256, FM = 8;
+  constexpr int NSA = 5, STAGE = BM * 128;   // activation stages: 256 rows x 128 bytes (one 64-wide k step)
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, g = lane >> 5;
+
+  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = p.N / BN;
+  const int total = tiles_m * tiles_n;
+  const int per_xcd = (total + 7) / 8;
+  const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (logical >= total) return;
+  const int GM = p.raster_gm > 0 ? p.raster_gm : 8;
+  const int group = logical / (GM * tiles_n);
+  const int first_m = group * GM;
+  const int gsz = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+  const int in_group = logical % (GM * tiles_n);
+  const int tm = first_m + in_group % gsz, tn = in_group / gsz;
+  const int m0 = tm * BM, n0 = tn * BN + wave * 64;   // n0: first column of this wave
+
+  // LDS-DMA sources: request i of this wave covers rows (wave*8 + i)*8 .. +7 of the tile, 128 bytes each;
+  // this lane fetches row +(lane>>3), the 16-byte chunk that lands at physical chunk lane&7
+  const bf16_t *a_ptr[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int r = (wave * 8 + i) * 8 + (lane >> 3);
+    int m = m0 + r;
+    m = m < p.M ? m : p.M - 1;
+    a_ptr[i] = p.A + (int64_t)m * p.lda + (((lane & 7) ^ ((r >> 1) & 7)) * 8);
+  }
+  // packed weight fragments of the wave's two 32-row blocks: (block, k16) at ((block * K/16) + k16) * 512 elements
+  const bf16_t *w_ptr[2];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) w_ptr[nb] = p.wpack + ((int64_t)(n0 / 32 + nb) * (p.K / 16)) * 512 + lane * 8;
+
+  typedef __attribute__((address_space(3))) void *lds_ptr_t;
+  const unsigned lds_base = (unsigned)(size_t)(lds_ptr_t)smem;
+
+  floatx16 acc[2][FM];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int bm = 0; bm < FM; ++bm)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[nb][bm][v] = 0.f;
+
+  // activation fragment of m block bm, sub-step kk: row bm*32 + l32, chunk (2*kk + g) ^ swizzle(row);
+  // the swizzle of a 128-byte row is (row >> 1) & 7, the same for every m block, and kk enters as an XOR with 32*kk
+  const unsigned a_lane = l32 * 128 + ((g ^ ((l32 >> 1) & 7)) << 4);
+
+  bf16x8 wf[4][8];   // [slot of the step][2*kk + nb]
+  bf16x8 af[2][FM];
+  const int nk = p.K / 64;
+
+  auto issue_a = [&](int i, int stage, int step) {
+    lds_dma16(a_ptr[i] + (int64_t)step * 64, lds_base + stage * STAGE + (wave * 8 + i) * 1024);
+  };
+  auto load_w = [&](bf16x8 &dst, int nb, int kk, int step) {
+    dst = *(const bf16x8 *)(w_ptr[nb] + ((int64_t)step * 4 + kk) * 512);
+  };
+
+  // prologue: steps 0, 1, 2 requested (16 requests per wave and step, activations and weights alternating)
+#pragma unroll
+  for (int s0 = 0; s0 < 3; ++s0) {
+    const int step = s0 < nk ? s0 : nk - 1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      issue_a(i, s0, step);
+      load_w(wf[s0][i], i & 1, i >> 1, step);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x8F70);   // vmcnt(32): step 0 has landed (this wave's part)
+  __builtin_amdgcn_s_barrier();
+#pragma unroll
+  for (int bm = 0; bm < FM; ++bm) af[0][bm] = *(const bf16x8 *)(smem + a_lane + bm * 4096);
+
+  int sa = 0;   // stage of the current step
+  auto step_fn = [&](auto slot_c, const int it) {
+    constexpr int slot = decltype(slot_c)::value;
+    constexpr int lslot = (slot + 3) & 3;                 // the slot freed by the previous step takes the weights of step it+3
+    const int sn = sa == NSA - 1 ? 0 : sa + 1;            // stage of step it+1
+    const int sld = sa >= 2 ? sa - 2 : sa + 3;            // stage of step it+3 = stage of step it-2 (free)
+    const int kl = it + 3 < nk ? it + 3 : nk - 1;         // clamped: the request count per step stays constant
+    const unsigned char *st = smem + sa * STAGE, *stn = smem + sn * STAGE;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      if (kk == 3) {
+        // step it+1 (requested during step it-2) must be resident before its first fragments are read:
+        // younger requests are the 16 of step it-1 and the 12 issued so far in this step
+        __builtin_amdgcn_s_waitcnt(0x4F7C);   // vmcnt(28)
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int nb = i / 8, bm = i % 8;
+        acc[nb][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][kk * 2 + nb], af[kk & 1][bm], acc[nb][bm], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (i < 8) af[(kk + 1) & 1][i] = *(const bf16x8 *)((kk < 3 ? st : stn) + (a_lane ^ (unsigned)(((kk + 1) & 3) * 32)) + i * 4096);
+        if (i % 8 == 3) issue_a(kk * 2 + i / 8, sld, kl);
+        if (i % 8 == 7) load_w(wf[lslot][kk * 2 + i / 8], i / 8, kk, kl);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    sa = sn;
+  };
+  for (int it = 0; it < nk; it += 4) {
+    step_fn(std::integral_constant<int, 0>{}, it);
+    step_fn(std::integral_constant<int, 1>{}, it + 1);
+    step_fn(std::integral_constant<int, 2>{}, it + 2);
+    step_fn(std::integral_constant<int, 3>{}, it + 3);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped extra requests ...
+  __builtin_amdgcn_s_barrier();         // ... of every wave, before LDS is reused by the epilogue
+  unsigned char *slab = smem + wave * (32 * (64 * 4 + 16));
+  gemm_epilogue_n64<EPI, FM>(p, acc, m0, n0, lane, slab);
+}
+
+template <int EPI>
+int launch_wreg(const GemmParams &p, hipStream_t st) {
+  constexpr int SMEM = 5 * 256 * 128;
+  auto kern = gemm_wreg_kernel<EPI>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+    if (e != hipSuccess) return (int)e;
+    attr_set = true;
+  }
+  const int tiles = ((p.M + 255) / 256) * (p.N / 256);
+  hipLaunchKernelGGL(kern, dim3(((tiles + 7) / 8) * 8), dim3(256), SMEM, st, p);
+  return 0;
+}
+
 template <int EPI, bool GAIN>
 int launch_epi(const GemmParams &p, int variant, hipStream_t st) {
   if (variant == 0) variant = (p.M >= 1024) ? ((!GAIN && (p.K % BK) == 0) ? g_big_variant : 1) : 2;
+  if constexpr (!GAIN && (EPI == EPI_STORE_BF16 || EPI == EPI_RESID || EPI == EPI_SWIGLU)) {
+    // weights available in fragment order: the loop that keeps them out of LDS
+    if (p.wpack && (variant == 27 || variant == g_big_variant) && p.M >= 1024 && (p.K % 256) == 0 && (p.N % 256) == 0)
+      return launch_wreg<EPI>(p, st);
+  }
+  if (variant == 27) variant = g_big_variant;
   if constexpr (!GAIN) {
     if ((variant == 4 || variant == 5) && (p.K % BK) != 0) variant = 1;
     if ((variant == 14 || variant == 15) && (p.K % BK) != 0) variant = 1;
