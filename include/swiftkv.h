@@ -20,7 +20,8 @@
  *  - Return value: SWIFTKV_OK (0) or a negative error; swiftkv_last_error()
  *    then gives a thread-local message.  Outputs are unspecified after an error.
  *  - The library never allocates device memory in swiftkv_prefill; it allocates
- *    a few small tables in swiftkv_create and frees them in swiftkv_destroy.
+ *    its tables and weight copies in swiftkv_create (sizes given there) and
+ *    frees them in swiftkv_destroy.
  *  - All matrices are bf16, row-major [out_features, in_features].
  */
 #ifndef SWIFTKV_H
@@ -101,7 +102,14 @@ typedef struct swiftkv_ctx swiftkv_ctx;
  * copying weights, and packs the operand of the single fused KV GEMM of Eq. 2:
  * the group leaders' [W_K;W_V] with their input-norm gain folded in (a device
  * allocation of (L-l)/g * 2*n_kv_heads*head_dim * hidden bf16 elements, plus a
- * few MB of tables).  Synchronises the device once. */
+ * few MB of tables).  When hidden, n_q_heads*head_dim and ffn are multiples of
+ * 256 it also copies W_O, [W_gate;W_up] and W_down of layers 1..l into the
+ * register-fragment order of the matrix instructions (l * (hidden*q_dim +
+ * 3*hidden*ffn) bf16 elements: 6.2 GB for the 8B shape at l = 16, 62 GB for the
+ * 70B shape at l = 40), which lets those GEMMs load weights without passing
+ * them through LDS; the environment variable SWIFTKV_PACKED_W=0 skips the copies
+ * and keeps the LDS-staged loop.  Fails with SWIFTKV_EHIP if an allocation
+ * fails.  Synchronises the device. */
 int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftkv_weights *w,
                    int32_t l, int32_t acrosskv_group);
 void swiftkv_destroy(swiftkv_ctx *ctx);
@@ -155,8 +163,12 @@ int swiftkv_export_hidden(swiftkv_ctx *ctx, const void *workspace, void *hidden_
  * direct-to-LDS loop with 4 / 8 waves (what 0 picks for large M), 20 / 21 = that
  * loop with 4 / 3 stages, 22..24 = with non-temporal loads of both / A / W,
  * 25 = with a shared L2 prefetch (20..25 apply to bf16 output; tuning aids
- * with correct results).  6..13 and 16..19 are timing experiments whose results
- * are not meaningful (10..13 and 16 also need room behind C for counters).
+ * with correct results), 27 = the loop that takes the weights in MFMA
+ * fragment order straight into registers (M >= 1024, N, K multiples of 256,
+ * bf16 output; W is repacked into a library-owned buffer on every call unless
+ * SWIFTKV_XP_KEEP_PACK is set and the pointer is unchanged).  6..13, 16..19 and 26 are timing experiments whose
+ * results are not meaningful (10..13, 16 and 26 also need room behind C for
+ * counters).
  * All dev. */
 int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K,
                     int32_t out_f32, int32_t variant, void *stream);

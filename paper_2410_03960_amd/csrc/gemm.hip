@@ -1165,6 +1165,11 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
   auto issue_a = [&](int i, int stage, int step) {
     lds_dma16(a_ptr[i] + (int64_t)step * 64, lds_base + stage * STAGE + (wave * 8 + i) * 1024);
   };
+  // Plain loads: the compiler places their vmcnt waits.  It counts only these loads, not the LDS-DMA
+  // requests issued from inline assembly in between, so its waits are stricter than necessary, never
+  // weaker.  (Hand-placed waits that relied on register loads and LDS-DMA completing in one common
+  // order gave results that changed from run to run: the two kinds do not complete in issue order
+  // relative to each other.)
   auto load_w = [&](bf16x8 &dst, int nb, int kk, int step) {
     dst = *(const bf16x8 *)(w_ptr[nb] + ((int64_t)step * 4 + kk) * 512);
   };
@@ -1179,7 +1184,7 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
       load_w(wf[s0][i], i & 1, i >> 1, step);
     }
   }
-  __builtin_amdgcn_s_waitcnt(0x8F70);   // vmcnt(32): step 0 has landed (this wave's part)
+  __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16): step 0 has landed (this wave's part; at most the 16 LDS-DMA requests of steps 1, 2 remain)
   __builtin_amdgcn_s_barrier();
 #pragma unroll
   for (int bm = 0; bm < FM; ++bm) af[0][bm] = *(const bf16x8 *)(smem + a_lane + bm * 4096);
@@ -1195,9 +1200,11 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       if (kk == 3) {
-        // step it+1 (requested during step it-2) must be resident before its first fragments are read:
-        // younger requests are the 16 of step it-1 and the 12 issued so far in this step
-        __builtin_amdgcn_s_waitcnt(0x4F7C);   // vmcnt(28)
+        // Step it+1 (requested during step it-2) must be resident before its first fragments are read.
+        // 14 LDS-DMA requests are younger than it (8 of step it-1, 6 of this step).  Register loads and
+        // LDS-DMA do not complete in one common order, so all 14 requests that may stay in flight could
+        // be LDS-DMA ones: the wait is for 14 in total, not for 14 + the 14 younger weight loads.
+        __builtin_amdgcn_s_waitcnt(0x0F7E);   // vmcnt(14)
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
       }

@@ -31,6 +31,7 @@ def _rand_bf16(seed, name, shape, std=1.0):
     (15, 256, 256, 64), (15, 700, 528, 448), (15, 2304, 768, 1024), (15, 517, 272, 192),
     (20, 700, 528, 448), (21, 700, 528, 448), (22, 700, 528, 448), (23, 2304, 768, 1024), (24, 1, 16, 128),
     (25, 256, 256, 64), (25, 700, 528, 448), (25, 2304, 768, 1024), (25, 1031, 1040, 320),
+    (27, 1024, 256, 256), (27, 2304, 768, 1024), (27, 1031, 512, 256), (27, 3000, 1024, 2048),
 ])
 def test_gemm_matches_definition(variant, M, N, K):
     """C = A W^T (Sec. 3.1 projections); fp32 accumulation of bf16 inputs."""
@@ -39,7 +40,7 @@ def test_gemm_matches_definition(variant, M, N, K):
     A = _rand_bf16(1, f"A{M}{K}", (M, K))
     W = _rand_bf16(2, f"W{N}{K}", (N, K), 0.05)
     ref = A.double() @ W.double().T
-    for out_f32 in (True, False):
+    for out_f32 in ((False,) if variant == 27 else (True, False)):
         got = B.op_gemm(A.cuda(), W.cuda(), out_f32=out_f32, variant=variant)
         torch.cuda.synchronize()
         tol = 1e-5 if out_f32 else 4e-3          # fp32 sum of exact products / one bf16 rounding
