@@ -103,10 +103,11 @@ typedef struct swiftkv_ctx swiftkv_ctx;
  * the group leaders' [W_K;W_V] with their input-norm gain folded in (a device
  * allocation of (L-l)/g * 2*n_kv_heads*head_dim * hidden bf16 elements, plus a
  * few MB of tables).  When hidden, n_q_heads*head_dim and ffn are multiples of
- * 256 it also copies W_O, [W_gate;W_up] and W_down of layers 1..l into the
- * register-fragment order of the matrix instructions (l * (hidden*q_dim +
- * 3*hidden*ffn) bf16 elements: 6.2 GB for the 8B shape at l = 16, 62 GB for the
- * 70B shape at l = 40), which lets those GEMMs load weights without passing
+ * 256 it also copies [W_Q;W_K;W_V], W_O, [W_gate;W_up] and W_down of layers
+ * 1..l and the fused KV operand into the register-fragment order of the matrix
+ * instructions (about l * (2*hidden*q_dim + 2*hidden*kv_dim + 3*hidden*ffn) bf16
+ * elements: 7.3 GB for the 8B shape at l = 16, 70 GB for the 70B shape at
+ * l = 40), which lets those GEMMs load weights without passing
  * them through LDS; the environment variable SWIFTKV_PACKED_W=0 skips the copies
  * and keeps the LDS-staged loop.  Fails with SWIFTKV_EHIP if an allocation
  * fails.  Synchronises the device. */

@@ -61,7 +61,8 @@ struct swiftkv_ctx {
   bf16_t *kv_pack = nullptr;   // [P * 2 * kv_dim, hidden]: leaders' [W_K; W_V] with their norm gain folded in
   // O, gate/up (interleaved) and down weights of the full layers (< l) in MFMA fragment order, or empty
   bf16_t *w_pack = nullptr;
-  std::vector<const bf16_t *> wo_pack, gu_pack, down_pack;
+  std::vector<const bf16_t *> qkv_pack, wo_pack, gu_pack, down_pack;
+  const bf16_t *kvf_pack = nullptr;   // the fused KV operand (kv_pack) in fragment order
   Layout last;
   bool have_last = false;
   // timing
@@ -281,7 +282,7 @@ int run_fused_kv(Run &r, const bf16_t *hidden, Timer &tm) {
   tm.end();
   GemmParams g{};
   g.A = hidden; g.lda = m.hidden; g.M = (int32_t)r.L.T; g.N = c->P * 2 * kvd; g.K = m.hidden;
-  g.W = c->kv_pack; g.ldw = m.hidden;   // gains are folded into kv_pack; rstd is applied in the epilogue
+  g.W = c->kv_pack; g.ldw = m.hidden; g.wpack = c->kvf_pack;   // gains are folded into kv_pack; rstd is applied in the epilogue
   g.rstd = r.at<float>(r.L.rstd); g.cos_sin = r.at<float2>(r.L.cos_sin);
   g.head_dim = m.head_dim; g.q_dim = m.n_q_heads * m.head_dim; g.kv_dim = kvd;
   g.slots = r.at<int64_t>(r.L.slots); g.cache = (bf16_t *)r.kv->data;
@@ -428,26 +429,36 @@ int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftk
   }
   // Fragment-order copies of the large GEMM weights of the layers every token runs (library-owned,
   // about 0.75 x the size of those layers' weights).  SWIFTKV_PACKED_W=0 keeps the LDS-staged loop.
-  c->wo_pack.assign(m.n_layers, nullptr); c->gu_pack.assign(m.n_layers, nullptr); c->down_pack.assign(m.n_layers, nullptr);
+  c->qkv_pack.assign(m.n_layers, nullptr); c->wo_pack.assign(m.n_layers, nullptr);
+  c->gu_pack.assign(m.n_layers, nullptr); c->down_pack.assign(m.n_layers, nullptr);
   const char *pw = getenv("SWIFTKV_PACKED_W");
-  const bool shapes_ok = (d % 256) == 0 && (qd % 256) == 0 && (m.ffn % 256) == 0;
+  const bool shapes_ok = (d % 256) == 0 && (qd % 256) == 0 && (m.ffn % 256) == 0 && (kvd % 128) == 0;
   if (shapes_ok && !(pw && atoi(pw) == 0)) {
-    const size_t e_o = (size_t)d * qd, e_gu = (size_t)2 * m.ffn * d, e_dn = (size_t)d * m.ffn;
-    const size_t per_layer = e_o + e_gu + e_dn;
-    e = hipMalloc((void **)&c->w_pack, per_layer * l * 2);
+    const size_t e_qkv = (size_t)(qd + 2 * kvd) * d, e_o = (size_t)d * qd, e_gu = (size_t)2 * m.ffn * d, e_dn = (size_t)d * m.ffn;
+    const size_t per_layer = e_qkv + e_o + e_gu + e_dn;
+    const size_t e_kvf = (size_t)c->P * 2 * kvd * d;
+    const size_t total_elems = per_layer * l + e_kvf;
+    e = hipMalloc((void **)&c->w_pack, total_elems * 2);
     if (e != hipSuccess) {
       if (c->kv_pack) (void)hipFree(c->kv_pack);
       (void)hipFree(c->dev_tables);
       delete c;
       return fail(SWIFTKV_EHIP, "allocating the fragment-order weight copies (%zu bytes; SWIFTKV_PACKED_W=0 does without): %s",
-                  per_layer * l * 2, hipGetErrorString(e));
+                  total_elems * 2, hipGetErrorString(e));
     }
+    const int rope_hd = m.head_dim == 128 ? 128 : 0;   // rotary partner blocks side by side (see pack_w_kernel)
     for (int j = 0; j < l; ++j) {
-      bf16_t *po = c->w_pack + (size_t)j * per_layer, *pgu = po + e_o, *pdn = pgu + e_gu;
-      launch_pack_w(nullptr, c->wo[j], qd, (int32_t)d, qd, po, nullptr);
-      launch_pack_w(c->gu_tab[j], nullptr, d, 2 * m.ffn, (int32_t)d, pgu, nullptr);
-      launch_pack_w(nullptr, c->wdown[j], m.ffn, (int32_t)d, m.ffn, pdn, nullptr);
-      c->wo_pack[j] = po; c->gu_pack[j] = pgu; c->down_pack[j] = pdn;
+      bf16_t *pq = c->w_pack + (size_t)j * per_layer, *po = pq + e_qkv, *pgu = po + e_o, *pdn = pgu + e_gu;
+      launch_pack_w(c->qkv_tab[j], nullptr, d, qd + 2 * kvd, (int32_t)d, rope_hd, pq, nullptr);
+      launch_pack_w(nullptr, c->wo[j], qd, (int32_t)d, qd, 0, po, nullptr);
+      launch_pack_w(c->gu_tab[j], nullptr, d, 2 * m.ffn, (int32_t)d, 0, pgu, nullptr);
+      launch_pack_w(nullptr, c->wdown[j], m.ffn, (int32_t)d, m.ffn, 0, pdn, nullptr);
+      c->qkv_pack[j] = pq; c->wo_pack[j] = po; c->gu_pack[j] = pgu; c->down_pack[j] = pdn;
+    }
+    if (c->P > 0 && ((c->P * 2 * kvd) % 256) == 0) {
+      bf16_t *pk = c->w_pack + per_layer * l;
+      launch_pack_w(nullptr, c->kv_pack, d, c->P * 2 * kvd, (int32_t)d, rope_hd, pk, nullptr);
+      c->kvf_pack = pk;
     }
     e = hipDeviceSynchronize();
     if (e != hipSuccess) {
@@ -575,7 +586,7 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     {
       GemmParams g{};
       g.A = ab; g.lda = d; g.M = T; g.N = qd + 2 * kvd; g.K = d;
-      g.wtab = c->qkv_tab[j]; g.ldw = d;
+      g.wtab = c->qkv_tab[j]; g.ldw = d; g.wpack = c->qkv_pack[j];
       g.cos_sin = r.at<float2>(r.L.cos_sin);
       g.head_dim = m.head_dim; g.q_dim = qd; g.kv_dim = kvd;
       g.q_out = qb; g.k_out = kb; g.v_out = vb;
@@ -747,7 +758,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
       HIP_TRY(hipMalloc((void **)&pack, need * 2));
       pack_elems = need;
     }
-    if (pack_src != W || !getenv("SWIFTKV_XP_KEEP_PACK")) launch_pack_w(nullptr, (const bf16_t *)W, K, N, K, pack, st);   // (the variable skips repacking an unchanged pointer, for timing)
+    if (pack_src != W || !getenv("SWIFTKV_XP_KEEP_PACK")) launch_pack_w(nullptr, (const bf16_t *)W, K, N, K, 0, pack, st);   // (the variable skips repacking an unchanged pointer, for timing)
     pack_src = W;
     g.wpack = pack;
   }

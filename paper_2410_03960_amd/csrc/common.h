@@ -184,8 +184,9 @@ int launch_rmsnorm_rows(const bf16_t *h, const bf16_t *gain, bf16_t *out, int32_
 int launch_gather_rows(const bf16_t *h, const int32_t *rows, bf16_t *out, int32_t n_rows, int32_t d, hipStream_t st);
 int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t st);
 // out[((n/32) * (K/16) + k/16) * 512 + ((k%16)/8 * 32 + n%32) * 8 + k%8] = W row n (through the optional
-// 16-row block pointer table), element k.  N % 32 == 0, K % 16 == 0.
-int launch_pack_w(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, bf16_t *out, hipStream_t st);
+// 16-row block pointer table), element k.  N % 32 == 0, K % 16 == 0.  rope_hd == 128 (N % 128 == 0) takes the
+// 32-row blocks of every 128 rows in the order 0, 2, 1, 3 (rotary partners side by side in a 64-row wave tile).
+int launch_pack_w(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, bf16_t *out, hipStream_t st);
 int launch_fold_gain(const bf16_t *W, const bf16_t *gain, bf16_t *out, int64_t rows, int32_t K, hipStream_t st);
 
 struct KVTile {  // 64 consecutive new tokens of one sequence

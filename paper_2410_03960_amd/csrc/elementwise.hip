@@ -195,23 +195,30 @@ __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
 }
-// One 16-byte chunk per thread: chunk id = ((block * K/16 + k16) * 64 + lane), lane = g*32 + l32
-__global__ void pack_w_kernel(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, uint4 *out) {
+// One 16-byte chunk per thread: chunk id = ((block * K/16 + k16) * 64 + lane), lane = g*32 + l32.
+// rope_hd == 128: inside every group of 128 rows (one head) the 32-row blocks are taken in the order
+// 0, 2, 1, 3, so that a 64-row wave tile holds a block of the first half of the head next to its
+// rotary partner block of the second half.
+__global__ void pack_w_kernel(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, uint4 *out) {
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t n_chunks = (int64_t)N * K / 8;
   if (id >= n_chunks) return;
   const int lane = (int)(id & 63);
   const int64_t frag = id >> 6;
   const int k16 = (int)(frag % (K / 16));
-  const int block = (int)(frag / (K / 16));
+  int block = (int)(frag / (K / 16));
+  if (rope_hd == 128) {
+    const int b = block & 3;
+    block = (block & ~3) | (b == 1 ? 2 : b == 2 ? 1 : b);
+  }
   const int n = block * 32 + (lane & 31), k = k16 * 16 + (lane >> 5) * 8;
   const bf16_t *row = wtab ? wtab[n >> 4] + (int64_t)(n & 15) * ldw : W + (int64_t)n * ldw;
   out[id] = *(const uint4 *)(row + k);
 }
-int launch_pack_w(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, bf16_t *out, hipStream_t st) {
+int launch_pack_w(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, bf16_t *out, hipStream_t st) {
   const int64_t n_chunks = (int64_t)N * K / 8;
   if (n_chunks <= 0) return 0;
-  hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, wtab, W, ldw, N, K, (uint4 *)out);
+  hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, wtab, W, ldw, N, K, rope_hd, (uint4 *)out);
   return 0;
 }
 int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t st) {

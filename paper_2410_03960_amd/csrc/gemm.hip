@@ -80,7 +80,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmParams &p, floatx16 (&ac
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             float gt = acc[bn][bm][4 * jg + e] * rs, up = acc[bn][bm][4 * (jg + 2) + e] * rs;
-            o[e] = gt / (1.f + __expf(-gt)) * up;
+            o[e] = gt * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt)) * up;   // silu(gate) * up
           }
           *(uint2 *)((bf16_t *)p.C + (int64_t)m * p.ldc + col) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
         }
@@ -552,7 +552,7 @@ __device__ __forceinline__ void gemm_epilogue_lds(const GemmParams &p, floatx16 
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const float gt = acc[bn][bm][4 * jg + e] * rs, up = acc[bn][bm][4 * (jg + 2) + e] * rs;
-              o[e] = gt / (1.f + __expf(-gt)) * up;
+              o[e] = gt * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt)) * up;   // silu(gate) * up
             }
             *(uint2 *)(srow + (bn * 16 + 8 * jg + 4 * g) * 2) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
           }
@@ -1038,6 +1038,16 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
   if constexpr (EPI == EPI_RESID) {
     constexpr int RS = 64 * 4 + 16;                // fp32 row stride in bytes
     bf16_t *cbase = (bf16_t *)p.C + n_base;
+    // the residual rows of the whole wave tile are requested up front (the operand registers of the
+    // main loop are free by now), so their latency is paid once, not once per 32 rows
+    uint4 res[FM][4];
+#pragma unroll
+    for (int bm = 0; bm < FM; ++bm)
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int m = m_base + bm * 32 + it * 8 + (lane >> 3);
+        res[bm][it] = *(const uint4 *)(cbase + (int64_t)(m < p.M ? m : p.M - 1) * p.ldc + (lane & 7) * 8);
+      }
 #pragma unroll
     for (int bm = 0; bm < FM; ++bm) {
 #pragma unroll
@@ -1053,12 +1063,90 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
         const int m = m_base + bm * 32 + row;
         const float4 lo = *(const float4 *)(slab + row * RS + ch * 32), hi = *(const float4 *)(slab + row * RS + ch * 32 + 16);
         if (m < p.M) {
-          bf16_t *dst = cbase + (int64_t)m * p.ldc + ch * 8;
-          const uint4 r = *(const uint4 *)dst;
-          *(uint4 *)dst = make_uint4(pack_bf16x2(lo.x + bf16lo(r.x), lo.y + bf16hi(r.x)), pack_bf16x2(lo.z + bf16lo(r.y), lo.w + bf16hi(r.y)),
-                                     pack_bf16x2(hi.x + bf16lo(r.z), hi.y + bf16hi(r.z)), pack_bf16x2(hi.z + bf16lo(r.w), hi.w + bf16hi(r.w)));
+          const uint4 r = res[bm][it];
+          *(uint4 *)(cbase + (int64_t)m * p.ldc + ch * 8) =
+              make_uint4(pack_bf16x2(lo.x + bf16lo(r.x), lo.y + bf16hi(r.x)), pack_bf16x2(lo.z + bf16lo(r.y), lo.w + bf16hi(r.y)),
+                         pack_bf16x2(hi.x + bf16lo(r.z), hi.y + bf16hi(r.z)), pack_bf16x2(hi.z + bf16lo(r.w), hi.w + bf16hi(r.w)));
         }
       }
+    }
+  } else if constexpr (EPI == EPI_QKV || EPI == EPI_KV) {
+    // The wave's 64 (virtual) columns are one head (head_dim 64: blocks = first / second half) or, for
+    // head_dim 128, half a head in the packed order: block 0 = columns s*32.. of the first half, block 1
+    // = their rotary partners s*32 + 64.. (s = parity of the wave tile inside the head).  Either way
+    // element v of block 0 and element v of block 1 are rotary partners.
+    const int hd = p.head_dim;
+    const int head_base = hd == 128 ? (n_base & ~127) : n_base;
+    const int s = hd == 128 ? ((n_base >> 6) & 1) : 0;
+    int kind, col0, proj = 0;                          // kind 0 = q, 1 = k, 2 = v; col0 = head's first column in its output
+    if constexpr (EPI == EPI_QKV) {
+      if (head_base < p.q_dim) { kind = 0; col0 = head_base; }
+      else if (head_base < p.q_dim + p.kv_dim) { kind = 1; col0 = head_base - p.q_dim; }
+      else { kind = 2; col0 = head_base - p.q_dim - p.kv_dim; }
+    } else {
+      proj = head_base / (2 * p.kv_dim);
+      const int within = head_base % (2 * p.kv_dim);
+      kind = within < p.kv_dim ? 1 : 2;
+      col0 = within % p.kv_dim;
+    }
+    const int blk_stride = hd == 128 ? 64 : 32;        // real columns between block 0 and block 1
+    constexpr int RS = 64 * 2 + 16;
+    float amax_h = 0.f;
+#pragma unroll
+    for (int bm = 0; bm < FM; ++bm) {
+      const int m = m_base + bm * 32 + l32;
+      const int mc = m < p.M ? m : p.M - 1;
+      const float rs = p.rstd ? p.rstd[mc] : 1.f;
+      unsigned char *srow = slab + l32 * RS;
+      const float2 *cs = p.cos_sin + (int64_t)mc * (hd / 2) + s * 32;
+#pragma unroll
+      for (int jg = 0; jg < 4; ++jg) {
+        float y1[4], y2[4];
+        const int i0 = 8 * jg + 4 * g;
+        float cv[4] = {1.f, 1.f, 1.f, 1.f}, sv[4] = {0.f, 0.f, 0.f, 0.f};
+        if (kind != 2) {
+          const float4 c01 = *(const float4 *)(cs + i0), c23 = *(const float4 *)(cs + i0 + 2);
+          cv[0] = c01.x; cv[1] = c01.z; cv[2] = c23.x; cv[3] = c23.z;
+          sv[0] = c01.y; sv[1] = c01.w; sv[2] = c23.y; sv[3] = c23.w;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float x1 = acc[0][bm][4 * jg + e] * rs, x2 = acc[1][bm][4 * jg + e] * rs;
+          y1[e] = x1 * cv[e] - x2 * sv[e];
+          y2[e] = x2 * cv[e] + x1 * sv[e];
+        }
+        const uint2 p1 = make_uint2(pack_bf16x2(y1[0], y1[1]), pack_bf16x2(y1[2], y1[3]));
+        const uint2 p2 = make_uint2(pack_bf16x2(y2[0], y2[1]), pack_bf16x2(y2[2], y2[3]));
+        *(uint2 *)(srow + i0 * 2) = p1;
+        *(uint2 *)(srow + (32 + i0) * 2) = p2;
+        if (p.amax && kind != 0 && m < p.M) {   // absmax of the values as stored (bf16-rounded)
+          const float a1 = fmaxf(fmaxf(fabsf(bf16lo(p1.x)), fabsf(bf16hi(p1.x))), fmaxf(fabsf(bf16lo(p1.y)), fabsf(bf16hi(p1.y))));
+          const float a2 = fmaxf(fmaxf(fabsf(bf16lo(p2.x)), fabsf(bf16hi(p2.x))), fmaxf(fabsf(bf16lo(p2.y)), fabsf(bf16hi(p2.y))));
+          amax_h = fmaxf(amax_h, fmaxf(a1, a2));
+        }
+      }
+      // stream out: 8 rows per instruction, chunk ch = 8 local columns; local block ch/4
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int row = it * 8 + (lane >> 3), ch = lane & 7;
+        const int mm = m_base + bm * 32 + row;
+        const uint4 val = *(const uint4 *)(slab + row * RS + ch * 16);
+        if (mm >= p.M) continue;
+        const int col = col0 + (ch >> 2) * blk_stride + s * 32 + (ch & 3) * 8;
+        bf16_t *dst;
+        if constexpr (EPI == EPI_QKV)
+          dst = kind == 0 ? p.q_out + (int64_t)mm * p.q_dim + col : (kind == 1 ? p.k_out : p.v_out) + (int64_t)mm * p.kv_dim + col;
+        else
+          dst = p.stage ? p.stage + (int64_t)mm * p.N + (int64_t)proj * 2 * p.kv_dim + (kind == 2 ? p.kv_dim : 0) + col
+                        : p.cache + (int64_t)(p.first_cache_layer + proj) * p.cache_layer_stride +
+                              (kind == 2 ? p.cache_kv_stride : 0) + p.slots[mm] * p.kv_dim + col;
+        *(uint4 *)dst = val;
+      }
+    }
+    if (p.amax && kind != 0) {
+      const float a = wave_max(amax_h);
+      if (lane == 0)
+        atomicMax(p.amax + ((int64_t)(p.first_cache_layer + proj) * 2 + (kind == 2 ? 1 : 0)) * (p.kv_dim / hd) + col0 / hd, __float_as_uint(a));
     }
   } else {
     static_assert(EPI == EPI_STORE_BF16 || EPI == EPI_SWIGLU, "epilogues of the 64-column wave tile");
@@ -1079,7 +1167,7 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const float gt = acc[bn][bm][4 * jg + e] * rs, up = acc[bn][bm][4 * (jg + 2) + e] * rs;
-              o[e] = gt / (1.f + __expf(-gt)) * up;
+              o[e] = gt * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt)) * up;   // silu(gate) * up
             }
             *(uint2 *)(srow + (bn * 16 + 8 * jg + 4 * g) * 2) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
           }
@@ -1251,7 +1339,7 @@ int launch_wreg(const GemmParams &p, hipStream_t st) {
 template <int EPI, bool GAIN>
 int launch_epi(const GemmParams &p, int variant, hipStream_t st) {
   if (variant == 0) variant = (p.M >= 1024) ? ((!GAIN && (p.K % BK) == 0) ? g_big_variant : 1) : 2;
-  if constexpr (!GAIN && (EPI == EPI_STORE_BF16 || EPI == EPI_RESID || EPI == EPI_SWIGLU)) {
+  if constexpr (!GAIN && EPI != EPI_STORE_F32) {
     // weights available in fragment order: the loop that keeps them out of LDS
     if (p.wpack && (variant == 27 || variant == g_big_variant) && p.M >= 1024 && (p.K % 256) == 0 && (p.N % 256) == 0)
       return launch_wreg<EPI>(p, st);
