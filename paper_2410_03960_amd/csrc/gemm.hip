@@ -1193,7 +1193,7 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
   }
 }
 
-template <int EPI>
+template <int EPI, bool PROF = false>   // PROF: cycle counters written through p.stage (timing experiment)
 __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
   constexpr int BM = 256, BN = 256, FM = 8;
   constexpr int NSA = 5, STAGE = BM * 128;   // activation stages: 256 rows x 128 bytes (one 64-wide k step)
@@ -1262,6 +1262,8 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
     dst = *(const bf16x8 *)(w_ptr[nb] + ((int64_t)step * 4 + kk) * 512);
   };
 
+  long long t_begin = 0, t_vm = 0, t_bar = 0;
+  if constexpr (PROF) t_begin = clock64();
   // prologue: steps 0, 1, 2 requested (16 requests per wave and step, activations and weights alternating)
 #pragma unroll
   for (int s0 = 0; s0 < 3; ++s0) {
@@ -1292,8 +1294,12 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
         // 14 LDS-DMA requests are younger than it (8 of step it-1, 6 of this step).  Register loads and
         // LDS-DMA do not complete in one common order, so all 14 requests that may stay in flight could
         // be LDS-DMA ones: the wait is for 14 in total, not for 14 + the 14 younger weight loads.
+        long long tp0 = 0, tp1 = 0;
+        if constexpr (PROF) { __builtin_amdgcn_s_waitcnt(0xC07F); tp0 = clock64(); }
         __builtin_amdgcn_s_waitcnt(0x0F7E);   // vmcnt(14)
+        if constexpr (PROF) tp1 = clock64();
         __builtin_amdgcn_s_barrier();
+        if constexpr (PROF) { t_vm += tp1 - tp0; t_bar += clock64() - tp1; }
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
@@ -1318,12 +1324,29 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
   __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped extra requests ...
   __builtin_amdgcn_s_barrier();         // ... of every wave, before LDS is reused by the epilogue
   unsigned char *slab = smem + wave * (32 * (64 * 4 + 16));
+  long long t_loop = 0;
+  if constexpr (PROF) t_loop = clock64() - t_begin;
   gemm_epilogue_n64<EPI, FM>(p, acc, m0, n0, lane, slab);
+  if constexpr (PROF) {
+    if (lane == 0 && p.stage) {   // experiment only: `stage` doubles as the int64 output [wg][wave][5]
+      long long *o = (long long *)p.stage + ((long long)blockIdx.x * 4 + wave) * 5;
+      o[0] = t_loop; o[1] = t_vm; o[2] = t_bar; o[3] = 0; o[4] = clock64() - t_begin;
+    }
+  }
 }
 
 template <int EPI>
 int launch_wreg(const GemmParams &p, hipStream_t st) {
   constexpr int SMEM = 5 * 256 * 128;
+  if constexpr (EPI == EPI_STORE_BF16) {
+    if (p.dbg == 8) {   // timing experiment: per-wave cycle breakdown written through p.stage
+      auto kp = gemm_wreg_kernel<EPI, true>;
+      (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+      const int tl = ((p.M + 255) / 256) * (p.N / 256);
+      hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(256), SMEM, st, p);
+      return 0;
+    }
+  }
   auto kern = gemm_wreg_kernel<EPI>;
   static bool attr_set = false;
   if (!attr_set) {
