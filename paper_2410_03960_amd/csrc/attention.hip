@@ -329,276 +329,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
   }
 }
 
-// ---------------------------------------------------------------------------
-// Two-group ("ping-pong") version of the prefill kernel.  A workgroup has 8 waves: waves 0-3 work on
-// query head h, waves 4-7 on head h+1 of the same KV head, both on the same 128 queries, so a K / V^T
-// tile is brought into LDS once for two heads.  The hardware places wave i on SIMD i mod 4: every SIMD
-// holds one wave of each group.  A tile is processed in two phases,
-//     GEMM(t):    O += V^T(t-1) P(t-1)  then  S(t) = K(t) Q^T        (32 MFMAs, almost no VALU work)
-//     softmax(t): mask, running max, exponentials, P(t) in bf16      (VALU only)
-// separated by workgroup barriers, and the second group runs one phase behind the first: while one
-// wave of a SIMD keeps the matrix unit busy, the other does the softmax arithmetic.  Tiles live in a
-// ring of four LDS slots (K(t) is read in phases 2t and 2t+1, V^T(t) in 2t+2 and 2t+3) and are
-// requested two tiles ahead, each wave issuing its share of a tile's K requests in the even phase and
-// of its V^T requests in the odd phase.
-template <int HD, bool PROF = false>
-__global__ __launch_bounds__(512) void attn_prefill_pp_kernel(AttnPrefillParams p) {
-  long long pt_gemm = 0, pt_sm = 0, pt_end = 0, pt_n = 0;
-  constexpr int KCH = HD / 8;              // 16-byte chunks per K row (16 or 8)
-  constexpr int K_RPI = 64 / KCH;          // K rows per 1 KB DMA request (4 or 8)
-  constexpr int K_BYTES = BKV * HD * 2, V_BYTES = HD * BKV * 2;
-  constexpr int STAGE = K_BYTES + V_BYTES;
-  constexpr int NSLOT = 4;
-  constexpr int RPW = K_BYTES / 1024 / 8;  // requests per wave per phase (2 or 1): 8 waves share the K (or V^T) requests of a tile
-  constexpr int DS = HD / 16;              // d steps of the QK^T contraction
-  constexpr int DB = HD / 32;              // 32-wide d blocks of the output
-
-  extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ int s_item;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int grp = wave >> 2, w4 = wave & 3;
-  const int l32 = lane & 31, g = lane >> 5;
-  const int R = p.n_q_heads / p.n_kv_heads;          // even (checked by the launcher)
-  const int n_pairs = p.n_q_heads / 2;
-  // one queue per XCD when the head pairs divide evenly; pair slot s stands for KV head s mod Hkv,
-  // pair s / Hkv of that KV head (all pairs of a KV head meet in one L2)
-  const int NQ = (n_pairs % 8 == 0) ? 8 : 1;
-  const int qid = blockIdx.x % NQ, ppq = n_pairs / NQ;
-  const int n_items = p.n_qblocks * ppq;   // per queue
-  const int q_dim = p.n_q_heads * HD, kv_dim = p.n_kv_heads * HD;
-  typedef __attribute__((address_space(3))) void *lds_ptr_t;
-  const unsigned lds_base = (unsigned)(size_t)(lds_ptr_t)smem;
-
-  // LDS read addresses of this lane (see attn_prefill_kernel)
-  const int krow = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
-  const unsigned k_lane = krow * (HD * 2) + ((g ^ (HD == 128 ? (krow & 15) : ((krow >> 1) & 7))) << 4);
-  const unsigned v_lane = K_BYTES + l32 * 128 + ((g ^ ((l32 >> 1) & 7)) << 4);
-  const float sc = 1.4426950408889634f * rsqrtf((float)HD);   // log2(e) / sqrt(hd)
-  const float inv_sc = 1.0f / sc;
-
-  if (tid == 0) s_item = atomicAdd(p.sched + qid, 1);
-  __syncthreads();
-  for (;;) {
-    const int item = s_item;
-    if (item >= n_items) break;
-    int item_next = 0;
-    if (tid == 0) item_next = atomicAdd(p.sched + qid, 1);   // consumed after the last phase
-    const int qblock = item / ppq;
-    const QBlock qb = p.qblocks[qblock];
-    const int pslot = (item % ppq) * NQ + qid;
-    const int kvh = pslot % p.n_kv_heads;
-    const int head = kvh * R + 2 * (pslot / p.n_kv_heads) + grp;
-
-    const int qpos = qb.q0 + w4 * 32 + l32;
-    const bool qvalid = qpos < qb.n;
-    const int qrow = qb.row0 + w4 * 32 + l32;
-    const int qrow_c = qvalid ? qrow : qb.seq_row0 + qb.n - 1;
-    bf16x8 qf[DS];
-    {
-      const bf16_t *qp = p.q + (int64_t)qrow_c * q_dim + head * HD;
-#pragma unroll
-      for (int ds = 0; ds < DS; ++ds) qf[ds] = *(const bf16x8 *)(qp + (ds * 2 + g) * 8);
-    }
-    const int k_end = (qb.q0 + BQ) < qb.n ? (qb.q0 + BQ) : qb.n;
-    const int n_tiles = (k_end + BKV - 1) / BKV;
-    const int wave_last = qb.q0 + w4 * 32 + 31;
-
-    const bf16_t *kbase = p.k + (int64_t)qb.seq_row0 * kv_dim + kvh * HD;
-    const bf16_t *vbase = p.vt + (int64_t)(kvh * HD) * p.vt_ld + qb.vt_col0;
-    // this wave's requests of a tile: K requests wave*RPW + j in the even phase, V^T requests likewise in the odd phase
-    int k_row[RPW], k_col[RPW];
-    const bf16_t *v_src[RPW];
-#pragma unroll
-    for (int j = 0; j < RPW; ++j) {
-      const int rq = wave * RPW + j;
-      const int r = rq * K_RPI + lane / KCH;
-      k_row[j] = r;
-      k_col[j] = ((lane % KCH) ^ (HD == 128 ? (r & 15) : ((r >> 1) & 7))) * 8;
-      const int d = rq * 8 + (lane >> 3);
-      v_src[j] = vbase + (int64_t)d * p.vt_ld + (((lane & 7) ^ ((d >> 1) & 7)) * 8);
-    }
-    auto issue = [&](int tile, int parity) {   // this wave's share of the tile's K (parity 0) or V^T (parity 1) requests
-      const int key0 = tile * BKV;
-      const unsigned st = lds_base + (tile & (NSLOT - 1)) * STAGE;
-#pragma unroll
-      for (int j = 0; j < RPW; ++j) {
-        if (parity == 0) {
-          int key = key0 + k_row[j];
-          key = key < qb.n ? key : qb.n - 1;   // rows past the end are masked later; any finite data will do
-          lds_dma16(kbase + ((int64_t)key * kv_dim + k_col[j]), st + (wave * RPW + j) * 1024);
-        } else {
-          lds_dma16(v_src[j] + key0, st + K_BYTES + (wave * RPW + j) * 1024);   // padded columns are zero
-        }
-      }
-    };
-    auto phase_dma = [&](int gp) {   // global phase gp requests tile gp/2 + 2
-      const int tile = (gp >> 1) + 2;
-      if (tile < n_tiles) issue(tile, gp & 1);
-    };
-    auto phase_end = [&]() {
-      // requests of the two youngest phases may stay in flight (a tile is first read two phases after its last request)
-      if (RPW == 2) __builtin_amdgcn_s_waitcnt(0x0F74); else __builtin_amdgcn_s_waitcnt(0x0F72);   // vmcnt(2 * RPW)
-      __builtin_amdgcn_s_barrier();
-      asm volatile("" ::: "memory");
-    };
-
-    floatx16 o[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
-    floatx16 s[2];
-    bf16x8 pf[4];
-    float m_run = -INFINITY, l_run = 0.f;
-
-    // prologue: tiles 0 and 1 in full
-#pragma unroll
-    for (int t0 = 0; t0 < 2; ++t0)
-      if (t0 < n_tiles) { issue(t0, 0); issue(t0, 1); }
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    if (grp == 1) { phase_dma(0); phase_end(); }   // the second group runs one phase behind
-
-    for (int t = 0; t <= n_tiles; ++t) {
-      // ------------------------------------------------ GEMM phase ----
-      long long pt0 = 0, pt1 = 0, pt2 = 0, pt3 = 0;
-      if constexpr (PROF) pt0 = clock64();
-      phase_dma(2 * t + grp);
-      __builtin_amdgcn_s_setprio(2);
-      // The other wave of the SIMD is busy with softmax arithmetic, so nobody else hides this wave's
-      // LDS latency: operand fragments are requested three (K) / two (V^T) MFMA groups ahead.
-      const bool do_pv = t > 0 && (t - 1) * BKV <= wave_last;
-      const bool do_qk = t < n_tiles && t * BKV <= wave_last;
-      const unsigned v_addr = ((t - 1) & (NSLOT - 1)) * STAGE + v_lane;
-      const unsigned k_addr = (t & (NSLOT - 1)) * STAGE + k_lane;
-      bf16x8 vfr[2][DB];
-      bf16x8 kfr[4][2];
-      auto load_v = [&](int st) {
-#pragma unroll
-        for (int db = 0; db < DB; ++db) vfr[st & 1][db] = *(const bf16x8 *)(smem + (v_addr ^ (unsigned)(st * 32)) + db * 4096);
-      };
-      auto load_k = [&](int ds) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) kfr[ds & 3][kb] = *(const bf16x8 *)(smem + (k_addr ^ (unsigned)(ds * 32)) + kb * (32 * HD * 2));
-      };
-      if (do_pv) { load_v(0); load_v(1); }
-      if (do_qk) { load_k(0); load_k(1); load_k(2); }
-      __builtin_amdgcn_sched_barrier(0);
-      if (do_pv) {   // O^T += V^T(t-1) P^T(t-1)
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-#pragma unroll
-          for (int db = 0; db < DB; ++db) o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[st & 1][db], pf[st], o[db], 0, 0, 0);
-          __builtin_amdgcn_sched_barrier(0);
-          if (st + 2 < 4) load_v(st + 2);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-      if (do_qk) {   // S^T(t) = K(t) Q^T
-#pragma unroll
-        for (int ds = 0; ds < DS; ++ds) {
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb) {
-            if (ds == 0) {
-              floatx16 z;
-#pragma unroll
-              for (int v = 0; v < 16; ++v) z[v] = 0.f;
-              s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[0][kb], qf[0], z, 0, 0, 0);
-            } else {
-              s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ds & 3][kb], qf[ds], s[kb], 0, 0, 0);
-            }
-          }
-          __builtin_amdgcn_sched_barrier(0);
-          if (ds + 3 < DS) load_k(ds + 3);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-      __builtin_amdgcn_s_setprio(0);
-      if constexpr (PROF) { if (s[1][15] == 12345.f && o[0][0] == 54321.f) pt_n = 0; pt1 = clock64(); }
-      phase_end();
-      if constexpr (PROF) pt2 = clock64();
-      // ---------------------------------------------- softmax phase ----
-      phase_dma(2 * t + grp + 1);
-      if (t < n_tiles && t * BKV <= wave_last) {
-        const int key0 = t * BKV;
-        // s[kb][v] = raw score(key = key0 + kb*32 + 16*(v>>3) + 8*g + (v&7), this lane's query)
-        const bool need_mask = (key0 + BKV - 1 > qb.q0 + w4 * 32) || (key0 + BKV > qb.n);
-        if (need_mask) {
-          const int lim = (qpos < qb.n - 1 ? qpos : qb.n - 1) - key0 - 8 * g;
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) s[kb][v] = (kb * 32 + 16 * (v >> 3) + (v & 7) > lim) ? -INFINITY : s[kb][v];
-        }
-        float mx = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) mx = __builtin_fmaxf(mx, s[kb][v]);
-        mx = cross_half_max(mx);
-        if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.0f * inv_sc) != 0) {   // lazy rescaling, see attn_prefill_kernel
-          const float m_new = __builtin_fmaxf(m_run, mx);
-          const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
-          m_run = m_new;
-          l_run *= alpha;
-#pragma unroll
-          for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
-        }
-        const float msc = m_run * sc;
-        float rs = 0.f;
-#pragma unroll
-        for (int st = 0; st < 4; ++st)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const float x = __builtin_amdgcn_exp2f(__builtin_fmaf(s[st >> 1][(st & 1) * 8 + e], sc, -msc));   // exp2 of (-inf) is 0
-            rs += x;
-            pf[st][e] = (__bf16)x;
-          }
-        l_run += rs;
-      }
-      if constexpr (PROF) { if (l_run == 12345.f) pt_n = 0; pt3 = clock64(); }
-      phase_end();
-      if constexpr (PROF) { pt_gemm += pt1 - pt0; pt_sm += pt3 - pt2; pt_end += (pt2 - pt1) + (clock64() - pt3); ++pt_n; }
-    }
-    if (grp == 0) { phase_dma(2 * n_tiles + 2); phase_end(); }   // the first group waits out the second group's last phase
-
-    // ---- normalise and store: o[db][4*jg+e] = O[query][d = db*32 + 8*jg + 4*g + e] ----
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (qvalid) {
-      const float inv = 1.f / l_tot;
-      bf16_t *op = p.out + (int64_t)qrow * q_dim + head * HD;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int jg = 0; jg < 4; ++jg) {
-          *(uint2 *)(op + db * 32 + 8 * jg + 4 * g) =
-              make_uint2(pack_bf16x2(o[db][4 * jg] * inv, o[db][4 * jg + 1] * inv), pack_bf16x2(o[db][4 * jg + 2] * inv, o[db][4 * jg + 3] * inv));
-        }
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // nothing of this item in flight when the slots are reused
-    if (tid == 0) s_item = item_next;
-    __syncthreads();
-  }
-  if constexpr (PROF) {
-    if ((tid & 63) == 0 && p.prof) {   // per wave: cycles in the GEMM phases, softmax phases, waits + barriers, phase pairs
-      long long *w4p = p.prof + ((long long)blockIdx.x * 8 + wave) * 4;
-      w4p[0] = pt_gemm; w4p[1] = pt_sm; w4p[2] = pt_end; w4p[3] = pt_n;
-    }
-  }
-  // the last workgroup to leave zeroes the counters for the next launch
-  if (tid == 0) {
-    __threadfence();
-    if (atomicAdd(p.sched + 8, 1) == (int)gridDim.x - 1) {
-      for (int i = 0; i < 9; ++i) p.sched[i] = 0;
-      __threadfence();
-    }
-  }
-}
-
 // --------------------------------------------------------------- decode ----
 // grid (n_rows, n_kv_heads, n_split); 256 threads.  Each group of LPK lanes
 // (hd/8) owns one key at a time and 8 dims of it; the R = Hq/Hkv query heads of
@@ -754,38 +484,6 @@ int launch_attention_prefill(const AttnPrefillParams &p, hipStream_t st) {
   if (n_cu == 0) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) n_cu = 256;
-  }
-  static int use_pp = -1;   // SWIFTKV_ATTN_PINGPONG=0 keeps the one-head-per-workgroup kernel
-  if (use_pp < 0) { const char *e = getenv("SWIFTKV_ATTN_PINGPONG"); use_pp = (e && atoi(e) == 0) ? 0 : 1; }
-  const int R = p.n_q_heads / p.n_kv_heads;
-  if (use_pp && (R % 2) == 0) {
-    // two heads of one KV head per workgroup, 8 waves, one workgroup per CU (a multiple of 8 workgroups)
-    dim3 grid((unsigned)n_cu);
-    if (p.head_dim == 128) {
-      constexpr int SMEM = 4 * (BKV * 128 * 2 + 128 * BKV * 2);
-      static bool set = false;
-      if (!set) {
-        hipError_t e = hipFuncSetAttribute((const void *)attn_prefill_pp_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-        if (e != hipSuccess) return (int)e;
-        set = true;
-      }
-      if (p.prof) {
-        (void)hipFuncSetAttribute((const void *)attn_prefill_pp_kernel<128, true>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-        hipLaunchKernelGGL((attn_prefill_pp_kernel<128, true>), grid, dim3(512), SMEM, st, p);
-        return 0;
-      }
-      hipLaunchKernelGGL(attn_prefill_pp_kernel<128>, grid, dim3(512), SMEM, st, p);
-    } else {
-      constexpr int SMEM = 4 * (BKV * 64 * 2 + 64 * BKV * 2);
-      static bool set = false;
-      if (!set) {
-        hipError_t e = hipFuncSetAttribute((const void *)attn_prefill_pp_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-        if (e != hipSuccess) return (int)e;
-        set = true;
-      }
-      hipLaunchKernelGGL(attn_prefill_pp_kernel<64>, grid, dim3(512), SMEM, st, p);
-    }
-    return 0;
   }
   // two resident workgroups per CU (a multiple of 8, so every XCD's queue has its workgroups)
   dim3 grid((unsigned)(2 * n_cu));
