@@ -290,8 +290,9 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
     sequences outside `seq_subset` are NaN) and leaves K/V in `cache`.
 
     token_ids: int [T] packed; sequence b has context_lens[b] cached tokens in
-    `cache` already and seq_lens[b] new ones.  (context > 0 with more than one
-    new token is not defined here.)
+    `cache` already and seq_lens[b] new ones (one new token = a decode step,
+    several = a chunk of a longer prompt: new token i sits at position
+    context + i and attends to the cached positions and to new tokens <= i).
     fp8_compute_scales: in FP8 mode, derive each (cache layer, K|V, head) scale
     from the absmax of what this call writes there (over the processed
     sequences); otherwise use the scales already in `cache`.
@@ -313,10 +314,6 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
     cu = [0]
     for n in seq_lens:
         cu.append(cu[-1] + int(n))
-    for b in seqs:
-        if int(context_lens[b]) > 0 and int(seq_lens[b]) != 1:
-            raise ValueError("a sequence with cached context must bring exactly one new token")
-
     def W(name, j0=None):
         return weights(name, j0).to(dtype)
 

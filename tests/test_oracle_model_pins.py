@@ -191,6 +191,54 @@ def test_decode_token_with_context_matches_prefill_of_longer_prompt(wd):
     assert torch.allclose(cache.data[:, :, :n], c_full.data[:, :, :n], atol=1e-12)
 
 
+@pytest.mark.parametrize("l,g,cuts", [(2, 2, [17]), (2, 1, [5, 6, 30]), (3, 1, [16, 32]), (4, 1, [1, 20])])
+def test_chunked_prefill_matches_one_shot(wd, l, g, cuts):
+    """A prompt fed in chunks (each call: what is cached so far as context, the
+    next chunk as new tokens) must leave the cache of a one-shot prefill and,
+    after the last chunk, its logits: attention is causal and every other step
+    acts per token.  The one-shot result is pinned to the library model above."""
+    n = 41
+    ids = _ids(n, 21)
+    full_logits, c_full, _ = _run_oracle(wd, ids, [n], l, g)
+    bt, nb = identity_tables([n], [0])
+    cache = O.PagedKVCache(c_full.C, nb, MS.n_kv_heads, MS.head_dim, bt)
+    bounds = [0] + cuts + [n]
+    logits = None
+    for a, b in zip(bounds[:-1], bounds[1:]):
+        logits, _ = O.swiftkv_prefill(oracle_shape(MS), dict_weight_fn(wd), ids[a:b], [b - a], [a], l, g, cache)
+        # positions past the chunk are still untouched
+        assert torch.count_nonzero(cache.data[:, :, b:n]) == 0
+    assert torch.allclose(logits[0], full_logits[0], atol=1e-10)
+    assert torch.allclose(cache.data[:, :, :n], c_full.data[:, :, :n], atol=1e-12)
+
+
+def test_chunk_and_decode_and_fresh_prompt_in_one_batch(wd):
+    """A batch mixing a chunk over a cached prefix, a decode token and a fresh
+    prompt gives, per sequence, what each gives alone (sequences never mix)."""
+    l, g = 2, 2
+    idsA, idsB, idsC = _ids(37, 31), _ids(12, 32), _ids(9, 33)
+    sh, wf = oracle_shape(MS), dict_weight_fn(wd)
+    fullA, cA, _ = _run_oracle(wd, idsA, [37], l, g)
+    fullB, cB, _ = _run_oracle(wd, idsB, [12], l, g)
+    fullC, cC, _ = _run_oracle(wd, idsC, [9], l, g)
+    lens, ctx = [17, 1, 9], [20, 11, 0]
+    bt, nb = identity_tables(lens, ctx)
+    cache = O.PagedKVCache(cA.C, nb, MS.n_kv_heads, MS.head_dim, bt)
+    for c in range(cA.C):
+        kA, vA = cA.read(c, 0, 20)
+        kB, vB = cB.read(c, 0, 11)
+        cache.write(c, 0, torch.arange(20), kA, vA)
+        cache.write(c, 1, torch.arange(11), kB, vB)
+    toks = torch.cat([idsA[20:], idsB[11:], idsC])
+    logits, _ = O.swiftkv_prefill(sh, wf, toks, lens, ctx, l, g, cache)
+    for b, (full, cref, n) in enumerate([(fullA, cA, 37), (fullB, cB, 12), (fullC, cC, 9)]):
+        assert torch.allclose(logits[b], full[0], atol=1e-10)
+        for c in range(cA.C):
+            k, v = cache.read(c, b, n)
+            kr, vr = cref.read(c, 0, n)
+            assert torch.allclose(k, kr, atol=1e-12) and torch.allclose(v, vr, atol=1e-12)
+
+
 def test_sequence_order_only_permutes_outputs(wd):
     lens = [9, 14]
     ids = _ids(23, 12)
