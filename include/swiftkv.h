@@ -116,9 +116,17 @@ int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftk
 void swiftkv_destroy(swiftkv_ctx *ctx);
 
 /* Bytes of dev workspace swiftkv_prefill needs for up to max_tokens new tokens
- * in up to max_seqs sequences with the given cache dtype. */
+ * in up to max_seqs sequences with the given cache dtype, when no sequence
+ * brings more than one new token on top of a cached context. */
 size_t swiftkv_workspace_bytes(const swiftkv_ctx *ctx, int64_t max_tokens, int32_t max_seqs,
                                int32_t kv_dtype);
+/* The same when prompts may continue over a cached prefix (Sec. 3.1: prefill
+ * in chunks): max_prefix_tokens bounds the sum of context_lens over the
+ * sequences that bring more than one new token.  The extra space holds the
+ * K rows and V^T columns of positions 0 .. context+new-1 of those sequences,
+ * copied out of the paged cache once per layer for the attention kernel. */
+size_t swiftkv_workspace_bytes_prefix(const swiftkv_ctx *ctx, int64_t max_tokens, int32_t max_seqs,
+                                      int32_t kv_dtype, int64_t max_prefix_tokens);
 
 /* SwiftKV prefill of a packed batch (Sec. 3.2 Eq. 2, Sec. 3.3, Sec. 3.5).
  *  token_ids  dev  int32 [T]  new tokens, sequence after sequence, T = sum(seq_lens)
@@ -126,7 +134,12 @@ size_t swiftkv_workspace_bytes(const swiftkv_ctx *ctx, int64_t max_tokens, int32
  *  kv         cache descriptor; kv->context_lens[b] cached tokens precede the new ones.
  *             context 0 with any number of new tokens = prompt prefill; context > 0
  *             with exactly one new token = decode token; context > 0 with more new
- *             tokens is rejected (SWIFTKV_EINVAL).
+ *             tokens = the next chunk of a prompt whose earlier chunks are cached
+ *             (new token i sits at position context + i and attends to the cached
+ *             positions and to the new tokens up to itself; size the workspace with
+ *             swiftkv_workspace_bytes_prefix, else SWIFTKV_ENOSPC).  With an FP8 cache
+ *             and cached context use SWIFTKV_SCALE_USE_GIVEN: computed scales cover
+ *             only the tokens this call stores.
  *  logits_out dev fp32 [n_seqs, vocab]: logits of the last new token of each sequence.
  * Writes K/V of all T new tokens into every cache layer (layers <= l from their
  * own layer input, later cache layers from the layer-l output), then runs the

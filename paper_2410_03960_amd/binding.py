@@ -24,7 +24,7 @@ TIME_CLASS_NAMES = ("qkv_gemm", "o_gemm", "gateup_gemm", "down_gemm", "fused_kv_
                     "attn_prefill", "other", "tail")
 
 EXPORTS = (
-    "swiftkv_create", "swiftkv_destroy", "swiftkv_workspace_bytes", "swiftkv_prefill",
+    "swiftkv_create", "swiftkv_destroy", "swiftkv_workspace_bytes", "swiftkv_workspace_bytes_prefix", "swiftkv_prefill",
     "swiftkv_kv_from_hidden", "swiftkv_export_plan", "swiftkv_export_hidden", "swiftkv_op_gemm",
     "swiftkv_op_attention_prefill", "swiftkv_op_attention_workspace", "swiftkv_op_fp8_quantize",
     "swiftkv_flops", "swiftkv_set_timing", "swiftkv_get_timing", "swiftkv_last_error",
@@ -76,6 +76,8 @@ def load() -> C.CDLL:
     lib.swiftkv_destroy.restype = None
     lib.swiftkv_workspace_bytes.argtypes = [vp, i64, i32, i32]
     lib.swiftkv_workspace_bytes.restype = C.c_size_t
+    lib.swiftkv_workspace_bytes_prefix.argtypes = [vp, i64, i32, i32, i64]
+    lib.swiftkv_workspace_bytes_prefix.restype = C.c_size_t
     lib.swiftkv_prefill.argtypes = [vp, vp, C.POINTER(i32), i32, C.POINTER(KVCacheDesc), vp, vp, C.c_size_t, vp]
     lib.swiftkv_kv_from_hidden.argtypes = [vp, vp, C.POINTER(i32), i32, C.POINTER(KVCacheDesc), vp, C.c_size_t, vp]
     lib.swiftkv_export_plan.argtypes = [vp, vp, vp, vp, vp, vp, vp]
@@ -157,7 +159,10 @@ class Context:
             pass
 
     # ---- thin wrappers, one per C entry point ----
-    def workspace_bytes(self, max_tokens: int, max_seqs: int, kv_dtype: int = SWIFTKV_KV_BF16) -> int:
+    def workspace_bytes(self, max_tokens: int, max_seqs: int, kv_dtype: int = SWIFTKV_KV_BF16,
+                        max_prefix_tokens: int = 0) -> int:
+        if max_prefix_tokens:
+            return int(load().swiftkv_workspace_bytes_prefix(self._h, max_tokens, max_seqs, kv_dtype, max_prefix_tokens))
         return int(load().swiftkv_workspace_bytes(self._h, max_tokens, max_seqs, kv_dtype))
 
     def prefill(self, token_ids: torch.Tensor, seq_lens: Sequence[int], kv: "KVCache", logits_out: torch.Tensor,
@@ -219,6 +224,10 @@ class KVCache:
         self.context_lens = _i32_array(context_lens)
         self.n_cache_layers, self.n_blocks = n_cache_layers, n_blocks
         self.scale_mode = scale_mode
+
+    def set_context_lens(self, context_lens: Sequence[int]) -> None:
+        """Tokens already cached per sequence, for the next call (host array)."""
+        self.context_lens = _i32_array(context_lens)
 
     def desc(self) -> KVCacheDesc:
         return KVCacheDesc(self.data.data_ptr(), self.scales.data_ptr() if self.scales is not None else None,

@@ -40,11 +40,12 @@ struct Layout {  // byte offsets into the workspace
   int64_t T = 0;
   int32_t B = 0;
   int64_t vt_ld = 0;
-  int32_t n_qblocks = 0, n_kvtiles = 0, n_dec = 0;
-  size_t err, meta, positions, seq_of, last_rows, slots, cos_sin, h, a, rstd, q, k, v, o, vt, z, stage, amax;
+  int32_t n_qblocks = 0, n_kvtiles = 0, n_dec = 0, n_gtiles = 0;
+  int64_t kcat_rows = 0;   // rows of the K buffer gathered from the cache (prompt chunks over a cached prefix), else 0
+  size_t err, meta, positions, seq_of, last_rows, slots, cos_sin, h, a, rstd, q, k, v, o, vt, kcat, z, stage, amax;
   size_t th, ta, tq, to, tz, partial, total;
   // offsets (in int32 units) inside the meta block copied from the host
-  size_t m_cu, m_ctx, m_qblocks, m_kvtiles, m_dec, m_tail, m_words;
+  size_t m_cu, m_ctx, m_qblocks, m_kvtiles, m_dec, m_tail, m_gtiles, m_words;
 };
 
 }  // namespace
@@ -77,11 +78,11 @@ namespace {
 constexpr int MAX_SPLIT = 32;
 
 Layout make_layout(const swiftkv_ctx *c, int64_t T, int32_t B, int64_t vt_ld, int32_t nqb, int32_t nkt,
-                   int32_t ndec, bool fp8) {
+                   int32_t ndec, bool fp8, int64_t kcat_rows = 0, int32_t ngt = 0) {
   const swiftkv_model_cfg &m = c->cfg;
   const int64_t d = m.hidden, qd = (int64_t)m.n_q_heads * m.head_dim, kvd = (int64_t)m.n_kv_heads * m.head_dim;
   Layout L;
-  L.T = T; L.B = B; L.vt_ld = vt_ld; L.n_qblocks = nqb; L.n_kvtiles = nkt; L.n_dec = ndec;
+  L.T = T; L.B = B; L.vt_ld = vt_ld; L.n_qblocks = nqb; L.n_kvtiles = nkt; L.n_dec = ndec; L.n_gtiles = ngt; L.kcat_rows = kcat_rows;
   size_t w = 0;
   L.m_cu = w; w += B + 1;
   L.m_ctx = w; w += B;
@@ -91,6 +92,7 @@ Layout make_layout(const swiftkv_ctx *c, int64_t T, int32_t B, int64_t vt_ld, in
   w = (w + 3) / 4 * 4;
   L.m_dec = w; w += (size_t)ndec * 8;
   L.m_tail = w; w += (size_t)B * 8;
+  L.m_gtiles = w; w += (size_t)ngt * 8;
   L.m_words = w;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
@@ -109,6 +111,7 @@ Layout make_layout(const swiftkv_ctx *c, int64_t T, int32_t B, int64_t vt_ld, in
   L.v = take(T * kvd * 2);
   L.o = take(T * qd * 2);
   L.vt = take((size_t)kvd * vt_ld * 2);
+  L.kcat = take((size_t)kcat_rows * kvd * 2);
   L.z = take(T * (int64_t)m.ffn * 2);
   L.stage = take(fp8 ? T * (int64_t)c->P * 2 * kvd * 2 : 0);
   L.amax = take(fp8 ? (size_t)c->C * 2 * m.n_kv_heads * 4 : 0);
@@ -160,43 +163,59 @@ int pick_split(int rows, int n_kv_heads, int max_keys) {
 
 struct HostPlan {
   std::vector<int32_t> meta;
-  int64_t T = 0, vt_ld = 0;
-  int32_t nqb = 0, nkt = 0, ndec = 0, max_keys_dec = 0, max_keys_tail = 0;
+  int64_t T = 0, vt_ld = 0, kcat_rows = 0;
+  int32_t nqb = 0, nkt = 0, ndec = 0, ngt = 0, max_keys_dec = 0, max_keys_tail = 0;
+  bool chunked = false;   // some sequence brings several new tokens on top of a cached context
 };
 
 // Host side of the plan: cumulative lengths, 128-query blocks (longest first),
-// 64-token KV tiles, the decode rows (sequences with cached context) and the
-// tail rows (last new token of every sequence).
+// 64-token KV tiles, the decode rows (one new token on a cached context) and the
+// tail rows (last new token of every sequence).  When some sequence brings several
+// new tokens on top of a cached context, the prefill attention of every multi-token
+// sequence reads K and V^T gathered from the paged cache (64-position gather tiles
+// over positions 0 .. context + new - 1) instead of the QKV GEMM's own output.
 int build_host_plan(const swiftkv_ctx *c, const int32_t *seq_lens, const int32_t *ctx_lens, int32_t B,
                     int32_t max_blocks_per_seq, HostPlan &hp, Layout &L, bool fp8) {
   std::vector<int64_t> cu(B + 1, 0);
   std::vector<int32_t> vt0(B, -1);
   int64_t vt_cols = 0;
-  struct QB { int32_t row0, q0, n, seq_row0, vt_col0; };
+  struct QB { int32_t row0, q0, n, seq_row0, vt_col0, q_last_row; };
   std::vector<QB> qbs;
-  std::vector<int32_t> kvt, dec, tail;
+  std::vector<int32_t> kvt, dec, tail, gt;
+  int64_t kcat_rows = 0;
+  for (int b = 0; b < B; ++b)
+    if (ctx_lens && ctx_lens[b] > 0 && seq_lens[b] > 1) hp.chunked = true;
   for (int b = 0; b < B; ++b) {
     const int64_t n = seq_lens[b], ctx = ctx_lens ? ctx_lens[b] : 0;
     if (n < 1) return fail(SWIFTKV_EINVAL, "seq_lens[%d] = %lld must be >= 1", b, (long long)n);
     if (ctx < 0) return fail(SWIFTKV_EINVAL, "context_lens[%d] is negative", b);
-    if (ctx > 0 && n != 1)
-      return fail(SWIFTKV_EINVAL, "sequence %d has cached context and %lld new tokens; only one is supported", b, (long long)n);
     if ((ctx + n + SKV_BLOCK - 1) / SKV_BLOCK > max_blocks_per_seq)
       return fail(SWIFTKV_ENOSPC, "sequence %d needs %lld blocks, block table has %d", b,
                   (long long)((ctx + n + SKV_BLOCK - 1) / SKV_BLOCK), max_blocks_per_seq);
     cu[b + 1] = cu[b] + n;
     if (cu[b + 1] > 0x7fffffff / 2) return fail(SWIFTKV_EINVAL, "too many tokens");
     const int32_t row0 = (int32_t)cu[b];
-    if (ctx == 0) {
+    const bool prompt = ctx == 0 || n > 1;
+    if (prompt) {
+      const int64_t keys = ctx + n;
       vt0[b] = (int32_t)vt_cols;
-      vt_cols += (n + 63) / 64 * 64;
-      for (int64_t q0 = 0; q0 < n; q0 += 128) qbs.push_back({(int32_t)(row0 + q0), (int32_t)q0, (int32_t)n, row0, vt0[b]});
+      vt_cols += ((hp.chunked ? keys : n) + 63) / 64 * 64;
+      int32_t k_row0 = row0;
+      if (hp.chunked) {
+        k_row0 = (int32_t)kcat_rows;
+        for (int64_t p0 = 0; p0 < keys; p0 += 64)
+          gt.insert(gt.end(), {b, (int32_t)p0, (int32_t)std::min<int64_t>(64, keys - p0), (int32_t)(k_row0 + p0), (int32_t)(vt0[b] + p0), 0, 0, 0});
+        kcat_rows += keys;
+        if (kcat_rows > 0x7fffffff / 2 || vt_cols > 0x7fffffff / 2) return fail(SWIFTKV_EINVAL, "too many cached + new tokens");
+      }
+      for (int64_t q0 = 0; q0 < n; q0 += 128)
+        qbs.push_back({(int32_t)(row0 + q0), (int32_t)(ctx + q0), (int32_t)keys, k_row0, vt0[b], (int32_t)(row0 + n - 1)});
     } else {
       dec.insert(dec.end(), {row0, row0, b, (int32_t)(ctx + 1), -1, 0, 0, 0});
       hp.max_keys_dec = std::max<int32_t>(hp.max_keys_dec, (int32_t)(ctx + 1));
     }
     for (int64_t p0 = 0; p0 < n; p0 += 64)
-      kvt.insert(kvt.end(), {(int32_t)(row0 + p0), (int32_t)std::min<int64_t>(64, n - p0), ctx == 0 ? (int32_t)(vt0[b] + p0) : -1, 0});
+      kvt.insert(kvt.end(), {(int32_t)(row0 + p0), (int32_t)std::min<int64_t>(64, n - p0), (prompt && !hp.chunked) ? (int32_t)(vt0[b] + p0) : -1, 0});
     // tail row: q row b of the tail buffer, rotated with the last token's angles
     tail.insert(tail.end(), {b, b, b, (int32_t)(ctx + n), (int32_t)(cu[b + 1] - 1), 0, 0, 0});
     hp.max_keys_tail = std::max<int32_t>(hp.max_keys_tail, (int32_t)(ctx + n));
@@ -209,17 +228,20 @@ int build_host_plan(const swiftkv_ctx *c, const int32_t *seq_lens, const int32_t
   hp.nqb = (int32_t)qbs.size();
   hp.nkt = (int32_t)(kvt.size() / 4);
   hp.ndec = (int32_t)(dec.size() / 8);
-  L = make_layout(c, hp.T, B, hp.vt_ld, hp.nqb, hp.nkt, hp.ndec, fp8);
+  hp.ngt = (int32_t)(gt.size() / 8);
+  hp.kcat_rows = kcat_rows;
+  L = make_layout(c, hp.T, B, hp.vt_ld, hp.nqb, hp.nkt, hp.ndec, fp8, kcat_rows, hp.ngt);
   hp.meta.assign(L.m_words, 0);
   for (int b = 0; b <= B; ++b) hp.meta[L.m_cu + b] = (int32_t)cu[b];
   for (int b = 0; b < B; ++b) hp.meta[L.m_ctx + b] = ctx_lens ? ctx_lens[b] : 0;
   for (size_t i = 0; i < qbs.size(); ++i) {
     int32_t *q = &hp.meta[L.m_qblocks + i * 8];
-    q[0] = qbs[i].row0; q[1] = qbs[i].q0; q[2] = qbs[i].n; q[3] = qbs[i].seq_row0; q[4] = qbs[i].vt_col0;
+    q[0] = qbs[i].row0; q[1] = qbs[i].q0; q[2] = qbs[i].n; q[3] = qbs[i].seq_row0; q[4] = qbs[i].vt_col0; q[5] = qbs[i].q_last_row;
   }
   std::copy(kvt.begin(), kvt.end(), hp.meta.begin() + L.m_kvtiles);
   std::copy(dec.begin(), dec.end(), hp.meta.begin() + L.m_dec);
   std::copy(tail.begin(), tail.end(), hp.meta.begin() + L.m_tail);
+  std::copy(gt.begin(), gt.end(), hp.meta.begin() + L.m_gtiles);
   return 0;
 }
 
@@ -482,12 +504,19 @@ void swiftkv_destroy(swiftkv_ctx *c) {
   delete c;
 }
 
-size_t swiftkv_workspace_bytes(const swiftkv_ctx *c, int64_t max_tokens, int32_t max_seqs, int32_t kv_dtype) {
-  if (!c || max_tokens < 1 || max_seqs < 1) return 0;
-  const int64_t vt_ld = max_tokens + 64LL * max_seqs;
+size_t swiftkv_workspace_bytes_prefix(const swiftkv_ctx *c, int64_t max_tokens, int32_t max_seqs, int32_t kv_dtype,
+                                      int64_t max_prefix_tokens) {
+  if (!c || max_tokens < 1 || max_seqs < 1 || max_prefix_tokens < 0) return 0;
+  const int64_t kcat_rows = max_prefix_tokens > 0 ? max_tokens + max_prefix_tokens : 0;
+  const int64_t vt_ld = max_tokens + max_prefix_tokens + 64LL * max_seqs;
   const int32_t nqb = (int32_t)(max_tokens / 128 + max_seqs), nkt = (int32_t)(max_tokens / 64 + max_seqs);
-  Layout L = make_layout(c, max_tokens, max_seqs, vt_ld, nqb, nkt, max_seqs, kv_dtype == SWIFTKV_KV_FP8_E4M3);
+  const int32_t ngt = kcat_rows ? (int32_t)(kcat_rows / 64 + max_seqs) : 0;
+  Layout L = make_layout(c, max_tokens, max_seqs, vt_ld, nqb, nkt, max_seqs, kv_dtype == SWIFTKV_KV_FP8_E4M3, kcat_rows, ngt);
   return L.total + 4096;
+}
+
+size_t swiftkv_workspace_bytes(const swiftkv_ctx *c, int64_t max_tokens, int32_t max_seqs, int32_t kv_dtype) {
+  return swiftkv_workspace_bytes_prefix(c, max_tokens, max_seqs, kv_dtype, 0);
 }
 
 int swiftkv_set_timing(swiftkv_ctx *c, int32_t enable) {
@@ -603,19 +632,29 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
       cp.k_src = kb; cp.v_src = vb; cp.ld_src = kvd;
       cp.cache_k = r.cache_plane(j, 0); cp.cache_v = r.cache_plane(j, 1);
       cp.slots = r.at<int64_t>(r.L.slots);
-      cp.fp8 = r.fp8; cp.compute_scale = compute_scale; cp.writeback = r.fp8;
+      cp.fp8 = r.fp8; cp.compute_scale = compute_scale; cp.writeback = r.fp8 && !r.hp.chunked;
       if (r.fp8) {
         cp.amax = r.at<uint32_t>(r.L.amax) + (int64_t)j * 2 * m.n_kv_heads;
         cp.scales = kv->scales + (int64_t)j * 2 * m.n_kv_heads;
       }
-      cp.vt = vt; cp.vt_ld = r.L.vt_ld;
+      cp.vt = r.hp.chunked ? nullptr : vt; cp.vt_ld = r.L.vt_ld;
       tm.begin(TC_OTHER);
       launch_kv_commit(cp, st);
+      if (r.hp.chunked) {   // cached prefix + the rows just committed -> contiguous K rows and V^T columns
+        GatherParams gp{};
+        gp.tiles = (const GatherTile *)r.meta(r.L.m_gtiles); gp.n_tiles = r.L.n_gtiles;
+        gp.n_kv_heads = m.n_kv_heads; gp.head_dim = m.head_dim;
+        gp.cache_k = r.cache_plane(j, 0); gp.cache_v = r.cache_plane(j, 1); gp.fp8 = r.fp8;
+        gp.scales = r.fp8 ? kv->scales + (int64_t)j * 2 * m.n_kv_heads : nullptr;
+        gp.block_tables = kv->block_tables; gp.max_blocks_per_seq = kv->max_blocks_per_seq; gp.n_blocks = kv->n_blocks;
+        gp.k_dst = r.at<bf16_t>(r.L.kcat); gp.vt = vt; gp.vt_ld = r.L.vt_ld;
+        launch_kv_gather(gp, st);
+      }
       tm.end();
     }
-    {
+    if (r.L.n_qblocks > 0) {
       AttnPrefillParams ap{};
-      ap.q = qb; ap.k = kb; ap.vt = vt; ap.vt_ld = r.L.vt_ld; ap.out = ob;
+      ap.q = qb; ap.k = r.hp.chunked ? r.at<bf16_t>(r.L.kcat) : kb; ap.vt = vt; ap.vt_ld = r.L.vt_ld; ap.out = ob;
       ap.qblocks = (const QBlock *)r.meta(r.L.m_qblocks); ap.n_qblocks = r.L.n_qblocks;
       ap.sched = r.at<int32_t>(r.L.err) + 4;
       ap.n_q_heads = m.n_q_heads; ap.n_kv_heads = m.n_kv_heads; ap.head_dim = m.head_dim;
@@ -796,7 +835,7 @@ int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, vo
   for (int b = 0; b < B; ++b) {
     const int n = seq_lens[b];
     if (n < 1) return fail(SWIFTKV_EINVAL, "seq_lens must be >= 1");
-    for (int q0 = 0; q0 < n; q0 += 128) qb_list.push_back({(int32_t)(row + q0), q0, n, (int32_t)row, (int32_t)col, 0, 0, 0});
+    for (int q0 = 0; q0 < n; q0 += 128) qb_list.push_back({(int32_t)(row + q0), q0, n, (int32_t)row, (int32_t)col, (int32_t)(row + n - 1), 0, 0});
     for (int p0 = 0; p0 < n; p0 += 64) kvt.insert(kvt.end(), {(int32_t)(row + p0), std::min(64, n - p0), (int32_t)(col + p0), 0});
     row += n;
     col += (n + 63) / 64 * 64;

@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
   const int qpos = qb.q0 + wave * 32 + l32;            // position in the sequence
   const bool qvalid = qpos < qb.n;
   const int qrow = qb.row0 + wave * 32 + l32;
-  const int qrow_c = qvalid ? qrow : qb.seq_row0 + qb.n - 1;
+  const int qrow_c = qvalid ? qrow : qb.q_last_row;
   bf16x8 qf[DS];
   {
     const bf16_t *qp = p.q + (int64_t)qrow_c * q_dim + head * HD;

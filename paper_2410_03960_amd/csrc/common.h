@@ -121,13 +121,14 @@ struct SkinnyParams {
 int launch_skinny(const SkinnyParams &p, int epi, hipStream_t st);
 
 // ------------------------------------------------------------- attention ----
-struct QBlock {  // one 128-row query block of a fresh sequence
+struct QBlock {  // one 128-row query block of a sequence
   int32_t row0;   // packed row of the block's first query
-  int32_t q0;     // position of that query inside the sequence
-  int32_t n;      // sequence length (keys available)
-  int32_t seq_row0;  // packed row of the sequence's first token
-  int32_t vt_col0;   // column of the sequence's first token in the V^T buffer
-  int32_t pad[3];
+  int32_t q0;     // position of that query inside the sequence (cached context included)
+  int32_t n;      // keys available: cached context + new tokens
+  int32_t seq_row0;  // row of the sequence's position 0 in the K buffer
+  int32_t vt_col0;   // column of the sequence's position 0 in the V^T buffer
+  int32_t q_last_row;  // packed row of the sequence's last query (stands in for rows past the end)
+  int32_t pad[2];
 };
 struct AttnPrefillParams {
   const bf16_t *q, *k;  // [T, q_dim], [T, kv_dim]
@@ -209,6 +210,30 @@ struct CommitParams {
   int64_t vt_ld;
 };
 int launch_kv_commit(const CommitParams &p, hipStream_t st);
+
+// Prompt chunks over a cached prefix: the prefill attention reads contiguous K rows and V^T columns,
+// so positions 0 .. context+new-1 of such sequences are copied out of the paged cache first.
+struct GatherTile {  // 64 consecutive positions of one sequence
+  int32_t seq;       // block-table row
+  int32_t pos0;      // first position
+  int32_t n_valid;   // positions present (the rest of the V^T columns is zero filled)
+  int32_t k_row0;    // destination row of pos0 in the K buffer
+  int32_t vt_col0;   // destination column of pos0 in the V^T buffer (64-aligned)
+  int32_t pad[3];
+};
+struct GatherParams {
+  const GatherTile *tiles;
+  int32_t n_tiles, n_kv_heads, head_dim;
+  const void *cache_k, *cache_v;   // planes of the cache layer [n_blocks*16][Hkv][hd], bf16 or e4m3 codes
+  int32_t fp8;
+  const float *scales;             // [2][Hkv] of this cache layer (fp8)
+  const int32_t *block_tables;
+  int32_t max_blocks_per_seq, n_blocks;
+  bf16_t *k_dst;                   // [rows, kv_dim]
+  bf16_t *vt;                      // [kv_dim, vt_ld]
+  int64_t vt_ld;
+};
+int launch_kv_gather(const GatherParams &p, hipStream_t st);
 int launch_fp8_quantize(const float *x, float scale, uint8_t *codes, int64_t n, hipStream_t st);
 int launch_decode_combine(const float *partial, bf16_t *out, const DecodeRow *rows, int32_t n_rows,
                           int32_t n_q_heads, int32_t head_dim, int32_t n_split, hipStream_t st);

@@ -322,6 +322,73 @@ int launch_kv_commit(const CommitParams &p, hipStream_t st) {
   return 0;
 }
 
+// ----------------------------------------------------------- KV gather -----
+// One workgroup per (64-position tile, KV head) of a sequence whose prompt continues over a cached
+// prefix: copies the tile's K rows out of the paged cache into consecutive rows and its V rows
+// into V^T columns (through LDS, as above), dequantising e4m3 codes with the layer's scales to
+// the bf16 values every other reader of the cache sees.  Columns past n_valid are zero filled.
+template <int HD>
+__global__ __launch_bounds__(256) void kv_gather_kernel(GatherParams p) {
+  constexpr int CH = HD / 8;  // 8-element chunks per row
+  __shared__ bf16_t sv[64][HD + 8];
+  const GatherTile tile = p.tiles[blockIdx.x];
+  const int head = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int kv_dim = p.n_kv_heads * HD;
+  float sk = 1.f, svs = 1.f;
+  if (p.fp8) { sk = p.scales[head]; svs = p.scales[p.n_kv_heads + head]; }
+  for (int i = tid; i < 64 * CH; i += 256) {
+    const int r = i / CH, c = i % CH;
+    uint4 kq = make_uint4(0, 0, 0, 0), vq = make_uint4(0, 0, 0, 0);
+    if (r < tile.n_valid) {
+      const int pos = tile.pos0 + r;
+      int blk = p.block_tables[(int64_t)tile.seq * p.max_blocks_per_seq + pos / SKV_BLOCK];
+      blk = blk < 0 ? 0 : (blk >= p.n_blocks ? p.n_blocks - 1 : blk);   // bad ids were reported by the plan; stay inside the pool
+      const int64_t src = (((int64_t)blk * SKV_BLOCK + pos % SKV_BLOCK) * p.n_kv_heads + head) * HD + c * 8;
+      if (!p.fp8) {
+        kq = *(const uint4 *)((const bf16_t *)p.cache_k + src);
+        vq = *(const uint4 *)((const bf16_t *)p.cache_v + src);
+      } else {
+        const uint2 kc = *(const uint2 *)((const uint8_t *)p.cache_k + src);
+        const uint2 vc = *(const uint2 *)((const uint8_t *)p.cache_v + src);
+        const uint32_t kcw[2] = {kc.x, kc.y}, vcw[2] = {vc.x, vc.y};
+        uint32_t kw[4], vw[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t k2 = kcw[e / 2] >> ((e & 1) * 16), v2 = vcw[e / 2] >> ((e & 1) * 16);
+          kw[e] = pack_bf16x2(e4m3fn_to_f32((uint8_t)k2) * sk, e4m3fn_to_f32((uint8_t)(k2 >> 8)) * sk);
+          vw[e] = pack_bf16x2(e4m3fn_to_f32((uint8_t)v2) * svs, e4m3fn_to_f32((uint8_t)(v2 >> 8)) * svs);
+        }
+        kq = make_uint4(kw[0], kw[1], kw[2], kw[3]);
+        vq = make_uint4(vw[0], vw[1], vw[2], vw[3]);
+      }
+      *(uint4 *)(p.k_dst + (int64_t)(tile.k_row0 + r) * kv_dim + head * HD + c * 8) = kq;
+    }
+    const uint32_t w[4] = {vq.x, vq.y, vq.z, vq.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      sv[r][c * 8 + 2 * e] = (bf16_t)(w[e] & 0xffff);
+      sv[r][c * 8 + 2 * e + 1] = (bf16_t)(w[e] >> 16);
+    }
+  }
+  __syncthreads();
+  // V^T: thread writes 8 consecutive positions of one dim (16 bytes)
+  for (int i = tid; i < HD * 8; i += 256) {
+    const int d = i / 8, tc = i % 8;
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = (uint32_t)sv[tc * 8 + 2 * e][d] | ((uint32_t)sv[tc * 8 + 2 * e + 1][d] << 16);
+    *(uint4 *)(p.vt + (int64_t)(head * HD + d) * p.vt_ld + tile.vt_col0 + tc * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+int launch_kv_gather(const GatherParams &p, hipStream_t st) {
+  if (p.n_tiles <= 0) return 0;
+  dim3 grid(p.n_tiles, p.n_kv_heads);
+  if (p.head_dim == 128) hipLaunchKernelGGL(kv_gather_kernel<128>, grid, dim3(256), 0, st, p);
+  else hipLaunchKernelGGL(kv_gather_kernel<64>, grid, dim3(256), 0, st, p);
+  return 0;
+}
+
 __global__ void fp8_quantize_kernel(const float *x, float scale, uint8_t *codes, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) {

@@ -27,7 +27,8 @@ def run_gpu(ctx, batch, fp8=False, scale_mode=0, cache=None, stream=None):
         cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, sh.n_kv_heads, sh.head_dim,
                           batch.block_tables, batch.context_lens.tolist(), fp8=fp8, scale_mode=scale_mode)
     T, nseq = batch.n_tokens, batch.n_seqs
-    nbytes = ctx.workspace_bytes(T, nseq, B.SWIFTKV_KV_FP8_E4M3 if fp8 else B.SWIFTKV_KV_BF16)
+    prefix = sum(int(c) for c, n in zip(batch.context_lens.tolist(), batch.seq_lens.tolist()) if n > 1)
+    nbytes = ctx.workspace_bytes(T, nseq, B.SWIFTKV_KV_FP8_E4M3 if fp8 else B.SWIFTKV_KV_BF16, prefix)
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     logits = torch.empty((nseq, sh.vocab), dtype=torch.float32, device="cuda")
     ids = batch.token_ids.cuda()

@@ -66,3 +66,36 @@ def test_mid_shapes_match_oracle(mid, packed, fp8):
     # a repeated call reproduces its bytes exactly
     logits2, cache2, _ = G.run_gpu(ctx, batch, fp8=fp8, scale_mode=B.SWIFTKV_SCALE_COMPUTE_ABSMAX if fp8 else 0)
     assert torch.equal(cache.data, cache2.data) and torch.equal(logits, logits2)
+
+
+def test_mid_prompt_in_two_chunks(mid):
+    """A 1500-token prompt fed as 1100 + 400 tokens next to a fresh prompt and a
+    decode token (the second call reads the first call's cache as its prefix);
+    compared with the oracle's one-shot prefill of the same sequences."""
+    from paper_2410_03960_amd import binding as B
+    wl, store, dev_w = mid
+    _say(f"{wl.name} prompt in two chunks")
+    ctx = B.Context(wl.shape, dev_w, wl.l, wl.g)
+    sh = wl.shape
+    n0, cut = 1500, 1100
+    full = WL.build_batch(wl, lens=[n0, 700, 61], shuffled=True)
+    cache = B.KVCache(ctx.n_cache_layers, full.n_blocks, sh.n_kv_heads, sh.head_dim, full.block_tables, [0, 0, 0])
+    off1, off2 = n0, n0 + 700
+    # call 1: first 1100 tokens of sequence 0, first 60 tokens of sequence 2
+    first = WL.build_batch(wl, lens=[cut, 60], shuffled=True)
+    first.block_tables, first.n_blocks = full.block_tables[[0, 2]].contiguous(), full.n_blocks
+    first.token_ids = torch.cat([full.token_ids[:cut], full.token_ids[off2:off2 + 60]])
+    c1 = B.KVCache(ctx.n_cache_layers, full.n_blocks, sh.n_kv_heads, sh.head_dim, first.block_tables, [0, 0])
+    c1.data = cache.data
+    G.run_gpu(ctx, first, cache=c1)
+    # call 2: the rest of sequence 0 over its cached prefix, sequence 1 fresh, sequence 2's last token as a decode token
+    second = WL.build_batch(wl, lens=[n0 - cut, 700, 1], ctx=[cut, 0, 60], shuffled=True)
+    second.block_tables, second.n_blocks = full.block_tables, full.n_blocks
+    second.token_ids = torch.cat([full.token_ids[cut:n0], full.token_ids[off1:off2], full.token_ids[off2 + 60:off2 + 61]])
+    cache.set_context_lens([cut, 0, 60])
+    logits, cache, ws = G.run_gpu(ctx, second, cache=cache)
+    G.check_plan(ctx, ws, second)
+    ologits, ocache, _ = G.run_oracle(sh, store, full, wl.l, wl.g)
+    wc = G.compare_caches(cache, ocache, full, label=wl.name)
+    wlg = G.compare_logits(logits, ologits, label=wl.name)
+    _say(f"  worst cache rel/cos {wc}, logits {wlg}")
