@@ -66,12 +66,17 @@ def main():
     scale_mode = B.SWIFTKV_SCALE_COMPUTE_ABSMAX
     cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, sh.n_kv_heads, sh.head_dim, batch.block_tables,
                       batch.context_lens.tolist(), fp8=wl.kv_fp8, scale_mode=scale_mode)
-    if wl.kv_fp8 and wl.n_decode:
+    has_ctx = bool((batch.context_lens > 0).any())
+    if wl.kv_fp8 and has_ctx:
         # pre-existing contexts: seeded codes under fixed scales
         cache.scale_mode = B.SWIFTKV_SCALE_USE_GIVEN
         cache.scales.fill_(0.02)
         cache.data.random_(0, 0x77, generator=torch.Generator(device="cuda").manual_seed(wl.seed))
-    ws = torch.empty(ctx.workspace_bytes(T, nseq, kvd), dtype=torch.uint8, device="cuda")
+    elif has_ctx:
+        # pre-existing contexts: seeded values of the size K/V rows have on these models
+        cache.data.normal_(0.0, 0.5, generator=torch.Generator(device="cuda").manual_seed(wl.seed))
+    prefix = sum(int(c) for c, n in zip(batch.context_lens.tolist(), batch.seq_lens.tolist()) if n > 1)
+    ws = torch.empty(ctx.workspace_bytes(T, nseq, kvd, prefix), dtype=torch.uint8, device="cuda")
     logits = torch.empty((nseq, sh.vocab), dtype=torch.float32, device="cuda")
     ids = batch.token_ids.cuda()
     lens = batch.seq_lens.tolist()
@@ -93,7 +98,8 @@ def main():
 
     gemm_fl, attn_fl = ctx.flops(lens, batch.context_lens.tolist())
     out = {
-        "metric": "prefill tokens/s, 8B-shape SwiftKV-50%; GEMM MFMA TFLOPS as % of bf16 peak",
+        "metric": ("prefill tokens/s, 8B-shape SwiftKV-50%; GEMM MFMA TFLOPS as % of bf16 peak" if T >= 1024
+                   else "decode-step tokens/s (one new token per sequence over its cached context)"),
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
@@ -138,6 +144,17 @@ def main():
                     "avg_launch_ms": classes[dom]["avg_launch_ms"],
                     "flops_per_launch": per_launch_flops[dom],
                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom))}
+    if T < 1024:
+        # a decode step streams every weight once and each sequence's cached K/V of every cache layer once: HBM-bound
+        n_par = 2 * sh.vocab * sh.hidden + sh.n_layers * (2 * sh.hidden * sh.q_dim + 3 * sh.hidden * sh.ffn) \
+            + ctx.n_cache_layers * 2 * sh.hidden * sh.kv_dim
+        n_par -= (sh.vocab - T) * sh.hidden if T < sh.vocab else 0     # embedding: only the rows of the T tokens
+        keys = float((batch.context_lens + batch.seq_lens).sum())
+        kv_bytes = keys * ctx.n_cache_layers * 2 * sh.kv_dim * (1 if wl.kv_fp8 else 2)
+        alg = 2.0 * n_par + kv_bytes
+        roof = {"bound": "hbm", "kernel": "whole decode step (weight-streaming GEMMs + paged single-query attention)",
+                "achieved": alg / (ms_per_step * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                "frac": alg / (ms_per_step * 1e-3) / 1e9 / 8000.0, "bytes_per_step": alg, "traffic": None}
     out["roofline"] = roof
 
     if not args.no_cpu_baseline:

@@ -223,9 +223,9 @@ def test_error_paths(tiny):
     with pytest.raises(B.SwiftKVError) as e:
         ctx.prefill(ids, [40], short, logits, ws)    # 40 tokens need 3 blocks
     assert e.value.code == B.SWIFTKV_ENOSPC
-    ctxd = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables, [5])
+    ctxd = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables, [-1])
     with pytest.raises(B.SwiftKVError) as e:
-        ctx.prefill(ids, [3], ctxd, logits, ws)      # context with several new tokens
+        ctx.prefill(ids, [3], ctxd, logits, ws)      # negative context
     assert e.value.code == B.SWIFTKV_EINVAL
     # a block id outside the pool is caught on the device and reported, not dereferenced
     bad = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim,

@@ -60,6 +60,7 @@ class Workload:
     n_decode: int = 0                      # extra 1-token sequences ...
     decode_ctx: int = 0                    # ... each with this many cached tokens
     shuffled_tables: bool = False
+    prefix_ctx: int = 0                    # tokens already cached in front of every prompt (prefill in chunks)
 
     @property
     def n_cache_layers(self):
@@ -77,6 +78,12 @@ WORKLOADS: Dict[str, Workload] = {
     "8b_l16_g4_fp8_32k_dec64": Workload("8b_l16_g4_fp8_32k_dec64", LLAMA_8B, l=16, g=4,
                                         seed=1005, kv_fp8=True, fixed_lens=(32768,),
                                         n_decode=64, decode_ctx=4096),
+    # beyond the five configurations: the last 2048-token chunk of 8K-token prompts (the paper's serving
+    # runs split prompts into 2048-token chunks), and one decode step of 64 sequences at 2K context
+    "8b_l16_b8x2048_ctx6144": Workload("8b_l16_b8x2048_ctx6144", LLAMA_8B, l=16, g=1, seed=1002,
+                                       fixed_lens=(2048,) * 8, prefix_ctx=6144),
+    "8b_l16_dec64_ctx2048": Workload("8b_l16_dec64_ctx2048", LLAMA_8B, l=16, g=1, seed=1002,
+                                     fixed_lens=(), n_decode=64, decode_ctx=2048),
 }
 
 
@@ -172,7 +179,7 @@ def build_batch(w: Workload, lens: Optional[List[int]] = None,
     """Sequences = prompts (ctx 0) followed by `n_decode` one-token sequences."""
     if lens is None:
         lens = draw_lengths(w) + [1] * w.n_decode
-        ctx = [0] * (len(lens) - w.n_decode) + [w.decode_ctx] * w.n_decode
+        ctx = [w.prefix_ctx] * (len(lens) - w.n_decode) + [w.decode_ctx] * w.n_decode
     if ctx is None:
         ctx = [0] * len(lens)
     if shuffled is None:
