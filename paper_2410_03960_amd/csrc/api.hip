@@ -42,7 +42,7 @@ struct Layout {  // byte offsets into the workspace
   int64_t vt_ld = 0;
   int32_t n_qblocks = 0, n_kvtiles = 0, n_dec = 0, n_gtiles = 0;
   int64_t kcat_rows = 0;   // rows of the K buffer gathered from the cache (prompt chunks over a cached prefix), else 0
-  size_t err, meta, positions, seq_of, last_rows, slots, cos_sin, h, a, rstd, q, k, v, o, vt, kcat, z, stage, amax;
+  size_t err, meta, positions, seq_of, last_rows, slots, cos_sin, h, a, rstd, q, k, v, o, vt, kcat, z, stage, amax, qkv32;
   size_t th, ta, tq, to, tz, partial, total;
   // offsets (in int32 units) inside the meta block copied from the host
   size_t m_cu, m_ctx, m_qblocks, m_kvtiles, m_dec, m_tail, m_gtiles, m_words;
@@ -76,6 +76,7 @@ struct swiftkv_ctx {
 namespace {
 
 constexpr int MAX_SPLIT = 32;
+constexpr int SKINNY_MAX_ROWS = 80;   // batches up to this many tokens run every GEMM on the weight-streaming kernel
 
 Layout make_layout(const swiftkv_ctx *c, int64_t T, int32_t B, int64_t vt_ld, int32_t nqb, int32_t nkt,
                    int32_t ndec, bool fp8, int64_t kcat_rows = 0, int32_t ngt = 0) {
@@ -115,6 +116,7 @@ Layout make_layout(const swiftkv_ctx *c, int64_t T, int32_t B, int64_t vt_ld, in
   L.z = take(T * (int64_t)m.ffn * 2);
   L.stage = take(fp8 ? T * (int64_t)c->P * 2 * kvd * 2 : 0);
   L.amax = take(fp8 ? (size_t)c->C * 2 * m.n_kv_heads * 4 : 0);
+  L.qkv32 = take((size_t)std::min<int64_t>(T, SKINNY_MAX_ROWS) * (qd + 2 * kvd) * 4);   // fp32 Q, K, V of few-row batches
   L.th = take((size_t)B * d * 2);
   L.ta = take((size_t)B * std::max<int64_t>(d, qd) * 2);
   L.tq = take((size_t)B * qd * 2);
@@ -606,13 +608,30 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   bf16_t *qb = r.at<bf16_t>(r.L.q), *kb = r.at<bf16_t>(r.L.k), *vb = r.at<bf16_t>(r.L.v), *ob = r.at<bf16_t>(r.L.o);
   bf16_t *vt = r.at<bf16_t>(r.L.vt), *zb = r.at<bf16_t>(r.L.z);
   const bool compute_scale = r.fp8 && kv->scale_mode == SWIFTKV_SCALE_COMPUTE_ABSMAX;
+  const bool few_rows = T <= SKINNY_MAX_ROWS;
 
   // ------------------------------------------ layers 1..l on every new token ----
   for (int j = 0; j < c->l; ++j) {
     tm.begin(TC_OTHER);
     launch_rmsnorm_rows(h, c->norm1[j], ab, T, d, m.rms_eps, st);
     tm.end();
-    {
+    if (few_rows) {
+      // decode steps and other few-token batches: weights stream once through the skinny kernel (fp32 out),
+      // then rotation, rounding and the FP8 absmax in one small pass
+      float *q32 = r.at<float>(r.L.qkv32), *k32 = q32 + (int64_t)T * qd, *v32 = k32 + (int64_t)T * kvd;
+      tm.begin(TC_QKV);
+      if (tail_gemm(c, ab, T, qd, d, c->wq[j], nullptr, nullptr, q32, EPI_STORE_F32, st) ||
+          tail_gemm(c, ab, T, kvd, d, c->wk[j], nullptr, nullptr, k32, EPI_STORE_F32, st) ||
+          tail_gemm(c, ab, T, kvd, d, c->wv[j], nullptr, nullptr, v32, EPI_STORE_F32, st))
+        return fail(SWIFTKV_EHIP, "QKV GEMM launch failed");
+      QkvFinishParams fp{};
+      fp.q32 = q32; fp.k32 = k32; fp.v32 = v32; fp.q = qb; fp.k = kb; fp.v = vb;
+      fp.T = T; fp.n_q_heads = m.n_q_heads; fp.n_kv_heads = m.n_kv_heads; fp.head_dim = m.head_dim;
+      fp.cos_sin = r.at<float2>(r.L.cos_sin);
+      fp.amax = compute_scale ? r.at<uint32_t>(r.L.amax) + (int64_t)j * 2 * m.n_kv_heads : nullptr;
+      launch_qkv_finish(fp, st);
+      tm.end();
+    } else {
       GemmParams g{};
       g.A = ab; g.lda = d; g.M = T; g.N = qd + 2 * kvd; g.K = d;
       g.wtab = c->qkv_tab[j]; g.ldw = d; g.wpack = c->qkv_pack[j];
@@ -676,7 +695,11 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
       launch_decode_combine(dp.partial, ob, dp.rows, dp.n_rows, m.n_q_heads, m.head_dim, dp.n_split, st);
       tm.end();
     }
-    {
+    if (few_rows) {
+      tm.begin(TC_O);
+      if (tail_gemm(c, ob, T, d, qd, c->wo[j], nullptr, nullptr, h, EPI_RESID, st)) return fail(SWIFTKV_EHIP, "O GEMM launch failed");
+      tm.end();
+    } else {
       GemmParams g{};
       g.A = ob; g.lda = qd; g.M = T; g.N = d; g.K = qd; g.W = c->wo[j]; g.ldw = qd; g.wpack = c->wo_pack[j]; g.C = h; g.ldc = d;
       tm.begin(TC_O);
@@ -686,20 +709,29 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     tm.begin(TC_OTHER);
     launch_rmsnorm_rows(h, c->norm2[j], ab, T, d, m.rms_eps, st);
     tm.end();
-    {
-      GemmParams g{};
-      g.A = ab; g.lda = d; g.M = T; g.N = 2 * m.ffn; g.K = d; g.wtab = c->gu_tab[j]; g.ldw = d; g.wpack = c->gu_pack[j];
-      g.C = zb; g.ldc = m.ffn;
+    if (few_rows) {
       tm.begin(TC_GATEUP);
-      if (launch_gemm(g, EPI_SWIGLU, 0, st) != 0) return fail(SWIFTKV_EHIP, "gate/up GEMM launch failed");
+      if (tail_gemm(c, ab, T, m.ffn, d, c->wgate[j], c->wup[j], c->gu_tab[j], zb, EPI_SWIGLU, st)) return fail(SWIFTKV_EHIP, "gate/up GEMM launch failed");
       tm.end();
-    }
-    {
-      GemmParams g{};
-      g.A = zb; g.lda = m.ffn; g.M = T; g.N = d; g.K = m.ffn; g.W = c->wdown[j]; g.ldw = m.ffn; g.wpack = c->down_pack[j]; g.C = h; g.ldc = d;
       tm.begin(TC_DOWN);
-      if (launch_gemm(g, EPI_RESID, 0, st) != 0) return fail(SWIFTKV_EHIP, "down GEMM launch failed");
+      if (tail_gemm(c, zb, T, d, m.ffn, c->wdown[j], nullptr, nullptr, h, EPI_RESID, st)) return fail(SWIFTKV_EHIP, "down GEMM launch failed");
       tm.end();
+    } else {
+      {
+        GemmParams g{};
+        g.A = ab; g.lda = d; g.M = T; g.N = 2 * m.ffn; g.K = d; g.wtab = c->gu_tab[j]; g.ldw = d; g.wpack = c->gu_pack[j];
+        g.C = zb; g.ldc = m.ffn;
+        tm.begin(TC_GATEUP);
+        if (launch_gemm(g, EPI_SWIGLU, 0, st) != 0) return fail(SWIFTKV_EHIP, "gate/up GEMM launch failed");
+        tm.end();
+      }
+      {
+        GemmParams g{};
+        g.A = zb; g.lda = m.ffn; g.M = T; g.N = d; g.K = m.ffn; g.W = c->wdown[j]; g.ldw = m.ffn; g.wpack = c->down_pack[j]; g.C = h; g.ldc = d;
+        tm.begin(TC_DOWN);
+        if (launch_gemm(g, EPI_RESID, 0, st) != 0) return fail(SWIFTKV_EHIP, "down GEMM launch failed");
+        tm.end();
+      }
     }
     if (int e = check_launch("decoder layer")) return e;
   }

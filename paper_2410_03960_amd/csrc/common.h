@@ -120,6 +120,18 @@ struct SkinnyParams {
 };
 int launch_skinny(const SkinnyParams &p, int epi, hipStream_t st);
 
+// Few-row batches (decode steps): the Q, K, V projections come out of the weight-streaming kernel as
+// fp32; this step rotates q and k (rotate-half, angles of the row's position), rounds to bf16 once and,
+// for an FP8 cache with computed scales, collects the absmax of the stored K and V values per KV head.
+struct QkvFinishParams {
+  const float *q32, *k32, *v32;   // [T, q_dim], [T, kv_dim], [T, kv_dim]
+  bf16_t *q, *k, *v;
+  int32_t T, n_q_heads, n_kv_heads, head_dim;
+  const float2 *cos_sin;          // [T][hd/2]
+  uint32_t *amax;                 // [2][Hkv] float bits of this cache layer, or null
+};
+int launch_qkv_finish(const QkvFinishParams &p, hipStream_t st);
+
 // ------------------------------------------------------------- attention ----
 struct QBlock {  // one 128-row query block of a sequence
   int32_t row0;   // packed row of the block's first query

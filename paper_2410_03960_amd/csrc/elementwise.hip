@@ -322,6 +322,37 @@ int launch_kv_commit(const CommitParams &p, hipStream_t st) {
   return 0;
 }
 
+// ----------------------------------------------------------- QKV finish ----
+// grid (T, Hq + 2*Hkv), hd/2 threads: thread i owns the rotary pair (i, i + hd/2) of one head of one row.
+__global__ void qkv_finish_kernel(QkvFinishParams p) {
+  const int row = blockIdx.x, hs = blockIdx.y, i = threadIdx.x;
+  const int hd = p.head_dim, half = hd / 2;
+  const int kind = hs < p.n_q_heads ? 0 : (hs < p.n_q_heads + p.n_kv_heads ? 1 : 2);
+  const int head = kind == 0 ? hs : (kind == 1 ? hs - p.n_q_heads : hs - p.n_q_heads - p.n_kv_heads);
+  const int64_t dim = (int64_t)(kind == 0 ? p.n_q_heads : p.n_kv_heads) * hd;
+  const float *src = (kind == 0 ? p.q32 : kind == 1 ? p.k32 : p.v32) + row * dim + head * hd;
+  bf16_t *dst = (kind == 0 ? p.q : kind == 1 ? p.k : p.v) + row * dim + head * hd;
+  float x0 = src[i], x1 = src[i + half];
+  if (kind != 2) {
+    const float2 cs = p.cos_sin[(int64_t)row * half + i];
+    const float y0 = x0 * cs.x - x1 * cs.y, y1 = x1 * cs.x + x0 * cs.y;
+    x0 = y0; x1 = y1;
+  }
+  const bf16_t b0 = f32_to_bf16(x0), b1 = f32_to_bf16(x1);
+  dst[i] = b0;
+  dst[i + half] = b1;
+  if (p.amax && kind != 0) {   // absmax of the values as stored (bf16-rounded)
+    float a = fmaxf(fabsf(bf16_to_f32(b0)), fabsf(bf16_to_f32(b1)));
+    for (int o = 32; o > 0; o >>= 1) a = fmaxf(a, __shfl_xor(a, o));
+    if ((i & 63) == 0) atomicMax(p.amax + (kind == 2 ? p.n_kv_heads : 0) + head, __float_as_uint(a));
+  }
+}
+int launch_qkv_finish(const QkvFinishParams &p, hipStream_t st) {
+  if (p.T <= 0) return 0;
+  hipLaunchKernelGGL(qkv_finish_kernel, dim3(p.T, p.n_q_heads + 2 * p.n_kv_heads), dim3(p.head_dim / 2), 0, st, p);
+  return 0;
+}
+
 // ----------------------------------------------------------- KV gather -----
 // One workgroup per (64-position tile, KV head) of a sequence whose prompt continues over a cached
 // prefix: copies the tile's K rows out of the paged cache into consecutive rows and its V rows

@@ -24,6 +24,7 @@ def _rand_bf16(seed, name, shape, std=1.0):
     (2, 128, 128, 64), (2, 300, 272, 200), (2, 1, 16, 8), (2, 517, 1040, 688),
     (1, 256, 256, 64), (1, 700, 528, 456), (1, 2304, 768, 1024),
     (3, 1, 16, 8), (3, 8, 1024, 256), (3, 16, 272, 688), (3, 17, 64, 96), (3, 65, 160, 1000),
+    (3, 32, 96, 264), (3, 33, 192, 520), (3, 48, 80, 1000), (3, 49, 1056, 4096), (3, 64, 4096, 688), (3, 80, 144, 72),
     (0, 2500, 512, 256),
     (4, 256, 256, 64), (4, 700, 528, 448), (4, 2304, 768, 1024), (4, 1, 16, 128),
     (5, 256, 256, 64), (5, 700, 528, 448), (5, 2304, 768, 1024), (5, 300, 272, 200),

@@ -139,7 +139,7 @@ def test_decode_tokens_with_context(tiny):
     G.compare_logits(logits, ologits, label="decode")
 
 
-@pytest.mark.parametrize("lens,ctx_lens", [([90, 20], None), ([64, 1, 1], [0, 30, 9])])
+@pytest.mark.parametrize("lens,ctx_lens", [([90, 20], None), ([40, 20], None), ([64, 1, 1], [0, 30, 9])])
 def test_fp8_kv_cache(tiny, lens, ctx_lens):
     """FP8 e4m3 cache with per-(layer, K|V, head) absmax scales (Appendix B.1)."""
     from paper_2410_03960_amd import binding as B
