@@ -329,6 +329,21 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
   }
 }
 
+// Sum over the LPK (8 or 16) consecutive lanes that share a key, result in all of them: data-parallel
+// primitives inside a row of 16 lanes (quad swaps, mirror of 8, mirror of 16), no LDS round trip.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+template <int LPK>
+__device__ __forceinline__ float key_group_sum(float x) {
+  x = dpp_add<0xB1>(x);    // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);    // quad_perm [2,3,0,1]
+  x = dpp_add<0x141>(x);   // row_half_mirror: lane i <-> 7 - i of each 8
+  if constexpr (LPK == 16) x = dpp_add<0x140>(x);   // row_mirror: lane i <-> 15 - i
+  return x;
+}
+
 // --------------------------------------------------------------- decode ----
 // grid (n_rows, n_kv_heads, n_split); 256 threads.  Each group of LPK lanes
 // (hd/8) owns one key at a time and 8 dims of it; the R = Hq/Hkv query heads of
@@ -389,51 +404,67 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
   const float ks = p.fp8 ? p.scale_k[kvh] : 1.f, vs = p.fp8 ? p.scale_v[kvh] : 1.f;
   const int32_t *bt = p.block_tables + (int64_t)row.seq * p.max_blocks_per_seq;
 
-  for (int kb = k_lo + wave * KPW; kb < k_hi; kb += KPS) {
-    const int key = kb + grp;
-    const bool valid = key < k_hi;
-    float kf[8], vf[8];
-    if (valid) {
-      int blk = bt[key / SKV_BLOCK];
-      blk = ((unsigned)blk < (unsigned)p.n_blocks) ? blk : 0;   // bad ids are flagged by the plan kernel; never dereference them
-      const int64_t slot = (int64_t)blk * SKV_BLOCK + key % SKV_BLOCK;
-      const int64_t off = (slot * p.n_kv_heads + kvh) * HD + sub * 8;
-      if (p.fp8) {
-        uint2 kc = *(const uint2 *)((const uint8_t *)p.cache_k + off);
-        uint2 vc = *(const uint2 *)((const uint8_t *)p.cache_v + off);
-        uint32_t kw[2] = {kc.x, kc.y}, vw[2] = {vc.x, vc.y};
+  // Two key steps per iteration, all four loads first.  The running reference m[r] (log2 units) only
+  // moves when a score exceeds it by more than 8, so most keys cost one exponential and no rescale of
+  // the accumulators; numerator and denominator share the reference, the result is unchanged.
+  for (int kb = k_lo + wave * KPW; kb < k_hi; kb += 2 * KPS) {
+    float kf[2][8], vf[2][8];
+    bool valid[2];
+    uint4 kraw[2], vraw[2];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          kf[e] = e4m3fn_to_f32((uint8_t)(kw[e >> 2] >> ((e & 3) * 8))) * ks;
-          vf[e] = e4m3fn_to_f32((uint8_t)(vw[e >> 2] >> ((e & 3) * 8))) * vs;
+    for (int u = 0; u < 2; ++u) {
+      const int key = kb + u * KPS + grp;
+      valid[u] = key < k_hi;
+      kraw[u] = make_uint4(0, 0, 0, 0); vraw[u] = make_uint4(0, 0, 0, 0);
+      if (valid[u]) {
+        int blk = bt[key / SKV_BLOCK];
+        blk = ((unsigned)blk < (unsigned)p.n_blocks) ? blk : 0;   // bad ids are flagged by the plan kernel; never dereference them
+        const int64_t slot = (int64_t)blk * SKV_BLOCK + key % SKV_BLOCK;
+        const int64_t off = (slot * p.n_kv_heads + kvh) * HD + sub * 8;
+        if (p.fp8) {
+          const uint2 kc = *(const uint2 *)((const uint8_t *)p.cache_k + off);
+          const uint2 vc = *(const uint2 *)((const uint8_t *)p.cache_v + off);
+          kraw[u].x = kc.x; kraw[u].y = kc.y; vraw[u].x = vc.x; vraw[u].y = vc.y;
+        } else {
+          kraw[u] = *(const uint4 *)((const bf16_t *)p.cache_k + off);
+          vraw[u] = *(const uint4 *)((const bf16_t *)p.cache_v + off);
         }
-      } else {
-        uint4 ku = *(const uint4 *)((const bf16_t *)p.cache_k + off);
-        uint4 vu = *(const uint4 *)((const bf16_t *)p.cache_v + off);
-        kf[0] = bf16lo(ku.x); kf[1] = bf16hi(ku.x); kf[2] = bf16lo(ku.y); kf[3] = bf16hi(ku.y);
-        kf[4] = bf16lo(ku.z); kf[5] = bf16hi(ku.z); kf[6] = bf16lo(ku.w); kf[7] = bf16hi(ku.w);
-        vf[0] = bf16lo(vu.x); vf[1] = bf16hi(vu.x); vf[2] = bf16lo(vu.y); vf[3] = bf16hi(vu.y);
-        vf[4] = bf16lo(vu.z); vf[5] = bf16hi(vu.z); vf[6] = bf16lo(vu.w); vf[7] = bf16hi(vu.w);
       }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { kf[e] = 0.f; vf[e] = 0.f; }
     }
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      float d = 0.f;
+    for (int u = 0; u < 2; ++u) {
+      if (p.fp8) {
+        const uint32_t kw[2] = {kraw[u].x, kraw[u].y}, vw[2] = {vraw[u].x, vraw[u].y};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) d += q[r][e] * kf[e];
+        for (int e = 0; e < 8; ++e) {
+          kf[u][e] = e4m3fn_to_f32((uint8_t)(kw[e >> 2] >> ((e & 3) * 8))) * ks;
+          vf[u][e] = e4m3fn_to_f32((uint8_t)(vw[e >> 2] >> ((e & 3) * 8))) * vs;
+        }
+      } else {
+        const uint32_t kw[4] = {kraw[u].x, kraw[u].y, kraw[u].z, kraw[u].w}, vw[4] = {vraw[u].x, vraw[u].y, vraw[u].z, vraw[u].w};
 #pragma unroll
-      for (int o = LPK / 2; o > 0; o >>= 1) d += __shfl_xor(d, o);
-      if (!valid) d = -INFINITY;
-      const float mn = fmaxf(m[r], d);
-      if (mn != -INFINITY) {
-        const float a = exp2f(m[r] - mn), w = exp2f(d - mn);
-        l[r] = l[r] * a + w;
+        for (int e = 0; e < 4; ++e) {
+          kf[u][2 * e] = bf16lo(kw[e]); kf[u][2 * e + 1] = bf16hi(kw[e]);
+          vf[u][2 * e] = bf16lo(vw[e]); vf[u][2 * e + 1] = bf16hi(vw[e]);
+        }
+      }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[r][e] = acc[r][e] * a + w * vf[e];
-        m[r] = mn;
+      for (int r = 0; r < R; ++r) {
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) d += q[r][e] * kf[u][e];
+        d = key_group_sum<LPK>(d);
+        if (valid[u] && d > m[r] + 8.0f) {   // uniform within the key's lanes
+          const float a = __builtin_amdgcn_exp2f(m[r] - d);   // exp2(-inf) = 0 the first time
+          l[r] *= a;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[r][e] *= a;
+          m[r] = d;
+        }
+        const float w = valid[u] ? __builtin_amdgcn_exp2f(d - m[r]) : 0.f;
+        l[r] += w;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[r][e] += w * vf[u][e];
       }
     }
   }
