@@ -172,7 +172,8 @@ int swiftkv_export_hidden(swiftkv_ctx *ctx, const void *workspace, void *hidden_
 /* C[M,N] = A[M,K] * W[N,K]^T, bf16 inputs, fp32 accumulation.  out_f32 != 0
  * stores fp32, else bf16.  variant: 0 = pick by shape, 1 = 256x256 tile with
  * register-staged loads, 2 = 128x128 tile, 3 = weight-streaming kernel for
- * M <= 80 rows, 4 / 5 = 256x256 tile with direct-to-LDS loads and 8 / 4 waves
+ * M <= 80 rows (29 = the same with a library-owned scratch buffer, which lets
+ * it split K over more workgroups when there are few column tiles), 4 / 5 = 256x256 tile with direct-to-LDS loads and 8 / 4 waves
  * (K % 64 == 0, else they fall back to 1), 14 / 15 = the five-stage
  * direct-to-LDS loop with 4 / 8 waves (what 0 picks for large M), 20 / 21 = that
  * loop with 4 / 3 stages, 22..24 = with non-temporal loads of both / A / W,

@@ -42,7 +42,7 @@ struct Layout {  // byte offsets into the workspace
   int64_t vt_ld = 0;
   int32_t n_qblocks = 0, n_kvtiles = 0, n_dec = 0, n_gtiles = 0;
   int64_t kcat_rows = 0;   // rows of the K buffer gathered from the cache (prompt chunks over a cached prefix), else 0
-  size_t err, meta, positions, seq_of, last_rows, slots, cos_sin, h, a, rstd, q, k, v, o, vt, kcat, z, stage, amax, qkv32;
+  size_t err, meta, positions, seq_of, last_rows, slots, cos_sin, h, a, rstd, q, k, v, o, vt, kcat, z, stage, amax, qkv32, skpart;
   size_t th, ta, tq, to, tz, partial, total;
   // offsets (in int32 units) inside the meta block copied from the host
   size_t m_cu, m_ctx, m_qblocks, m_kvtiles, m_dec, m_tail, m_gtiles, m_words;
@@ -116,6 +116,7 @@ Layout make_layout(const swiftkv_ctx *c, int64_t T, int32_t B, int64_t vt_ld, in
   L.z = take(T * (int64_t)m.ffn * 2);
   L.stage = take(fp8 ? T * (int64_t)c->P * 2 * kvd * 2 : 0);
   L.amax = take(fp8 ? (size_t)c->C * 2 * m.n_kv_heads * 4 : 0);
+  L.skpart = take(SKINNY_PARTIAL_BYTES);   // K-split partial sums of the weight-streaming GEMMs
   L.qkv32 = take((size_t)std::min<int64_t>(T, SKINNY_MAX_ROWS) * (qd + 2 * kvd) * 4);   // fp32 Q, K, V of few-row batches
   L.th = take((size_t)B * d * 2);
   L.ta = take((size_t)B * std::max<int64_t>(d, qd) * 2);
@@ -342,9 +343,9 @@ int run_fused_kv(Run &r, const bf16_t *hidden, Timer &tm) {
 }
 
 int tail_gemm(const swiftkv_ctx *c, const bf16_t *A, int M, int N, int K, const bf16_t *W, const bf16_t *W2,
-              const bf16_t *const *gu_tab, void *C, int epi, hipStream_t st) {
+              const bf16_t *const *gu_tab, void *C, int epi, float *partial, hipStream_t st) {
   if (M <= 80) {
-    SkinnyParams s{A, M, N, K, W, W2, C};
+    SkinnyParams s{A, M, N, K, W, W2, C, partial};
     return launch_skinny(s, epi, st);
   }
   GemmParams g{};
@@ -609,6 +610,7 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   bf16_t *vt = r.at<bf16_t>(r.L.vt), *zb = r.at<bf16_t>(r.L.z);
   const bool compute_scale = r.fp8 && kv->scale_mode == SWIFTKV_SCALE_COMPUTE_ABSMAX;
   const bool few_rows = T <= SKINNY_MAX_ROWS;
+  float *skp = r.at<float>(r.L.skpart);
 
   // ------------------------------------------ layers 1..l on every new token ----
   for (int j = 0; j < c->l; ++j) {
@@ -620,9 +622,9 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
       // then rotation, rounding and the FP8 absmax in one small pass
       float *q32 = r.at<float>(r.L.qkv32), *k32 = q32 + (int64_t)T * qd, *v32 = k32 + (int64_t)T * kvd;
       tm.begin(TC_QKV);
-      if (tail_gemm(c, ab, T, qd, d, c->wq[j], nullptr, nullptr, q32, EPI_STORE_F32, st) ||
-          tail_gemm(c, ab, T, kvd, d, c->wk[j], nullptr, nullptr, k32, EPI_STORE_F32, st) ||
-          tail_gemm(c, ab, T, kvd, d, c->wv[j], nullptr, nullptr, v32, EPI_STORE_F32, st))
+      if (tail_gemm(c, ab, T, qd, d, c->wq[j], nullptr, nullptr, q32, EPI_STORE_F32, skp, st) ||
+          tail_gemm(c, ab, T, kvd, d, c->wk[j], nullptr, nullptr, k32, EPI_STORE_F32, skp, st) ||
+          tail_gemm(c, ab, T, kvd, d, c->wv[j], nullptr, nullptr, v32, EPI_STORE_F32, skp, st))
         return fail(SWIFTKV_EHIP, "QKV GEMM launch failed");
       QkvFinishParams fp{};
       fp.q32 = q32; fp.k32 = k32; fp.v32 = v32; fp.q = qb; fp.k = kb; fp.v = vb;
@@ -697,7 +699,7 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     }
     if (few_rows) {
       tm.begin(TC_O);
-      if (tail_gemm(c, ob, T, d, qd, c->wo[j], nullptr, nullptr, h, EPI_RESID, st)) return fail(SWIFTKV_EHIP, "O GEMM launch failed");
+      if (tail_gemm(c, ob, T, d, qd, c->wo[j], nullptr, nullptr, h, EPI_RESID, skp, st)) return fail(SWIFTKV_EHIP, "O GEMM launch failed");
       tm.end();
     } else {
       GemmParams g{};
@@ -711,10 +713,10 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     tm.end();
     if (few_rows) {
       tm.begin(TC_GATEUP);
-      if (tail_gemm(c, ab, T, m.ffn, d, c->wgate[j], c->wup[j], c->gu_tab[j], zb, EPI_SWIGLU, st)) return fail(SWIFTKV_EHIP, "gate/up GEMM launch failed");
+      if (tail_gemm(c, ab, T, m.ffn, d, c->wgate[j], c->wup[j], c->gu_tab[j], zb, EPI_SWIGLU, skp, st)) return fail(SWIFTKV_EHIP, "gate/up GEMM launch failed");
       tm.end();
       tm.begin(TC_DOWN);
-      if (tail_gemm(c, zb, T, d, m.ffn, c->wdown[j], nullptr, nullptr, h, EPI_RESID, st)) return fail(SWIFTKV_EHIP, "down GEMM launch failed");
+      if (tail_gemm(c, zb, T, d, m.ffn, c->wdown[j], nullptr, nullptr, h, EPI_RESID, skp, st)) return fail(SWIFTKV_EHIP, "down GEMM launch failed");
       tm.end();
     } else {
       {
@@ -747,7 +749,7 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   for (int j = c->l; j < m.n_layers; ++j) {
     const int cl = c->l + (j - c->l) / c->g;
     launch_rmsnorm_rows(th, c->norm1[j], ta, B, d, m.rms_eps, st);
-    if (tail_gemm(c, ta, B, qd, d, c->wq[j], nullptr, nullptr, tq, EPI_STORE_BF16, st)) return fail(SWIFTKV_EHIP, "tail q GEMM failed");
+    if (tail_gemm(c, ta, B, qd, d, c->wq[j], nullptr, nullptr, tq, EPI_STORE_BF16, skp, st)) return fail(SWIFTKV_EHIP, "tail q GEMM failed");
     AttnDecodeParams dp{};
     dp.q = tq; dp.out = to; dp.rows = (const DecodeRow *)r.meta(r.L.m_tail); dp.n_rows = B;
     dp.n_q_heads = m.n_q_heads; dp.n_kv_heads = m.n_kv_heads; dp.head_dim = m.head_dim;
@@ -758,13 +760,13 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     dp.n_split = pick_split(B, m.n_kv_heads, r.hp.max_keys_tail);
     if (launch_attention_decode(dp, st) != 0) return fail(SWIFTKV_EHIP, "tail attention launch failed");
     launch_decode_combine(dp.partial, to, dp.rows, B, m.n_q_heads, m.head_dim, dp.n_split, st);
-    if (tail_gemm(c, to, B, d, qd, c->wo[j], nullptr, nullptr, th, EPI_RESID, st)) return fail(SWIFTKV_EHIP, "tail o GEMM failed");
+    if (tail_gemm(c, to, B, d, qd, c->wo[j], nullptr, nullptr, th, EPI_RESID, skp, st)) return fail(SWIFTKV_EHIP, "tail o GEMM failed");
     launch_rmsnorm_rows(th, c->norm2[j], ta, B, d, m.rms_eps, st);
-    if (tail_gemm(c, ta, B, m.ffn, d, c->wgate[j], c->wup[j], c->gu_tab[j], tz, EPI_SWIGLU, st)) return fail(SWIFTKV_EHIP, "tail MLP GEMM failed");
-    if (tail_gemm(c, tz, B, d, m.ffn, c->wdown[j], nullptr, nullptr, th, EPI_RESID, st)) return fail(SWIFTKV_EHIP, "tail down GEMM failed");
+    if (tail_gemm(c, ta, B, m.ffn, d, c->wgate[j], c->wup[j], c->gu_tab[j], tz, EPI_SWIGLU, skp, st)) return fail(SWIFTKV_EHIP, "tail MLP GEMM failed");
+    if (tail_gemm(c, tz, B, d, m.ffn, c->wdown[j], nullptr, nullptr, th, EPI_RESID, skp, st)) return fail(SWIFTKV_EHIP, "tail down GEMM failed");
   }
   launch_rmsnorm_rows(th, c->final_norm, ta, B, d, m.rms_eps, st);
-  if (tail_gemm(c, ta, B, m.vocab, d, c->lm_head, nullptr, nullptr, logits_out, EPI_STORE_F32, st)) return fail(SWIFTKV_EHIP, "LM head GEMM failed");
+  if (tail_gemm(c, ta, B, m.vocab, d, c->lm_head, nullptr, nullptr, logits_out, EPI_STORE_F32, skp, st)) return fail(SWIFTKV_EHIP, "LM head GEMM failed");
   tm.end();
   if (int e = check_launch("tail")) return e;
   c->last = r.L; c->have_last = true;
@@ -803,11 +805,13 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
                     int32_t variant, void *stream) {
   if (!A || !W || !C) return fail(SWIFTKV_EINVAL, "null argument");
   if (M < 1 || N < 16 || K < 8 || (N % 16) || (K % 8)) return fail(SWIFTKV_EINVAL, "need M >= 1, N %% 16 == 0, K %% 8 == 0");
-  if (variant < 0 || variant > 28) return fail(SWIFTKV_EINVAL, "variant must be 0..28");
+  if (variant < 0 || variant > 29) return fail(SWIFTKV_EINVAL, "variant must be 0..29");
   hipStream_t st = (hipStream_t)stream;
-  if (variant == 3) {
+  if (variant == 3 || variant == 29) {   // 29: with the scratch that lets the kernel split K (library-owned, allocated once)
     if (M > 80) return fail(SWIFTKV_EINVAL, "weight-streaming kernel handles M <= 80");
-    SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C};
+    static float *partial = nullptr;
+    if (variant == 29 && !partial) HIP_TRY(hipMalloc((void **)&partial, SKINNY_PARTIAL_BYTES));
+    SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, variant == 29 ? partial : nullptr};
     if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, st)) return fail(SWIFTKV_EHIP, "skinny launch failed");
     return check_launch("skinny gemm");
   }

@@ -117,7 +117,9 @@ struct SkinnyParams {
   const bf16_t *W;   // [N, K]
   const bf16_t *W2;  // SWIGLU: up-projection [N, K]
   void *C;           // bf16 [M,N] (STORE_BF16, RESID in place, SWIGLU) or fp32 (STORE_F32)
+  float *partial;    // scratch of SKINNY_PARTIAL_BYTES for K-split partial sums, or null (then K is never split)
 };
+constexpr size_t SKINNY_PARTIAL_BYTES = (size_t)4 * 80 * 8192 * 4;   // 4 splits x 80 rows x 8192 columns fp32
 int launch_skinny(const SkinnyParams &p, int epi, hipStream_t st);
 
 // Few-row batches (decode steps): the Q, K, V projections come out of the weight-streaming kernel as

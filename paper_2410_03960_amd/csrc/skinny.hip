@@ -9,7 +9,14 @@
 // rows: with many rows the activation reads would outweigh the weights, so NB
 // grows with MB (fewer, wider workgroups); with up to 16 rows NB = 1 keeps the
 // most workgroups streaming.
+// A CU sustains only a fraction of its share of HBM bandwidth on one such stream
+// (loads in flight / latency), so every CU has to stream: when there are fewer
+// column tiles than CUs, K is split over blockIdx.y, the splits write fp32
+// partial sums and a second small kernel adds them in a fixed order and applies
+// the epilogue (deterministic, unlike atomic accumulation).
 #include "common.h"
+
+#include <algorithm>
 
 namespace {
 
@@ -44,8 +51,12 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_kernel(SkinnyParams p) {
 #pragma unroll
     for (int j = 0; j < NJ; ++j) acc[mb][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  const int nsteps = (p.K + 31) / 32;
-  for (int s0 = wave; s0 < nsteps; s0 += SK_WAVES * UN) {
+  // k steps of this split
+  const int all_steps = (p.K + 31) / 32;
+  const int per_split = (all_steps + (int)gridDim.y - 1) / (int)gridDim.y;
+  const int s_begin = blockIdx.y * per_split;
+  const int nsteps = (s_begin + per_split) < all_steps ? (s_begin + per_split) : all_steps;
+  for (int s0 = s_begin + wave; s0 < nsteps; s0 += SK_WAVES * UN) {
     uint4 wv[UN][NJ], av[UN][MB];
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
@@ -87,7 +98,13 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_kernel(SkinnyParams p) {
           x[w][v] = sum;
         }
       const int m = mb * 16 + l16, n = n0 + nb * 16 + 4 * kq;
-      if (m < p.M) {
+      if (gridDim.y > 1) {   // partial[split][w][m][n]
+        if (m < p.M) {
+#pragma unroll
+          for (int w = 0; w < NW; ++w)
+            *(float4 *)(p.partial + (((int64_t)blockIdx.y * NW + w) * p.M + m) * p.N + n) = make_float4(x[w][0], x[w][1], x[w][2], x[w][3]);
+        }
+      } else if (m < p.M) {
         if constexpr (EPI == EPI_STORE_F32) {
           *(float4 *)((float *)p.C + (int64_t)m * p.N + n) = make_float4(x[0][0], x[0][1], x[0][2], x[0][3]);
         } else {
@@ -109,15 +126,67 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_kernel(SkinnyParams p) {
   }
 }
 
+// sum of the K splits in split order + epilogue, 4 columns per thread
+template <int EPI>
+__global__ void skinny_reduce_kernel(SkinnyParams p, int ksplit) {
+  constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
+  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= (int64_t)p.M * p.N) return;
+  float x[NW][4];
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int ks = 0; ks < ksplit; ++ks) {
+      const float4 v = *(const float4 *)(p.partial + ((int64_t)ks * NW + w) * p.M * p.N + i);
+      sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+    }
+    x[w][0] = sum.x; x[w][1] = sum.y; x[w][2] = sum.z; x[w][3] = sum.w;
+  }
+  if constexpr (EPI == EPI_STORE_F32) {
+    *(float4 *)((float *)p.C + i) = make_float4(x[0][0], x[0][1], x[0][2], x[0][3]);
+  } else {
+    bf16_t *dst = (bf16_t *)p.C + i;
+    float o[4] = {x[0][0], x[0][1], x[0][2], x[0][3]};
+    if constexpr (EPI == EPI_RESID) {
+      const uint2 r = *(const uint2 *)dst;
+      o[0] += bf16lo(r.x); o[1] += bf16hi(r.x); o[2] += bf16lo(r.y); o[3] += bf16hi(r.y);
+    }
+    if constexpr (EPI == EPI_SWIGLU) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) o[v] = x[0][v] / (1.f + __expf(-x[0][v])) * x[NW - 1][v];
+    }
+    *(uint2 *)dst = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+  }
+}
+
+template <int MB, int NB, int EPI>
+int launch_kernels(const SkinnyParams &p, hipStream_t st) {
+  constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
+  const int tiles = p.N / (16 * NB);
+  // split K while the column tiles leave CUs idle: up to 4 splits, each at least 16 k steps per wave pass
+  int ksplit = 1;
+  if (p.partial && MB >= 3 && tiles < 256) {
+    ksplit = std::min(4, 256 / tiles);
+    ksplit = std::min(ksplit, std::max(1, p.K / (32 * SK_WAVES * 4)));
+    if ((size_t)ksplit * NW * p.M * p.N * 4 > SKINNY_PARTIAL_BYTES) ksplit = 1;
+  }
+  dim3 grid(tiles, ksplit), block(SK_WAVES * 64);
+  hipLaunchKernelGGL((skinny_kernel<MB, NB, EPI>), grid, block, 0, st, p);
+  if (ksplit > 1) {
+    const int64_t quads = (int64_t)p.M * p.N / 4;
+    hipLaunchKernelGGL((skinny_reduce_kernel<EPI>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, p, ksplit);
+  }
+  return 0;
+}
+
 template <int MB, int NB>
 int launch_mb(const SkinnyParams &p, int epi, hipStream_t st) {
-  dim3 grid(p.N / (16 * NB)), block(SK_WAVES * 64);
   switch (epi) {
-    case EPI_STORE_BF16: hipLaunchKernelGGL((skinny_kernel<MB, NB, EPI_STORE_BF16>), grid, block, 0, st, p); return 0;
-    case EPI_STORE_F32: hipLaunchKernelGGL((skinny_kernel<MB, NB, EPI_STORE_F32>), grid, block, 0, st, p); return 0;
-    case EPI_RESID: hipLaunchKernelGGL((skinny_kernel<MB, NB, EPI_RESID>), grid, block, 0, st, p); return 0;
+    case EPI_STORE_BF16: return launch_kernels<MB, NB, EPI_STORE_BF16>(p, st);
+    case EPI_STORE_F32: return launch_kernels<MB, NB, EPI_STORE_F32>(p, st);
+    case EPI_RESID: return launch_kernels<MB, NB, EPI_RESID>(p, st);
     case EPI_SWIGLU:
-      if constexpr (NB <= 2) { hipLaunchKernelGGL((skinny_kernel<MB, NB, EPI_SWIGLU>), grid, block, 0, st, p); return 0; }
+      if constexpr (NB <= 2) return launch_kernels<MB, NB, EPI_SWIGLU>(p, st);
       break;
   }
   return -1;

@@ -25,6 +25,7 @@ def _rand_bf16(seed, name, shape, std=1.0):
     (1, 256, 256, 64), (1, 700, 528, 456), (1, 2304, 768, 1024),
     (3, 1, 16, 8), (3, 8, 1024, 256), (3, 16, 272, 688), (3, 17, 64, 96), (3, 65, 160, 1000),
     (3, 32, 96, 264), (3, 33, 192, 520), (3, 48, 80, 1000), (3, 49, 1056, 4096), (3, 64, 4096, 688), (3, 80, 144, 72),
+    (29, 33, 192, 520), (29, 49, 1056, 4096), (29, 64, 4096, 1376), (29, 80, 1024, 4096), (29, 16, 1024, 4096),
     (0, 2500, 512, 256),
     (4, 256, 256, 64), (4, 700, 528, 448), (4, 2304, 768, 1024), (4, 1, 16, 128),
     (5, 256, 256, 64), (5, 700, 528, 448), (5, 2304, 768, 1024), (5, 300, 272, 200),
