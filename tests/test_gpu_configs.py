@@ -211,3 +211,67 @@ def test_config5_8b_fp8_32k_prompt_with_64_decode_tokens():
                 em = emu_c.read(c, 0, wl.decode_ctx + 1)[kvsel][-1]
                 rel_bar, cos_bar = _bar(G.FP8_REL, G.FP8_COS, rel_err(em, want), cosine(em, want))
                 assert rel_err(got, want) <= rel_bar and cosine(got, want) >= cos_bar, (b, c, kvsel, rel_err(got, want))
+
+
+def test_chunk_workload_8b_2048_new_over_6144_cached():
+    """The prompt-chunk workload bench.py offers (8 sequences, 6144 tokens cached
+    + 2048 new each) at full size.  The cached rows are seeded bf16 values in all
+    cache layers; the oracle gets the same rows of one sequence and the first
+    300 tokens of its chunk (later chunk tokens cannot influence them), and the
+    rows the call stores for those tokens are compared.  Logits: a small GPU call
+    with the same context and those 300 tokens, against the oracle's."""
+    from paper_2410_03960_amd import binding as B
+    wl, store, ctx = _gpu_setup("8b_l16_b8x2048_ctx6144")
+    sh = wl.shape
+    batch = WL.build_batch(wl)
+    nctx, b, n = wl.prefix_ctx, 5, 300
+    assert batch.n_seqs == 8 and int(batch.context_lens[b]) == nctx and ctx.n_cache_layers == 32
+    cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, sh.n_kv_heads, sh.head_dim, batch.block_tables,
+                      batch.context_lens.tolist())
+    cache.data.normal_(0.0, 0.5, generator=torch.Generator(device="cuda").manual_seed(wl.seed))
+    ar = torch.arange(nctx)
+    ctx_slots = batch.block_tables[b].long()[ar // 16] * 16 + ar % 16
+    prefix = cache.data[:, :, ctx_slots.cuda()].float().cpu()          # [C, 2, nctx, Hkv, hd], before the call
+    logits, cache, ws = G.run_gpu(ctx, batch, cache=cache)
+    G.check_plan(ctx, ws, batch)
+    assert torch.isfinite(logits).all()
+    assert torch.equal(cache.data[:, :, ctx_slots.cuda()].float().cpu(), prefix), "cached rows must stay untouched"
+    cu = torch.cumsum(torch.cat([torch.zeros(1, dtype=torch.int64), batch.seq_lens.long()]), 0)
+    ids = batch.token_ids[cu[b]:cu[b] + n].clone()
+    nb = (nctx + n + 15) // 16
+    bt = torch.arange(nb, dtype=torch.int32)[None]
+    outs = []
+    t0 = time.time()
+    for rnd in (None, _bf16_round):
+        oc = O.PagedKVCache(ctx.n_cache_layers, nb, sh.n_kv_heads, sh.head_dim, bt, dtype=torch.float32)
+        oc.data[:, :, :nctx] = prefix
+        lg_o, _ = O.swiftkv_prefill(oracle_shape(sh), _host_weight_fn(store), ids, [n], [nctx], wl.l, wl.g, oc,
+                                    dtype=torch.float32, act_round=rnd)
+        outs.append((lg_o[0], oc))
+        _say(f"  chunk: oracle ({'bf16-stored activations' if rnd else 'plain'}) done at {time.time() - t0:.1f}s")
+    (ref_l, ref), (emu_l, emu) = outs
+    pos = nctx + torch.arange(n)
+    new_slots = batch.block_tables[b].long()[pos // 16] * 16 + pos % 16
+    worst = (0.0,)
+    for c in range(ref.C):
+        for kvsel in (0, 1):
+            want = ref.read(c, 0, nctx + n)[kvsel][nctx:]
+            em = emu.read(c, 0, nctx + n)[kvsel][nctx:]
+            got = G.gpu_cache_logical(cache, c, kvsel, new_slots).cpu()
+            r, cs = rel_err(got, want), cosine(got, want)
+            rel_bar, cos_bar = _bar(G.BF16_REL, G.BF16_COS, rel_err(em, want), cosine(em, want))
+            worst = max(worst, (r / rel_bar, c, kvsel, r, cs, rel_bar))
+            assert r <= rel_bar and cs >= cos_bar, \
+                f"chunk cache layer {c} {'KV'[kvsel]}: rel {r:.3e} (bar {rel_bar:.3e}) cos {cs:.6f} (bar {cos_bar:.6f})"
+    _say(f"  chunk: worst cache tensor layer {worst[1]} {'KV'[worst[2]]}: rel {worst[3]:.3e} (bar {worst[5]:.3e}) cos {worst[4]:.6f}")
+    # logits of token n-1: a small GPU call, same context rows, the same 300 tokens
+    sub = WL.build_batch(wl, lens=[n], ctx=[nctx], shuffled=False)
+    sub.token_ids = ids
+    small = B.KVCache(ctx.n_cache_layers, sub.n_blocks, sh.n_kv_heads, sh.head_dim, sub.block_tables, [nctx])
+    small.data[:, :, :nctx] = prefix.to(torch.bfloat16).cuda()
+    lg, small, ws = G.run_gpu(ctx, sub, cache=small)
+    G.check_plan(ctx, ws, sub)
+    r, cs = rel_err(lg[0].cpu(), ref_l), cosine(lg[0].cpu(), ref_l)
+    rel_bar, cos_bar = _bar(G.BF16_REL, G.BF16_COS, rel_err(emu_l, ref_l), cosine(emu_l, ref_l))
+    _say(f"  chunk: logits rel {r:.3e} (bar {rel_bar:.3e}) cos {cs:.6f} (bar {cos_bar:.6f})")
+    assert r <= rel_bar and cs >= cos_bar
