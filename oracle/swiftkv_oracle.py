@@ -209,17 +209,24 @@ class PagedKVCache:
     """Physical cache [n_cache_layers][2 (K,V)][n_blocks][16][Hkv][hd].
 
     Float mode stores values in `dtype`.  FP8 mode stores uint8 e4m3fn codes
-    plus float32 scales [n_cache_layers][2][Hkv]; reads return code * scale.
+    plus float32 scales; reads return code * scale.  Scales are either one per
+    (cache layer, K|V, KV head), [n_cache_layers][2][Hkv], set by the caller or
+    by swiftkv_prefill, or, with `per_token` (the granularity of Appendix B.1),
+    one per (cache layer, K|V, token), [n_cache_layers][2][n_blocks*16], taken
+    from the token's own absmax over all KV heads when the token is written.
     """
 
     def __init__(self, n_layers: int, n_blocks: int, n_kv_heads: int, head_dim: int,
-                 block_tables: torch.Tensor, dtype=torch.float64, fp8: bool = False):
+                 block_tables: torch.Tensor, dtype=torch.float64, fp8: bool = False, per_token: bool = False):
         self.C, self.NB, self.Hkv, self.hd = n_layers, n_blocks, n_kv_heads, head_dim
         self.block_tables = block_tables.to(torch.int64)
-        self.dtype, self.fp8 = dtype, fp8
+        self.dtype, self.fp8, self.per_token = dtype, fp8, per_token and fp8
         shape = (n_layers, 2, n_blocks * BLOCK, n_kv_heads, head_dim)
         self.data = torch.zeros(shape, dtype=torch.uint8 if fp8 else dtype)
-        self.scales = torch.zeros((n_layers, 2, n_kv_heads), dtype=torch.float32) if fp8 else None
+        if self.per_token:
+            self.scales = torch.zeros((n_layers, 2, n_blocks * BLOCK), dtype=torch.float32)
+        else:
+            self.scales = torch.zeros((n_layers, 2, n_kv_heads), dtype=torch.float32) if fp8 else None
 
     def slots(self, b: int, pos: torch.Tensor) -> torch.Tensor:
         pos = pos.to(torch.int64)
@@ -227,7 +234,12 @@ class PagedKVCache:
 
     def write(self, c: int, b: int, pos: torch.Tensor, k: torch.Tensor, v: torch.Tensor):
         s = self.slots(b, pos)
-        if self.fp8:
+        if self.per_token:
+            for t, x in ((0, k), (1, v)):
+                sc = fp8_scale(x.abs().amax(dim=(1, 2)))                    # one scale per written token
+                self.scales[c, t, s] = sc
+                self.data[c, t, s] = fp8_quantize(x, sc[:, None, None])
+        elif self.fp8:
             self.data[c, 0, s] = fp8_quantize(k, self.scales[c, 0][None, :, None])
             self.data[c, 1, s] = fp8_quantize(v, self.scales[c, 1][None, :, None])
         else:
@@ -238,7 +250,10 @@ class PagedKVCache:
         """K, V of positions 0..n-1 of sequence b in cache layer c (dequantised)."""
         s = self.slots(b, torch.arange(n))
         k, v = self.data[c, 0, s], self.data[c, 1, s]
-        if self.fp8:
+        if self.per_token:
+            k = fp8_dequantize(k, self.scales[c, 0, s][:, None, None], self.dtype)
+            v = fp8_dequantize(v, self.scales[c, 1, s][:, None, None], self.dtype)
+        elif self.fp8:
             k = fp8_dequantize(k, self.scales[c, 0][None, :, None], self.dtype)
             v = fp8_dequantize(v, self.scales[c, 1][None, :, None], self.dtype)
         return k, v
@@ -293,9 +308,10 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
     `cache` already and seq_lens[b] new ones (one new token = a decode step,
     several = a chunk of a longer prompt: new token i sits at position
     context + i and attends to the cached positions and to new tokens <= i).
-    fp8_compute_scales: in FP8 mode, derive each (cache layer, K|V, head) scale
-    from the absmax of what this call writes there (over the processed
-    sequences); otherwise use the scales already in `cache`.
+    fp8_compute_scales: in FP8 mode with per-head scales, derive each (cache
+    layer, K|V, head) scale from the absmax of what this call writes there (over
+    the processed sequences); otherwise use the scales already in `cache`.  A
+    cache with per-token scales sets each token's scales when it writes it.
     all_token_tail: run layers l+1..L on every new token instead of only the
     last (checking aid); logits are still those of the last token.
     act_round: None gives the plain definition.  A function (e.g. round to
@@ -323,7 +339,7 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
 
     def store(c: int, kv: Dict[int, tuple]):
         """Write one cache layer for all processed sequences (FP8: scales first)."""
-        if cache.fp8 and fp8_compute_scales:
+        if cache.fp8 and fp8_compute_scales and not cache.per_token:
             for t in (0, 1):
                 amax = torch.stack([kv[b][t].abs().amax(dim=(0, 2)) for b in seqs]).amax(dim=0)
                 cache.scales[c, t] = fp8_scale(amax)

@@ -55,6 +55,7 @@ def _oracle_contexts(store, batch, ctx_lens, l, g, fp8=False, scales=None):
     (2, 2, [70, 1, 5, 200], [40, 17, 0, 130]),      # chunk, decode token, fresh prompt, chunk over several tiles
     (3, 1, [129, 64], [63, 64]),                    # query blocks and key tiles off the 64/128 grid, and on it
     (4, 1, [2, 300], [1, 0]),                       # l = L (no later layers), shortest chunk
+    (2, 1, [30, 1, 7], [50, 9, 0]),                 # at most 80 tokens: the weight-streaming GEMM path
 ])
 def test_chunk_over_cached_prefix(tiny, l, g, lens, ctx_lens):
     from paper_2410_03960_amd import binding as B

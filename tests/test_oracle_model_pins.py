@@ -239,6 +239,37 @@ def test_chunk_and_decode_and_fresh_prompt_in_one_batch(wd):
             assert torch.allclose(k, kr, atol=1e-12) and torch.allclose(v, vr, atol=1e-12)
 
 
+def test_per_token_fp8_cache_is_independent_of_batching(wd):
+    """With per-token scales nothing a token stores depends on what else is in
+    the call: a prompt fed in chunks leaves exactly the codes and scales of the
+    one-shot prefill, and a batch of two prompts those of each prompt alone."""
+    l, g, n = 2, 2, 41
+    sh, wf = oracle_shape(MS), dict_weight_fn(wd)
+    ids = _ids(n, 21)
+    C = O.n_cache_layers(MS.n_layers, l, g)
+    bt, nb = identity_tables([n], [0])
+    one = O.PagedKVCache(C, nb, MS.n_kv_heads, MS.head_dim, bt, fp8=True, per_token=True)
+    full_logits, _ = O.swiftkv_prefill(sh, wf, ids, [n], [0], l, g, one)
+    parts = O.PagedKVCache(C, nb, MS.n_kv_heads, MS.head_dim, bt, fp8=True, per_token=True)
+    for a, b in ((0, 16), (16, 17), (17, n)):
+        logits, _ = O.swiftkv_prefill(sh, wf, ids[a:b], [b - a], [a], l, g, parts)
+    assert torch.equal(one.data[:, :, :n], parts.data[:, :, :n]) and torch.equal(one.scales[:, :, :n], parts.scales[:, :, :n])
+    assert torch.allclose(logits[0], full_logits[0], atol=1e-10)
+    # and close to the unquantised result (relative error of e4m3 is at most 2^-4 per element)
+    plain_logits, plain, _ = _run_oracle(wd, ids, [n], l, g)
+    for c in range(C):
+        kq, vq = one.read(c, 0, n)
+        kp, vp = plain.read(c, 0, n)
+        assert (kq - kp).abs().max() <= 0.07 * kp.abs().max() and (vq - vp).abs().max() <= 0.07 * vp.abs().max()
+    # two prompts in one batch
+    ids2 = _ids(13, 22)
+    bt2, nb2 = identity_tables([n, 13], [0, 0])
+    both = O.PagedKVCache(C, nb2, MS.n_kv_heads, MS.head_dim, bt2, fp8=True, per_token=True)
+    O.swiftkv_prefill(sh, wf, torch.cat([ids, ids2]), [n, 13], [0, 0], l, g, both)
+    s0 = both.slots(0, torch.arange(n))
+    assert torch.equal(both.data[:, :, s0], one.data[:, :, :n]) and torch.equal(both.scales[:, :, s0], one.scales[:, :, :n])
+
+
 def test_sequence_order_only_permutes_outputs(wd):
     lens = [9, 14]
     ids = _ids(23, 12)

@@ -159,6 +159,42 @@ def test_fp8_scale_and_error_bound():
     assert ((dq - x).abs()[normal] <= 2.0 ** -4 * x.abs()[normal] * (1 + 1e-6)).all()
 
 
+def test_fp8_per_token_cache_scales():
+    """Per-token scales (Appendix B.1): each written token carries its own K and V
+    scale = its absmax over all heads / 448; its largest element becomes +-448;
+    tokens written in separate calls get the same codes as tokens written
+    together; rows differing by a factor keep their codes and scale by it; the
+    library's float8 cast of x / scale gives the same codes."""
+    bt = torch.tensor([[2, 0, 1]], dtype=torch.int32)
+    g = torch.Generator().manual_seed(9)
+    n, H, hd = 37, 2, 8
+    k = torch.randn(n, H, hd, generator=g) * torch.logspace(-3, 2, n)[:, None, None]   # rows of very different size
+    v = torch.randn(n, H, hd, generator=g)
+    c1 = O.PagedKVCache(1, 3, H, hd, bt, dtype=torch.float32, fp8=True, per_token=True)
+    c1.write(0, 0, torch.arange(n), k, v)
+    slots = c1.slots(0, torch.arange(n))
+    assert torch.equal(c1.scales[0, 0, slots], k.abs().amax(dim=(1, 2)).float() / 448)
+    assert torch.equal(c1.scales[0, 1, slots], v.abs().amax(dim=(1, 2)).float() / 448)
+    assert ((c1.data[0, 0, slots].view(n, -1) & 0x7F).amax(dim=1) == 0x7E).all()
+    want = (k / c1.scales[0, 0, slots][:, None, None]).to(torch.float8_e4m3fn).view(torch.uint8)
+    assert torch.equal(c1.data[0, 0, slots], want)
+    kd, vd = c1.read(0, 0, n)
+    big = k.abs() >= 2.0 ** -6 * c1.scales[0, 0, slots][:, None, None]
+    assert ((kd - k).abs()[big] <= 2.0 ** -4 * k.abs()[big] * (1 + 1e-6)).all()        # every row, small or large
+    # written in two calls
+    c2 = O.PagedKVCache(1, 3, H, hd, bt, dtype=torch.float32, fp8=True, per_token=True)
+    c2.write(0, 0, torch.arange(20), k[:20], v[:20])
+    c2.write(0, 0, torch.arange(20, n), k[20:], v[20:])
+    assert torch.equal(c1.data, c2.data) and torch.equal(c1.scales, c2.scales)
+    # scaling a row by a power of two moves only its scale
+    c3 = O.PagedKVCache(1, 3, H, hd, bt, dtype=torch.float32, fp8=True, per_token=True)
+    k3 = k.clone()
+    k3[5] *= 8.0
+    c3.write(0, 0, torch.arange(n), k3, v)
+    assert torch.equal(c3.data, c1.data)
+    assert c3.scales[0, 0, slots[5]] == 8 * c1.scales[0, 0, slots[5]]
+
+
 # ------------------------------------------------------------ integer plans
 def test_slot_mapping_enumeration():
     bt = torch.tensor([[7, 2, 9, 0], [4, 1, 0, 0]], dtype=torch.int32)
