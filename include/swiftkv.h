@@ -43,7 +43,7 @@ enum {
 };
 
 enum { SWIFTKV_KV_BF16 = 0, SWIFTKV_KV_FP8_E4M3 = 1 };
-enum { SWIFTKV_SCALE_COMPUTE_ABSMAX = 0, SWIFTKV_SCALE_USE_GIVEN = 1 };
+enum { SWIFTKV_SCALE_COMPUTE_ABSMAX = 0, SWIFTKV_SCALE_USE_GIVEN = 1, SWIFTKV_SCALE_PER_TOKEN = 2 };
 
 #define SWIFTKV_BLOCK_SIZE 16 /* tokens per paged KV block (fixed) */
 
@@ -81,16 +81,22 @@ typedef struct {
  * Model layer j (1-based) uses cache layer j-1 for j <= l and
  * l + (j-l-1)/g for j > l, so n_cache_layers = l + (L-l)/g (Sec. 3.3: one
  * cache layer per AcrossKV group).  K is stored after RoPE.
- * FP8 mode stores OCP e4m3fn codes; value = code * scales[c][kv][head]. */
+ * FP8 mode stores OCP e4m3fn codes; value = code * scales[c][kv][head], or,
+ * with per-token scales (the granularity of Appendix B.1), code *
+ * scales[c][kv][slot] with slot = block*16 + offset of the token. */
 typedef struct {
   void *data;                  /* dev, bf16 (2 B) or e4m3 (1 B) elements, layout above     */
-  float *scales;               /* dev [n_cache_layers][2][n_kv_heads] fp32; FP8 only       */
+  float *scales;               /* dev fp32, FP8 only: [n_cache_layers][2][n_kv_heads], or
+                                  [n_cache_layers][2][n_blocks*16] with PER_TOKEN          */
   const int32_t *block_tables; /* dev [n_seqs][max_blocks_per_seq] physical block ids      */
   const int32_t *context_lens; /* host [n_seqs] tokens of each sequence already cached     */
   int32_t n_cache_layers, n_blocks, block_size /* must be 16 */, max_blocks_per_seq;
   int32_t dtype;               /* SWIFTKV_KV_BF16 | SWIFTKV_KV_FP8_E4M3                     */
   int32_t scale_mode;          /* FP8: COMPUTE_ABSMAX writes scales = absmax/448 over the
-                                  tokens this call stores; USE_GIVEN reads caller's scales */
+                                  tokens this call stores; USE_GIVEN reads caller's scales;
+                                  PER_TOKEN writes, for every token this call stores, its own
+                                  K and V scale (absmax over all KV heads / 448) and reads
+                                  cached tokens with theirs                                */
 } swiftkv_kv_cache;
 
 typedef struct swiftkv_ctx swiftkv_ctx;

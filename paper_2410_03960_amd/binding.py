@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libswiftkv.so")
 
 SWIFTKV_OK, SWIFTKV_EINVAL, SWIFTKV_ENOSPC, SWIFTKV_EHIP, SWIFTKV_EDATA = 0, -1, -2, -3, -4
 SWIFTKV_KV_BF16, SWIFTKV_KV_FP8_E4M3 = 0, 1
-SWIFTKV_SCALE_COMPUTE_ABSMAX, SWIFTKV_SCALE_USE_GIVEN = 0, 1
+SWIFTKV_SCALE_COMPUTE_ABSMAX, SWIFTKV_SCALE_USE_GIVEN, SWIFTKV_SCALE_PER_TOKEN = 0, 1, 2
 N_TIME_CLASSES = 8
 TIME_CLASS_NAMES = ("qkv_gemm", "o_gemm", "gateup_gemm", "down_gemm", "fused_kv_gemm",
                     "attn_prefill", "other", "tail")
@@ -219,7 +219,9 @@ class KVCache:
         self.fp8 = fp8
         shape = (n_cache_layers, 2, n_blocks * 16, n_kv_heads, head_dim)
         self.data = torch.zeros(shape, dtype=torch.uint8 if fp8 else torch.bfloat16, device=device)
-        self.scales = torch.zeros((n_cache_layers, 2, n_kv_heads), dtype=torch.float32, device=device) if fp8 else None
+        per_token = fp8 and scale_mode == SWIFTKV_SCALE_PER_TOKEN
+        self.scales = torch.zeros((n_cache_layers, 2, n_blocks * 16 if per_token else n_kv_heads), dtype=torch.float32,
+                                  device=device) if fp8 else None
         self.block_tables = block_tables.to(device=device, dtype=torch.int32).contiguous()
         self.context_lens = _i32_array(context_lens)
         self.n_cache_layers, self.n_blocks = n_cache_layers, n_blocks

@@ -256,7 +256,8 @@ int validate_cache(const swiftkv_ctx *c, const swiftkv_kv_cache *kv) {
   if (kv->n_blocks < 1 || kv->max_blocks_per_seq < 1) return fail(SWIFTKV_EINVAL, "empty block pool or table");
   if (kv->dtype != SWIFTKV_KV_BF16 && kv->dtype != SWIFTKV_KV_FP8_E4M3) return fail(SWIFTKV_EINVAL, "bad kv dtype");
   if (kv->dtype == SWIFTKV_KV_FP8_E4M3 && !kv->scales) return fail(SWIFTKV_EINVAL, "FP8 cache needs scales");
-  if (kv->dtype == SWIFTKV_KV_FP8_E4M3 && kv->scale_mode != SWIFTKV_SCALE_COMPUTE_ABSMAX && kv->scale_mode != SWIFTKV_SCALE_USE_GIVEN)
+  if (kv->dtype == SWIFTKV_KV_FP8_E4M3 && kv->scale_mode != SWIFTKV_SCALE_COMPUTE_ABSMAX && kv->scale_mode != SWIFTKV_SCALE_USE_GIVEN &&
+      kv->scale_mode != SWIFTKV_SCALE_PER_TOKEN)
     return fail(SWIFTKV_EINVAL, "bad scale_mode");
   return 0;
 }
@@ -270,11 +271,18 @@ struct Run {
   HostPlan hp;
   hipStream_t st;
   bool fp8;
+  bool per_token;             // FP8 with one scale per cache slot
+  int64_t n_slots;
   size_t esz;                 // cache element bytes
   int64_t plane, layer_stride;  // elements per K (or V) plane / per cache layer
 
   template <class T> T *at(size_t off) const { return (T *)(ws + off); }
   const int32_t *meta(size_t word) const { return at<int32_t>(L.meta) + word; }
+  // scales of cache layer c: [2][Hkv], or [2][n_slots] with per-token scales
+  float *layer_scales(int c_layer) const {
+    return kv->scales + (int64_t)c_layer * 2 * (per_token ? n_slots : (int64_t)c->cfg.n_kv_heads);
+  }
+  int fp8_kind() const { return !fp8 ? 0 : (per_token ? 2 : 1); }
   void *cache_plane(int c_layer, int kvsel) const {
     return (unsigned char *)kv->data + ((int64_t)c_layer * layer_stride + (int64_t)kvsel * plane) * esz;
   }
@@ -332,8 +340,13 @@ int run_fused_kv(Run &r, const bf16_t *hidden, Timer &tm) {
       cp.slots = r.at<int64_t>(r.L.slots); cp.fp8 = 1;
       cp.compute_scale = r.kv->scale_mode == SWIFTKV_SCALE_COMPUTE_ABSMAX;
       cp.amax = r.at<uint32_t>(r.L.amax) + (int64_t)cl * 2 * m.n_kv_heads;
-      cp.scales = r.kv->scales + (int64_t)cl * 2 * m.n_kv_heads;
+      cp.scales = r.layer_scales(cl);
+      cp.per_token = r.per_token; cp.n_slots = r.n_slots;
       cp.vt = nullptr; cp.writeback = 0;
+      if (r.per_token) {
+        TokenScaleParams tp{cp.k_src, cp.v_src, cp.ld_src, (int32_t)r.L.T, kvd, cp.slots, cp.scales, r.n_slots};
+        launch_token_scales(tp, r.st);
+      }
       launch_kv_commit(cp, r.st);
     }
     tm.end();
@@ -568,6 +581,8 @@ static int setup_run(Run &r, swiftkv_ctx *c, const int32_t *seq_lens, int32_t B,
   if (int e = validate_cache(c, kv)) return e;
   r.c = c; r.kv = kv; r.ws = (unsigned char *)workspace; r.st = (hipStream_t)stream;
   r.fp8 = kv->dtype == SWIFTKV_KV_FP8_E4M3;
+  r.per_token = r.fp8 && kv->scale_mode == SWIFTKV_SCALE_PER_TOKEN;
+  r.n_slots = (int64_t)kv->n_blocks * SKV_BLOCK;
   r.esz = r.fp8 ? 1 : 2;
   r.plane = (int64_t)kv->n_blocks * SKV_BLOCK * c->cfg.n_kv_heads * c->cfg.head_dim;
   r.layer_stride = 2 * r.plane;
@@ -656,17 +671,22 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
       cp.fp8 = r.fp8; cp.compute_scale = compute_scale; cp.writeback = r.fp8 && !r.hp.chunked;
       if (r.fp8) {
         cp.amax = r.at<uint32_t>(r.L.amax) + (int64_t)j * 2 * m.n_kv_heads;
-        cp.scales = kv->scales + (int64_t)j * 2 * m.n_kv_heads;
+        cp.scales = r.layer_scales(j);
+        cp.per_token = r.per_token; cp.n_slots = r.n_slots;
       }
       cp.vt = r.hp.chunked ? nullptr : vt; cp.vt_ld = r.L.vt_ld;
       tm.begin(TC_OTHER);
+      if (r.per_token) {
+        TokenScaleParams tp{kb, vb, kvd, T, kvd, cp.slots, cp.scales, r.n_slots};
+        launch_token_scales(tp, st);
+      }
       launch_kv_commit(cp, st);
       if (r.hp.chunked) {   // cached prefix + the rows just committed -> contiguous K rows and V^T columns
         GatherParams gp{};
         gp.tiles = (const GatherTile *)r.meta(r.L.m_gtiles); gp.n_tiles = r.L.n_gtiles;
         gp.n_kv_heads = m.n_kv_heads; gp.head_dim = m.head_dim;
-        gp.cache_k = r.cache_plane(j, 0); gp.cache_v = r.cache_plane(j, 1); gp.fp8 = r.fp8;
-        gp.scales = r.fp8 ? kv->scales + (int64_t)j * 2 * m.n_kv_heads : nullptr;
+        gp.cache_k = r.cache_plane(j, 0); gp.cache_v = r.cache_plane(j, 1); gp.fp8 = r.fp8_kind();
+        gp.scales = r.fp8 ? r.layer_scales(j) : nullptr;
         gp.block_tables = kv->block_tables; gp.max_blocks_per_seq = kv->max_blocks_per_seq; gp.n_blocks = kv->n_blocks;
         gp.k_dst = r.at<bf16_t>(r.L.kcat); gp.vt = vt; gp.vt_ld = r.L.vt_ld;
         launch_kv_gather(gp, st);
@@ -687,8 +707,8 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
       AttnDecodeParams dp{};
       dp.q = qb; dp.out = ob; dp.rows = (const DecodeRow *)r.meta(r.L.m_dec); dp.n_rows = r.L.n_dec;
       dp.n_q_heads = m.n_q_heads; dp.n_kv_heads = m.n_kv_heads; dp.head_dim = m.head_dim;
-      dp.cache_k = r.cache_plane(j, 0); dp.cache_v = r.cache_plane(j, 1); dp.fp8 = r.fp8;
-      if (r.fp8) { dp.scale_k = kv->scales + (int64_t)j * 2 * m.n_kv_heads; dp.scale_v = dp.scale_k + m.n_kv_heads; }
+      dp.cache_k = r.cache_plane(j, 0); dp.cache_v = r.cache_plane(j, 1); dp.fp8 = r.fp8_kind();
+      if (r.fp8) { dp.scale_k = r.layer_scales(j); dp.scale_v = dp.scale_k + (r.per_token ? r.n_slots : (int64_t)m.n_kv_heads); }
       dp.block_tables = kv->block_tables; dp.max_blocks_per_seq = kv->max_blocks_per_seq; dp.n_blocks = kv->n_blocks;
       dp.cos_sin = r.at<float2>(r.L.cos_sin); dp.partial = r.at<float>(r.L.partial);
       dp.n_split = pick_split(r.L.n_dec, m.n_kv_heads, r.hp.max_keys_dec);
@@ -753,8 +773,8 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     AttnDecodeParams dp{};
     dp.q = tq; dp.out = to; dp.rows = (const DecodeRow *)r.meta(r.L.m_tail); dp.n_rows = B;
     dp.n_q_heads = m.n_q_heads; dp.n_kv_heads = m.n_kv_heads; dp.head_dim = m.head_dim;
-    dp.cache_k = r.cache_plane(cl, 0); dp.cache_v = r.cache_plane(cl, 1); dp.fp8 = r.fp8;
-    if (r.fp8) { dp.scale_k = kv->scales + (int64_t)cl * 2 * m.n_kv_heads; dp.scale_v = dp.scale_k + m.n_kv_heads; }
+    dp.cache_k = r.cache_plane(cl, 0); dp.cache_v = r.cache_plane(cl, 1); dp.fp8 = r.fp8_kind();
+    if (r.fp8) { dp.scale_k = r.layer_scales(cl); dp.scale_v = dp.scale_k + (r.per_token ? r.n_slots : (int64_t)m.n_kv_heads); }
     dp.block_tables = kv->block_tables; dp.max_blocks_per_seq = kv->max_blocks_per_seq; dp.n_blocks = kv->n_blocks;
     dp.cos_sin = r.at<float2>(r.L.cos_sin); dp.partial = r.at<float>(r.L.partial);
     dp.n_split = pick_split(B, m.n_kv_heads, r.hp.max_keys_tail);

@@ -401,7 +401,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
   }
-  const float ks = p.fp8 ? p.scale_k[kvh] : 1.f, vs = p.fp8 ? p.scale_v[kvh] : 1.f;
+  const float ks = p.fp8 == 1 ? p.scale_k[kvh] : 1.f, vs = p.fp8 == 1 ? p.scale_v[kvh] : 1.f;   // per-slot scales are read with the keys
   const int32_t *bt = p.block_tables + (int64_t)row.seq * p.max_blocks_per_seq;
 
   // Two key steps per iteration, all four loads first.  The running reference m[r] (log2 units) only
@@ -411,6 +411,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
     float kf[2][8], vf[2][8];
     bool valid[2];
     uint4 kraw[2], vraw[2];
+    float ksl[2] = {ks, ks}, vsl[2] = {vs, vs};
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int key = kb + u * KPS + grp;
@@ -425,6 +426,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
           const uint2 kc = *(const uint2 *)((const uint8_t *)p.cache_k + off);
           const uint2 vc = *(const uint2 *)((const uint8_t *)p.cache_v + off);
           kraw[u].x = kc.x; kraw[u].y = kc.y; vraw[u].x = vc.x; vraw[u].y = vc.y;
+          if (p.fp8 == 2) { ksl[u] = p.scale_k[slot]; vsl[u] = p.scale_v[slot]; }
         } else {
           kraw[u] = *(const uint4 *)((const bf16_t *)p.cache_k + off);
           vraw[u] = *(const uint4 *)((const bf16_t *)p.cache_v + off);
@@ -437,8 +439,8 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
         const uint32_t kw[2] = {kraw[u].x, kraw[u].y}, vw[2] = {vraw[u].x, vraw[u].y};
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          kf[u][e] = e4m3fn_to_f32((uint8_t)(kw[e >> 2] >> ((e & 3) * 8))) * ks;
-          vf[u][e] = e4m3fn_to_f32((uint8_t)(vw[e >> 2] >> ((e & 3) * 8))) * vs;
+          kf[u][e] = e4m3fn_to_f32((uint8_t)(kw[e >> 2] >> ((e & 3) * 8))) * ksl[u];
+          vf[u][e] = e4m3fn_to_f32((uint8_t)(vw[e >> 2] >> ((e & 3) * 8))) * vsl[u];
         }
       } else {
         const uint32_t kw[4] = {kraw[u].x, kraw[u].y, kraw[u].z, kraw[u].w}, vw[4] = {vraw[u].x, vraw[u].y, vraw[u].z, vraw[u].w};

@@ -170,8 +170,8 @@ struct AttnDecodeParams {
   const DecodeRow *rows;
   int32_t n_rows, n_q_heads, n_kv_heads, head_dim;
   const void *cache_k, *cache_v;  // this cache layer's K and V planes [n_blocks*16][Hkv][hd]
-  int32_t fp8;
-  const float *scale_k, *scale_v;  // [Hkv] (fp8)
+  int32_t fp8;                     // 0 = bf16, 1 = e4m3 with per-head scales, 2 = e4m3 with per-slot scales
+  const float *scale_k, *scale_v;  // [Hkv] (fp8 = 1) or [n_blocks*16] (fp8 = 2)
   const int32_t *block_tables;
   int32_t max_blocks_per_seq, n_blocks;
   const float2 *cos_sin;  // [T][hd/2]
@@ -218,12 +218,26 @@ struct CommitParams {
   void *cache_k, *cache_v;  // planes of the destination cache layer
   const int64_t *slots;
   int32_t fp8, compute_scale, writeback;
+  int32_t per_token;     // fp8 with one scale per cache slot: scales is [2][n_slots], set beforehand by the token-scale kernel
+  int64_t n_slots;
   const uint32_t *amax;  // [2][Hkv] absmax bits of this cache layer (fp8 compute mode)
-  float *scales;         // [2][Hkv] of this cache layer (fp8)
+  float *scales;         // [2][Hkv] of this cache layer (fp8), or [2][n_slots]
   bf16_t *vt;            // [kv_dim, vt_ld] or null
   int64_t vt_ld;
 };
 int launch_kv_commit(const CommitParams &p, hipStream_t st);
+
+// FP8 cache with per-token scales (Appendix B.1): scale of a token = absmax of its K (V) row over all
+// KV heads / 448, stored at the token's cache slot.
+struct TokenScaleParams {
+  const bf16_t *k_src, *v_src;   // row-major [T, ld_src]
+  int64_t ld_src;
+  int32_t T, kv_dim;
+  const int64_t *slots;
+  float *scales;                 // [2][n_slots] of this cache layer
+  int64_t n_slots;
+};
+int launch_token_scales(const TokenScaleParams &p, hipStream_t st);
 
 // Prompt chunks over a cached prefix: the prefill attention reads contiguous K rows and V^T columns,
 // so positions 0 .. context+new-1 of such sequences are copied out of the paged cache first.
@@ -239,8 +253,8 @@ struct GatherParams {
   const GatherTile *tiles;
   int32_t n_tiles, n_kv_heads, head_dim;
   const void *cache_k, *cache_v;   // planes of the cache layer [n_blocks*16][Hkv][hd], bf16 or e4m3 codes
-  int32_t fp8;
-  const float *scales;             // [2][Hkv] of this cache layer (fp8)
+  int32_t fp8;                     // 0 = bf16, 1 = e4m3 with per-head scales, 2 = e4m3 with per-slot scales
+  const float *scales;             // [2][Hkv] of this cache layer (fp8 = 1) or [2][n_blocks*16] (fp8 = 2)
   const int32_t *block_tables;
   int32_t max_blocks_per_seq, n_blocks;
   bf16_t *k_dst;                   // [rows, kv_dim]

@@ -241,7 +241,7 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(CommitParams p) {
   const int head = blockIdx.y;
   const int tid = threadIdx.x;
   float sk = 1.f, svs = 1.f, isk = 1.f, isv = 1.f;
-  if (p.fp8) {
+  if (p.fp8 && !p.per_token) {
     if (p.compute_scale) {
       sk = fmaxf(__uint_as_float(p.amax[head]), 1e-12f) / 448.0f;
       svs = fmaxf(__uint_as_float(p.amax[p.n_kv_heads + head]), 1e-12f) / 448.0f;
@@ -266,6 +266,7 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(CommitParams p) {
       kq = *(const uint4 *)kp;
       vq = *(const uint4 *)vp;
       int64_t dst = p.cache_k ? (p.slots[row] * p.n_kv_heads + head) * HD + c * 8 : 0;
+      if (p.per_token) { sk = p.scales[p.slots[row]]; svs = p.scales[p.n_slots + p.slots[row]]; }
       if (!p.cache_k) {
         // no cache wanted (stand-alone attention): only V^T is produced
       } else if (!p.fp8) {
@@ -322,6 +323,36 @@ int launch_kv_commit(const CommitParams &p, hipStream_t st) {
   return 0;
 }
 
+// -------------------------------------------------------- token scales -----
+// One wave per token: absmax of its K row and of its V row (bf16 values as they will be stored),
+// scale = max(absmax, 1e-12) / 448 written at the token's cache slot.
+__global__ __launch_bounds__(256) void token_scale_kernel(TokenScaleParams p) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= p.T) return;
+  float ak = 0.f, av = 0.f;
+  for (int c = lane; c < p.kv_dim / 8; c += 64) {
+    const uint4 k = *(const uint4 *)(p.k_src + (int64_t)row * p.ld_src + c * 8);
+    const uint4 v = *(const uint4 *)(p.v_src + (int64_t)row * p.ld_src + c * 8);
+    const uint32_t kw[4] = {k.x, k.y, k.z, k.w}, vw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      ak = fmaxf(ak, fmaxf(fabsf(bf16lo(kw[e])), fabsf(bf16hi(kw[e]))));
+      av = fmaxf(av, fmaxf(fabsf(bf16lo(vw[e])), fabsf(bf16hi(vw[e]))));
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) { ak = fmaxf(ak, __shfl_xor(ak, o)); av = fmaxf(av, __shfl_xor(av, o)); }
+  if (lane == 0) {
+    const int64_t slot = p.slots[row];
+    p.scales[slot] = fmaxf(ak, 1e-12f) / 448.0f;
+    p.scales[p.n_slots + slot] = fmaxf(av, 1e-12f) / 448.0f;
+  }
+}
+int launch_token_scales(const TokenScaleParams &p, hipStream_t st) {
+  if (p.T <= 0) return 0;
+  hipLaunchKernelGGL(token_scale_kernel, dim3((p.T + 3) / 4), dim3(256), 0, st, p);
+  return 0;
+}
+
 // ----------------------------------------------------------- QKV finish ----
 // grid (T, Hq + 2*Hkv), hd/2 threads: thread i owns the rotary pair (i, i + hd/2) of one head of one row.
 __global__ void qkv_finish_kernel(QkvFinishParams p) {
@@ -367,7 +398,7 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(GatherParams p) {
   const int tid = threadIdx.x;
   const int kv_dim = p.n_kv_heads * HD;
   float sk = 1.f, svs = 1.f;
-  if (p.fp8) { sk = p.scales[head]; svs = p.scales[p.n_kv_heads + head]; }
+  if (p.fp8 == 1) { sk = p.scales[head]; svs = p.scales[p.n_kv_heads + head]; }
   for (int i = tid; i < 64 * CH; i += 256) {
     const int r = i / CH, c = i % CH;
     uint4 kq = make_uint4(0, 0, 0, 0), vq = make_uint4(0, 0, 0, 0);
@@ -375,7 +406,9 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(GatherParams p) {
       const int pos = tile.pos0 + r;
       int blk = p.block_tables[(int64_t)tile.seq * p.max_blocks_per_seq + pos / SKV_BLOCK];
       blk = blk < 0 ? 0 : (blk >= p.n_blocks ? p.n_blocks - 1 : blk);   // bad ids were reported by the plan; stay inside the pool
-      const int64_t src = (((int64_t)blk * SKV_BLOCK + pos % SKV_BLOCK) * p.n_kv_heads + head) * HD + c * 8;
+      const int64_t slot = (int64_t)blk * SKV_BLOCK + pos % SKV_BLOCK;
+      const int64_t src = (slot * p.n_kv_heads + head) * HD + c * 8;
+      if (p.fp8 == 2) { sk = p.scales[slot]; svs = p.scales[(int64_t)p.n_blocks * SKV_BLOCK + slot]; }
       if (!p.fp8) {
         kq = *(const uint4 *)((const bf16_t *)p.cache_k + src);
         vq = *(const uint4 *)((const bf16_t *)p.cache_v + src);

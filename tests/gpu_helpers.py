@@ -38,11 +38,11 @@ def run_gpu(ctx, batch, fp8=False, scale_mode=0, cache=None, stream=None):
 
 
 def run_oracle(shape, store, batch, l, g, dtype=torch.float64, fp8=False, compute_scales=True,
-               cache=None, seq_subset=None):
+               cache=None, seq_subset=None, per_token=False):
     C = O.n_cache_layers(shape.n_layers, l, g)
     if cache is None:
         cache = O.PagedKVCache(C, batch.n_blocks, shape.n_kv_heads, shape.head_dim, batch.block_tables,
-                               dtype=dtype, fp8=fp8)
+                               dtype=dtype, fp8=fp8, per_token=per_token)
     logits, hl = O.swiftkv_prefill(oracle_shape(shape), weight_fn(store), batch.token_ids,
                                    batch.seq_lens.tolist(), batch.context_lens.tolist(), l, g, cache,
                                    dtype=dtype, fp8_compute_scales=compute_scales, seq_subset=seq_subset)
@@ -54,6 +54,8 @@ def gpu_cache_logical(cache, c, kvsel, slots):
     raw = cache.data[c, kvsel][slots.to(cache.data.device)]
     if cache.fp8:
         tab = O.fp8_e4m3fn_decode_table().float().to(raw.device)
+        if cache.scales.shape[-1] == cache.data.shape[2]:       # one scale per slot
+            return tab[raw.long()] * cache.scales[c, kvsel][slots.to(raw.device)][:, None, None]
         return tab[raw.long()] * cache.scales[c, kvsel][None, :, None]
     return raw.float()
 
