@@ -31,6 +31,8 @@ def main():
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-launch HIP events (roofline is then null)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=256)
+    ap.add_argument("--kv-scales", choices=("per_head", "per_token"), default="per_head",
+                    help="FP8-cache workloads: one scale per (cache layer, K|V, KV head) or one per token")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first copy 1 GiB device-to-device (a plain copy of known size, to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -63,13 +65,15 @@ def main():
     T, nseq = batch.n_tokens, batch.n_seqs
     ctx = B.Context(sh, dev_w, wl.l, wl.g)
     kvd = B.SWIFTKV_KV_FP8_E4M3 if wl.kv_fp8 else B.SWIFTKV_KV_BF16
-    scale_mode = B.SWIFTKV_SCALE_COMPUTE_ABSMAX
+    per_token = wl.kv_fp8 and args.kv_scales == "per_token"
+    scale_mode = B.SWIFTKV_SCALE_PER_TOKEN if per_token else B.SWIFTKV_SCALE_COMPUTE_ABSMAX
     cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, sh.n_kv_heads, sh.head_dim, batch.block_tables,
                       batch.context_lens.tolist(), fp8=wl.kv_fp8, scale_mode=scale_mode)
     has_ctx = bool((batch.context_lens > 0).any())
     if wl.kv_fp8 and has_ctx:
         # pre-existing contexts: seeded codes under fixed scales
-        cache.scale_mode = B.SWIFTKV_SCALE_USE_GIVEN
+        if not per_token:
+            cache.scale_mode = B.SWIFTKV_SCALE_USE_GIVEN
         cache.scales.fill_(0.02)
         cache.data.random_(0, 0x77, generator=torch.Generator(device="cuda").manual_seed(wl.seed))
     elif has_ctx:
@@ -104,7 +108,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "n_seqs": nseq, "n_tokens": T, "l": wl.l, "acrosskv_group": wl.g,
-                   "kv_cache": "fp8_e4m3" if wl.kv_fp8 else "bf16", "n_layers": sh.n_layers,
+                   "kv_cache": ("fp8_e4m3/" + args.kv_scales) if wl.kv_fp8 else "bf16", "n_layers": sh.n_layers,
                    "hidden": sh.hidden},
         "executed_tflops": (gemm_fl + attn_fl) / (ms_per_step * 1e-3) / 1e12,
         "executed_frac_of_bf16_peak": (gemm_fl + attn_fl) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
