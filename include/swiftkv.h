@@ -110,8 +110,10 @@ typedef struct swiftkv_ctx swiftkv_ctx;
  * allocation of (L-l)/g * 2*n_kv_heads*head_dim * hidden bf16 elements, plus a
  * few MB of tables).  When hidden, n_q_heads*head_dim and ffn are multiples of
  * 256 it also copies [W_Q;W_K;W_V], W_O, [W_gate;W_up] and W_down of layers
- * 1..l and the fused KV operand into the register-fragment order of the matrix
- * instructions (about l * (2*hidden*q_dim + 2*hidden*kv_dim + 3*hidden*ffn) bf16
+ * 1..l (the first and third with the gain of the RMSNorm in front of them
+ * folded in, so that the normalisation reduces to a per-row factor applied in
+ * the GEMM epilogue) and the fused KV operand into the register-fragment order
+ * of the matrix instructions (about l * (2*hidden*q_dim + 2*hidden*kv_dim + 3*hidden*ffn) bf16
  * elements: 7.3 GB for the 8B shape at l = 16, 70 GB for the 70B shape at
  * l = 40), which lets those GEMMs load weights without passing
  * them through LDS; the environment variable SWIFTKV_PACKED_W=0 skips the copies

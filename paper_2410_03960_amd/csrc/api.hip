@@ -487,15 +487,15 @@ int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftk
     const int rope_hd = m.head_dim == 128 ? 128 : 0;   // rotary partner blocks side by side (see pack_w_kernel)
     for (int j = 0; j < l; ++j) {
       bf16_t *pq = c->w_pack + (size_t)j * per_layer, *po = pq + e_qkv, *pgu = po + e_o, *pdn = pgu + e_gu;
-      launch_pack_w(c->qkv_tab[j], nullptr, d, qd + 2 * kvd, (int32_t)d, rope_hd, pq, nullptr);
-      launch_pack_w(nullptr, c->wo[j], qd, (int32_t)d, qd, 0, po, nullptr);
-      launch_pack_w(c->gu_tab[j], nullptr, d, 2 * m.ffn, (int32_t)d, 0, pgu, nullptr);
-      launch_pack_w(nullptr, c->wdown[j], m.ffn, (int32_t)d, m.ffn, 0, pdn, nullptr);
+      launch_pack_w(c->qkv_tab[j], nullptr, d, qd + 2 * kvd, (int32_t)d, rope_hd, c->norm1[j], pq, nullptr);   // input-norm gain folded in
+      launch_pack_w(nullptr, c->wo[j], qd, (int32_t)d, qd, 0, nullptr, po, nullptr);
+      launch_pack_w(c->gu_tab[j], nullptr, d, 2 * m.ffn, (int32_t)d, 0, c->norm2[j], pgu, nullptr);   // post-attention-norm gain folded in
+      launch_pack_w(nullptr, c->wdown[j], m.ffn, (int32_t)d, m.ffn, 0, nullptr, pdn, nullptr);
       c->qkv_pack[j] = pq; c->wo_pack[j] = po; c->gu_pack[j] = pgu; c->down_pack[j] = pdn;
     }
     if (c->P > 0 && ((c->P * 2 * kvd) % 256) == 0) {
       bf16_t *pk = c->w_pack + per_layer * l;
-      launch_pack_w(nullptr, c->kv_pack, d, c->P * 2 * kvd, (int32_t)d, rope_hd, pk, nullptr);
+      launch_pack_w(nullptr, c->kv_pack, d, c->P * 2 * kvd, (int32_t)d, rope_hd, nullptr, pk, nullptr);
       c->kvf_pack = pk;
     }
     e = hipDeviceSynchronize();
@@ -628,9 +628,20 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   float *skp = r.at<float>(r.L.skpart);
 
   // ------------------------------------------ layers 1..l on every new token ----
+  // The fragment-order copies of [Wq;Wk;Wv] and [Wgate;Wup] carry the gain of the RMSNorm in front of
+  // them.  When a GEMM reads that copy, its A operand is the residual stream itself and 1/rms of each
+  // row (one read-only pass) is applied in the epilogue; otherwise the rows are normalised first.
+  auto uses_packed = [&](const bf16_t *wpack, int N) {
+    GemmParams t{};
+    t.wpack = wpack; t.M = T; t.K = d; t.N = N;
+    return !few_rows && gemm_uses_packed_weights(t);
+  };
+  float *rstd = r.at<float>(r.L.rstd);
   for (int j = 0; j < c->l; ++j) {
+    const bool fold1 = uses_packed(c->qkv_pack[j], qd + 2 * kvd), fold2 = uses_packed(c->gu_pack[j], 2 * m.ffn);
     tm.begin(TC_OTHER);
-    launch_rmsnorm_rows(h, c->norm1[j], ab, T, d, m.rms_eps, st);
+    if (fold1) launch_rstd(h, rstd, T, d, m.rms_eps, st);
+    else launch_rmsnorm_rows(h, c->norm1[j], ab, T, d, m.rms_eps, st);
     tm.end();
     if (few_rows) {
       // decode steps and other few-token batches: weights stream once through the skinny kernel (fp32 out),
@@ -650,8 +661,8 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
       tm.end();
     } else {
       GemmParams g{};
-      g.A = ab; g.lda = d; g.M = T; g.N = qd + 2 * kvd; g.K = d;
-      g.wtab = c->qkv_tab[j]; g.ldw = d; g.wpack = c->qkv_pack[j];
+      g.A = fold1 ? h : ab; g.lda = d; g.M = T; g.N = qd + 2 * kvd; g.K = d;
+      g.wtab = c->qkv_tab[j]; g.ldw = d; g.wpack = fold1 ? c->qkv_pack[j] : nullptr; g.rstd = fold1 ? rstd : nullptr;
       g.cos_sin = r.at<float2>(r.L.cos_sin);
       g.head_dim = m.head_dim; g.q_dim = qd; g.kv_dim = kvd;
       g.q_out = qb; g.k_out = kb; g.v_out = vb;
@@ -729,7 +740,8 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
       tm.end();
     }
     tm.begin(TC_OTHER);
-    launch_rmsnorm_rows(h, c->norm2[j], ab, T, d, m.rms_eps, st);
+    if (fold2) launch_rstd(h, rstd, T, d, m.rms_eps, st);
+    else launch_rmsnorm_rows(h, c->norm2[j], ab, T, d, m.rms_eps, st);
     tm.end();
     if (few_rows) {
       tm.begin(TC_GATEUP);
@@ -741,7 +753,8 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     } else {
       {
         GemmParams g{};
-        g.A = ab; g.lda = d; g.M = T; g.N = 2 * m.ffn; g.K = d; g.wtab = c->gu_tab[j]; g.ldw = d; g.wpack = c->gu_pack[j];
+        g.A = fold2 ? h : ab; g.lda = d; g.M = T; g.N = 2 * m.ffn; g.K = d; g.wtab = c->gu_tab[j]; g.ldw = d;
+        g.wpack = fold2 ? c->gu_pack[j] : nullptr; g.rstd = fold2 ? rstd : nullptr;
         g.C = zb; g.ldc = m.ffn;
         tm.begin(TC_GATEUP);
         if (launch_gemm(g, EPI_SWIGLU, 0, st) != 0) return fail(SWIFTKV_EHIP, "gate/up GEMM launch failed");
@@ -855,7 +868,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
       HIP_TRY(hipMalloc((void **)&pack, need * 2));
       pack_elems = need;
     }
-    if (pack_src != W || !getenv("SWIFTKV_XP_KEEP_PACK")) launch_pack_w(nullptr, (const bf16_t *)W, K, N, K, 0, pack, st);   // (the variable skips repacking an unchanged pointer, for timing)
+    if (pack_src != W || !getenv("SWIFTKV_XP_KEEP_PACK")) launch_pack_w(nullptr, (const bf16_t *)W, K, N, K, 0, nullptr, pack, st);   // (the variable skips repacking an unchanged pointer, for timing)
     pack_src = W;
     g.wpack = pack;
   }

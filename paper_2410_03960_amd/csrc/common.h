@@ -109,6 +109,7 @@ struct GemmParams {
 };
 
 int launch_gemm(const GemmParams &p, int epi, int variant, hipStream_t st);
+bool gemm_uses_packed_weights(const GemmParams &p);
 
 // skinny (weight-streaming) GEMM for M <= 80 rows
 struct SkinnyParams {
@@ -201,7 +202,7 @@ int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t st);
 // out[((n/32) * (K/16) + k/16) * 512 + ((k%16)/8 * 32 + n%32) * 8 + k%8] = W row n (through the optional
 // 16-row block pointer table), element k.  N % 32 == 0, K % 16 == 0.  rope_hd == 128 (N % 128 == 0) takes the
 // 32-row blocks of every 128 rows in the order 0, 2, 1, 3 (rotary partners side by side in a 64-row wave tile).
-int launch_pack_w(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, bf16_t *out, hipStream_t st);
+int launch_pack_w(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, const bf16_t *gain, bf16_t *out, hipStream_t st);
 int launch_fold_gain(const bf16_t *W, const bf16_t *gain, bf16_t *out, int64_t rows, int32_t K, hipStream_t st);
 
 struct KVTile {  // 64 consecutive new tokens of one sequence

@@ -199,7 +199,7 @@ __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n) {
 // rope_hd == 128: inside every group of 128 rows (one head) the 32-row blocks are taken in the order
 // 0, 2, 1, 3, so that a 64-row wave tile holds a block of the first half of the head next to its
 // rotary partner block of the second half.
-__global__ void pack_w_kernel(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, uint4 *out) {
+__global__ void pack_w_kernel(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, const bf16_t *gain, uint4 *out) {
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t n_chunks = (int64_t)N * K / 8;
   if (id >= n_chunks) return;
@@ -213,12 +213,20 @@ __global__ void pack_w_kernel(const bf16_t *const *wtab, const bf16_t *W, int64_
   }
   const int n = block * 32 + (lane & 31), k = k16 * 16 + (lane >> 5) * 8;
   const bf16_t *row = wtab ? wtab[n >> 4] + (int64_t)(n & 15) * ldw : W + (int64_t)n * ldw;
-  out[id] = *(const uint4 *)(row + k);
+  uint4 u = *(const uint4 *)(row + k);
+  if (gain) {   // fold a per-input-column gain (the RMSNorm weight in front of this projection) into the copy
+    const uint4 g = *(const uint4 *)(gain + k);
+    u.x = pack_bf16x2(bf16lo(u.x) * bf16lo(g.x), bf16hi(u.x) * bf16hi(g.x));
+    u.y = pack_bf16x2(bf16lo(u.y) * bf16lo(g.y), bf16hi(u.y) * bf16hi(g.y));
+    u.z = pack_bf16x2(bf16lo(u.z) * bf16lo(g.z), bf16hi(u.z) * bf16hi(g.z));
+    u.w = pack_bf16x2(bf16lo(u.w) * bf16lo(g.w), bf16hi(u.w) * bf16hi(g.w));
+  }
+  out[id] = u;
 }
-int launch_pack_w(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, bf16_t *out, hipStream_t st) {
+int launch_pack_w(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, const bf16_t *gain, bf16_t *out, hipStream_t st) {
   const int64_t n_chunks = (int64_t)N * K / 8;
   if (n_chunks <= 0) return 0;
-  hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, wtab, W, ldw, N, K, rope_hd, (uint4 *)out);
+  hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, wtab, W, ldw, N, K, rope_hd, gain, (uint4 *)out);
   return 0;
 }
 int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t st) {

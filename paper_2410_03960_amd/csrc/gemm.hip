@@ -1092,11 +1092,18 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
     const int blk_stride = hd == 128 ? 64 : 32;        // real columns between block 0 and block 1
     constexpr int RS = 64 * 2 + 16;
     float amax_h = 0.f;
+    // 1/rms of this lane's rows, all requested before the first use (one latency, not one per 32 rows)
+    float rsv[FM];
+#pragma unroll
+    for (int bm = 0; bm < FM; ++bm) {
+      const int m = m_base + bm * 32 + l32;
+      rsv[bm] = p.rstd ? p.rstd[m < p.M ? m : p.M - 1] : 1.f;
+    }
 #pragma unroll
     for (int bm = 0; bm < FM; ++bm) {
       const int m = m_base + bm * 32 + l32;
       const int mc = m < p.M ? m : p.M - 1;
-      const float rs = p.rstd ? p.rstd[mc] : 1.f;
+      const float rs = rsv[bm];
       unsigned char *srow = slab + l32 * RS;
       const float2 *cs = p.cos_sin + (int64_t)mc * (hd / 2) + s * 32;
 #pragma unroll
@@ -1153,12 +1160,19 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
     constexpr int NC = (EPI == EPI_SWIGLU) ? 32 : 64;   // output columns of the wave tile
     constexpr int RS = NC * 2 + 16;                      // bf16 row stride in bytes
     constexpr int CPR = NC / 8, RPI = 64 / CPR;          // 16-byte chunks per row, rows per store instruction
+    float rsv[FM];
+    if constexpr (EPI == EPI_SWIGLU) {   // 1/rms of this lane's rows, all requested before the first use
+#pragma unroll
+      for (int bm = 0; bm < FM; ++bm) {
+        const int m = m_base + bm * 32 + l32;
+        rsv[bm] = p.rstd ? p.rstd[m < p.M ? m : p.M - 1] : 1.f;
+      }
+    }
 #pragma unroll
     for (int bm = 0; bm < FM; ++bm) {
       unsigned char *srow = slab + l32 * RS;
       if constexpr (EPI == EPI_SWIGLU) {
-        const int m = m_base + bm * 32 + l32;
-        const float rs = p.rstd ? p.rstd[m < p.M ? m : p.M - 1] : 1.f;
+        const float rs = rsv[bm];
 #pragma unroll
         for (int bn = 0; bn < 2; ++bn)
 #pragma unroll
@@ -1381,6 +1395,12 @@ int launch_epi(const GemmParams &p, int variant, hipStream_t st) {
 }
 
 }  // namespace
+
+// Whether launch_gemm(p, epi, 0, ...) reads the fragment-order copy p.wpack (and not p.W / p.wtab): the
+// driver needs to know, because that copy of a projection behind an RMSNorm has the norm's gain folded in.
+bool gemm_uses_packed_weights(const GemmParams &p) {
+  return p.wpack && !p.gain_tab && p.M >= 1024 && (p.K % 256) == 0 && (p.N % 256) == 0;
+}
 
 int launch_gemm(const GemmParams &p_in, int epi, int variant, hipStream_t st) {
   if (p_in.M <= 0 || p_in.N <= 0 || p_in.K <= 0) return 0;
