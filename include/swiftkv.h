@@ -189,7 +189,7 @@ int swiftkv_export_hidden(swiftkv_ctx *ctx, const void *workspace, void *hidden_
  * with correct results), 27 = the loop that takes the weights in MFMA
  * fragment order straight into registers (M >= 1024, N, K multiples of 256,
  * bf16 output; W is repacked into a library-owned buffer on every call unless
- * SWIFTKV_XP_KEEP_PACK is set and the pointer is unchanged).  6..13, 16..19, 26, 30 and 31 are timing experiments whose
+ * SWIFTKV_XP_KEEP_PACK is set and the pointer is unchanged).  6..13, 16..19, 26 and 30..33 are timing experiments whose
  * results are not meaningful (10..13, 16 and 26 also need room behind C for
  * counters).
  * All dev. */

@@ -838,7 +838,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
                     int32_t variant, void *stream) {
   if (!A || !W || !C) return fail(SWIFTKV_EINVAL, "null argument");
   if (M < 1 || N < 16 || K < 8 || (N % 16) || (K % 8)) return fail(SWIFTKV_EINVAL, "need M >= 1, N %% 16 == 0, K %% 8 == 0");
-  if (variant < 0 || variant > 31) return fail(SWIFTKV_EINVAL, "variant must be 0..31");
+  if (variant < 0 || variant > 33) return fail(SWIFTKV_EINVAL, "variant must be 0..33");
   hipStream_t st = (hipStream_t)stream;
   if (variant == 3 || variant == 29) {   // 29: with the scratch that lets the kernel split K (library-owned, allocated once)
     if (M > 80) return fail(SWIFTKV_EINVAL, "weight-streaming kernel handles M <= 80");
@@ -854,7 +854,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
   if (variant == 7) { g.dbg = 2; variant = 4; }
   if (variant == 8) { g.dbg = 6; variant = 5; }
   if (variant == 9) { g.dbg = 7; variant = 5; }
-  if (variant == 30 || variant == 31) { g.dbg = variant + 1; variant = 27; }   // 30 / 31: as 27 without the loop's weight / activation requests (timing only)
+  if (variant >= 30 && variant <= 33) { g.dbg = variant + 1; variant = 27; }   // 30..33: as 27 without the loop's weight requests / activation requests / LDS fragment reads / barrier (timing only)
   const bool wreg_prof = variant == 28;   // 28: as 27 with cycle counters behind C (see 10..13)
   if (wreg_prof) { variant = 27; g.dbg = 8; g.stage = (bf16_t *)C + (int64_t)M * N; }
   if (variant == 27) {   // weights repacked into fragment order (library-owned buffer), then the loop that keeps them out of LDS

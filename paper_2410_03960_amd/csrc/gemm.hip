@@ -1207,7 +1207,7 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
   }
 }
 
-template <int EPI, bool PROF = false, int XP = 0>   // PROF: cycle counters written through p.stage; XP 1 / 2: the loop without its weight / activation requests (timing experiments, results meaningless)
+template <int EPI, bool PROF = false, int XP = 0>   // PROF: cycle counters written through p.stage; XP 1 / 2 / 3 / 4: the loop without its weight requests / activation requests / LDS fragment reads / barrier (timing experiments, results meaningless)
 __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
   constexpr int BM = 256, BN = 256, FM = 8;
   constexpr int NSA = 5, STAGE = BM * 128;   // activation stages: 256 rows x 128 bytes (one 64-wide k step)
@@ -1312,7 +1312,7 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
         if constexpr (PROF) { __builtin_amdgcn_s_waitcnt(0xC07F); tp0 = clock64(); }
         __builtin_amdgcn_s_waitcnt(0x0F7E);   // vmcnt(14)
         if constexpr (PROF) tp1 = clock64();
-        __builtin_amdgcn_s_barrier();
+        if constexpr (XP != 4) __builtin_amdgcn_s_barrier();
         if constexpr (PROF) { t_vm += tp1 - tp0; t_bar += clock64() - tp1; }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -1321,7 +1321,7 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
         const int nb = i / 8, bm = i % 8;
         acc[nb][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][kk * 2 + nb], af[kk & 1][bm], acc[nb][bm], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (i < 8) af[(kk + 1) & 1][i] = *(const bf16x8 *)((kk < 3 ? st : stn) + (a_lane ^ (unsigned)(((kk + 1) & 3) * 32)) + i * 4096);
+        if (i < 8 && (XP != 3 || it == 0)) af[(kk + 1) & 1][i] = *(const bf16x8 *)((kk < 3 ? st : stn) + (a_lane ^ (unsigned)(((kk + 1) & 3) * 32)) + i * 4096);
         if (i % 8 == 3 && XP != 2) issue_a(kk * 2 + i / 8, sld, kl);
         if (i % 8 == 7 && XP != 1) load_w(wf[lslot][kk * 2 + i / 8], i / 8, kk, kl);
         __builtin_amdgcn_sched_barrier(0);
@@ -1360,8 +1360,9 @@ int launch_wreg(const GemmParams &p, hipStream_t st) {
       hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(256), SMEM, st, p);
       return 0;
     }
-    if (p.dbg == 31 || p.dbg == 32) {   // timing experiments: the loop without its weight / activation requests
-      auto kp = p.dbg == 31 ? gemm_wreg_kernel<EPI, false, 1> : gemm_wreg_kernel<EPI, false, 2>;
+    if (p.dbg >= 31 && p.dbg <= 34) {   // timing experiments: the loop without its weight requests / activation requests / LDS fragment reads / barrier
+      auto kp = p.dbg == 31 ? gemm_wreg_kernel<EPI, false, 1> : p.dbg == 32 ? gemm_wreg_kernel<EPI, false, 2>
+              : p.dbg == 33 ? gemm_wreg_kernel<EPI, false, 3> : gemm_wreg_kernel<EPI, false, 4>;
       (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
       const int tl = ((p.M + 255) / 256) * (p.N / 256);
       hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(256), SMEM, st, p);
