@@ -407,18 +407,32 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
   // Two key steps per iteration, all four loads first.  The running reference m[r] (log2 units) only
   // moves when a score exceeds it by more than 8, so most keys cost one exponential and no rescale of
   // the accumulators; numerator and denominator share the reference, the result is unchanged.
+  // The block ids of the next iteration's keys are looked up one iteration ahead, so that a K/V load
+  // does not wait for a table lookup first (keys past the end read the entry of the last key).
+  int blk_nxt[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int key = k_lo + wave * KPW + u * KPS + grp;
+    blk_nxt[u] = k_hi > 0 ? bt[(key < k_hi ? key : k_hi - 1) / SKV_BLOCK] : 0;
+  }
   for (int kb = k_lo + wave * KPW; kb < k_hi; kb += 2 * KPS) {
     float kf[2][8], vf[2][8];
     bool valid[2];
     uint4 kraw[2], vraw[2];
     float ksl[2] = {ks, ks}, vsl[2] = {vs, vs};
+    const int blk_cur[2] = {blk_nxt[0], blk_nxt[1]};
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int key = kb + 2 * KPS + u * KPS + grp;
+      blk_nxt[u] = bt[(key < k_hi ? key : k_hi - 1) / SKV_BLOCK];
+    }
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int key = kb + u * KPS + grp;
       valid[u] = key < k_hi;
       kraw[u] = make_uint4(0, 0, 0, 0); vraw[u] = make_uint4(0, 0, 0, 0);
       if (valid[u]) {
-        int blk = bt[key / SKV_BLOCK];
+        int blk = blk_cur[u];
         blk = ((unsigned)blk < (unsigned)p.n_blocks) ? blk : 0;   // bad ids are flagged by the plan kernel; never dereference them
         const int64_t slot = (int64_t)blk * SKV_BLOCK + key % SKV_BLOCK;
         const int64_t off = (slot * p.n_kv_heads + kvh) * HD + sub * 8;
