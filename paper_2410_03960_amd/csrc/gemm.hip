@@ -1092,6 +1092,25 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
     const int blk_stride = hd == 128 ? 64 : 32;        // real columns between block 0 and block 1
     constexpr int RS = 64 * 2 + 16;
     float amax_h = 0.f;
+    // Destination of this wave's columns, selected once (uniform over the wave): base pointer of the
+    // head's first column and the row stride in elements; rows of the paged cache go through p.slots.
+    // (Selecting per store, through a table indexed by `kind`, cost a private-memory lookup, a full
+    // vmcnt wait and a flat store for each of the 32 stores of a wave tile.)
+    bf16_t *obase;
+    int64_t ostride;
+    bool paged = false;
+    if constexpr (EPI == EPI_QKV) {
+      obase = p.q_out; ostride = p.q_dim;
+      if (kind == 1) { obase = p.k_out; ostride = p.kv_dim; }
+      if (kind == 2) { obase = p.v_out; ostride = p.kv_dim; }
+    } else {
+      obase = p.stage + (int64_t)proj * 2 * p.kv_dim + (kind == 2 ? p.kv_dim : 0); ostride = p.N;
+      if (!p.stage) {
+        obase = p.cache + (int64_t)(p.first_cache_layer + proj) * p.cache_layer_stride + (kind == 2 ? p.cache_kv_stride : 0);
+        ostride = p.kv_dim; paged = true;
+      }
+    }
+    obase += col0 + s * 32;
     // 1/rms of this lane's rows, all requested before the first use (one latency, not one per 32 rows)
     float rsv[FM];
 #pragma unroll
@@ -1099,20 +1118,46 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
       const int m = m_base + bm * 32 + l32;
       rsv[bm] = p.rstd ? p.rstd[m < p.M ? m : p.M - 1] : 1.f;
     }
+    // Two passes, so that no load follows a store: loads and stores share one counter, and with both
+    // kinds pending every wait for a load becomes a wait for everything, stores included (which made
+    // each 32-row block of the epilogue wait for the previous block's stores to reach memory).
+    // Pass 1: per 32-row block the cos/sin pieces (requested one block ahead) and, for the paged cache,
+    // the rows' slots; rotation, rounding, bf16 rows into the wave's LDS slab (FM blocks of 32 rows).
+    // Pass 2: the slab leaves as 16-byte stores in which consecutive lanes cover a contiguous row piece.
+    constexpr int SLAB_BM = 32 * RS;   // bytes per 32-row block
+    float4 csb[2][8];
+    auto load_cs = [&](int bm) {
+      const int m = m_base + bm * 32 + l32;
+      const float2 *cs = p.cos_sin + (int64_t)(m < p.M ? m : p.M - 1) * (hd / 2) + s * 32 + 4 * g;
+#pragma unroll
+      for (int jg = 0; jg < 4; ++jg) {
+        csb[bm & 1][2 * jg] = *(const float4 *)(cs + 8 * jg);
+        csb[bm & 1][2 * jg + 1] = *(const float4 *)(cs + 8 * jg + 2);
+      }
+    };
+    if (kind != 2) load_cs(0);
+    int64_t orow[FM][4];   // output rows of this lane's stores (the paged cache: their slots)
+#pragma unroll
+    for (int bm = 0; bm < FM; ++bm)
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int mm = m_base + bm * 32 + it * 8 + (lane >> 3);
+        orow[bm][it] = mm;
+        if constexpr (EPI == EPI_KV) { if (paged) orow[bm][it] = p.slots[mm < p.M ? mm : p.M - 1]; }
+      }
 #pragma unroll
     for (int bm = 0; bm < FM; ++bm) {
       const int m = m_base + bm * 32 + l32;
-      const int mc = m < p.M ? m : p.M - 1;
       const float rs = rsv[bm];
-      unsigned char *srow = slab + l32 * RS;
-      const float2 *cs = p.cos_sin + (int64_t)mc * (hd / 2) + s * 32;
+      unsigned char *srow = slab + bm * SLAB_BM + l32 * RS;
+      if (kind != 2 && bm + 1 < FM) load_cs(bm + 1);
 #pragma unroll
       for (int jg = 0; jg < 4; ++jg) {
         float y1[4], y2[4];
         const int i0 = 8 * jg + 4 * g;
         float cv[4] = {1.f, 1.f, 1.f, 1.f}, sv[4] = {0.f, 0.f, 0.f, 0.f};
         if (kind != 2) {
-          const float4 c01 = *(const float4 *)(cs + i0), c23 = *(const float4 *)(cs + i0 + 2);
+          const float4 c01 = csb[bm & 1][2 * jg], c23 = csb[bm & 1][2 * jg + 1];
           cv[0] = c01.x; cv[1] = c01.z; cv[2] = c23.x; cv[3] = c23.z;
           sv[0] = c01.y; sv[1] = c01.w; sv[2] = c23.y; sv[3] = c23.w;
         }
@@ -1132,24 +1177,17 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
           amax_h = fmaxf(amax_h, fmaxf(a1, a2));
         }
       }
-      // stream out: 8 rows per instruction, chunk ch = 8 local columns; local block ch/4
+    }
+    // a wave's LDS operations execute in order: the reads below see the writes above
 #pragma unroll
-      for (int it = 0; it < 4; ++it) {
+    for (int bm = 0; bm < FM; ++bm)
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {   // 8 rows per instruction, chunk ch = 8 local columns; local block ch/4
         const int row = it * 8 + (lane >> 3), ch = lane & 7;
         const int mm = m_base + bm * 32 + row;
-        const uint4 val = *(const uint4 *)(slab + row * RS + ch * 16);
-        if (mm >= p.M) continue;
-        const int col = col0 + (ch >> 2) * blk_stride + s * 32 + (ch & 3) * 8;
-        bf16_t *dst;
-        if constexpr (EPI == EPI_QKV)
-          dst = kind == 0 ? p.q_out + (int64_t)mm * p.q_dim + col : (kind == 1 ? p.k_out : p.v_out) + (int64_t)mm * p.kv_dim + col;
-        else
-          dst = p.stage ? p.stage + (int64_t)mm * p.N + (int64_t)proj * 2 * p.kv_dim + (kind == 2 ? p.kv_dim : 0) + col
-                        : p.cache + (int64_t)(p.first_cache_layer + proj) * p.cache_layer_stride +
-                              (kind == 2 ? p.cache_kv_stride : 0) + p.slots[mm] * p.kv_dim + col;
-        *(uint4 *)dst = val;
+        const uint4 val = *(const uint4 *)(slab + bm * SLAB_BM + row * RS + ch * 16);
+        if (mm < p.M) *(uint4 *)(obase + orow[bm][it] * ostride + (ch >> 2) * blk_stride + (ch & 3) * 8) = val;
       }
-    }
     if (p.amax && kind != 0) {
       const float a = wave_max(amax_h);
       if (lane == 0)
@@ -1337,7 +1375,8 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped extra requests ...
   __builtin_amdgcn_s_barrier();         // ... of every wave, before LDS is reused by the epilogue
-  unsigned char *slab = smem + wave * (32 * (64 * 4 + 16));
+  // per-wave slab: one 32-row block of fp32 (272-byte rows), or, for the rotating epilogues, all eight blocks of bf16 (144-byte rows)
+  unsigned char *slab = smem + wave * ((EPI == EPI_QKV || EPI == EPI_KV) ? FM * 32 * (64 * 2 + 16) : 32 * (64 * 4 + 16));
   long long t_loop = 0;
   if constexpr (PROF) t_loop = clock64() - t_begin;
   gemm_epilogue_n64<EPI, FM>(p, acc, m0, n0, lane, slab);
