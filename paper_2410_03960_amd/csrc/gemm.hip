@@ -1121,21 +1121,26 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
     // Two passes, so that no load follows a store: loads and stores share one counter, and with both
     // kinds pending every wait for a load becomes a wait for everything, stores included (which made
     // each 32-row block of the epilogue wait for the previous block's stores to reach memory).
-    // Pass 1: per 32-row block the cos/sin pieces (requested one block ahead) and, for the paged cache,
-    // the rows' slots; rotation, rounding, bf16 rows into the wave's LDS slab (FM blocks of 32 rows).
+    // Pass 1: per 32-row block the cos/sin pieces (requested CSD - 1 blocks ahead: they are 32-row gathers
+    // that mostly miss L2, and one block of arithmetic covers only a third of their latency) and, for the
+    // paged cache, the rows' slots; rotation, rounding, bf16 rows into the wave's LDS slab (FM blocks of 32 rows).
     // Pass 2: the slab leaves as 16-byte stores in which consecutive lanes cover a contiguous row piece.
     constexpr int SLAB_BM = 32 * RS;   // bytes per 32-row block
-    float4 csb[2][8];
+    constexpr int CSD = (EPI == EPI_QKV) ? 4 : 2;   // the paged variant keeps 64 registers of slots instead
+    float4 csb[CSD][8];
     auto load_cs = [&](int bm) {
       const int m = m_base + bm * 32 + l32;
       const float2 *cs = p.cos_sin + (int64_t)(m < p.M ? m : p.M - 1) * (hd / 2) + s * 32 + 4 * g;
 #pragma unroll
       for (int jg = 0; jg < 4; ++jg) {
-        csb[bm & 1][2 * jg] = *(const float4 *)(cs + 8 * jg);
-        csb[bm & 1][2 * jg + 1] = *(const float4 *)(cs + 8 * jg + 2);
+        csb[bm % CSD][2 * jg] = *(const float4 *)(cs + 8 * jg);
+        csb[bm % CSD][2 * jg + 1] = *(const float4 *)(cs + 8 * jg + 2);
       }
     };
-    if (kind != 2) load_cs(0);
+    if (kind != 2) {
+#pragma unroll
+      for (int b = 0; b < CSD - 1; ++b) load_cs(b);
+    }
     int64_t orow[FM][4];   // output rows of this lane's stores (the paged cache: their slots)
 #pragma unroll
     for (int bm = 0; bm < FM; ++bm)
@@ -1150,14 +1155,14 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
       const int m = m_base + bm * 32 + l32;
       const float rs = rsv[bm];
       unsigned char *srow = slab + bm * SLAB_BM + l32 * RS;
-      if (kind != 2 && bm + 1 < FM) load_cs(bm + 1);
+      if (kind != 2 && bm + CSD - 1 < FM) load_cs(bm + CSD - 1);
 #pragma unroll
       for (int jg = 0; jg < 4; ++jg) {
         float y1[4], y2[4];
         const int i0 = 8 * jg + 4 * g;
         float cv[4] = {1.f, 1.f, 1.f, 1.f}, sv[4] = {0.f, 0.f, 0.f, 0.f};
         if (kind != 2) {
-          const float4 c01 = csb[bm & 1][2 * jg], c23 = csb[bm & 1][2 * jg + 1];
+          const float4 c01 = csb[bm % CSD][2 * jg], c23 = csb[bm % CSD][2 * jg + 1];
           cv[0] = c01.x; cv[1] = c01.z; cv[2] = c23.x; cv[3] = c23.z;
           sv[0] = c01.y; sv[1] = c01.w; sv[2] = c23.y; sv[3] = c23.w;
         }
