@@ -45,3 +45,29 @@ def test_product_never_imports_the_oracle():
                 assert "oracle" not in src.replace("no CPU fallback", ""), f
     osrc = open(os.path.join(ROOT, "oracle", "swiftkv_oracle.py")).read()
     assert "paper_2410_03960_amd" not in osrc and "workloads" not in osrc
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build is single-GPU: bench.py --gpus N (N > 1) must say so and exit
+    non-zero before touching a GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_workloads_beyond_the_five_configurations_are_consistent():
+    """The prompt-chunk and decode-step workloads: batch geometry (cached
+    context per sequence, block tables with room for context + new tokens)."""
+    import workloads as WL
+    wl = WL.get_workload("8b_l16_b8x2048_ctx6144")
+    b = WL.build_batch(wl)
+    assert b.seq_lens.tolist() == [2048] * 8 and b.context_lens.tolist() == [6144] * 8
+    assert b.block_tables.shape[1] == (6144 + 2048) // 16 and b.n_blocks >= 8 * 512
+    wl = WL.get_workload("8b_l16_dec64_ctx2048")
+    b = WL.build_batch(wl)
+    assert b.seq_lens.tolist() == [1] * 64 and b.context_lens.tolist() == [2048] * 64
+    assert b.block_tables.shape[1] == 129
+    used = b.block_tables.flatten().tolist()
+    assert len(set(used)) == len(used)          # no block shared between sequences
