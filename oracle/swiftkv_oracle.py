@@ -300,7 +300,7 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
                     l: int, g: int, cache: PagedKVCache,
                     dtype=torch.float64, fp8_compute_scales: bool = True,
                     seq_subset: Optional[Sequence[int]] = None,
-                    all_token_tail: bool = False, act_round=None):
+                    all_token_tail: bool = False, act_round=None, early_exit=None):
     """SwiftKV prefill of a packed batch.  Returns logits [B, vocab] (rows of
     sequences outside `seq_subset` are NaN) and leaves K/V in `cache`.
 
@@ -314,6 +314,14 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
     cache with per-token scales sets each token's scales when it writes it.
     all_token_tail: run layers l+1..L on every new token instead of only the
     last (checking aid); logits are still those of the last token.
+    early_exit: None, or (gain [hidden], head [vocab, hidden], threshold): the
+    simple early exit of Appendix B.4.  An extra head reads the layer-l output of
+    the last new token, logits_ee = head @ RMSNorm(h_l; gain); when its largest
+    softmax probability exceeds the threshold these logits are the result and
+    layers l+1..L are not needed for that token, otherwise the remaining layers
+    run as usual.  The K/V cache is the same either way (every later layer's
+    K/V comes from h_l).  With early_exit the function returns a third value,
+    the per-sequence exit flags.
     act_round: None gives the plain definition.  A function (e.g. round to
     bfloat16 and back) is applied to every activation a reduced-precision
     pipeline would store between matrix products (normed inputs, q/k/v,
@@ -393,6 +401,16 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
     for b in seqs:
         logits[b] = R(rmsnorm(t[b][-1], gf, sh.rms_eps)) @ Wlm.T
     hidden_l = {b: h[b] for b in seqs}
+    if early_exit is not None:
+        g_ee, w_ee, thr = early_exit
+        g_ee, w_ee = g_ee.to(dtype), w_ee.to(dtype)
+        exited = torch.zeros(B, dtype=torch.bool)
+        for b in seqs:
+            lg = R(rmsnorm(h[b][-1], g_ee, sh.rms_eps)) @ w_ee.T
+            if float(torch.softmax(lg, dim=-1).max()) > thr:
+                exited[b] = True
+                logits[b] = lg
+        return logits, hidden_l, exited
     return logits, hidden_l
 
 

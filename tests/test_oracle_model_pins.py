@@ -35,8 +35,8 @@ def _run_oracle(wd, ids, lens, l, g, ctx=None, **kw):
     bt, nb = identity_tables(lens, ctx)
     C = O.n_cache_layers(MS.n_layers, l, g)
     cache = O.PagedKVCache(C, nb, MS.n_kv_heads, MS.head_dim, bt)
-    logits, hl = O.swiftkv_prefill(oracle_shape(MS), dict_weight_fn(wd), ids, lens, ctx, l, g, cache, **kw)
-    return logits, cache, hl
+    out = O.swiftkv_prefill(oracle_shape(MS), dict_weight_fn(wd), ids, lens, ctx, l, g, cache, **kw)
+    return (out[0], cache, out[1]) + tuple(out[2:])
 
 
 def _hf_forward(hf, ids):
@@ -268,6 +268,36 @@ def test_per_token_fp8_cache_is_independent_of_batching(wd):
     O.swiftkv_prefill(sh, wf, torch.cat([ids, ids2]), [n, 13], [0, 0], l, g, both)
     s0 = both.slots(0, torch.arange(n))
     assert torch.equal(both.data[:, :, s0], one.data[:, :, :n]) and torch.equal(both.scales[:, :, s0], one.scales[:, :, :n])
+
+
+def test_early_exit_rule(wd):
+    """Appendix B.4: a threshold nobody reaches changes nothing; a threshold
+    everybody passes returns the extra head applied to the normalised layer-l
+    output (rebuilt here from the returned hidden state with library ops); a
+    peaked head makes exactly the confident rows exit; the cache never changes."""
+    l, g = 2, 2
+    lens = [19, 7, 30]
+    ids = _ids(sum(lens), 41)
+    sh, wf = oracle_shape(MS), dict_weight_fn(wd)
+    plain, c_plain, hl = _run_oracle(wd, ids, lens, l, g)
+    gen = torch.Generator().manual_seed(5)
+    g_ee = 1 + 0.02 * torch.randn(MS.hidden, generator=gen, dtype=torch.float64)
+    w_ee = 0.02 * torch.randn(MS.vocab, MS.hidden, generator=gen, dtype=torch.float64)
+    never, c1, _, ex = _run_oracle(wd, ids, lens, l, g, early_exit=(g_ee, w_ee, 1.0))
+    assert not ex.any() and torch.equal(never, plain) and torch.equal(c1.data, c_plain.data)
+    always, c2, _, ex = _run_oracle(wd, ids, lens, l, g, early_exit=(g_ee, w_ee, -1.0))
+    assert ex.all() and torch.equal(c2.data, c_plain.data)
+    for b in range(3):
+        x = hl[b][-1]
+        want = torch.nn.functional.linear(torch.nn.functional.rms_norm(x, (MS.hidden,), g_ee, MS.rms_eps), w_ee)
+        assert torch.allclose(always[b], want, atol=1e-10)
+    # a head that is confident on some rows only: scale the logits until the row maxima straddle 0.95
+    pm = torch.softmax(always * 60.0, dim=-1).amax(dim=-1)
+    assert pm.min() < 0.94 and (pm > 0.96).any() and not ((pm > 0.94) & (pm < 0.96)).any(), pm
+    mixed, c3, _, ex = _run_oracle(wd, ids, lens, l, g, early_exit=(g_ee, 60.0 * w_ee, 0.95))
+    assert ex.tolist() == (pm > 0.95).tolist() and torch.equal(c3.data, c_plain.data)
+    for b in range(3):
+        assert torch.allclose(mixed[b], 60.0 * always[b] if ex[b] else plain[b], atol=1e-9)
 
 
 def test_sequence_order_only_permutes_outputs(wd):
