@@ -163,6 +163,23 @@ int swiftkv_kv_from_hidden(swiftkv_ctx *ctx, const void *hidden_l, const int32_t
                            int32_t n_seqs, const swiftkv_kv_cache *kv, void *workspace,
                            size_t workspace_bytes, void *stream);
 
+/* Simple early exit of the continuing tokens (Appendix B.4).  gain (dev bf16
+ * [hidden]) and head (dev bf16 [vocab, hidden]) describe an extra language-model
+ * head that reads the layer-l output of each sequence's last new token:
+ * logits_ee = head * RMSNorm(h_l; gain).  After this call swiftkv_prefill
+ * returns logits_ee for the sequences whose largest softmax probability
+ * exceeds `threshold` (the paper uses 0.95) and the ordinary logits for the
+ * others; the K/V cache is the same either way.  Both NULL switches it off.
+ * The remaining layers still run for every row (they stream each weight once
+ * whatever the number of rows, so dropping single rows saves nothing; a serving
+ * loop that wants to skip them when every row exits has to look at the flags).
+ * The pointers are kept, not copied.  Workspace sizes depend on this setting:
+ * call swiftkv_workspace_bytes afterwards. */
+int swiftkv_set_early_exit(swiftkv_ctx *ctx, const void *gain, const void *head, float threshold);
+/* Exit flags of the most recent swiftkv_prefill that used `workspace`: dev int32
+ * [n_seqs], 1 = the row's logits are the extra head's (all 0 when off). */
+int swiftkv_export_exit_flags(swiftkv_ctx *ctx, const void *workspace, int32_t *flags_out, void *stream);
+
 /* Copy out the integer plan of the most recent swiftkv_prefill /
  * swiftkv_kv_from_hidden that used `workspace` (all dev outputs, any may be NULL):
  * slot_mapping int64 [T] (= block_table[b][p/16]*16 + p%16), positions int32 [T],

@@ -25,7 +25,7 @@ TIME_CLASS_NAMES = ("qkv_gemm", "o_gemm", "gateup_gemm", "down_gemm", "fused_kv_
 
 EXPORTS = (
     "swiftkv_create", "swiftkv_destroy", "swiftkv_workspace_bytes", "swiftkv_workspace_bytes_prefix", "swiftkv_prefill",
-    "swiftkv_kv_from_hidden", "swiftkv_export_plan", "swiftkv_export_hidden", "swiftkv_op_gemm",
+    "swiftkv_kv_from_hidden", "swiftkv_set_early_exit", "swiftkv_export_exit_flags", "swiftkv_export_plan", "swiftkv_export_hidden", "swiftkv_op_gemm",
     "swiftkv_op_attention_prefill", "swiftkv_op_attention_workspace", "swiftkv_op_fp8_quantize",
     "swiftkv_flops", "swiftkv_set_timing", "swiftkv_get_timing", "swiftkv_last_error",
     "swiftkv_version",
@@ -81,6 +81,8 @@ def load() -> C.CDLL:
     lib.swiftkv_prefill.argtypes = [vp, vp, C.POINTER(i32), i32, C.POINTER(KVCacheDesc), vp, vp, C.c_size_t, vp]
     lib.swiftkv_kv_from_hidden.argtypes = [vp, vp, C.POINTER(i32), i32, C.POINTER(KVCacheDesc), vp, C.c_size_t, vp]
     lib.swiftkv_export_plan.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.swiftkv_set_early_exit.argtypes = [vp, vp, vp, C.c_float]
+    lib.swiftkv_export_exit_flags.argtypes = [vp, vp, vp, vp]
     lib.swiftkv_export_hidden.argtypes = [vp, vp, vp, vp]
     lib.swiftkv_op_gemm.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp]
     lib.swiftkv_op_attention_prefill.argtypes = [vp, vp, vp, vp, C.POINTER(i32), i32, i32, i32, i32, vp, C.c_size_t, vp]
@@ -188,6 +190,17 @@ class Context:
         _check(load().swiftkv_export_plan(self._h, _dev(workspace), _dev(slots), _dev(pos), _dev(cu), _dev(last),
                                           _stream_ptr(stream)))
         return slots, pos, cu, last
+
+    def set_early_exit(self, gain: Optional[torch.Tensor], head: Optional[torch.Tensor], threshold: float = 0.95) -> None:
+        """Extra head on the layer-l output (both None switches it off); the tensors are kept alive here."""
+        self._ee = (gain, head)
+        _check(load().swiftkv_set_early_exit(self._h, _dev(gain) if gain is not None else None,
+                                             _dev(head) if head is not None else None, float(threshold)))
+
+    def export_exit_flags(self, workspace: torch.Tensor, n_seqs: int, stream=None) -> torch.Tensor:
+        out = torch.empty(n_seqs, dtype=torch.int32, device=workspace.device)
+        _check(load().swiftkv_export_exit_flags(self._h, _dev(workspace), _dev(out), _stream_ptr(stream)))
+        return out
 
     def export_hidden(self, workspace: torch.Tensor, n_tokens: int, stream=None) -> torch.Tensor:
         out = torch.empty((n_tokens, self.shape.hidden), dtype=torch.bfloat16, device=workspace.device)

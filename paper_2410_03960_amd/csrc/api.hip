@@ -42,7 +42,7 @@ struct Layout {  // byte offsets into the workspace
   int64_t vt_ld = 0;
   int32_t n_qblocks = 0, n_kvtiles = 0, n_dec = 0, n_gtiles = 0;
   int64_t kcat_rows = 0;   // rows of the K buffer gathered from the cache (prompt chunks over a cached prefix), else 0
-  size_t err, meta, positions, seq_of, last_rows, slots, cos_sin, h, a, rstd, q, k, v, o, vt, kcat, z, stage, amax, qkv32, skpart;
+  size_t err, meta, positions, seq_of, last_rows, slots, cos_sin, h, a, rstd, q, k, v, o, vt, kcat, z, stage, amax, qkv32, skpart, ee_logits, ee_flags;
   size_t th, ta, tq, to, tz, partial, total;
   // offsets (in int32 units) inside the meta block copied from the host
   size_t m_cu, m_ctx, m_qblocks, m_kvtiles, m_dec, m_tail, m_gtiles, m_words;
@@ -64,6 +64,9 @@ struct swiftkv_ctx {
   bf16_t *w_pack = nullptr;
   std::vector<const bf16_t *> qkv_pack, wo_pack, gu_pack, down_pack;
   const bf16_t *kvf_pack = nullptr;   // the fused KV operand (kv_pack) in fragment order
+  // simple early exit of the continuing tokens (off unless swiftkv_set_early_exit was called)
+  const bf16_t *ee_gain = nullptr, *ee_head = nullptr;
+  float ee_threshold = 0.f;
   Layout last;
   bool have_last = false;
   // timing
@@ -116,6 +119,8 @@ Layout make_layout(const swiftkv_ctx *c, int64_t T, int32_t B, int64_t vt_ld, in
   L.z = take(T * (int64_t)m.ffn * 2);
   L.stage = take(fp8 ? T * (int64_t)c->P * 2 * kvd * 2 : 0);
   L.amax = take(fp8 ? (size_t)c->C * 2 * m.n_kv_heads * 4 : 0);
+  L.ee_logits = take(c->ee_head ? (size_t)B * m.vocab * 4 : 0);   // logits of the extra head
+  L.ee_flags = take((size_t)B * 4);
   L.skpart = take(SKINNY_PARTIAL_BYTES);   // K-split partial sums of the weight-streaming GEMMs
   L.qkv32 = take((size_t)std::min<int64_t>(T, SKINNY_MAX_ROWS) * (qd + 2 * kvd) * 4);   // fp32 Q, K, V of few-row batches
   L.th = take((size_t)B * d * 2);
@@ -535,6 +540,21 @@ size_t swiftkv_workspace_bytes(const swiftkv_ctx *c, int64_t max_tokens, int32_t
   return swiftkv_workspace_bytes_prefix(c, max_tokens, max_seqs, kv_dtype, 0);
 }
 
+int swiftkv_set_early_exit(swiftkv_ctx *c, const void *gain, const void *head, float threshold) {
+  if (!c) return fail(SWIFTKV_EINVAL, "null ctx");
+  if ((gain == nullptr) != (head == nullptr)) return fail(SWIFTKV_EINVAL, "gain and head must both be given or both be null");
+  c->ee_gain = (const bf16_t *)gain; c->ee_head = (const bf16_t *)head; c->ee_threshold = threshold;
+  return SWIFTKV_OK;
+}
+
+int swiftkv_export_exit_flags(swiftkv_ctx *c, const void *workspace, int32_t *flags_out, void *stream) {
+  if (!c || !workspace || !flags_out) return fail(SWIFTKV_EINVAL, "null argument");
+  if (!c->have_last) return fail(SWIFTKV_EINVAL, "no prefill has run on this ctx");
+  HIP_TRY(hipMemcpyAsync(flags_out, (const unsigned char *)workspace + c->last.ee_flags, (size_t)c->last.B * 4, hipMemcpyDeviceToDevice,
+                         (hipStream_t)stream));
+  return SWIFTKV_OK;
+}
+
 int swiftkv_set_timing(swiftkv_ctx *c, int32_t enable) {
   if (!c) return fail(SWIFTKV_EINVAL, "null ctx");
   c->timing = enable != 0;
@@ -779,6 +799,14 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   tm.begin(TC_TAIL);
   bf16_t *th = r.at<bf16_t>(r.L.th), *ta = r.at<bf16_t>(r.L.ta), *tq = r.at<bf16_t>(r.L.tq), *to = r.at<bf16_t>(r.L.to), *tz = r.at<bf16_t>(r.L.tz);
   launch_gather_rows(h, r.at<int32_t>(r.L.last_rows), th, B, d, st);
+  if (c->ee_head) {   // extra head on the layer-l output; the flagged rows' logits replace the final ones below
+    launch_rmsnorm_rows(th, c->ee_gain, ta, B, d, m.rms_eps, st);
+    if (tail_gemm(c, ta, B, m.vocab, d, c->ee_head, nullptr, nullptr, r.at<float>(r.L.ee_logits), EPI_STORE_F32, skp, st))
+      return fail(SWIFTKV_EHIP, "early-exit head GEMM failed");
+    launch_early_exit_flags(r.at<float>(r.L.ee_logits), B, m.vocab, c->ee_threshold, r.at<int32_t>(r.L.ee_flags), st);
+  } else {
+    launch_fill_u32(r.at<uint32_t>(r.L.ee_flags), 0, B, st);
+  }
   for (int j = c->l; j < m.n_layers; ++j) {
     const int cl = c->l + (j - c->l) / c->g;
     launch_rmsnorm_rows(th, c->norm1[j], ta, B, d, m.rms_eps, st);
@@ -800,6 +828,7 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   }
   launch_rmsnorm_rows(th, c->final_norm, ta, B, d, m.rms_eps, st);
   if (tail_gemm(c, ta, B, m.vocab, d, c->lm_head, nullptr, nullptr, logits_out, EPI_STORE_F32, skp, st)) return fail(SWIFTKV_EHIP, "LM head GEMM failed");
+  if (c->ee_head) launch_early_exit_select(r.at<float>(r.L.ee_logits), r.at<int32_t>(r.L.ee_flags), logits_out, B, m.vocab, st);
   tm.end();
   if (int e = check_launch("tail")) return e;
   c->last = r.L; c->have_last = true;

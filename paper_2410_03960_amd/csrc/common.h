@@ -135,6 +135,11 @@ struct QkvFinishParams {
 };
 int launch_qkv_finish(const QkvFinishParams &p, hipStream_t st);
 
+// Simple early exit of the continuing tokens: flags[b] = 1 when the largest softmax probability of row b
+// of `early` (fp32 [B, V]) exceeds `threshold`; select copies the flagged rows of `early` over `logits`.
+int launch_early_exit_flags(const float *early, int32_t B, int32_t V, float threshold, int32_t *flags, hipStream_t st);
+int launch_early_exit_select(const float *early, const int32_t *flags, float *logits, int32_t B, int32_t V, hipStream_t st);
+
 // ------------------------------------------------------------- attention ----
 struct QBlock {  // one 128-row query block of a sequence
   int32_t row0;   // packed row of the block's first query

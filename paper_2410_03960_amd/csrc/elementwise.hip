@@ -392,6 +392,42 @@ int launch_qkv_finish(const QkvFinishParams &p, hipStream_t st) {
   return 0;
 }
 
+// ----------------------------------------------------------- early exit ----
+// One workgroup per row: max, then sum of exp(x - max); the largest probability is 1 / that sum.
+__global__ __launch_bounds__(256) void early_exit_flags_kernel(const float *early, int32_t V, float threshold, int32_t *flags) {
+  __shared__ float red[4];
+  const float *x = early + (int64_t)blockIdx.x * V;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float mx = -INFINITY;
+  for (int i = tid; i < V; i += 256) mx = fmaxf(mx, x[i]);
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  if (lane == 0) red[wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float sum = 0.f;
+  for (int i = tid; i < V; i += 256) sum += __expf(x[i] - mx);
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+  if (lane == 0) red[wave] = sum;
+  __syncthreads();
+  if (tid == 0) flags[blockIdx.x] = (1.0f / (red[0] + red[1] + red[2] + red[3])) > threshold ? 1 : 0;
+}
+__global__ void early_exit_select_kernel(const float *early, const int32_t *flags, float *logits, int32_t V) {
+  if (!flags[blockIdx.y]) return;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < V) logits[(int64_t)blockIdx.y * V + i] = early[(int64_t)blockIdx.y * V + i];
+}
+int launch_early_exit_flags(const float *early, int32_t B, int32_t V, float threshold, int32_t *flags, hipStream_t st) {
+  if (B <= 0) return 0;
+  hipLaunchKernelGGL(early_exit_flags_kernel, dim3(B), dim3(256), 0, st, early, V, threshold, flags);
+  return 0;
+}
+int launch_early_exit_select(const float *early, const int32_t *flags, float *logits, int32_t B, int32_t V, hipStream_t st) {
+  if (B <= 0) return 0;
+  hipLaunchKernelGGL(early_exit_select_kernel, dim3((V + 255) / 256, B), dim3(256), 0, st, early, flags, logits, V);
+  return 0;
+}
+
 // ----------------------------------------------------------- KV gather -----
 // One workgroup per (64-position tile, KV head) of a sequence whose prompt continues over a cached
 // prefix: copies the tile's K rows out of the paged cache into consecutive rows and its V rows

@@ -173,3 +173,56 @@ def test_generation_after_prompt(tiny):
         cur = [c + 1 for c in cur]
         G.compare_caches(cache, ocache, dec, label=f"step {step}")
     G.compare_logits(logits, ologits, label="last step")
+
+
+def test_early_exit_selects_confident_rows(tiny):
+    """Appendix B.4: an extra head on the layer-l output; rows whose largest
+    probability exceeds the threshold return its logits, the others the ordinary
+    ones; the cache is that of the plain call.  The decision compares a float32
+    probability with the threshold on both sides; the head is scaled so that no
+    row sits near the threshold."""
+    from paper_2410_03960_amd import binding as B
+    wl, store, dev_w = tiny
+    l, g = 2, 2
+    lens, ctx_lens = [19, 7, 30, 1, 64], [0, 0, 0, 12, 0]
+    _say("early exit")
+    batch = WL.build_batch(wl, lens=lens, ctx=ctx_lens, shuffled=True)
+    gen = torch.Generator().manual_seed(5)
+    g_ee = (1 + 0.02 * torch.randn(TINY.hidden, generator=gen)).to(torch.bfloat16)
+    w_base = (0.02 * torch.randn(TINY.vocab, TINY.hidden, generator=gen))
+    ocache = _oracle_contexts(store, batch, ctx_lens, l, g)
+    ocache.data = ocache.data.to(torch.bfloat16).double()
+    base = ocache.data.clone()
+    # pick a scale for which the oracle's row maxima stay clear of the threshold
+    for scale in (40.0, 60.0, 90.0, 140.0):
+        w_ee = (scale * w_base).to(torch.bfloat16)
+        oc = O.PagedKVCache(ocache.C, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables)
+        oc.data = base.clone()
+        ologits, _, oflags = O.swiftkv_prefill(G.oracle_shape(TINY), G.weight_fn(store), batch.token_ids, lens, ctx_lens, l, g, oc,
+                                               early_exit=(g_ee.double(), w_ee.double(), -1.0))
+        pm = torch.softmax(ologits, dim=-1).amax(dim=-1)
+        if (pm > 0.97).any() and (pm < 0.92).any() and not ((pm >= 0.92) & (pm <= 0.97)).any():
+            break
+    else:
+        pytest.skip("no scale separates the rows")
+    oc = O.PagedKVCache(ocache.C, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables)
+    oc.data = base.clone()
+    ologits, _, oflags = O.swiftkv_prefill(G.oracle_shape(TINY), G.weight_fn(store), batch.token_ids, lens, ctx_lens, l, g, oc,
+                                           early_exit=(g_ee.double(), w_ee.double(), 0.95))
+    assert oflags.any() and not oflags.all()
+    ctx = _ctx(dev_w, l, g)
+    ctx.set_early_exit(g_ee.cuda(), w_ee.cuda(), 0.95)
+    cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables, ctx_lens)
+    cache.data.copy_(base.to(torch.bfloat16))
+    logits, cache, ws = G.run_gpu(ctx, batch, cache=cache)
+    flags = ctx.export_exit_flags(ws, batch.n_seqs)
+    torch.cuda.synchronize()
+    assert flags.cpu().bool().tolist() == oflags.tolist()
+    G.compare_caches(cache, oc, batch, label="early exit")
+    G.compare_logits(logits, ologits, label="early exit")
+    # switched off again: plain logits, no flags
+    ctx.set_early_exit(None, None)
+    logits2, cache2, ws2 = G.run_gpu(ctx, batch, cache=cache)
+    assert int(ctx.export_exit_flags(ws2, batch.n_seqs).sum()) == 0
+    plain, _, _ = G.run_oracle(TINY, store, batch, l, g, cache=oc)
+    G.compare_logits(logits2, plain, label="early exit off")
