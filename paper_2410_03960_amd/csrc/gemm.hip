@@ -104,6 +104,23 @@ __device__ __forceinline__ void gemm_epilogue(const GemmParams &p, floatx16 (&ac
       col0 = within % p.kv_dim;
     }
     float amax_h[2] = {0.f, 0.f};
+    // destination of this wave's columns, selected once (uniform over the wave): base pointer and row
+    // stride in elements; rows of the paged cache go through p.slots
+    bf16_t *obase;
+    int64_t ostride;
+    bool paged = false;
+    if constexpr (EPI == EPI_QKV) {
+      obase = p.q_out; ostride = p.q_dim;
+      if (kind == 1) { obase = p.k_out; ostride = p.kv_dim; }
+      if (kind == 2) { obase = p.v_out; ostride = p.kv_dim; }
+      obase += col0;
+    } else {
+      obase = p.stage + n_base; ostride = p.N;
+      if (!p.stage) {
+        obase = p.cache + (int64_t)(p.first_cache_layer + proj) * p.cache_layer_stride + (kind == 2 ? p.cache_kv_stride : 0) + col0;
+        ostride = p.kv_dim; paged = true;
+      }
+    }
 #pragma unroll
     for (int bm = 0; bm < FM; ++bm) {
       const int m = m_base + bm * 32 + l32;
@@ -144,15 +161,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmParams &p, floatx16 (&ac
           }
       }
       // destination row pointer for this token
-      bf16_t *dst;
-      if constexpr (EPI == EPI_QKV) {
-        dst = kind == 0 ? p.q_out + (int64_t)mc * p.q_dim + col0
-                        : (kind == 1 ? p.k_out : p.v_out) + (int64_t)mc * p.kv_dim + col0;
-      } else {
-        if (p.stage) dst = p.stage + (int64_t)mc * p.N + n_base;
-        else dst = p.cache + (int64_t)(p.first_cache_layer + proj) * p.cache_layer_stride +
-                   (kind == 2 ? p.cache_kv_stride : 0) + p.slots[mc] * p.kv_dim + col0;
-      }
+      int64_t orow = mc;
+      if constexpr (EPI == EPI_KV) { if (paged) orow = p.slots[mc]; }
+      bf16_t *dst = obase + orow * ostride;
 #pragma unroll
       for (int bn = 0; bn < FN; ++bn)
 #pragma unroll
@@ -619,25 +630,44 @@ __device__ __forceinline__ void gemm_epilogue_lds(const GemmParams &p, floatx16 
       }
     }
     // ---- stream the slab out: lane -> (row it*RPI + lane/CPR, 16-byte chunk lane%CPR) ----
+    // Destination selected once (uniform over the wave): base pointer and row stride in elements; the rows
+    // of the paged cache go through p.slots, all read before the first store (loads and stores share one
+    // counter: a load issued between stores would wait for the stores before it).
     const int ch = lane % CPR;
+    bf16_t *obase;
+    int64_t ostride;
+    bool paged = false;
+    if constexpr (EPI == EPI_STORE_BF16) { obase = (bf16_t *)p.C + n_base; ostride = p.ldc; }
+    else if constexpr (EPI == EPI_SWIGLU) { obase = (bf16_t *)p.C + n_base / 2; ostride = p.ldc; }
+    else if constexpr (EPI == EPI_QKV) {
+      obase = p.q_out; ostride = p.q_dim;
+      if (kind == 1) { obase = p.k_out; ostride = p.kv_dim; }
+      if (kind == 2) { obase = p.v_out; ostride = p.kv_dim; }
+      obase += col0;
+    } else {
+      obase = p.stage + n_base; ostride = p.N;
+      if (!p.stage) {
+        obase = p.cache + (int64_t)(p.first_cache_layer + proj) * p.cache_layer_stride + (kind == 2 ? p.cache_kv_stride : 0) + col0;
+        ostride = p.kv_dim; paged = true;
+      }
+    }
+    constexpr int N_IT = FM * 32 / RPI;
+    int64_t orow[N_IT];
 #pragma unroll
-    for (int it = 0; it < FM * 32 / RPI; ++it) {
+    for (int it = 0; it < N_IT; ++it) {
+      const int m = m_base + it * RPI + lane / CPR;
+      orow[it] = m;
+      if constexpr (EPI == EPI_KV) { if (paged) orow[it] = p.slots[m < p.M ? m : p.M - 1]; }
+    }
+#pragma unroll
+    for (int it = 0; it < N_IT; ++it) {
       const int row = it * RPI + lane / CPR;
       const int m = m_base + row;
       const uint4 val = *(const uint4 *)(slab + row * RS + ch * 16);
       if (m >= p.M) continue;
-      bf16_t *dst;
-      if constexpr (EPI == EPI_STORE_BF16) dst = (bf16_t *)p.C + (int64_t)m * p.ldc + n_base;
-      else if constexpr (EPI == EPI_SWIGLU) dst = (bf16_t *)p.C + (int64_t)m * p.ldc + n_base / 2;
-      else if constexpr (EPI == EPI_QKV)
-        dst = kind == 0 ? p.q_out + (int64_t)m * p.q_dim + col0 : (kind == 1 ? p.k_out : p.v_out) + (int64_t)m * p.kv_dim + col0;
-      else
-        dst = p.stage ? p.stage + (int64_t)m * p.N + n_base
-                      : p.cache + (int64_t)(p.first_cache_layer + proj) * p.cache_layer_stride +
-                            (kind == 2 ? p.cache_kv_stride : 0) + p.slots[m] * p.kv_dim + col0;
       if constexpr (EPI == EPI_STORE_BF16) { if (n_base + ch * 8 >= p.N) continue; }
       if constexpr (EPI == EPI_SWIGLU) { if (n_base + ch * 16 >= p.N) continue; }
-      *(uint4 *)(dst + ch * 8) = val;
+      *(uint4 *)(obase + orow[it] * ostride + ch * 8) = val;
     }
   }
 }
