@@ -264,17 +264,36 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(CommitParams p) {
   }
   (void)isk; (void)isv;
   const int kv_dim = p.n_kv_heads * HD;
-  for (int i = tid; i < 64 * CH; i += 256) {
+  // everything this thread reads is requested before its first store (loads and stores share one
+  // counter: a load issued after a store would wait for that store to reach memory)
+  constexpr int NI = 64 * CH / 256;
+  uint4 kin[NI], vin[NI];
+  int64_t slot_in[NI];
+  float sk_in[NI], sv_in[NI];
+#pragma unroll
+  for (int ii = 0; ii < NI; ++ii) {
+    const int i = tid + ii * 256, r = i / CH, c = i % CH;
+    kin[ii] = make_uint4(0, 0, 0, 0); vin[ii] = make_uint4(0, 0, 0, 0);
+    slot_in[ii] = 0; sk_in[ii] = sk; sv_in[ii] = svs;
+    if (r < tile.n_valid) {
+      const int64_t row = tile.row0 + r;
+      kin[ii] = *(const uint4 *)(p.k_src + row * p.ld_src + head * HD + c * 8);
+      vin[ii] = *(const uint4 *)(p.v_src + row * p.ld_src + head * HD + c * 8);
+      if (p.cache_k) slot_in[ii] = p.slots[row];
+      if (p.per_token) { sk_in[ii] = p.scales[p.slots[row]]; sv_in[ii] = p.scales[p.n_slots + p.slots[row]]; }
+    }
+  }
+#pragma unroll
+  for (int ii = 0; ii < NI; ++ii) {
+    const int i = tid + ii * 256;
     int r = i / CH, c = i % CH;
-    uint4 kq = make_uint4(0, 0, 0, 0), vq = make_uint4(0, 0, 0, 0);
+    uint4 kq = kin[ii], vq = vin[ii];
     if (r < tile.n_valid) {
       int64_t row = tile.row0 + r;
       bf16_t *kp = p.k_src + row * p.ld_src + head * HD + c * 8;
       bf16_t *vp = p.v_src + row * p.ld_src + head * HD + c * 8;
-      kq = *(const uint4 *)kp;
-      vq = *(const uint4 *)vp;
-      int64_t dst = p.cache_k ? (p.slots[row] * p.n_kv_heads + head) * HD + c * 8 : 0;
-      if (p.per_token) { sk = p.scales[p.slots[row]]; svs = p.scales[p.n_slots + p.slots[row]]; }
+      int64_t dst = (slot_in[ii] * p.n_kv_heads + head) * HD + c * 8;
+      sk = sk_in[ii]; svs = sv_in[ii];
       if (!p.cache_k) {
         // no cache wanted (stand-alone attention): only V^T is produced
       } else if (!p.fp8) {
