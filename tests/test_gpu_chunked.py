@@ -226,3 +226,37 @@ def test_early_exit_selects_confident_rows(tiny):
     assert int(ctx.export_exit_flags(ws2, batch.n_seqs).sum()) == 0
     plain, _, _ = G.run_oracle(TINY, store, batch, l, g, cache=oc)
     G.compare_logits(logits2, plain, label="early exit off")
+
+
+@pytest.mark.parametrize("hq,hkv,hd", [(4, 4, 64), (16, 2, 64), (2, 2, 128), (8, 1, 128)])
+def test_head_groupings(hq, hkv, hd):
+    """Query heads per KV head 1 (plain multi-head attention), 8, and a single KV
+    head (multi-query attention), with prompts, a chunk over a cached prefix and
+    a decode token in one batch."""
+    from paper_2410_03960_amd import binding as B
+    from workloads.configs import ModelShape, Workload
+    shape = ModelShape(3, 256, hq, hkv, hd, 512, 1024, 1e4, 1e-5)
+    wl = Workload(f"heads_{hq}_{hkv}_{hd}", shape, l=2, g=1, seed=2301)
+    store = WL.make_weights(wl, "cpu", keep=True)
+    dev_w = G.device_weights(store)
+    lens, ctx_lens = [150, 40, 1, 9], [0, 70, 33, 0]
+    _say(f"head grouping Hq={hq} Hkv={hkv} hd={hd}")
+    batch = WL.build_batch(wl, lens=lens, ctx=ctx_lens, shuffled=True)
+    C = O.n_cache_layers(shape.n_layers, wl.l, wl.g)
+    ocache = O.PagedKVCache(C, batch.n_blocks, hkv, hd, batch.block_tables)
+    for b, cl in enumerate(ctx_lens):
+        if cl:
+            ids = WL.seeded_token_ids(7, f"ctx{b}", cl, shape.vocab)
+            sub = O.PagedKVCache(C, batch.n_blocks, hkv, hd, batch.block_tables[b:b + 1])
+            O.swiftkv_prefill(G.oracle_shape(shape), G.weight_fn(store), ids, [cl], [0], wl.l, wl.g, sub)
+            s = sub.slots(0, torch.arange(cl))
+            ocache.data[:, :, s] = sub.data[:, :, s]
+    ctx = B.Context(shape, dev_w, wl.l, wl.g)
+    cache = B.KVCache(C, batch.n_blocks, hkv, hd, batch.block_tables, ctx_lens)
+    cache.data.copy_(ocache.data.to(torch.bfloat16))
+    ocache.data = ocache.data.to(torch.bfloat16).double()
+    logits, cache, ws = G.run_gpu(ctx, batch, cache=cache)
+    G.check_plan(ctx, ws, batch)
+    ologits, ocache, _ = G.run_oracle(shape, store, batch, wl.l, wl.g, cache=ocache)
+    G.compare_caches(cache, ocache, batch, label="heads")
+    G.compare_logits(logits, ologits, label="heads")
