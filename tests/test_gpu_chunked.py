@@ -260,3 +260,27 @@ def test_head_groupings(hq, hkv, hd):
     ologits, ocache, _ = G.run_oracle(shape, store, batch, wl.l, wl.g, cache=ocache)
     G.compare_caches(cache, ocache, batch, label="heads")
     G.compare_logits(logits, ologits, label="heads")
+
+
+def test_many_short_sequences(tiny):
+    """300 sequences of 1..20 tokens, a third of them over cached contexts: more
+    tail rows than the weight-streaming GEMM takes (it switches to the tiled
+    one), many single-query rows, most 128-query blocks nearly empty."""
+    from paper_2410_03960_amd import binding as B
+    wl, store, dev_w = tiny
+    l, g = 2, 1
+    gen = torch.Generator().manual_seed(17)
+    lens = torch.randint(1, 21, (300,), generator=gen).tolist()
+    ctx_lens = [int(c) if i % 3 == 0 else 0 for i, c in enumerate(torch.randint(1, 60, (300,), generator=gen).tolist())]
+    _say("many short sequences")
+    batch = WL.build_batch(wl, lens=lens, ctx=ctx_lens, shuffled=True)
+    ocache = _oracle_contexts(store, batch, ctx_lens, l, g)
+    ctx = _ctx(dev_w, l, g)
+    cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables, ctx_lens)
+    cache.data.copy_(ocache.data.to(torch.bfloat16))
+    ocache.data = ocache.data.to(torch.bfloat16).double()
+    logits, cache, ws = G.run_gpu(ctx, batch, cache=cache)
+    G.check_plan(ctx, ws, batch)
+    ologits, ocache, _ = G.run_oracle(TINY, store, batch, l, g, cache=ocache)
+    G.compare_caches(cache, ocache, batch, label="many")
+    G.compare_logits(logits, ologits, label="many")
