@@ -198,17 +198,18 @@ int swiftkv_export_hidden(swiftkv_ctx *ctx, const void *workspace, void *hidden_
  * stores fp32, else bf16.  variant: 0 = pick by shape, 1 = 256x256 tile with
  * register-staged loads, 2 = 128x128 tile, 3 = weight-streaming kernel for
  * M <= 80 rows (29 = the same with a library-owned scratch buffer, which lets
- * it split K over more workgroups when there are few column tiles), 4 / 5 = 256x256 tile with direct-to-LDS loads and 8 / 4 waves
- * (K % 64 == 0, else they fall back to 1), 14 / 15 = the five-stage
+ * it split K over more workgroups when there are few column tiles), 4 / 5 =
+ * 256x256 tile with direct-to-LDS loads and 8 / 4 waves (K % 64 == 0, else
+ * they fall back to 1), 14 / 15 = the five-stage
  * direct-to-LDS loop with 4 / 8 waves (what 0 picks for large M), 20 / 21 = that
  * loop with 4 / 3 stages, 22..24 = with non-temporal loads of both / A / W,
  * 25 = with a shared L2 prefetch (20..25 apply to bf16 output; tuning aids
  * with correct results), 27 = the loop that takes the weights in MFMA
  * fragment order straight into registers (M >= 1024, N, K multiples of 256,
  * bf16 output; W is repacked into a library-owned buffer on every call unless
- * SWIFTKV_XP_KEEP_PACK is set and the pointer is unchanged).  6..13, 16..19, 26 and 30..33 are timing experiments whose
- * results are not meaningful (10..13, 16 and 26 also need room behind C for
- * counters).
+ * SWIFTKV_XP_KEEP_PACK is set and the pointer is unchanged).  6..13, 16..19,
+ * 26, 28 and 30..33 are timing experiments whose results are not meaningful
+ * (10..13, 16, 26 and 28 also need room behind C for counters).
  * All dev. */
 int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K,
                     int32_t out_f32, int32_t variant, void *stream);
