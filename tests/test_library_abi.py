@@ -71,3 +71,21 @@ def test_workloads_beyond_the_five_configurations_are_consistent():
     assert b.block_tables.shape[1] == 129
     used = b.block_tables.flatten().tolist()
     assert len(set(used)) == len(used)          # no block shared between sequences
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/swiftkv.h is a C header (plain pointers and sizes, no C++ or HIP
+    types): a C11 translation unit that includes it and takes the address of
+    every declared function must compile with gcc."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    names = _declared()
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "swiftkv.h"\n'
+                   + "const void *const table[] = {" + ", ".join(f"(const void *){n}" for n in names) + "};\n"
+                   + "int n_entries(void) { return (int)(sizeof(table) / sizeof(table[0])); }\n")
+    r = subprocess.run(["gcc", "-std=c11", "-Wall", "-Werror", "-pedantic", "-Wno-pedantic", "-I", os.path.join(ROOT, "include"),
+                        "-c", str(src), "-o", str(tmp_path / "use_header.o")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
