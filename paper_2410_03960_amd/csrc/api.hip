@@ -631,6 +631,7 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   Run r;
   if (int e = setup_run(r, c, seq_lens, B, kv, workspace, workspace_bytes, stream)) return e;
   if (!token_ids || !logits_out) return fail(SWIFTKV_EINVAL, "null token_ids or logits_out");
+  if (c->ee_head && B > 65535) return fail(SWIFTKV_EINVAL, "early exit handles at most 65535 sequences per call");
   const swiftkv_model_cfg &m = c->cfg;
   const int T = (int)r.L.T, d = m.hidden, qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
   hipStream_t st = r.st;
