@@ -31,6 +31,8 @@ def main():
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-launch HIP events (roofline is then null)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=256)
+    ap.add_argument("--no-mfma-rate", action="store_true",
+                    help="skip the measurement of the matrix-instruction rate on random operands")
     ap.add_argument("--kv-scales", choices=("per_head", "per_token"), default="per_head",
                     help="FP8-cache workloads: one scale per (cache layer, K|V, KV head) or one per token")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -160,6 +162,16 @@ def main():
                 "achieved": alg / (ms_per_step * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
                 "frac": alg / (ms_per_step * 1e-3) / 1e9 / 8000.0, "bytes_per_step": alg, "traffic": None}
     out["roofline"] = roof
+    if not args.no_mfma_rate and T >= 1024:
+        # what the matrix unit alone sustains on operand data like the model's (the chip is power-limited;
+        # the data-sheet peak assumes nothing toggles): A-like N(0,1) and W-like N(0,0.02) fragments
+        g = torch.Generator(device="cuda").manual_seed(wl.seed)
+        ops = torch.cat([torch.randn(8192, generator=g, device="cuda"), 0.02 * torch.randn(8192, generator=g, device="cuda")])
+        ops = ops.view(2, 4, 4, 512).transpose(0, 1).contiguous().view(-1).to(torch.bfloat16)   # per wave: 4 A-like, 4 W-like fragments
+        rate = B.op_mfma_rate(ops, 40000)
+        out["mfma_only_tflops"] = rate
+        if "gemm_tflops" in out:
+            out["gemm_frac_of_mfma_only"] = out["gemm_tflops"] / rate
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, store, ctx, args.cpu_sample_tokens)

@@ -214,6 +214,15 @@ int swiftkv_export_hidden(swiftkv_ctx *ctx, const void *workspace, void *hidden_
 int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K,
                     int32_t out_f32, int32_t variant, void *stream);
 
+/* Measurement aid: the rate (TFLOP/s, host double) at which the chip executes
+ * nothing but v_mfma_f32_32x32x16_bf16 on the caller's data -- `operands` is
+ * dev bf16, at least 16384 elements, e.g. values distributed like the model's
+ * activations and weights -- with one 4-wave workgroup per CU, `iters` x 16
+ * instructions per wave.  The chip is power-limited, so this rate depends on the
+ * operand bits and is well below the data-sheet peak on random data; the GEMMs'
+ * achieved rate can be set against it.  Allocates a small buffer, synchronises. */
+int swiftkv_op_mfma_rate(const void *operands, int32_t iters, double *tflops_out, void *stream);
+
 /* Causal grouped-query attention over packed fresh sequences (Sec. 3.1):
  * q dev bf16 [T, Hq*hd], k, v dev bf16 [T, Hkv*hd] (already rotated), out dev
  * bf16 [T, Hq*hd]; seq_lens host.  workspace as from swiftkv_op_attention_workspace. */

@@ -26,7 +26,7 @@ TIME_CLASS_NAMES = ("qkv_gemm", "o_gemm", "gateup_gemm", "down_gemm", "fused_kv_
 EXPORTS = (
     "swiftkv_create", "swiftkv_destroy", "swiftkv_workspace_bytes", "swiftkv_workspace_bytes_prefix", "swiftkv_prefill",
     "swiftkv_kv_from_hidden", "swiftkv_set_early_exit", "swiftkv_export_exit_flags", "swiftkv_export_plan", "swiftkv_export_hidden", "swiftkv_op_gemm",
-    "swiftkv_op_attention_prefill", "swiftkv_op_attention_workspace", "swiftkv_op_fp8_quantize",
+    "swiftkv_op_attention_prefill", "swiftkv_op_attention_workspace", "swiftkv_op_fp8_quantize", "swiftkv_op_mfma_rate",
     "swiftkv_flops", "swiftkv_set_timing", "swiftkv_get_timing", "swiftkv_last_error",
     "swiftkv_version",
 )
@@ -89,6 +89,7 @@ def load() -> C.CDLL:
     lib.swiftkv_op_attention_workspace.argtypes = [i64, i32, i32, i32]
     lib.swiftkv_op_attention_workspace.restype = C.c_size_t
     lib.swiftkv_op_fp8_quantize.argtypes = [vp, C.c_float, vp, i64, vp]
+    lib.swiftkv_op_mfma_rate.argtypes = [vp, i32, C.POINTER(C.c_double), vp]
     lib.swiftkv_flops.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.swiftkv_set_timing.argtypes = [vp, i32]
     lib.swiftkv_get_timing.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
@@ -249,6 +250,14 @@ class KVCache:
                            self.block_tables.data_ptr(), C.cast(self.context_lens, C.POINTER(C.c_int32)),
                            self.n_cache_layers, self.n_blocks, 16, self.block_tables.shape[1],
                            SWIFTKV_KV_FP8_E4M3 if self.fp8 else SWIFTKV_KV_BF16, self.scale_mode)
+
+
+def op_mfma_rate(operands: torch.Tensor, iters: int = 20000, stream=None) -> float:
+    """TFLOP/s of MFMA instructions alone on `operands` (bf16 CUDA tensor, >= 16384 elements)."""
+    assert operands.dtype == torch.bfloat16 and operands.numel() >= 16384 and operands.is_contiguous()
+    out = C.c_double(0.0)
+    _check(load().swiftkv_op_mfma_rate(_dev(operands), iters, C.byref(out), _stream_ptr(stream)))
+    return float(out.value)
 
 
 def op_gemm(A: torch.Tensor, W: torch.Tensor, out_f32: bool = False, variant: int = 0, stream=None,

@@ -970,6 +970,30 @@ int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, vo
   return check_launch("attention");
 }
 
+int swiftkv_op_mfma_rate(const void *operands, int32_t iters, double *tflops_out, void *stream) {
+  if (!operands || !tflops_out || iters < 1) return fail(SWIFTKV_EINVAL, "bad argument");
+  hipStream_t st = (hipStream_t)stream;
+  int dev = 0, n_cu = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+  float *sink = nullptr;
+  HIP_TRY(hipMalloc((void **)&sink, (size_t)n_cu * 256 * 4));
+  hipEvent_t e0, e1;
+  HIP_TRY(hipEventCreate(&e0));
+  HIP_TRY(hipEventCreate(&e1));
+  launch_mfma_rate((const bf16_t *)operands, sink, n_cu, iters / 8 + 1, st);   // warm-up (clocks settle)
+  HIP_TRY(hipEventRecord(e0, st));
+  launch_mfma_rate((const bf16_t *)operands, sink, n_cu, iters, st);
+  HIP_TRY(hipEventRecord(e1, st));
+  HIP_TRY(hipEventSynchronize(e1));
+  float ms = 0.f;
+  HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); (void)hipFree(sink);
+  if (int e = check_launch("mfma rate")) return e;
+  *tflops_out = (double)n_cu * 4 * iters * 16 * (2.0 * 32 * 32 * 16) / (ms * 1e-3) / 1e12;
+  return SWIFTKV_OK;
+}
+
 int swiftkv_op_fp8_quantize(const float *x, float scale, uint8_t *codes, int64_t n, void *stream) {
   if (!x || !codes || n < 0) return fail(SWIFTKV_EINVAL, "bad argument");
   launch_fp8_quantize(x, scale, codes, n, (hipStream_t)stream);

@@ -108,6 +108,9 @@ struct GemmParams {
   int32_t raster_gm;           // five-stage kernel: m tiles per rasterisation group (0 = default)
 };
 
+// Matrix-instruction rate on given operand data, nothing else in the loop: `iters` x 16 independent
+// v_mfma_f32_32x32x16_bf16 per wave, 4 waves per workgroup, one workgroup per CU.
+int launch_mfma_rate(const bf16_t *operands, float *sink, int32_t n_workgroups, int32_t iters, hipStream_t st);
 int launch_gemm(const GemmParams &p, int epi, int variant, hipStream_t st);
 bool gemm_uses_packed_weights(const GemmParams &p);
 

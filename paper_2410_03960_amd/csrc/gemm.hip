@@ -1478,6 +1478,39 @@ int launch_epi(const GemmParams &p, int variant, hipStream_t st) {
 
 }  // namespace
 
+// ---------------------------------------------------------------------------
+// The rate the matrix unit sustains on given data (the chip is power-limited: it depends on the
+// operand bits): every wave keeps 4 + 4 operand fragments of the caller's data in registers and
+// issues 16 independent MFMAs per iteration into 16 accumulator tiles.
+__global__ __launch_bounds__(256) void mfma_rate_kernel(const bf16_t *operands, float *sink, int iters) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {   // 8 KB per wave, 32 KB per workgroup, the same for every workgroup
+    a[i] = *(const bf16x8 *)(operands + ((wave * 8 + i) * 64 + lane) * 8);
+    b[i] = *(const bf16x8 *)(operands + ((wave * 8 + 4 + i) * 64 + lane) * 8);
+  }
+  floatx16 acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[i >> 2], acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s += acc[i][v];
+  sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+int launch_mfma_rate(const bf16_t *operands, float *sink, int32_t n_workgroups, int32_t iters, hipStream_t st) {
+  hipLaunchKernelGGL(mfma_rate_kernel, dim3(n_workgroups), dim3(256), 0, st, operands, sink, iters);
+  return 0;
+}
+
 // Whether launch_gemm(p, epi, 0, ...) reads the fragment-order copy p.wpack (and not p.W / p.wtab): the
 // driver needs to know, because that copy of a projection behind an RMSNorm has the norm's gain folded in.
 bool gemm_uses_packed_weights(const GemmParams &p) {
