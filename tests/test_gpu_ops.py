@@ -87,3 +87,15 @@ def test_fp8_quantiser_is_bit_exact():
         got = B.op_fp8_quantize((x * scale).cuda(), scale)
         torch.cuda.synchronize()
         assert torch.equal(got.cpu(), want), scale
+
+
+def test_mfma_rate_measurement_runs():
+    """The matrix-instruction rate probe returns a plausible figure (between a
+    tenth of and the data-sheet peak) and rejects bad arguments."""
+    from paper_2410_03960_amd import binding as B
+    _say("mfma rate")
+    ops = _rand_bf16(5, "ops", (16384,)).cuda()
+    rate = B.op_mfma_rate(ops, 2000)
+    assert 250.0 < rate < 2600.0, rate
+    with pytest.raises(B.SwiftKVError):
+        B.op_mfma_rate(ops, 0)
