@@ -104,6 +104,27 @@ def silu(x: torch.Tensor) -> torch.Tensor:
     return x / (1.0 + torch.exp(-x))
 
 
+ROUND_POINTS = ("a", "qkv", "p", "o", "h", "z")
+"""Places where a reduced-precision pipeline stores an activation between
+matrix products: "a" normed layer inputs, "qkv" rotated queries and the K/V
+rows, "p" softmax weights, "o" attention output, "h" residual stream, "z" the
+SwiGLU product.  All but "h" are inputs of a matrix product."""
+
+
+def _rounder(act_round):
+    """R(x, point) from the `act_round` argument of swiftkv_prefill: None (plain
+    definition), one function for every point, or a dict point -> function
+    (points not named stay exact)."""
+    if act_round is None:
+        return lambda x, point: x
+    if callable(act_round):
+        return lambda x, point: act_round(x)
+    unknown = set(act_round) - set(ROUND_POINTS)
+    if unknown:
+        raise ValueError(f"unknown rounding points {sorted(unknown)}")
+    return lambda x, point: act_round[point](x) if point in act_round else x
+
+
 # --------------------------------------------------------------------------
 # AcrossKV layer -> cache-layer map (Sec. 3.3) and paged-cache addressing
 # --------------------------------------------------------------------------
@@ -281,18 +302,18 @@ norm gains); layer0 is the 0-based layer or None for embed/final_norm/lm_head.""
 
 
 def _attn_and_mlp(sh: Shape, W, j0: int, h: torch.Tensor, q_pos: torch.Tensor,
-                  k: torch.Tensor, v: torch.Tensor, a: torch.Tensor, R=lambda x: x, act_round=None) -> torch.Tensor:
+                  k: torch.Tensor, v: torch.Tensor, a: torch.Tensor, R=lambda x, point: x) -> torch.Tensor:
     """Rest of decoder layer j0 (0-based) after its K/V are known: queries from
     the normed input `a`, attention over (k, v), O-projection, residual,
     second norm, SwiGLU MLP, residual."""
     n = h.shape[0]
     q = (a @ W("wq", j0).T).view(n, sh.n_q_heads, sh.head_dim)
-    q = R(rope(q, q_pos, sh.rope_theta))
-    o = R(gqa_attention(q, q_pos, k, v, act_round).reshape(n, sh.n_q_heads * sh.head_dim))
-    u = R(h + o @ W("wo", j0).T)
-    m = R(rmsnorm(u, W("norm2", j0), sh.rms_eps))
-    z = R(silu(m @ W("wgate", j0).T) * (m @ W("wup", j0).T))
-    return R(u + z @ W("wdown", j0).T)
+    q = R(rope(q, q_pos, sh.rope_theta), "qkv")
+    o = R(gqa_attention(q, q_pos, k, v, lambda w: R(w, "p")).reshape(n, sh.n_q_heads * sh.head_dim), "o")
+    u = R(h + o @ W("wo", j0).T, "h")
+    m = R(rmsnorm(u, W("norm2", j0), sh.rms_eps), "a")
+    z = R(silu(m @ W("wgate", j0).T) * (m @ W("wup", j0).T), "z")
+    return R(u + z @ W("wdown", j0).T, "h")
 
 
 def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
@@ -324,12 +345,14 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
     the per-sequence exit flags.
     act_round: None gives the plain definition.  A function (e.g. round to
     bfloat16 and back) is applied to every activation a reduced-precision
-    pipeline would store between matrix products (normed inputs, q/k/v,
-    softmax weights, attention output, residual stream, MLP product); the tests
+    pipeline would store between matrix products (the ROUND_POINTS: normed
+    inputs, q/k/v, softmax weights, attention output, residual stream, MLP
+    product); a dict point -> function rounds only the named points.  The tests
     use it to measure how far such storage alone moves the result on a given
-    model, which bounds what any bf16 implementation can achieve.
+    model: rounding every point but the residual stream is what bf16 matrix
+    instructions force on any implementation.  Not part of the method.
     """
-    R = (lambda x: x) if act_round is None else act_round
+    R = _rounder(act_round)
     L = sh.n_layers
     C = n_cache_layers(L, l, g)
     assert cache.C == C
@@ -359,15 +382,15 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
         a, kv = {}, {}
         for b in seqs:
             n = h[b].shape[0]
-            a[b] = R(rmsnorm(h[b], W("norm1", j0), sh.rms_eps))
+            a[b] = R(rmsnorm(h[b], W("norm1", j0), sh.rms_eps), "a")
             k = rope((a[b] @ W("wk", j0).T).view(n, sh.n_kv_heads, sh.head_dim), pos[b], sh.rope_theta)
             v = (a[b] @ W("wv", j0).T).view(n, sh.n_kv_heads, sh.head_dim)
-            kv[b] = (R(k), R(v))
+            kv[b] = (R(k, "qkv"), R(v, "qkv"))
         store(j0, kv)
         for b in seqs:
             n_ctx = int(context_lens[b]) + int(seq_lens[b])
             k_all, v_all = cache.read(j0, b, n_ctx)          # as stored (FP8: dequantised)
-            h[b] = _attn_and_mlp(sh, W, j0, h[b], pos[b], k_all, v_all, a[b], R, act_round)
+            h[b] = _attn_and_mlp(sh, W, j0, h[b], pos[b], k_all, v_all, a[b], R)
 
     # ---- Eq. 2 + AcrossKV: K/V of every later layer from x_{l+1} -----------
     for p, j in enumerate(leader_layers(L, l, g)):
@@ -375,10 +398,10 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
         kv = {}
         for b in seqs:
             n = h[b].shape[0]
-            a_p = R(rmsnorm(h[b], W("norm1", j0), sh.rms_eps))
+            a_p = R(rmsnorm(h[b], W("norm1", j0), sh.rms_eps), "a")
             k = rope((a_p @ W("wk", j0).T).view(n, sh.n_kv_heads, sh.head_dim), pos[b], sh.rope_theta)
             v = (a_p @ W("wv", j0).T).view(n, sh.n_kv_heads, sh.head_dim)
-            kv[b] = (R(k), R(v))
+            kv[b] = (R(k, "qkv"), R(v, "qkv"))
         store(l + p, kv)
 
     # ---- only the last new token continues (footnote of Sec. 3.2, Sec. 3.5) -
@@ -393,20 +416,20 @@ def swiftkv_prefill(sh: Shape, weights: WeightFn, token_ids: torch.Tensor,
         for b in seqs:
             n_ctx = int(context_lens[b]) + int(seq_lens[b])
             k_all, v_all = cache.read(c, b, n_ctx)
-            a = R(rmsnorm(t[b], W("norm1", j0), sh.rms_eps))
-            t[b] = _attn_and_mlp(sh, W, j0, t[b], tpos[b], k_all, v_all, a, R, act_round)
+            a = R(rmsnorm(t[b], W("norm1", j0), sh.rms_eps), "a")
+            t[b] = _attn_and_mlp(sh, W, j0, t[b], tpos[b], k_all, v_all, a, R)
 
     logits = torch.full((B, sh.vocab), float("nan"), dtype=dtype)
     gf, Wlm = W("final_norm"), W("lm_head")
     for b in seqs:
-        logits[b] = R(rmsnorm(t[b][-1], gf, sh.rms_eps)) @ Wlm.T
+        logits[b] = R(rmsnorm(t[b][-1], gf, sh.rms_eps), "a") @ Wlm.T
     hidden_l = {b: h[b] for b in seqs}
     if early_exit is not None:
         g_ee, w_ee, thr = early_exit
         g_ee, w_ee = g_ee.to(dtype), w_ee.to(dtype)
         exited = torch.zeros(B, dtype=torch.bool)
         for b in seqs:
-            lg = R(rmsnorm(h[b][-1], g_ee, sh.rms_eps)) @ w_ee.T
+            lg = R(rmsnorm(h[b][-1], g_ee, sh.rms_eps), "a") @ w_ee.T
             if float(torch.softmax(lg, dim=-1).max()) > thr:
                 exited[b] = True
                 logits[b] = lg
