@@ -16,9 +16,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
-# HBM-side bytes per launch of the dominant kernel (gate/up GEMM), from rocprofv3 FETCH_SIZE / WRITE_SIZE
-# scaled on a 1 GiB copy: see profiles/bench_8b_l16_b8x2048_hbm_traffic.txt (rocprofv3 cannot run inside the bench)
-MEASURED_TRAFFIC_BYTES = {("8b_l16_b8x2048", "gateup_gemm"): 5824.3 * 2 ** 20}
+# HBM-side bytes per launch of the dominant kernel (gate/up GEMM): NOT measured in this run (rocprofv3 cannot run
+# inside the bench) but taken from the committed counter run of the same command, FETCH_SIZE / WRITE_SIZE scaled
+# on a 1 GiB copy: profiles/bench_8b_l16_b8x2048_hbm_traffic.txt
+PROFILED_TRAFFIC_BYTES = {("8b_l16_b8x2048", "gateup_gemm"): 5824.3 * 2 ** 20}
+PROFILED_TRAFFIC_SOURCE = "profiles/bench_8b_l16_b8x2048_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, copy-calibrated)"
 
 
 def main():
@@ -92,17 +94,28 @@ def main():
         ctx.prefill(ids, lens, cache, logits, ws, stream)
     torch.cuda.synchronize()
     ctx.set_timing(not args.no_kernel_timing)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # step boundaries on the launch stream
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        marks[i].record(stream)
         ctx.prefill(ids, lens, cache, logits, ws, stream)
+    marks[args.steps].record(stream)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / args.steps
     tok_s = T * args.steps / dt
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     assert torch.isfinite(logits).all(), "non-finite logits"
 
     gemm_fl, attn_fl = ctx.flops(lens, batch.context_lens.tolist())
+    # the same tokens through all L layers of the unmodified model (what the paper normalises its TFLOPS
+    # figures to: footnote of the introduction, Sec. 4.2), next to the parameter-count form 2 * params * tokens
+    d, qd, kvdim, f, L = sh.hidden, sh.q_dim, sh.kv_dim, sh.ffn, sh.n_layers
+    layer_gemm = 2.0 * d * (qd + 2 * kvdim) + 2.0 * d * qd + 6.0 * d * f
+    pairs = sum(n * c + n * (n + 1) / 2.0 for c, n in zip(batch.context_lens.tolist(), lens))
+    base_fl = T * L * layer_gemm + nseq * 2.0 * d * sh.vocab + L * 4.0 * qd * pairs
+    n_params = L * (d * (qd + 2 * kvdim) + d * qd + 3 * d * f + 2 * d) + 2 * sh.vocab * d + d
     out = {
         "metric": ("prefill tokens/s, 8B-shape SwiftKV-50%; GEMM MFMA TFLOPS as % of bf16 peak" if T >= 1024
                    else "decode-step tokens/s (one new token per sequence over its cached context)"),
@@ -112,8 +125,14 @@ def main():
         "config": {"workload": wl.name, "n_seqs": nseq, "n_tokens": T, "l": wl.l, "acrosskv_group": wl.g,
                    "kv_cache": ("fp8_e4m3/" + args.kv_scales) if wl.kv_fp8 else "bf16", "n_layers": sh.n_layers,
                    "hidden": sh.hidden},
+        "ms_per_step_median": step_ms[len(step_ms) // 2], "ms_per_step_min": step_ms[0],
+        "executed_flops_per_step": gemm_fl + attn_fl,
         "executed_tflops": (gemm_fl + attn_fl) / (ms_per_step * 1e-3) / 1e12,
         "executed_frac_of_bf16_peak": (gemm_fl + attn_fl) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "normalised_to_baseline_model": {      # NOT executed work: what the unmodified L-layer model would have done
+            "flops_per_step": base_fl, "tflops": base_fl / (ms_per_step * 1e-3) / 1e12,
+            "two_params_tokens_tflops": 2.0 * n_params * T / (ms_per_step * 1e-3) / 1e12,
+            "executed_over_baseline": (gemm_fl + attn_fl) / base_fl},
         "weight_gen_s": t_gen,
     }
 
@@ -121,15 +140,26 @@ def main():
     if not args.no_kernel_timing:
         tim = ctx.get_timing()
         ctx.set_timing(False)
-        d, qd, kvdim, f = sh.hidden, sh.q_dim, sh.kv_dim, sh.ffn
         P = (sh.n_layers - wl.l) // wl.g
         per_launch_flops = {"qkv_gemm": 2.0 * T * d * (qd + 2 * kvdim), "o_gemm": 2.0 * T * d * qd,
                             "gateup_gemm": 4.0 * T * d * f, "down_gemm": 2.0 * T * d * f,
                             "fused_kv_gemm": 2.0 * T * d * P * 2 * kvdim,
                             "attn_prefill": attn_fl / max(wl.l, 1) if wl.l else 0.0}
+        # algorithmic HBM bytes per step of the bandwidth-bound classes: the normalising passes (one pass over
+        # the fp32 embeddings writing bf16 rows, then only per-row sums: 64 partial sums read, one value written),
+        # and the KV commit (reads K and V rows, writes them to their paged slots and V once more transposed)
+        esz = 1 if wl.kv_fp8 else 2
+        per_step_bytes = {
+            "norm": T * d * 6.0 + 2 * wl.l * T * (d // 64 + 1) * 4.0 if T >= 1024 else None,
+            "kv_commit": wl.l * T * kvdim * (2 * 2 + 2 * esz + 2.0) + (P * T * kvdim * 2 * (2 + esz) if wl.kv_fp8 else 0.0),
+        }
         classes, gemm_ms, gemm_flops = {}, 0.0, 0.0
         for name, (ms, n) in tim.items():
             ent = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps}
+            if per_step_bytes.get(name) and ms > 0:
+                ent["algorithmic_gbytes_per_step"] = per_step_bytes[name] / 1e9
+                ent["achieved_gb_s"] = per_step_bytes[name] / (ms / args.steps * 1e-3) / 1e9
+                ent["frac_of_hbm_peak"] = ent["achieved_gb_s"] / 8000.0
             if name in per_launch_flops and n:
                 avg_ms = ms / n
                 ent["avg_launch_ms"] = avg_ms
@@ -149,7 +179,8 @@ def main():
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": classes[dom]["tflops"] / PEAK_BF16_TFLOPS,
                     "avg_launch_ms": classes[dom]["avg_launch_ms"],
                     "flops_per_launch": per_launch_flops[dom],
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom))}
+                    "traffic": PROFILED_TRAFFIC_BYTES.get((wl.name, dom)),
+                    "traffic_source": PROFILED_TRAFFIC_SOURCE if (wl.name, dom) in PROFILED_TRAFFIC_BYTES else None}
     if T < 1024:
         # a decode step streams every weight once and each sequence's cached K/V of every cache layer once: HBM-bound
         n_par = 2 * sh.vocab * sh.hidden + sh.n_layers * (2 * sh.hidden * sh.q_dim + 3 * sh.hidden * sh.ffn) \
@@ -214,6 +245,14 @@ def cpu_baseline(wl, store, ctx, n_sample):
     t0 = time.perf_counter()
     ologits, _ = O.swiftkv_prefill(osh, wfn, sub.token_ids, [n], [0], wl.l, wl.g, ocache, dtype=torch.float32)
     dt = time.perf_counter() - t0
+    # untimed: the same prompt with the oracle rounding every matrix-product input to bf16 (what bf16 matrix
+    # instructions force on any implementation): the error floor the GPU figure below is to be read against
+    def bf16(x):
+        return x.to(torch.bfloat16).to(x.dtype)
+    fcache = O.PagedKVCache(ctx.n_cache_layers, sub.n_blocks, sh.n_kv_heads, sh.head_dim, sub.block_tables,
+                            dtype=torch.float32, fp8=wl.kv_fp8)
+    flogits, _ = O.swiftkv_prefill(osh, wfn, sub.token_ids, [n], [0], wl.l, wl.g, fcache, dtype=torch.float32,
+                                   act_round={p: bf16 for p in ("a", "qkv", "p", "o", "z")})
     # same prompt through the HIP path, for a parity figure at this shape
     cache = B.KVCache(ctx.n_cache_layers, sub.n_blocks, sh.n_kv_heads, sh.head_dim, sub.block_tables, [0],
                       fp8=wl.kv_fp8)
@@ -222,12 +261,14 @@ def cpu_baseline(wl, store, ctx, n_sample):
     logits = torch.empty((1, sh.vocab), dtype=torch.float32, device="cuda")
     ctx.prefill(sub.token_ids.cuda(), [n], cache, logits, ws)
     torch.cuda.synchronize()
-    a, b = logits[0].double().cpu(), ologits[0].double()
+    a, b, fl = logits[0].double().cpu(), ologits[0].double(), flogits[0].double()
     rel = float((a - b).abs().max() / b.abs().max())
     cos = float((a @ b) / (a.norm() * b.norm()))
     return {"value": n / dt, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
             "sample": f"first {n} tokens of sequence 0 of {wl.name} as one prompt, whole path, float32",
-            "seconds": dt, "gpu_vs_oracle_logits_rel_err": rel, "gpu_vs_oracle_logits_cosine": cos}
+            "seconds": dt, "gpu_vs_oracle_logits_rel_err": rel, "gpu_vs_oracle_logits_cosine": cos,
+            "bf16_matrix_input_floor_logits_rel_err": float((fl - b).abs().max() / b.abs().max()),
+            "bf16_matrix_input_floor_logits_cosine": float((fl @ b) / (fl.norm() * b.norm()))}
 
 
 if __name__ == "__main__":

@@ -19,13 +19,15 @@ LIB_PATH = os.path.join(_HERE, "libswiftkv.so")
 SWIFTKV_OK, SWIFTKV_EINVAL, SWIFTKV_ENOSPC, SWIFTKV_EHIP, SWIFTKV_EDATA = 0, -1, -2, -3, -4
 SWIFTKV_KV_BF16, SWIFTKV_KV_FP8_E4M3 = 0, 1
 SWIFTKV_SCALE_COMPUTE_ABSMAX, SWIFTKV_SCALE_USE_GIVEN, SWIFTKV_SCALE_PER_TOKEN = 0, 1, 2
-N_TIME_CLASSES = 8
+N_TIME_CLASSES = 10
 TIME_CLASS_NAMES = ("qkv_gemm", "o_gemm", "gateup_gemm", "down_gemm", "fused_kv_gemm",
-                    "attn_prefill", "other", "tail")
+                    "attn_prefill", "other", "tail", "norm", "kv_commit")
 
 EXPORTS = (
+    "swiftkv_pack_bytes", "swiftkv_pack_bytes_min",
     "swiftkv_create", "swiftkv_destroy", "swiftkv_workspace_bytes", "swiftkv_workspace_bytes_prefix", "swiftkv_prefill",
     "swiftkv_kv_from_hidden", "swiftkv_set_early_exit", "swiftkv_export_exit_flags", "swiftkv_export_plan", "swiftkv_export_hidden", "swiftkv_op_gemm",
+    "swiftkv_op_gemm_packed", "swiftkv_op_gemm_rows", "swiftkv_op_gemm_rows_workspace",
     "swiftkv_op_attention_prefill", "swiftkv_op_attention_workspace", "swiftkv_op_fp8_quantize", "swiftkv_op_mfma_rate",
     "swiftkv_flops", "swiftkv_set_timing", "swiftkv_get_timing", "swiftkv_last_error",
     "swiftkv_version",
@@ -71,7 +73,11 @@ def load() -> C.CDLL:
             "(or __graft_entry__.build()); there is no CPU fallback")
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
-    lib.swiftkv_create.argtypes = [C.POINTER(vp), C.POINTER(ModelCfg), C.POINTER(Weights), i32, i32]
+    lib.swiftkv_pack_bytes.argtypes = [C.POINTER(ModelCfg), i32, i32]
+    lib.swiftkv_pack_bytes.restype = C.c_size_t
+    lib.swiftkv_pack_bytes_min.argtypes = [C.POINTER(ModelCfg), i32, i32]
+    lib.swiftkv_pack_bytes_min.restype = C.c_size_t
+    lib.swiftkv_create.argtypes = [C.POINTER(vp), C.POINTER(ModelCfg), C.POINTER(Weights), i32, i32, vp, C.c_size_t, vp]
     lib.swiftkv_destroy.argtypes = [vp]
     lib.swiftkv_destroy.restype = None
     lib.swiftkv_workspace_bytes.argtypes = [vp, i64, i32, i32]
@@ -85,11 +91,15 @@ def load() -> C.CDLL:
     lib.swiftkv_export_exit_flags.argtypes = [vp, vp, vp, vp]
     lib.swiftkv_export_hidden.argtypes = [vp, vp, vp, vp]
     lib.swiftkv_op_gemm.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp]
+    lib.swiftkv_op_gemm_packed.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
+    lib.swiftkv_op_gemm_rows.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, C.c_size_t, vp]
+    lib.swiftkv_op_gemm_rows_workspace.argtypes = [i32, i32]
+    lib.swiftkv_op_gemm_rows_workspace.restype = C.c_size_t
     lib.swiftkv_op_attention_prefill.argtypes = [vp, vp, vp, vp, C.POINTER(i32), i32, i32, i32, i32, vp, C.c_size_t, vp]
     lib.swiftkv_op_attention_workspace.argtypes = [i64, i32, i32, i32]
     lib.swiftkv_op_attention_workspace.restype = C.c_size_t
     lib.swiftkv_op_fp8_quantize.argtypes = [vp, C.c_float, vp, i64, vp]
-    lib.swiftkv_op_mfma_rate.argtypes = [vp, i32, C.POINTER(C.c_double), vp]
+    lib.swiftkv_op_mfma_rate.argtypes = [vp, i32, vp, C.c_size_t, C.POINTER(C.c_double), vp]
     lib.swiftkv_flops.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.swiftkv_set_timing.argtypes = [vp, i32]
     lib.swiftkv_get_timing.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
@@ -123,17 +133,32 @@ def _dev(t: torch.Tensor, dtype=None) -> int:
 _PER_LAYER = ("norm1", "wq", "wk", "wv", "wo", "norm2", "wgate", "wup", "wdown")
 
 
+def pack_bytes(shape, l: int, g: int, minimum: bool = False) -> int:
+    """swiftkv_pack_bytes / swiftkv_pack_bytes_min."""
+    cfg = ModelCfg(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                   shape.ffn, shape.vocab, shape.rope_theta, shape.rms_eps)
+    fn = load().swiftkv_pack_bytes_min if minimum else load().swiftkv_pack_bytes
+    return int(fn(C.byref(cfg), l, g))
+
+
 class Context:
     """swiftkv_create / swiftkv_destroy.  `weights` maps "embed", "final_norm",
     "lm_head" and "<name>.<layer>" to bf16 CUDA tensors; they must outlive the
-    context (a reference is kept here)."""
+    context (a reference is kept here).  The pack buffer is a torch allocation
+    of swiftkv_pack_bytes() bytes (swiftkv_pack_bytes_min() with
+    packed_weights=False), kept alive here as well."""
 
-    def __init__(self, shape, weights: Dict[str, torch.Tensor], l: int, g: int):
+    def __init__(self, shape, weights: Dict[str, torch.Tensor], l: int, g: int, packed_weights: bool = True,
+                 stream=None):
         lib = load()
         self.shape, self.l, self.g = shape, l, g
         self._weights = weights
         cfg = ModelCfg(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                        shape.ffn, shape.vocab, shape.rope_theta, shape.rms_eps)
+        n_pack = pack_bytes(shape, l, g, minimum=not packed_weights)
+        if n_pack == 0:
+            _check(lib.swiftkv_create(C.byref(C.c_void_p()), C.byref(cfg), C.byref(Weights()), l, g, None, 0, None))
+        self.pack_buf = torch.empty(n_pack, dtype=torch.uint8, device=weights["embed"].device)
         w = Weights()
         self._arrays = {}
         for n in _PER_LAYER:
@@ -147,7 +172,8 @@ class Context:
         w.final_norm = _dev(weights["final_norm"], torch.bfloat16)
         w.lm_head = _dev(weights["lm_head"], torch.bfloat16)
         self._h = C.c_void_p()
-        _check(lib.swiftkv_create(C.byref(self._h), C.byref(cfg), C.byref(w), l, g))
+        _check(lib.swiftkv_create(C.byref(self._h), C.byref(cfg), C.byref(w), l, g, _dev(self.pack_buf),
+                                  self.pack_buf.numel(), _stream_ptr(stream)))
         self.n_cache_layers = l + (shape.n_layers - l) // g
 
     def close(self):
@@ -256,7 +282,8 @@ def op_mfma_rate(operands: torch.Tensor, iters: int = 20000, stream=None) -> flo
     """TFLOP/s of MFMA instructions alone on `operands` (bf16 CUDA tensor, >= 16384 elements)."""
     assert operands.dtype == torch.bfloat16 and operands.numel() >= 16384 and operands.is_contiguous()
     out = C.c_double(0.0)
-    _check(load().swiftkv_op_mfma_rate(_dev(operands), iters, C.byref(out), _stream_ptr(stream)))
+    sink = torch.empty(1 << 20, dtype=torch.uint8, device=operands.device)
+    _check(load().swiftkv_op_mfma_rate(_dev(operands), iters, _dev(sink), sink.numel(), C.byref(out), _stream_ptr(stream)))
     return float(out.value)
 
 
@@ -268,6 +295,29 @@ def op_gemm(A: torch.Tensor, W: torch.Tensor, out_f32: bool = False, variant: in
         out = torch.empty((M, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device=A.device)
     _check(load().swiftkv_op_gemm(_dev(A, torch.bfloat16), _dev(W, torch.bfloat16), _dev(out), M, N, K,
                                   int(out_f32), variant, _stream_ptr(stream)))
+    return out
+
+
+def op_gemm_packed(A: torch.Tensor, W: torch.Tensor, stream=None) -> torch.Tensor:
+    """bf16 product through the packed-weight loop (W is re-arranged into a scratch tensor first)."""
+    M, K = A.shape
+    N = W.shape[0]
+    out = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+    scratch = torch.empty_like(W)
+    _check(load().swiftkv_op_gemm_packed(_dev(A, torch.bfloat16), _dev(W, torch.bfloat16), _dev(scratch), _dev(out),
+                                         M, N, K, _stream_ptr(stream)))
+    return out
+
+
+def op_gemm_rows(A: torch.Tensor, W: torch.Tensor, out_f32: bool = False, stream=None) -> torch.Tensor:
+    """Weight-streaming GEMM for M <= 80 rows with its K-split scratch in a caller workspace."""
+    M, K = A.shape
+    N = W.shape[0]
+    lib = load()
+    ws = torch.empty(int(lib.swiftkv_op_gemm_rows_workspace(M, N)), dtype=torch.uint8, device=A.device)
+    out = torch.empty((M, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device=A.device)
+    _check(lib.swiftkv_op_gemm_rows(_dev(A, torch.bfloat16), _dev(W, torch.bfloat16), _dev(out), M, N, K, int(out_f32),
+                                    _dev(ws), ws.numel(), _stream_ptr(stream)))
     return out
 
 

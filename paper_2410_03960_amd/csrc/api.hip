@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <memory>
 #include <string>
 #include <array>
 #include <vector>
@@ -33,8 +34,10 @@ int fail(int code, const char *fmt, ...) {
   } while (0)
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+constexpr int PIN_SLOTS = 8;
 
-enum TimeClass { TC_QKV = 0, TC_O, TC_GATEUP, TC_DOWN, TC_KV, TC_ATTN, TC_OTHER, TC_TAIL, TC_COUNT };
+enum TimeClass { TC_QKV = 0, TC_O, TC_GATEUP, TC_DOWN, TC_KV, TC_ATTN, TC_OTHER, TC_TAIL, TC_NORM, TC_COMMIT, TC_COUNT };
+static_assert(TC_COUNT == SWIFTKV_N_TIME_CLASSES, "time classes");
 
 struct Layout {  // byte offsets into the workspace
   int64_t T = 0;
@@ -42,7 +45,7 @@ struct Layout {  // byte offsets into the workspace
   int64_t vt_ld = 0;
   int32_t n_qblocks = 0, n_kvtiles = 0, n_dec = 0, n_gtiles = 0;
   int64_t kcat_rows = 0;   // rows of the K buffer gathered from the cache (prompt chunks over a cached prefix), else 0
-  size_t err, meta, positions, seq_of, last_rows, slots, cos_sin, h, a, rstd, q, k, v, o, vt, kcat, z, stage, amax, qkv32, skpart, ee_logits, ee_flags;
+  size_t err, meta, positions, seq_of, last_rows, slots, cos_sin, h, a, rstd, ssq, q, k, v, o, vt, kcat, z, stage, amax, qkv32, skpart, ee_logits, ee_flags;
   size_t th, ta, tq, to, tz, partial, total;
   // offsets (in int32 units) inside the meta block copied from the host
   size_t m_cu, m_ctx, m_qblocks, m_kvtiles, m_dec, m_tail, m_gtiles, m_words;
@@ -56,14 +59,19 @@ struct swiftkv_ctx {
   int device;
   std::vector<const bf16_t *> norm1, wq, wk, wv, wo, norm2, wgate, wup, wdown;
   const bf16_t *embed, *final_norm, *lm_head;
-  // device tables
-  void *dev_tables = nullptr;
-  std::vector<const bf16_t *const *> qkv_tab, gu_tab, norm1_tab, norm2_tab;
+  // everything below up to kvf_pack points into the caller's pack buffer
+  std::vector<const bf16_t *const *> qkv_tab, gu_tab;   // row-block pointer tables (16 rows per entry)
   bf16_t *kv_pack = nullptr;   // [P * 2 * kv_dim, hidden]: leaders' [W_K; W_V] with their norm gain folded in
-  // O, gate/up (interleaved) and down weights of the full layers (< l) in MFMA fragment order, or empty
-  bf16_t *w_pack = nullptr;
+  // QKV, O, gate/up (interleaved) and down weights of the full layers (< l) in MFMA fragment order, or null
+  bool have_wpack = false;
   std::vector<const bf16_t *> qkv_pack, wo_pack, gu_pack, down_pack;
   const bf16_t *kvf_pack = nullptr;   // the fused KV operand (kv_pack) in fragment order
+  // pinned staging ring for the per-call plan words: a slot is reused only after the copy that read it has run
+  unsigned char *pin = nullptr;
+  size_t pin_slot_bytes = 0;
+  int pin_next = 0;
+  hipEvent_t pin_ev[PIN_SLOTS] = {};
+  bool pin_used[PIN_SLOTS] = {};
   // simple early exit of the continuing tokens (off unless swiftkv_set_early_exit was called)
   const bf16_t *ee_gain = nullptr, *ee_head = nullptr;
   float ee_threshold = 0.f;
@@ -74,6 +82,12 @@ struct swiftkv_ctx {
   std::vector<hipEvent_t> ev;
   std::vector<int> ev_class;
   size_t ev_used = 0;
+  ~swiftkv_ctx() {   // host memory and events only
+    if (pin) (void)hipHostFree(pin);
+    for (hipEvent_t e : pin_ev)
+      if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+  }
 };
 
 namespace {
@@ -107,9 +121,10 @@ Layout make_layout(const swiftkv_ctx *c, int64_t T, int32_t B, int64_t vt_ld, in
   L.last_rows = take((size_t)B * 4);
   L.slots = take(T * 8);
   L.cos_sin = take(T * (m.head_dim / 2) * 8);
-  L.h = take(T * d * 2);
-  L.a = take(T * d * 2);
+  L.h = take(T * d * 4);      // residual stream, fp32
+  L.a = take(T * d * 2);      // bf16 operand of the next projection (normed rows, or rows times the norm gain)
   L.rstd = take(T * 4);
+  L.ssq = take((size_t)((d + 63) / 64) * T * 4);   // sums of squares per 64-column block from the residual epilogues
   L.q = take(T * qd * 2);
   L.k = take(T * kvd * 2);
   L.v = take(T * kvd * 2);
@@ -123,7 +138,7 @@ Layout make_layout(const swiftkv_ctx *c, int64_t T, int32_t B, int64_t vt_ld, in
   L.ee_flags = take((size_t)B * 4);
   L.skpart = take(SKINNY_PARTIAL_BYTES);   // K-split partial sums of the weight-streaming GEMMs
   L.qkv32 = take((size_t)std::min<int64_t>(T, SKINNY_MAX_ROWS) * (qd + 2 * kvd) * 4);   // fp32 Q, K, V of few-row batches
-  L.th = take((size_t)B * d * 2);
+  L.th = take((size_t)B * d * 4);
   L.ta = take((size_t)B * std::max<int64_t>(d, qd) * 2);
   L.tq = take((size_t)B * qd * 2);
   L.to = take((size_t)B * qd * 2);
@@ -293,9 +308,34 @@ struct Run {
   }
 };
 
+// (Re)allocate the pinned staging ring with slots of at least `need` bytes.  Host memory only.
+int pin_reserve(swiftkv_ctx *c, size_t need) {
+  if (c->pin && need <= c->pin_slot_bytes) return 0;
+  for (int i = 0; i < PIN_SLOTS; ++i)
+    if (c->pin_used[i]) { HIP_TRY(hipEventSynchronize(c->pin_ev[i])); c->pin_used[i] = false; }
+  if (c->pin) { HIP_TRY(hipHostFree(c->pin)); c->pin = nullptr; c->pin_slot_bytes = 0; }
+  const size_t slot = align_up(std::max<size_t>(2 * need, 64 << 10), 4096);
+  HIP_TRY(hipHostMalloc((void **)&c->pin, slot * PIN_SLOTS, hipHostMallocDefault));
+  c->pin_slot_bytes = slot;
+  for (int i = 0; i < PIN_SLOTS; ++i)
+    if (!c->pin_ev[i]) HIP_TRY(hipEventCreateWithFlags(&c->pin_ev[i], hipEventDisableTiming));
+  return 0;
+}
+
 int run_plan(Run &r, const int32_t *token_ids) {
   swiftkv_ctx *c = r.c;
-  HIP_TRY(hipMemcpyAsync(r.ws + r.L.meta, r.hp.meta.data(), r.hp.meta.size() * 4, hipMemcpyHostToDevice, r.st));
+  // plan words: host vector -> pinned slot -> device, without waiting for the stream (a slot is only
+  // waited for when the ring wraps around onto a copy that has not run yet)
+  const size_t bytes = r.hp.meta.size() * 4;
+  if (int e = pin_reserve(c, bytes)) return e;
+  const int slot = c->pin_next;
+  c->pin_next = (slot + 1) % PIN_SLOTS;
+  if (c->pin_used[slot]) HIP_TRY(hipEventSynchronize(c->pin_ev[slot]));
+  unsigned char *stage = c->pin + (size_t)slot * c->pin_slot_bytes;
+  memcpy(stage, r.hp.meta.data(), bytes);
+  HIP_TRY(hipMemcpyAsync(r.ws + r.L.meta, stage, bytes, hipMemcpyHostToDevice, r.st));
+  HIP_TRY(hipEventRecord(c->pin_ev[slot], r.st));
+  c->pin_used[slot] = true;
   launch_fill_u32(r.at<uint32_t>(r.L.err), 0, 16, r.st);   // error flags, and (words 4..12) the attention kernel's item counters
   if (r.fp8) launch_fill_u32(r.at<uint32_t>(r.L.amax), 0, (int64_t)c->C * 2 * c->cfg.n_kv_heads, r.st);
   PlanParams pp{};
@@ -311,13 +351,16 @@ int run_plan(Run &r, const int32_t *token_ids) {
 }
 
 // Eq. 2 + AcrossKV: one GEMM over the concatenated leader [W_K;W_V] matrices.
-int run_fused_kv(Run &r, const bf16_t *hidden, Timer &tm) {
+// `hidden` = the layer-l output rounded to bf16; 1/rms of its rows is already in the workspace when rstd_ready
+int run_fused_kv(Run &r, const bf16_t *hidden, bool rstd_ready, Timer &tm) {
   swiftkv_ctx *c = r.c;
   const swiftkv_model_cfg &m = c->cfg;
   const int kvd = m.n_kv_heads * m.head_dim;
-  tm.begin(TC_OTHER);
-  launch_rstd(hidden, r.at<float>(r.L.rstd), (int32_t)r.L.T, m.hidden, m.rms_eps, r.st);
-  tm.end();
+  if (!rstd_ready) {
+    tm.begin(TC_NORM);
+    launch_rstd(hidden, r.at<float>(r.L.rstd), (int32_t)r.L.T, m.hidden, m.rms_eps, r.st);
+    tm.end();
+  }
   GemmParams g{};
   g.A = hidden; g.lda = m.hidden; g.M = (int32_t)r.L.T; g.N = c->P * 2 * kvd; g.K = m.hidden;
   g.W = c->kv_pack; g.ldw = m.hidden; g.wpack = c->kvf_pack;   // gains are folded into kv_pack; rstd is applied in the epilogue
@@ -334,7 +377,7 @@ int run_fused_kv(Run &r, const bf16_t *hidden, Timer &tm) {
   tm.end();
   if (int e = check_launch("fused KV GEMM")) return e;
   if (r.fp8) {
-    tm.begin(TC_OTHER);
+    tm.begin(TC_COMMIT);
     for (int p = 0; p < c->P; ++p) {
       const int cl = c->l + p;
       CommitParams cp{};
@@ -363,7 +406,7 @@ int run_fused_kv(Run &r, const bf16_t *hidden, Timer &tm) {
 int tail_gemm(const swiftkv_ctx *c, const bf16_t *A, int M, int N, int K, const bf16_t *W, const bf16_t *W2,
               const bf16_t *const *gu_tab, void *C, int epi, float *partial, hipStream_t st) {
   if (M <= 80) {
-    SkinnyParams s{A, M, N, K, W, W2, C, partial};
+    SkinnyParams s{A, M, N, K, W, W2, C, partial, SKINNY_PARTIAL_BYTES};
     return launch_skinny(s, epi, st);
   }
   GemmParams g{};
@@ -381,10 +424,8 @@ extern "C" {
 const char *swiftkv_last_error(void) { return g_err; }
 const char *swiftkv_version(void) { return "swiftkv-gfx950 0.1"; }
 
-int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftkv_weights *w, int32_t l, int32_t g) {
-  if (!out || !cfg || !w) return fail(SWIFTKV_EINVAL, "null argument");
-  *out = nullptr;
-  const swiftkv_model_cfg &m = *cfg;
+// Validation of (shape, l, g) shared by the size calls and swiftkv_create; 0 = fine.
+static int check_model(const swiftkv_model_cfg &m, int32_t l, int32_t g) {
   if (m.n_layers < 1 || m.hidden < 16 || m.n_q_heads < 1 || m.n_kv_heads < 1 || m.ffn < 16 || m.vocab < 16)
     return fail(SWIFTKV_EINVAL, "bad model shape");
   if (m.head_dim != 64 && m.head_dim != 128) return fail(SWIFTKV_EINVAL, "head_dim must be 64 or 128, got %d", m.head_dim);
@@ -396,10 +437,59 @@ int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftk
   if (m.hidden % 16 || m.ffn % 16 || m.vocab % 16) return fail(SWIFTKV_EINVAL, "hidden, ffn and vocab must be multiples of 16");
   if (l < 1 || l > m.n_layers) return fail(SWIFTKV_EINVAL, "l = %d outside [1, %d]", l, m.n_layers);
   if (g < 1 || (m.n_layers - l) % g) return fail(SWIFTKV_EINVAL, "(n_layers - l) = %d is not divisible by acrosskv_group = %d", m.n_layers - l, g);
+  return 0;
+}
+
+// Layout of the caller's pack buffer (byte offsets, 256-byte aligned pieces).
+struct PackLayout {
+  size_t tab_entries, tables, kv_pack, w_pack, min_total, full_total;
+  size_t e_qkv, e_o, e_gu, e_dn, per_layer, e_kvf;   // elements of the fragment-order copies
+  bool can_pack;
+};
+static PackLayout pack_layout(const swiftkv_model_cfg &m, int32_t l, int32_t g) {
+  PackLayout p{};
+  const size_t d = m.hidden, qd = (size_t)m.n_q_heads * m.head_dim, kvd = (size_t)m.n_kv_heads * m.head_dim;
+  const size_t P = (size_t)(m.n_layers - l) / g;
+  p.tab_entries = (size_t)m.n_layers * ((qd + 2 * kvd) / 16 + 2 * ((size_t)m.ffn / 16)) + 1;
+  p.tables = 0;
+  p.kv_pack = align_up(p.tab_entries * sizeof(void *));
+  p.w_pack = p.kv_pack + align_up(P * 2 * kvd * d * 2);
+  p.min_total = p.w_pack;
+  p.can_pack = (d % 256) == 0 && (qd % 256) == 0 && (m.ffn % 256) == 0 && (kvd % 128) == 0;
+  p.e_qkv = (qd + 2 * kvd) * d; p.e_o = d * qd; p.e_gu = (size_t)2 * m.ffn * d; p.e_dn = d * (size_t)m.ffn;
+  p.per_layer = p.e_qkv + p.e_o + p.e_gu + p.e_dn;
+  p.e_kvf = P * 2 * kvd * d;
+  p.full_total = p.can_pack ? p.w_pack + align_up((p.per_layer * l + p.e_kvf) * 2) : p.min_total;
+  return p;
+}
+
+size_t swiftkv_pack_bytes(const swiftkv_model_cfg *cfg, int32_t l, int32_t g) {
+  if (!cfg || check_model(*cfg, l, g)) return 0;
+  return pack_layout(*cfg, l, g).full_total;
+}
+size_t swiftkv_pack_bytes_min(const swiftkv_model_cfg *cfg, int32_t l, int32_t g) {
+  if (!cfg || check_model(*cfg, l, g)) return 0;
+  return pack_layout(*cfg, l, g).min_total;
+}
+
+int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftkv_weights *w, int32_t l, int32_t g,
+                   void *pack_buf, size_t pack_bytes, void *stream) {
+  if (!out || !cfg || !w) return fail(SWIFTKV_EINVAL, "null argument");
+  *out = nullptr;
+  const swiftkv_model_cfg &m = *cfg;
+  if (int e = check_model(m, l, g)) return e;
+  const int qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
   if (!w->embed || !w->final_norm || !w->lm_head || !w->norm1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->norm2 ||
       !w->wgate || !w->wup || !w->wdown)
     return fail(SWIFTKV_EINVAL, "null weight array");
-  swiftkv_ctx *c = new swiftkv_ctx();
+  const PackLayout pl = pack_layout(m, l, g);
+  if (!pack_buf || pack_bytes < pl.min_total)
+    return fail(SWIFTKV_ENOSPC, "pack buffer has %zu bytes, at least %zu needed (%zu for the fragment-order copies as well)",
+                pack_buf ? pack_bytes : (size_t)0, pl.min_total, pl.full_total);
+  if (((uintptr_t)pack_buf & 255) != 0) return fail(SWIFTKV_EINVAL, "pack_buf must be 256-byte aligned");
+  hipStream_t st = (hipStream_t)stream;
+  unsigned char *pb = (unsigned char *)pack_buf;
+  std::unique_ptr<swiftkv_ctx> c(new swiftkv_ctx());
   c->cfg = m; c->l = l; c->g = g; c->P = (m.n_layers - l) / g; c->C = l + c->P;
   c->embed = (const bf16_t *)w->embed; c->final_norm = (const bf16_t *)w->final_norm; c->lm_head = (const bf16_t *)w->lm_head;
   auto grab = [&](std::vector<const bf16_t *> &v, const void *const *src) {
@@ -411,14 +501,14 @@ int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftk
   for (int j = 0; j < m.n_layers; ++j) {
     const bool need_kv = j < l || ((j - l) % g == 0);
     if (!c->norm1[j] || !c->wq[j] || !c->wo[j] || !c->norm2[j] || !c->wgate[j] || !c->wup[j] || !c->wdown[j] ||
-        (need_kv && (!c->wk[j] || !c->wv[j]))) {
-      delete c;
+        (need_kv && (!c->wk[j] || !c->wv[j])))
       return fail(SWIFTKV_EINVAL, "layer %d has a null weight pointer", j);
-    }
   }
-  // ---- row-block pointer tables (16 rows per entry) ----
+  if (hipGetDevice(&c->device) != hipSuccess) return fail(SWIFTKV_EHIP, "no current device");
+  if (int e = pin_reserve(c.get(), 0)) return e;
+  // ---- row-block pointer tables (16 rows per entry): [W_Q;W_K;W_V] and the 16-row interleave of W_gate/W_up ----
   std::vector<const bf16_t *> tab;
-  std::vector<size_t> off_qkv(m.n_layers), off_gu(m.n_layers), off_n1(m.n_layers), off_n2(m.n_layers);
+  std::vector<size_t> off_qkv(m.n_layers), off_gu(m.n_layers);
   const int64_t d = m.hidden;
   for (int j = 0; j < m.n_layers; ++j) {
     off_qkv[j] = tab.size();
@@ -430,100 +520,52 @@ int swiftkv_create(swiftkv_ctx **out, const swiftkv_model_cfg *cfg, const swiftk
       tab.push_back(c->wgate[j] + (int64_t)r * d);
       tab.push_back(c->wup[j] + (int64_t)r * d);
     }
-    off_n1[j] = tab.size(); tab.push_back(c->norm1[j]);
-    off_n2[j] = tab.size(); tab.push_back(c->norm2[j]);
   }
   tab.push_back(nullptr);
-  hipError_t e = hipGetDevice(&c->device);
-  if (e == hipSuccess) e = hipMalloc(&c->dev_tables, tab.size() * sizeof(void *));
-  if (e == hipSuccess) e = hipMemcpy(c->dev_tables, tab.data(), tab.size() * sizeof(void *), hipMemcpyHostToDevice);
-  if (e != hipSuccess) {
-    if (c->dev_tables) (void)hipFree(c->dev_tables);
-    delete c;
-    return fail(SWIFTKV_EHIP, "building weight tables: %s", hipGetErrorString(e));
-  }
-  const bf16_t *const *base = (const bf16_t *const *)c->dev_tables;
-  c->qkv_tab.resize(m.n_layers); c->gu_tab.resize(m.n_layers); c->norm1_tab.resize(m.n_layers); c->norm2_tab.resize(m.n_layers);
-  for (int j = 0; j < m.n_layers; ++j) {
-    c->qkv_tab[j] = base + off_qkv[j]; c->gu_tab[j] = base + off_gu[j];
-    c->norm1_tab[j] = base + off_n1[j]; c->norm2_tab[j] = base + off_n2[j];
-  }
+  if (tab.size() != pl.tab_entries) return fail(SWIFTKV_EINVAL, "internal: table size");
+  HIP_TRY(hipMemcpyAsync(pb + pl.tables, tab.data(), tab.size() * sizeof(void *), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipStreamSynchronize(st));   // `tab` is pageable host memory: the copy must have read it before it goes away
+  const bf16_t *const *base = (const bf16_t *const *)(pb + pl.tables);
+  c->qkv_tab.resize(m.n_layers); c->gu_tab.resize(m.n_layers);
+  for (int j = 0; j < m.n_layers; ++j) { c->qkv_tab[j] = base + off_qkv[j]; c->gu_tab[j] = base + off_gu[j]; }
   if (c->P > 0) {
     // one operand for the single KV GEMM of Eq. 2: [W_K^j; W_V^j] diag(g1_j) of every group leader j
-    const size_t pack_elems = (size_t)c->P * 2 * kvd * d;
-    e = hipMalloc((void **)&c->kv_pack, pack_elems * 2);
-    if (e != hipSuccess) {
-      (void)hipFree(c->dev_tables);
-      delete c;
-      return fail(SWIFTKV_EHIP, "allocating the fused KV weight (%zu bytes): %s", pack_elems * 2, hipGetErrorString(e));
-    }
+    c->kv_pack = (bf16_t *)(pb + pl.kv_pack);
     for (int p = 0; p < c->P; ++p) {
       const int j = l + p * g;
       bf16_t *dst = c->kv_pack + (size_t)p * 2 * kvd * d;
-      launch_fold_gain(c->wk[j], c->norm1[j], dst, kvd, m.hidden, nullptr);
-      launch_fold_gain(c->wv[j], c->norm1[j], dst + (size_t)kvd * d, kvd, m.hidden, nullptr);
-    }
-    e = hipDeviceSynchronize();
-    if (e != hipSuccess) {
-      (void)hipFree(c->kv_pack); (void)hipFree(c->dev_tables);
-      delete c;
-      return fail(SWIFTKV_EHIP, "folding gains into the fused KV weight: %s", hipGetErrorString(e));
+      launch_fold_gain(c->wk[j], c->norm1[j], dst, kvd, m.hidden, st);
+      launch_fold_gain(c->wv[j], c->norm1[j], dst + (size_t)kvd * d, kvd, m.hidden, st);
     }
   }
-  // Fragment-order copies of the large GEMM weights of the layers every token runs (library-owned,
-  // about 0.75 x the size of those layers' weights).  SWIFTKV_PACKED_W=0 keeps the LDS-staged loop.
+  // Fragment-order copies of the large GEMM weights of the layers every token runs, when the caller gave room
   c->qkv_pack.assign(m.n_layers, nullptr); c->wo_pack.assign(m.n_layers, nullptr);
   c->gu_pack.assign(m.n_layers, nullptr); c->down_pack.assign(m.n_layers, nullptr);
-  const char *pw = getenv("SWIFTKV_PACKED_W");
-  const bool shapes_ok = (d % 256) == 0 && (qd % 256) == 0 && (m.ffn % 256) == 0 && (kvd % 128) == 0;
-  if (shapes_ok && !(pw && atoi(pw) == 0)) {
-    const size_t e_qkv = (size_t)(qd + 2 * kvd) * d, e_o = (size_t)d * qd, e_gu = (size_t)2 * m.ffn * d, e_dn = (size_t)d * m.ffn;
-    const size_t per_layer = e_qkv + e_o + e_gu + e_dn;
-    const size_t e_kvf = (size_t)c->P * 2 * kvd * d;
-    const size_t total_elems = per_layer * l + e_kvf;
-    e = hipMalloc((void **)&c->w_pack, total_elems * 2);
-    if (e != hipSuccess) {
-      if (c->kv_pack) (void)hipFree(c->kv_pack);
-      (void)hipFree(c->dev_tables);
-      delete c;
-      return fail(SWIFTKV_EHIP, "allocating the fragment-order weight copies (%zu bytes; SWIFTKV_PACKED_W=0 does without): %s",
-                  total_elems * 2, hipGetErrorString(e));
-    }
+  if (pl.can_pack && pack_bytes >= pl.full_total) {
+    bf16_t *wp = (bf16_t *)(pb + pl.w_pack);
     const int rope_hd = m.head_dim == 128 ? 128 : 0;   // rotary partner blocks side by side (see pack_w_kernel)
     for (int j = 0; j < l; ++j) {
-      bf16_t *pq = c->w_pack + (size_t)j * per_layer, *po = pq + e_qkv, *pgu = po + e_o, *pdn = pgu + e_gu;
-      launch_pack_w(c->qkv_tab[j], nullptr, d, qd + 2 * kvd, (int32_t)d, rope_hd, c->norm1[j], pq, nullptr);   // input-norm gain folded in
-      launch_pack_w(nullptr, c->wo[j], qd, (int32_t)d, qd, 0, nullptr, po, nullptr);
-      launch_pack_w(c->gu_tab[j], nullptr, d, 2 * m.ffn, (int32_t)d, 0, c->norm2[j], pgu, nullptr);   // post-attention-norm gain folded in
-      launch_pack_w(nullptr, c->wdown[j], m.ffn, (int32_t)d, m.ffn, 0, nullptr, pdn, nullptr);
+      bf16_t *pq = wp + (size_t)j * pl.per_layer, *po = pq + pl.e_qkv, *pgu = po + pl.e_o, *pdn = pgu + pl.e_gu;
+      launch_pack_w(c->qkv_tab[j], nullptr, d, qd + 2 * kvd, (int32_t)d, rope_hd, pq, st);
+      launch_pack_w(nullptr, c->wo[j], qd, (int32_t)d, qd, 0, po, st);
+      launch_pack_w(c->gu_tab[j], nullptr, d, 2 * m.ffn, (int32_t)d, 0, pgu, st);
+      launch_pack_w(nullptr, c->wdown[j], m.ffn, (int32_t)d, m.ffn, 0, pdn, st);
       c->qkv_pack[j] = pq; c->wo_pack[j] = po; c->gu_pack[j] = pgu; c->down_pack[j] = pdn;
     }
-    if (c->P > 0 && ((c->P * 2 * kvd) % 256) == 0) {
-      bf16_t *pk = c->w_pack + per_layer * l;
-      launch_pack_w(nullptr, c->kv_pack, d, c->P * 2 * kvd, (int32_t)d, rope_hd, nullptr, pk, nullptr);
+    if (c->P > 0) {
+      bf16_t *pk = wp + pl.per_layer * l;
+      launch_pack_w(nullptr, c->kv_pack, d, c->P * 2 * kvd, (int32_t)d, rope_hd, pk, st);
       c->kvf_pack = pk;
     }
-    e = hipDeviceSynchronize();
-    if (e != hipSuccess) {
-      (void)hipFree(c->w_pack);
-      if (c->kv_pack) (void)hipFree(c->kv_pack);
-      (void)hipFree(c->dev_tables);
-      delete c;
-      return fail(SWIFTKV_EHIP, "packing weights: %s", hipGetErrorString(e));
-    }
+    c->have_wpack = true;
   }
-  *out = c;
+  if (int e = check_launch("weight packing")) return e;
+  HIP_TRY(hipStreamSynchronize(st));
+  *out = c.release();
   return SWIFTKV_OK;
 }
 
-void swiftkv_destroy(swiftkv_ctx *c) {
-  if (!c) return;
-  if (c->dev_tables) (void)hipFree(c->dev_tables);
-  if (c->kv_pack) (void)hipFree(c->kv_pack);
-  if (c->w_pack) (void)hipFree(c->w_pack);
-  for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
-  delete c;
-}
+void swiftkv_destroy(swiftkv_ctx *c) { delete c; }
 
 size_t swiftkv_workspace_bytes_prefix(const swiftkv_ctx *c, int64_t max_tokens, int32_t max_seqs, int32_t kv_dtype,
                                       int64_t max_prefix_tokens) {
@@ -606,6 +648,11 @@ static int setup_run(Run &r, swiftkv_ctx *c, const int32_t *seq_lens, int32_t B,
   r.esz = r.fp8 ? 1 : 2;
   r.plane = (int64_t)kv->n_blocks * SKV_BLOCK * c->cfg.n_kv_heads * c->cfg.head_dim;
   r.layer_stride = 2 * r.plane;
+  if (r.fp8 && kv->scale_mode == SWIFTKV_SCALE_COMPUTE_ABSMAX && kv->context_lens)
+    for (int b = 0; b < B; ++b)
+      if (kv->context_lens[b] > 0)
+        return fail(SWIFTKV_EINVAL, "FP8 cache with computed per-head scales: sequence %d has %d cached tokens, whose codes were "
+                    "stored under other scales (use SWIFTKV_SCALE_USE_GIVEN or SWIFTKV_SCALE_PER_TOKEN)", b, kv->context_lens[b]);
   if (int e = build_host_plan(c, seq_lens, kv->context_lens, B, kv->max_blocks_per_seq, r.hp, r.L, r.fp8)) return e;
   if (r.L.total > workspace_bytes)
     return fail(SWIFTKV_ENOSPC, "workspace has %zu bytes, %zu needed", workspace_bytes, r.L.total);
@@ -621,7 +668,7 @@ int swiftkv_kv_from_hidden(swiftkv_ctx *c, const void *hidden_l, const int32_t *
   if (c->P == 0) return fail(SWIFTKV_EINVAL, "l == n_layers: there are no later layers to project for");
   if (int e = run_plan(r, nullptr)) return e;
   Timer tm{c, r.st};
-  if (int e = run_fused_kv(r, (const bf16_t *)hidden_l, tm)) return e;
+  if (int e = run_fused_kv(r, (const bf16_t *)hidden_l, false, tm)) return e;
   c->last = r.L; c->have_last = true;
   return SWIFTKV_OK;
 }
@@ -638,32 +685,36 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   Timer tm{c, st};
   tm.begin(TC_OTHER);
   if (int e = run_plan(r, token_ids)) return e;
-  bf16_t *h = r.at<bf16_t>(r.L.h);
+  float *h = r.at<float>(r.L.h);             // residual stream, fp32 [T, d]
   launch_embed(token_ids, c->embed, h, T, d, m.vocab, st);
   tm.end();
-  bf16_t *ab = r.at<bf16_t>(r.L.a);
+  bf16_t *ab = r.at<bf16_t>(r.L.a);          // bf16 operand of the projection behind an RMSNorm
   bf16_t *qb = r.at<bf16_t>(r.L.q), *kb = r.at<bf16_t>(r.L.k), *vb = r.at<bf16_t>(r.L.v), *ob = r.at<bf16_t>(r.L.o);
   bf16_t *vt = r.at<bf16_t>(r.L.vt), *zb = r.at<bf16_t>(r.L.z);
   const bool compute_scale = r.fp8 && kv->scale_mode == SWIFTKV_SCALE_COMPUTE_ABSMAX;
   const bool few_rows = T <= SKINNY_MAX_ROWS;
   float *skp = r.at<float>(r.L.skpart);
+  float *rstd = r.at<float>(r.L.rstd), *ssq = r.at<float>(r.L.ssq);
 
   // ------------------------------------------ layers 1..l on every new token ----
-  // The fragment-order copies of [Wq;Wk;Wv] and [Wgate;Wup] carry the gain of the RMSNorm in front of
-  // them.  When a GEMM reads that copy, its A operand is the residual stream itself and 1/rms of each
-  // row (one read-only pass) is applied in the epilogue; otherwise the rows are normalised first.
-  auto uses_packed = [&](const bf16_t *wpack, int N) {
-    GemmParams t{};
-    t.wpack = wpack; t.M = T; t.K = d; t.N = N;
-    return !few_rows && gemm_uses_packed_weights(t);
-  };
-  float *rstd = r.at<float>(r.L.rstd);
-  for (int j = 0; j < c->l; ++j) {
-    const bool fold1 = uses_packed(c->qkv_pack[j], qd + 2 * kvd), fold2 = uses_packed(c->gu_pack[j], 2 * m.ffn);
-    tm.begin(TC_OTHER);
-    if (fold1) launch_rstd(h, rstd, T, d, m.rms_eps, st);
-    else launch_rmsnorm_rows(h, c->norm1[j], ab, T, d, m.rms_eps, st);
+  // Two forms of the RMSNorm in front of the QKV and gate/up projections.
+  // (a) Fragment-order weights (large batches): the residual epilogue of the O / down GEMM leaves, next to
+  //     the fp32 residual stream, ab = bf16(h * gain of the next norm) and the rows' sums of squares; the
+  //     next projection reads ab and applies 1/rms as a row factor in its own epilogue.  No pass over h.
+  // (b) Otherwise one kernel per norm turns fp32 rows into normed bf16 rows.
+  const bool packed = !few_rows && c->have_wpack && T >= 1024;
+  const int n_ssq = d / 64;
+  if (packed) {
+    tm.begin(TC_NORM);
+    launch_rmsnorm_rows(h, c->norm1[0], ab, T, d, m.rms_eps, rstd, st);
     tm.end();
+  }
+  for (int j = 0; j < c->l; ++j) {
+    if (!packed) {
+      tm.begin(TC_NORM);
+      launch_rmsnorm_rows(h, c->norm1[j], ab, T, d, m.rms_eps, nullptr, st);
+      tm.end();
+    }
     if (few_rows) {
       // decode steps and other few-token batches: weights stream once through the skinny kernel (fp32 out),
       // then rotation, rounding and the FP8 absmax in one small pass
@@ -682,8 +733,8 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
       tm.end();
     } else {
       GemmParams g{};
-      g.A = fold1 ? h : ab; g.lda = d; g.M = T; g.N = qd + 2 * kvd; g.K = d;
-      g.wtab = c->qkv_tab[j]; g.ldw = d; g.wpack = fold1 ? c->qkv_pack[j] : nullptr; g.rstd = fold1 ? rstd : nullptr;
+      g.A = ab; g.lda = d; g.M = T; g.N = qd + 2 * kvd; g.K = d;
+      g.wtab = c->qkv_tab[j]; g.ldw = d; g.wpack = packed ? c->qkv_pack[j] : nullptr; g.rstd = packed ? rstd : nullptr;
       g.cos_sin = r.at<float2>(r.L.cos_sin);
       g.head_dim = m.head_dim; g.q_dim = qd; g.kv_dim = kvd;
       g.q_out = qb; g.k_out = kb; g.v_out = vb;
@@ -707,12 +758,13 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
         cp.per_token = r.per_token; cp.n_slots = r.n_slots;
       }
       cp.vt = r.hp.chunked ? nullptr : vt; cp.vt_ld = r.L.vt_ld;
-      tm.begin(TC_OTHER);
+      tm.begin(TC_COMMIT);
       if (r.per_token) {
         TokenScaleParams tp{kb, vb, kvd, T, kvd, cp.slots, cp.scales, r.n_slots};
         launch_token_scales(tp, st);
       }
       launch_kv_commit(cp, st);
+      tm.end();
       if (r.hp.chunked) {   // cached prefix + the rows just committed -> contiguous K rows and V^T columns
         GatherParams gp{};
         gp.tiles = (const GatherTile *)r.meta(r.L.m_gtiles); gp.n_tiles = r.L.n_gtiles;
@@ -721,9 +773,10 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
         gp.scales = r.fp8 ? r.layer_scales(j) : nullptr;
         gp.block_tables = kv->block_tables; gp.max_blocks_per_seq = kv->max_blocks_per_seq; gp.n_blocks = kv->n_blocks;
         gp.k_dst = r.at<bf16_t>(r.L.kcat); gp.vt = vt; gp.vt_ld = r.L.vt_ld;
+        tm.begin(TC_OTHER);
         launch_kv_gather(gp, st);
+        tm.end();
       }
-      tm.end();
     }
     if (r.L.n_qblocks > 0) {
       AttnPrefillParams ap{};
@@ -755,14 +808,15 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
       tm.end();
     } else {
       GemmParams g{};
-      g.A = ob; g.lda = qd; g.M = T; g.N = d; g.K = qd; g.W = c->wo[j]; g.ldw = qd; g.wpack = c->wo_pack[j]; g.C = h; g.ldc = d;
+      g.A = ob; g.lda = qd; g.M = T; g.N = d; g.K = qd; g.W = c->wo[j]; g.ldw = qd; g.C = h; g.ldc = d;
+      if (packed) { g.wpack = c->wo_pack[j]; g.hb = ab; g.hb_gain = c->norm2[j]; g.ssq = ssq; }
       tm.begin(TC_O);
       if (launch_gemm(g, EPI_RESID, 0, st) != 0) return fail(SWIFTKV_EHIP, "O GEMM launch failed");
       tm.end();
     }
-    tm.begin(TC_OTHER);
-    if (fold2) launch_rstd(h, rstd, T, d, m.rms_eps, st);
-    else launch_rmsnorm_rows(h, c->norm2[j], ab, T, d, m.rms_eps, st);
+    tm.begin(TC_NORM);
+    if (packed) launch_rstd_from_ssq(ssq, n_ssq, rstd, T, d, m.rms_eps, st);
+    else launch_rmsnorm_rows(h, c->norm2[j], ab, T, d, m.rms_eps, nullptr, st);
     tm.end();
     if (few_rows) {
       tm.begin(TC_GATEUP);
@@ -774,8 +828,8 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     } else {
       {
         GemmParams g{};
-        g.A = fold2 ? h : ab; g.lda = d; g.M = T; g.N = 2 * m.ffn; g.K = d; g.wtab = c->gu_tab[j]; g.ldw = d;
-        g.wpack = fold2 ? c->gu_pack[j] : nullptr; g.rstd = fold2 ? rstd : nullptr;
+        g.A = ab; g.lda = d; g.M = T; g.N = 2 * m.ffn; g.K = d; g.wtab = c->gu_tab[j]; g.ldw = d;
+        g.wpack = packed ? c->gu_pack[j] : nullptr; g.rstd = packed ? rstd : nullptr;
         g.C = zb; g.ldc = m.ffn;
         tm.begin(TC_GATEUP);
         if (launch_gemm(g, EPI_SWIGLU, 0, st) != 0) return fail(SWIFTKV_EHIP, "gate/up GEMM launch failed");
@@ -783,9 +837,17 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
       }
       {
         GemmParams g{};
-        g.A = zb; g.lda = m.ffn; g.M = T; g.N = d; g.K = m.ffn; g.W = c->wdown[j]; g.ldw = m.ffn; g.wpack = c->down_pack[j]; g.C = h; g.ldc = d;
+        g.A = zb; g.lda = m.ffn; g.M = T; g.N = d; g.K = m.ffn; g.W = c->wdown[j]; g.ldw = m.ffn; g.C = h; g.ldc = d;
+        if (packed) {   // the next reader of h: the next layer's input norm, or (gain one) the fused K/V projection
+          g.wpack = c->down_pack[j]; g.hb = ab; g.hb_gain = j + 1 < c->l ? c->norm1[j + 1] : nullptr; g.ssq = ssq;
+        }
         tm.begin(TC_DOWN);
         if (launch_gemm(g, EPI_RESID, 0, st) != 0) return fail(SWIFTKV_EHIP, "down GEMM launch failed");
+        tm.end();
+      }
+      if (packed && (j + 1 < c->l || c->P > 0)) {
+        tm.begin(TC_NORM);
+        launch_rstd_from_ssq(ssq, n_ssq, rstd, T, d, m.rms_eps, st);
         tm.end();
       }
     }
@@ -793,15 +855,23 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   }
 
   // -------------------------- later layers' K/V from the layer-l output ----
-  if (c->P > 0)
-    if (int e = run_fused_kv(r, h, tm)) return e;
+  // operand: the layer-l output rounded to bf16 (the leaders' gains live in the packed weight), 1/rms per row
+  if (c->P > 0) {
+    if (!packed) {
+      tm.begin(TC_NORM);
+      launch_rmsnorm_rows(h, nullptr, ab, T, d, m.rms_eps, rstd, st);
+      tm.end();
+    }
+    if (int e = run_fused_kv(r, ab, true, tm)) return e;
+  }
 
   // ----------------------------- last token of every sequence: layers l+1..L ----
   tm.begin(TC_TAIL);
-  bf16_t *th = r.at<bf16_t>(r.L.th), *ta = r.at<bf16_t>(r.L.ta), *tq = r.at<bf16_t>(r.L.tq), *to = r.at<bf16_t>(r.L.to), *tz = r.at<bf16_t>(r.L.tz);
+  float *th = r.at<float>(r.L.th);
+  bf16_t *ta = r.at<bf16_t>(r.L.ta), *tq = r.at<bf16_t>(r.L.tq), *to = r.at<bf16_t>(r.L.to), *tz = r.at<bf16_t>(r.L.tz);
   launch_gather_rows(h, r.at<int32_t>(r.L.last_rows), th, B, d, st);
   if (c->ee_head) {   // extra head on the layer-l output; the flagged rows' logits replace the final ones below
-    launch_rmsnorm_rows(th, c->ee_gain, ta, B, d, m.rms_eps, st);
+    launch_rmsnorm_rows(th, c->ee_gain, ta, B, d, m.rms_eps, nullptr, st);
     if (tail_gemm(c, ta, B, m.vocab, d, c->ee_head, nullptr, nullptr, r.at<float>(r.L.ee_logits), EPI_STORE_F32, skp, st))
       return fail(SWIFTKV_EHIP, "early-exit head GEMM failed");
     launch_early_exit_flags(r.at<float>(r.L.ee_logits), B, m.vocab, c->ee_threshold, r.at<int32_t>(r.L.ee_flags), st);
@@ -810,7 +880,7 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   }
   for (int j = c->l; j < m.n_layers; ++j) {
     const int cl = c->l + (j - c->l) / c->g;
-    launch_rmsnorm_rows(th, c->norm1[j], ta, B, d, m.rms_eps, st);
+    launch_rmsnorm_rows(th, c->norm1[j], ta, B, d, m.rms_eps, nullptr, st);
     if (tail_gemm(c, ta, B, qd, d, c->wq[j], nullptr, nullptr, tq, EPI_STORE_BF16, skp, st)) return fail(SWIFTKV_EHIP, "tail q GEMM failed");
     AttnDecodeParams dp{};
     dp.q = tq; dp.out = to; dp.rows = (const DecodeRow *)r.meta(r.L.m_tail); dp.n_rows = B;
@@ -823,11 +893,11 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     if (launch_attention_decode(dp, st) != 0) return fail(SWIFTKV_EHIP, "tail attention launch failed");
     launch_decode_combine(dp.partial, to, dp.rows, B, m.n_q_heads, m.head_dim, dp.n_split, st);
     if (tail_gemm(c, to, B, d, qd, c->wo[j], nullptr, nullptr, th, EPI_RESID, skp, st)) return fail(SWIFTKV_EHIP, "tail o GEMM failed");
-    launch_rmsnorm_rows(th, c->norm2[j], ta, B, d, m.rms_eps, st);
+    launch_rmsnorm_rows(th, c->norm2[j], ta, B, d, m.rms_eps, nullptr, st);
     if (tail_gemm(c, ta, B, m.ffn, d, c->wgate[j], c->wup[j], c->gu_tab[j], tz, EPI_SWIGLU, skp, st)) return fail(SWIFTKV_EHIP, "tail MLP GEMM failed");
     if (tail_gemm(c, tz, B, d, m.ffn, c->wdown[j], nullptr, nullptr, th, EPI_RESID, skp, st)) return fail(SWIFTKV_EHIP, "tail down GEMM failed");
   }
-  launch_rmsnorm_rows(th, c->final_norm, ta, B, d, m.rms_eps, st);
+  launch_rmsnorm_rows(th, c->final_norm, ta, B, d, m.rms_eps, nullptr, st);
   if (tail_gemm(c, ta, B, m.vocab, d, c->lm_head, nullptr, nullptr, logits_out, EPI_STORE_F32, skp, st)) return fail(SWIFTKV_EHIP, "LM head GEMM failed");
   if (c->ee_head) launch_early_exit_select(r.at<float>(r.L.ee_logits), r.at<int32_t>(r.L.ee_flags), logits_out, B, m.vocab, st);
   tm.end();
@@ -859,8 +929,8 @@ int swiftkv_export_hidden(swiftkv_ctx *c, const void *workspace, void *hidden_ou
   if (!c || !workspace || !hidden_out) return fail(SWIFTKV_EINVAL, "null argument");
   if (!c->have_last) return fail(SWIFTKV_EINVAL, "no prefill has run on this ctx");
   const Layout &L = c->last;
-  HIP_TRY(hipMemcpyAsync(hidden_out, (const unsigned char *)workspace + L.h, (size_t)L.T * c->cfg.hidden * 2, hipMemcpyDeviceToDevice, (hipStream_t)stream));
-  return SWIFTKV_OK;
+  launch_f32_to_bf16((const float *)((const unsigned char *)workspace + L.h), (bf16_t *)hidden_out, (int64_t)L.T * c->cfg.hidden, (hipStream_t)stream);
+  return check_launch("hidden export");
 }
 
 // ------------------------------------------------------- single operations ----
@@ -868,66 +938,61 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
                     int32_t variant, void *stream) {
   if (!A || !W || !C) return fail(SWIFTKV_EINVAL, "null argument");
   if (M < 1 || N < 16 || K < 8 || (N % 16) || (K % 8)) return fail(SWIFTKV_EINVAL, "need M >= 1, N %% 16 == 0, K %% 8 == 0");
-  if (variant < 0 || variant > 33) return fail(SWIFTKV_EINVAL, "variant must be 0..33");
+  if (variant != 0 && variant != 1 && variant != 2 && variant != 3 && variant != 14 && variant != 15)
+    return fail(SWIFTKV_EINVAL, "variant must be 0, 1, 2, 3, 14 or 15");
   hipStream_t st = (hipStream_t)stream;
-  if (variant == 3 || variant == 29) {   // 29: with the scratch that lets the kernel split K (library-owned, allocated once)
-    if (M > 80) return fail(SWIFTKV_EINVAL, "weight-streaming kernel handles M <= 80");
-    static float *partial = nullptr;
-    if (variant == 29 && !partial) HIP_TRY(hipMalloc((void **)&partial, SKINNY_PARTIAL_BYTES));
-    SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, variant == 29 ? partial : nullptr};
+  if (variant == 3) {
+    if (M > SKINNY_MAX_ROWS) return fail(SWIFTKV_EINVAL, "weight-streaming kernel handles M <= 80");
+    SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, nullptr, 0};
     if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, st)) return fail(SWIFTKV_EHIP, "skinny launch failed");
     return check_launch("skinny gemm");
   }
   GemmParams g{};
   g.A = (const bf16_t *)A; g.lda = K; g.M = M; g.N = N; g.K = K; g.W = (const bf16_t *)W; g.ldw = K; g.C = C; g.ldc = N;
-  if (variant == 6) { g.dbg = 2; variant = 5; }
-  if (variant == 7) { g.dbg = 2; variant = 4; }
-  if (variant == 8) { g.dbg = 6; variant = 5; }
-  if (variant == 9) { g.dbg = 7; variant = 5; }
-  if (variant >= 30 && variant <= 33) { g.dbg = variant + 1; variant = 27; }   // 30..33: as 27 without the loop's weight requests / activation requests / LDS fragment reads / barrier (timing only)
-  const bool wreg_prof = variant == 28;   // 28: as 27 with cycle counters behind C (see 10..13)
-  if (wreg_prof) { variant = 27; g.dbg = 8; g.stage = (bf16_t *)C + (int64_t)M * N; }
-  if (variant == 27) {   // weights repacked into fragment order (library-owned buffer), then the loop that keeps them out of LDS
-    if (M < 1024 || (N % 256) || (K % 256) || out_f32) return fail(SWIFTKV_EINVAL, "variant 27 needs M >= 1024, N %% 256 == 0, K %% 256 == 0, bf16 output");
-    static bf16_t *pack = nullptr;
-    static size_t pack_elems = 0;
-    static const void *pack_src = nullptr;
-    const size_t need = (size_t)N * K;
-    if (need > pack_elems) {
-      if (pack) (void)hipFree(pack);
-      pack = nullptr; pack_elems = 0; pack_src = nullptr;
-      HIP_TRY(hipMalloc((void **)&pack, need * 2));
-      pack_elems = need;
-    }
-    if (pack_src != W || !getenv("SWIFTKV_XP_KEEP_PACK")) launch_pack_w(nullptr, (const bf16_t *)W, K, N, K, 0, nullptr, pack, st);   // (the variable skips repacking an unchanged pointer, for timing)
-    pack_src = W;
-    g.wpack = pack;
-  }
-  if (variant == 26) { g.dbg = 9; g.stage = (bf16_t *)C + (int64_t)M * N; variant = 14; }   // 26: as 12 without the timers inside the k loop
-  if (variant >= 17 && variant <= 25) { g.dbg = 20 + (variant - 17); variant = 14; }   // 17/18/19: five-stage loop without LDS reads / DMA / both (timing only); 20/21: the same loop with 4 / 3 stages
-  if (variant == 16) { g.head_dim = 1; variant = 12; }   // 16: as 12 but every load re-reads k tile 0 (cache-hot)
-  if (variant >= 10 && variant <= 13) {  // 10/11: cycle breakdown of variant 5/4; C must have room for 5*8*n_waves*n_workgroups bytes of int64 counters after the M x N result
-    g.dbg = 8; g.stage = (bf16_t *)C + (int64_t)M * N;
-    if (variant >= 12) { variant = variant == 12 ? 14 : 15; }   // 12/13: the five-stage loop with 4 / 8 waves
-    else variant = variant == 10 ? 5 : 4;   // counters go after the M x N result
-    if (out_f32) return fail(SWIFTKV_EINVAL, "profiling variants need bf16 output");
-  }
   if (launch_gemm(g, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, variant, st)) return fail(SWIFTKV_EHIP, "gemm launch failed");
   return check_launch("gemm");
+}
+
+int swiftkv_op_gemm_packed(const void *A, const void *W, void *w_packed, void *C, int32_t M, int32_t N, int32_t K, void *stream) {
+  if (!A || !W || !w_packed || !C) return fail(SWIFTKV_EINVAL, "null argument");
+  if (M < 1024 || N < 256 || K < 256 || (N % 256) || (K % 256)) return fail(SWIFTKV_EINVAL, "need M >= 1024, N %% 256 == 0, K %% 256 == 0");
+  hipStream_t st = (hipStream_t)stream;
+  launch_pack_w(nullptr, (const bf16_t *)W, K, N, K, 0, (bf16_t *)w_packed, st);
+  GemmParams g{};
+  g.A = (const bf16_t *)A; g.lda = K; g.M = M; g.N = N; g.K = K; g.W = (const bf16_t *)W; g.ldw = K; g.C = C; g.ldc = N;
+  g.wpack = (const bf16_t *)w_packed;
+  if (launch_gemm(g, EPI_STORE_BF16, 27, st)) return fail(SWIFTKV_EHIP, "gemm launch failed");
+  return check_launch("packed-weight gemm");
+}
+
+size_t swiftkv_op_gemm_rows_workspace(int32_t M, int32_t N) {
+  if (M < 1 || N < 1) return 0;
+  return align_up((size_t)SKINNY_MAX_SPLIT * M * N * 4);
+}
+
+int swiftkv_op_gemm_rows(const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K, int32_t out_f32,
+                         void *workspace, size_t workspace_bytes, void *stream) {
+  if (!A || !W || !C || !workspace) return fail(SWIFTKV_EINVAL, "null argument");
+  if (M < 1 || M > SKINNY_MAX_ROWS || N < 16 || K < 8 || (N % 16) || (K % 8))
+    return fail(SWIFTKV_EINVAL, "need 1 <= M <= 80, N %% 16 == 0, K %% 8 == 0");
+  if (workspace_bytes < swiftkv_op_gemm_rows_workspace(M, N))
+    return fail(SWIFTKV_ENOSPC, "workspace has %zu bytes, %zu needed", workspace_bytes, swiftkv_op_gemm_rows_workspace(M, N));
+  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, (float *)workspace, workspace_bytes};
+  if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, (hipStream_t)stream)) return fail(SWIFTKV_EHIP, "skinny launch failed");
+  return check_launch("weight-streaming gemm");
 }
 
 size_t swiftkv_op_attention_workspace(int64_t n_tokens, int32_t n_seqs, int32_t n_kv_heads, int32_t head_dim) {
   const int64_t vt_ld = n_tokens + 64LL * n_seqs;
   return align_up((size_t)n_kv_heads * head_dim * vt_ld * 2) + align_up((size_t)(n_tokens / 128 + n_seqs) * 32) +
-         align_up((size_t)(n_tokens / 64 + n_seqs) * 16) + 4096 +
-         (size_t)(n_tokens / 128 + n_seqs) * 64 * 16 * 8;   // + room for the optional cycle counters (<= 64 heads)
+         align_up((size_t)(n_tokens / 64 + n_seqs) * 16) + 4096;
 }
 
 int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, void *out, const int32_t *seq_lens,
                                  int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, void *workspace,
                                  size_t workspace_bytes, void *stream) {
   if (!q || !k || !v || !out || !seq_lens || !workspace) return fail(SWIFTKV_EINVAL, "null argument");
-  if ((hd != 64 && hd != 128) || Hq % Hkv || (Hkv * hd) % 128 || (Hq * hd) % 128) return fail(SWIFTKV_EINVAL, "bad head shape");
+  if ((hd != 64 && hd != 128) || Hkv < 1 || Hq % Hkv || (Hkv * hd) % 128 || (Hq * hd) % 128) return fail(SWIFTKV_EINVAL, "bad head shape");
   hipStream_t st = (hipStream_t)stream;
   std::vector<int32_t> qbs, kvt;
   std::vector<std::array<int32_t, 8>> qb_list;
@@ -962,33 +1027,30 @@ int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, vo
   ap.n_q_heads = Hq; ap.n_kv_heads = Hkv; ap.head_dim = hd;
   ap.sched = (int32_t *)(ws + o_sched);
   launch_fill_u32((uint32_t *)(ws + o_sched), 0, 9, st);   // the workspace is the caller's and arrives uninitialised
-  if (getenv("SWIFTKV_ATTN_PROF")) {   // timing experiment: per-wave cycle counters after the tables
-    const size_t need = (size_t)ap.n_qblocks * Hq * 16 * 8 + 1024 * 4 * 8;   // per (item, wave) records, then per workgroup records
-    if (total + need <= workspace_bytes) ap.prof = (long long *)(ws + total);
-  }
   if (launch_attention_prefill(ap, st)) return fail(SWIFTKV_EHIP, "attention launch failed");
-  return check_launch("attention");
+  if (int e = check_launch("attention")) return e;
+  HIP_TRY(hipStreamSynchronize(st));   // the tables above were staged from this call's own (pageable) host vectors
+  return SWIFTKV_OK;
 }
 
-int swiftkv_op_mfma_rate(const void *operands, int32_t iters, double *tflops_out, void *stream) {
-  if (!operands || !tflops_out || iters < 1) return fail(SWIFTKV_EINVAL, "bad argument");
+int swiftkv_op_mfma_rate(const void *operands, int32_t iters, void *sink, size_t sink_bytes, double *tflops_out, void *stream) {
+  if (!operands || !tflops_out || !sink || iters < 1) return fail(SWIFTKV_EINVAL, "bad argument");
   hipStream_t st = (hipStream_t)stream;
   int dev = 0, n_cu = 0;
   HIP_TRY(hipGetDevice(&dev));
   HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-  float *sink = nullptr;
-  HIP_TRY(hipMalloc((void **)&sink, (size_t)n_cu * 256 * 4));
+  if (sink_bytes < (size_t)n_cu * 256 * 4) return fail(SWIFTKV_ENOSPC, "sink has %zu bytes, %zu needed", sink_bytes, (size_t)n_cu * 256 * 4);
   hipEvent_t e0, e1;
   HIP_TRY(hipEventCreate(&e0));
   HIP_TRY(hipEventCreate(&e1));
-  launch_mfma_rate((const bf16_t *)operands, sink, n_cu, iters / 8 + 1, st);   // warm-up (clocks settle)
+  launch_mfma_rate((const bf16_t *)operands, (float *)sink, n_cu, iters / 8 + 1, st);   // warm-up (clocks settle)
   HIP_TRY(hipEventRecord(e0, st));
-  launch_mfma_rate((const bf16_t *)operands, sink, n_cu, iters, st);
+  launch_mfma_rate((const bf16_t *)operands, (float *)sink, n_cu, iters, st);
   HIP_TRY(hipEventRecord(e1, st));
   HIP_TRY(hipEventSynchronize(e1));
   float ms = 0.f;
   HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
-  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); (void)hipFree(sink);
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
   if (int e = check_launch("mfma rate")) return e;
   *tflops_out = (double)n_cu * 4 * iters * 16 * (2.0 * 32 * 32 * 16) / (ms * 1e-3) / 1e12;
   return SWIFTKV_OK;

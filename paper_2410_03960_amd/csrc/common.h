@@ -67,7 +67,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 enum GemmEpi {
   EPI_STORE_BF16 = 0,  // C bf16 [M, ldc]
   EPI_STORE_F32 = 1,   // C fp32 [M, ldc]
-  EPI_RESID = 2,       // C bf16 [M, ldc] += acc  (in place on the residual stream)
+  EPI_RESID = 2,       // C fp32 [M, ldc] += acc  (in place on the residual stream, which is kept in fp32)
   EPI_SWIGLU = 3,      // virtual N = 2*ffn in 16-row gate/up interleave; C bf16 [M, ffn]
   EPI_QKV = 4,         // rstd row scale, RoPE on q/k columns, q/k/v to separate row-major buffers
   EPI_KV = 5           // rstd row scale, RoPE on K columns, paged scatter (bf16) or staging (+absmax)
@@ -86,13 +86,10 @@ struct GemmParams {
   int64_t ldw;
   // the same weights in MFMA fragment order (see launch_pack_w), or null: [N/32][K/16][64 lanes][8] bf16
   const bf16_t *wpack;
-  // optional A prologue: A[m,k] *= gain[k]; gain vector chosen per block of gain_seg output columns
-  const bf16_t *const *gain_tab;  // device table of gain pointers (nullptr = no gain)
-  int32_t gain_seg;
   // epilogue
   void *C;
   int64_t ldc;
-  const float *rstd;      // [M] row scale (QKV / KV / SWIGLU with gain), may be null
+  const float *rstd;      // [M] row scale 1/rms (QKV / KV / SWIGLU), may be null
   const float2 *cos_sin;  // [M][hd/2] (QKV / KV)
   int32_t head_dim, q_dim, kv_dim;
   bf16_t *q_out, *k_out, *v_out;  // QKV: [M,q_dim], [M,kv_dim], [M,kv_dim]
@@ -104,8 +101,13 @@ struct GemmParams {
   int32_t first_cache_layer;   // KV: cache layer of projection 0
   bf16_t *stage;               // KV FP8 mode: staging [M, N] bf16 instead of the cache
   uint32_t *amax;              // FP8: [n_cache_layers][2][Hkv] absmax bit patterns (atomicMax), or null
-  int32_t dbg;                 // timing experiments only: 1 = no global loads in the k loop, 2 = always k-tile 0
-  int32_t raster_gm;           // five-stage kernel: m tiles per rasterisation group (0 = default)
+  // RESID in the packed-weight loop, optional: besides C += acc, write the operand of the next
+  // projection, hb[m][n] = bf16(C_new[m][n] * hb_gain[n]) (hb_gain null = 1), and the sums of squares of
+  // C_new over each 64-column block, ssq[n / 64][m] (leading dimension M), from which 1/rms follows
+  bf16_t *hb;
+  const bf16_t *hb_gain;
+  float *ssq;
+  int32_t raster_gm;           // m tiles per rasterisation group (0 = default)
 };
 
 // Matrix-instruction rate on given operand data, nothing else in the loop: `iters` x 16 independent
@@ -120,10 +122,12 @@ struct SkinnyParams {
   int32_t M, N, K;
   const bf16_t *W;   // [N, K]
   const bf16_t *W2;  // SWIGLU: up-projection [N, K]
-  void *C;           // bf16 [M,N] (STORE_BF16, RESID in place, SWIGLU) or fp32 (STORE_F32)
-  float *partial;    // scratch of SKINNY_PARTIAL_BYTES for K-split partial sums, or null (then K is never split)
+  void *C;           // bf16 [M,N] (STORE_BF16, SWIGLU) or fp32 (STORE_F32; RESID adds in place)
+  float *partial;    // scratch for K-split partial sums, or null (then K is never split)
+  size_t partial_bytes;   // its size; a split whose partial sums would not fit is not taken
 };
-constexpr size_t SKINNY_PARTIAL_BYTES = (size_t)4 * 80 * 8192 * 4;   // 4 splits x 80 rows x 8192 columns fp32
+constexpr int SKINNY_MAX_SPLIT = 4;
+constexpr size_t SKINNY_PARTIAL_BYTES = (size_t)SKINNY_MAX_SPLIT * 80 * 8192 * 4;   // the driver's scratch: 4 splits x 80 rows x 8192 columns fp32
 int launch_skinny(const SkinnyParams &p, int epi, hipStream_t st);
 
 // Few-row batches (decode steps): the Q, K, V projections come out of the weight-streaming kernel as
@@ -202,15 +206,23 @@ struct PlanParams {
   float2 *cos_sin;
 };
 int launch_plan(const PlanParams &p, hipStream_t st);
-int launch_embed(const int32_t *ids, const bf16_t *E, bf16_t *h, int32_t T, int32_t d, int32_t vocab, hipStream_t st);
+// The residual stream h is fp32 [rows, d] everywhere.
+int launch_embed(const int32_t *ids, const bf16_t *E, float *h, int32_t T, int32_t d, int32_t vocab, hipStream_t st);
+// rstd[t] = rsqrt(mean(h[t,:]^2) + eps) of bf16 rows (a layer-l output handed in by the caller)
 int launch_rstd(const bf16_t *h, float *rstd, int32_t T, int32_t d, float eps, hipStream_t st);
-int launch_rmsnorm_rows(const bf16_t *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, hipStream_t st);
-int launch_gather_rows(const bf16_t *h, const int32_t *rows, bf16_t *out, int32_t n_rows, int32_t d, hipStream_t st);
+// the same from per-block sums of squares ssq[n_blocks][T] written by the RESID epilogue, added in block order
+int launch_rstd_from_ssq(const float *ssq, int32_t n_blocks, float *rstd, int32_t T, int32_t d, float eps, hipStream_t st);
+// RMSNorm of fp32 rows into a bf16 GEMM operand.  rstd_out == null: out = bf16(h * rstd * gain).  Otherwise
+// the row factor is left to the consumer's epilogue: out = bf16(h * gain) and rstd_out[row] = rstd.
+// gain == null stands for a gain of one.
+int launch_rmsnorm_rows(const float *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, float *rstd_out, hipStream_t st);
+int launch_gather_rows(const float *h, const int32_t *rows, float *out, int32_t n_rows, int32_t d, hipStream_t st);
+int launch_f32_to_bf16(const float *x, bf16_t *out, int64_t n, hipStream_t st);
 int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t st);
 // out[((n/32) * (K/16) + k/16) * 512 + ((k%16)/8 * 32 + n%32) * 8 + k%8] = W row n (through the optional
 // 16-row block pointer table), element k.  N % 32 == 0, K % 16 == 0.  rope_hd == 128 (N % 128 == 0) takes the
 // 32-row blocks of every 128 rows in the order 0, 2, 1, 3 (rotary partners side by side in a 64-row wave tile).
-int launch_pack_w(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, const bf16_t *gain, bf16_t *out, hipStream_t st);
+int launch_pack_w(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, bf16_t *out, hipStream_t st);
 int launch_fold_gain(const bf16_t *W, const bf16_t *gain, bf16_t *out, int64_t rows, int32_t K, hipStream_t st);
 
 struct KVTile {  // 64 consecutive new tokens of one sequence

@@ -44,18 +44,21 @@ int launch_plan(const PlanParams &p, hipStream_t st) {
 }
 
 // --------------------------------------------------------------- embed -----
-__global__ void embed_kernel(const int32_t *ids, const uint4 *E, uint4 *h, int T, int chunks, int vocab) {
+// h[t, :] = E[id[t], :] widened to fp32 (the residual stream is kept in fp32).
+__global__ void embed_kernel(const int32_t *ids, const uint4 *E, float4 *h, int T, int chunks, int vocab) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)T * chunks) return;
   int t = (int)(i / chunks), c = (int)(i % chunks);
   int id = ids[t];
   id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
-  h[i] = E[(int64_t)id * chunks + c];
+  const uint4 u = E[(int64_t)id * chunks + c];
+  h[2 * i] = make_float4(bf16lo(u.x), bf16hi(u.x), bf16lo(u.y), bf16hi(u.y));
+  h[2 * i + 1] = make_float4(bf16lo(u.z), bf16hi(u.z), bf16lo(u.w), bf16hi(u.w));
 }
-int launch_embed(const int32_t *ids, const bf16_t *E, bf16_t *h, int32_t T, int32_t d, int32_t vocab, hipStream_t st) {
+int launch_embed(const int32_t *ids, const bf16_t *E, float *h, int32_t T, int32_t d, int32_t vocab, hipStream_t st) {
   int chunks = d / 8;
   int64_t n = (int64_t)T * chunks;
-  hipLaunchKernelGGL(embed_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, ids, (const uint4 *)E, (uint4 *)h, T, chunks, vocab);
+  hipLaunchKernelGGL(embed_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, ids, (const uint4 *)E, (float4 *)h, T, chunks, vocab);
   return 0;
 }
 
@@ -83,78 +86,84 @@ int launch_rstd(const bf16_t *h, float *rstd, int32_t T, int32_t d, float eps, h
   return 0;
 }
 
-// ------------------------------------------------- RMSNorm of a few rows ----
-__global__ void rmsnorm_rows_kernel(const uint4 *h, const uint4 *gain, uint4 *out, int rows, int chunks, float eps, float inv_d) {
+// 1/rms from the per-block sums of squares the residual epilogue of the packed-weight GEMM leaves:
+// ssq[b][t], b < n_blocks, added in block order (fixed order: results do not change from run to run).
+__global__ void rstd_from_ssq_kernel(const float *ssq, int n_blocks, float *rstd, int T, float eps, float inv_d) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  float s = 0.f;
+  for (int b = 0; b < n_blocks; ++b) s += ssq[(int64_t)b * T + t];
+  rstd[t] = rsqrtf(s * inv_d + eps);
+}
+int launch_rstd_from_ssq(const float *ssq, int32_t n_blocks, float *rstd, int32_t T, int32_t d, float eps, hipStream_t st) {
+  hipLaunchKernelGGL(rstd_from_ssq_kernel, dim3((T + 255) / 256), dim3(256), 0, st, ssq, n_blocks, rstd, T, eps, 1.0f / (float)d);
+  return 0;
+}
+
+// ------------------------------------------------------- RMSNorm of rows ----
+// fp32 rows -> bf16 GEMM operand; one wave per row.  With rstd_out the row factor is left to the
+// consumer: out = bf16(h * gain), rstd_out[row] = 1/rms; else out = bf16(h * 1/rms * gain).
+__device__ __forceinline__ uint2 norm4(const float4 u, const float rs, const bf16_t *gain, int c) {
+  float g0 = 1.f, g1 = 1.f, g2 = 1.f, g3 = 1.f;
+  if (gain) {
+    const uint2 g = *(const uint2 *)(gain + 4 * c);
+    g0 = bf16lo(g.x); g1 = bf16hi(g.x); g2 = bf16lo(g.y); g3 = bf16hi(g.y);
+  }
+  return make_uint2(pack_bf16x2(u.x * rs * g0, u.y * rs * g1), pack_bf16x2(u.z * rs * g2, u.w * rs * g3));
+}
+__global__ void rmsnorm_rows_kernel(const float4 *h, const bf16_t *gain, uint2 *out, int rows, int chunks, float eps, float inv_d, float *rstd_out) {
   int row = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
   int lane = threadIdx.x & 63;
   if (row >= rows) return;
-  const uint4 *r = h + (int64_t)row * chunks;
+  const float4 *r = h + (int64_t)row * chunks;
   float s = 0.f;
   for (int c = lane; c < chunks; c += 64) {
-    uint4 u = r[c];
-    float a;
-    a = bf16lo(u.x); s += a * a; a = bf16hi(u.x); s += a * a;
-    a = bf16lo(u.y); s += a * a; a = bf16hi(u.y); s += a * a;
-    a = bf16lo(u.z); s += a * a; a = bf16hi(u.z); s += a * a;
-    a = bf16lo(u.w); s += a * a; a = bf16hi(u.w); s += a * a;
+    const float4 u = r[c];
+    s += u.x * u.x; s += u.y * u.y; s += u.z * u.z; s += u.w * u.w;
   }
   s = wave_sum(s);
-  float rs = rsqrtf(s * inv_d + eps);
-  for (int c = lane; c < chunks; c += 64) {
-    uint4 u = r[c], g = gain[c], o;
-    o.x = pack_bf16x2(bf16lo(u.x) * rs * bf16lo(g.x), bf16hi(u.x) * rs * bf16hi(g.x));
-    o.y = pack_bf16x2(bf16lo(u.y) * rs * bf16lo(g.y), bf16hi(u.y) * rs * bf16hi(g.y));
-    o.z = pack_bf16x2(bf16lo(u.z) * rs * bf16lo(g.z), bf16hi(u.z) * rs * bf16hi(g.z));
-    o.w = pack_bf16x2(bf16lo(u.w) * rs * bf16lo(g.w), bf16hi(u.w) * rs * bf16hi(g.w));
-    out[(int64_t)row * chunks + c] = o;
-  }
+  const float rs = rsqrtf(s * inv_d + eps);
+  if (rstd_out && lane == 0) rstd_out[row] = rs;
+  const float f = rstd_out ? 1.f : rs;
+  for (int c = lane; c < chunks; c += 64) out[(int64_t)row * chunks + c] = norm4(r[c], f, gain, c);
 }
-// Single-pass variant: the row (d = 512 * CH elements) stays in registers between the reduction and the scaling.
+// Single-pass variant: the row (d = 256 * CH elements) stays in registers between the reduction and the scaling.
 template <int CH>
-__global__ void rmsnorm_rows_reg_kernel(const uint4 *h, const uint4 *gain, uint4 *out, int rows, float eps, float inv_d) {
+__global__ void rmsnorm_rows_reg_kernel(const float4 *h, const bf16_t *gain, uint2 *out, int rows, float eps, float inv_d, float *rstd_out) {
   const int row = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
   const int lane = threadIdx.x & 63;
   if (row >= rows) return;
-  const uint4 *r = h + (int64_t)row * (CH * 64);
-  uint4 u[CH];
+  const float4 *r = h + (int64_t)row * (CH * 64);
+  float4 u[CH];
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < CH; ++i) {
     u[i] = r[i * 64 + lane];
-    float a;
-    a = bf16lo(u[i].x); s += a * a; a = bf16hi(u[i].x); s += a * a;
-    a = bf16lo(u[i].y); s += a * a; a = bf16hi(u[i].y); s += a * a;
-    a = bf16lo(u[i].z); s += a * a; a = bf16hi(u[i].z); s += a * a;
-    a = bf16lo(u[i].w); s += a * a; a = bf16hi(u[i].w); s += a * a;
+    s += u[i].x * u[i].x; s += u[i].y * u[i].y; s += u[i].z * u[i].z; s += u[i].w * u[i].w;
   }
   s = wave_sum(s);
   const float rs = rsqrtf(s * inv_d + eps);
+  if (rstd_out && lane == 0) rstd_out[row] = rs;
+  const float f = rstd_out ? 1.f : rs;
 #pragma unroll
-  for (int i = 0; i < CH; ++i) {
-    const uint4 g = gain[i * 64 + lane];
-    uint4 o;
-    o.x = pack_bf16x2(bf16lo(u[i].x) * rs * bf16lo(g.x), bf16hi(u[i].x) * rs * bf16hi(g.x));
-    o.y = pack_bf16x2(bf16lo(u[i].y) * rs * bf16lo(g.y), bf16hi(u[i].y) * rs * bf16hi(g.y));
-    o.z = pack_bf16x2(bf16lo(u[i].z) * rs * bf16lo(g.z), bf16hi(u[i].z) * rs * bf16hi(g.z));
-    o.w = pack_bf16x2(bf16lo(u[i].w) * rs * bf16lo(g.w), bf16hi(u[i].w) * rs * bf16hi(g.w));
-    out[(int64_t)row * (CH * 64) + i * 64 + lane] = o;
-  }
+  for (int i = 0; i < CH; ++i) out[(int64_t)row * (CH * 64) + i * 64 + lane] = norm4(u[i], f, gain, i * 64 + lane);
 }
-int launch_rmsnorm_rows(const bf16_t *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, hipStream_t st) {
+int launch_rmsnorm_rows(const float *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, float *rstd_out, hipStream_t st) {
+  if (rows <= 0) return 0;
   const dim3 grid((rows + 3) / 4), block(256);
   const float inv_d = 1.0f / (float)d;
 #define SKV_RMS_CASE(CH_)                                                                                          \
   case CH_:                                                                                                        \
-    hipLaunchKernelGGL(rmsnorm_rows_reg_kernel<CH_>, grid, block, 0, st, (const uint4 *)h, (const uint4 *)gain, (uint4 *)out, rows, eps, inv_d); \
+    hipLaunchKernelGGL(rmsnorm_rows_reg_kernel<CH_>, grid, block, 0, st, (const float4 *)h, gain, (uint2 *)out, rows, eps, inv_d, rstd_out); \
     return 0;
-  if (d % 512 == 0) {
-    switch (d / 512) {
-      SKV_RMS_CASE(1) SKV_RMS_CASE(2) SKV_RMS_CASE(4) SKV_RMS_CASE(8) SKV_RMS_CASE(10) SKV_RMS_CASE(12) SKV_RMS_CASE(16)
+  if (d % 256 == 0) {
+    switch (d / 256) {
+      SKV_RMS_CASE(1) SKV_RMS_CASE(2) SKV_RMS_CASE(4) SKV_RMS_CASE(8) SKV_RMS_CASE(16) SKV_RMS_CASE(20) SKV_RMS_CASE(24) SKV_RMS_CASE(32)
       default: break;
     }
   }
 #undef SKV_RMS_CASE
-  hipLaunchKernelGGL(rmsnorm_rows_kernel, grid, block, 0, st, (const uint4 *)h, (const uint4 *)gain, (uint4 *)out, rows, d / 8, eps, inv_d);
+  hipLaunchKernelGGL(rmsnorm_rows_kernel, grid, block, 0, st, (const float4 *)h, gain, (uint2 *)out, rows, d / 4, eps, inv_d, rstd_out);
   return 0;
 }
 
@@ -178,16 +187,28 @@ int launch_fold_gain(const bf16_t *W, const bf16_t *gain, bf16_t *out, int64_t r
 }
 
 // -------------------------------------------------------------- gather -----
-__global__ void gather_rows_kernel(const uint4 *h, const int32_t *rows, uint4 *out, int n_rows, int chunks) {
+__global__ void gather_rows_kernel(const float4 *h, const int32_t *rows, float4 *out, int n_rows, int chunks) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)n_rows * chunks) return;
   int r = (int)(i / chunks), c = (int)(i % chunks);
   out[i] = h[(int64_t)rows[r] * chunks + c];
 }
-int launch_gather_rows(const bf16_t *h, const int32_t *rows, bf16_t *out, int32_t n_rows, int32_t d, hipStream_t st) {
-  int chunks = d / 8;
+int launch_gather_rows(const float *h, const int32_t *rows, float *out, int32_t n_rows, int32_t d, hipStream_t st) {
+  int chunks = d / 4;
   int64_t n = (int64_t)n_rows * chunks;
-  hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const uint4 *)h, rows, (uint4 *)out, n_rows, chunks);
+  hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float4 *)h, rows, (float4 *)out, n_rows, chunks);
+  return 0;
+}
+
+__global__ void f32_to_bf16_kernel(const float4 *x, uint2 *out, int64_t n4) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  const float4 u = x[i];
+  out[i] = make_uint2(pack_bf16x2(u.x, u.y), pack_bf16x2(u.z, u.w));
+}
+int launch_f32_to_bf16(const float *x, bf16_t *out, int64_t n, hipStream_t st) {   // n % 4 == 0
+  if (n <= 0) return 0;
+  hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, st, (const float4 *)x, (uint2 *)out, n / 4);
   return 0;
 }
 
@@ -199,7 +220,7 @@ __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n) {
 // rope_hd == 128: inside every group of 128 rows (one head) the 32-row blocks are taken in the order
 // 0, 2, 1, 3, so that a 64-row wave tile holds a block of the first half of the head next to its
 // rotary partner block of the second half.
-__global__ void pack_w_kernel(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, const bf16_t *gain, uint4 *out) {
+__global__ void pack_w_kernel(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, uint4 *out) {
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t n_chunks = (int64_t)N * K / 8;
   if (id >= n_chunks) return;
@@ -213,20 +234,13 @@ __global__ void pack_w_kernel(const bf16_t *const *wtab, const bf16_t *W, int64_
   }
   const int n = block * 32 + (lane & 31), k = k16 * 16 + (lane >> 5) * 8;
   const bf16_t *row = wtab ? wtab[n >> 4] + (int64_t)(n & 15) * ldw : W + (int64_t)n * ldw;
-  uint4 u = *(const uint4 *)(row + k);
-  if (gain) {   // fold a per-input-column gain (the RMSNorm weight in front of this projection) into the copy
-    const uint4 g = *(const uint4 *)(gain + k);
-    u.x = pack_bf16x2(bf16lo(u.x) * bf16lo(g.x), bf16hi(u.x) * bf16hi(g.x));
-    u.y = pack_bf16x2(bf16lo(u.y) * bf16lo(g.y), bf16hi(u.y) * bf16hi(g.y));
-    u.z = pack_bf16x2(bf16lo(u.z) * bf16lo(g.z), bf16hi(u.z) * bf16hi(g.z));
-    u.w = pack_bf16x2(bf16lo(u.w) * bf16lo(g.w), bf16hi(u.w) * bf16hi(g.w));
-  }
+  const uint4 u = *(const uint4 *)(row + k);
   out[id] = u;
 }
-int launch_pack_w(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, const bf16_t *gain, bf16_t *out, hipStream_t st) {
+int launch_pack_w(const bf16_t *const *wtab, const bf16_t *W, int64_t ldw, int32_t N, int32_t K, int32_t rope_hd, bf16_t *out, hipStream_t st) {
   const int64_t n_chunks = (int64_t)N * K / 8;
   if (n_chunks <= 0) return 0;
-  hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, wtab, W, ldw, N, K, rope_hd, gain, (uint4 *)out);
+  hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, wtab, W, ldw, N, K, rope_hd, (uint4 *)out);
   return 0;
 }
 int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t st) {

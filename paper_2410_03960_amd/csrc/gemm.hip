@@ -1,6 +1,6 @@
-// bf16 MFMA GEMM for gfx950:  C[M,N] = A[M,K] * W[N,K]^T  with fused prologue
-// (per-column RMSNorm gain on A) and epilogues (residual add, SwiGLU, rstd row
-// scale + RoPE + q/k/v split, rstd + RoPE + paged KV scatter).
+// bf16 MFMA GEMM for gfx950:  C[M,N] = A[M,K] * W[N,K]^T  with fused epilogues
+// (fp32 residual add, SwiGLU, 1/rms row scale + RoPE + q/k/v split, 1/rms + RoPE
+// + paged KV scatter).
 //
 // Layout of the computation.  A workgroup owns a BM x BN tile of C and walks K
 // in steps of 64.  Global -> registers -> LDS double buffering (one barrier per
@@ -21,12 +21,9 @@
 #include "common.h"
 #include <type_traits>
 
-#include <cstdlib>
-
 namespace {
 
 constexpr int BK = 64;
-int g_big_variant = 14;   // main loop used for large plain GEMMs: 14 = five-stage direct-to-LDS, 5 = two-stage
 
 // Shared epilogue.  acc[bn][bm][4*jg + e] is C[m][n + e] with
 // m = m_base + bm*32 + (lane & 31), n = n_base + bn*32 + 8*jg + 4*(lane >> 5).
@@ -52,12 +49,12 @@ __device__ __forceinline__ void gemm_epilogue(const GemmParams &p, floatx16 (&ac
           float x0 = acc[bn][bm][4 * jg], x1 = acc[bn][bm][4 * jg + 1], x2 = acc[bn][bm][4 * jg + 2], x3 = acc[bn][bm][4 * jg + 3];
           if constexpr (EPI == EPI_STORE_F32) {
             *(float4 *)((float *)p.C + (int64_t)m * p.ldc + n) = make_float4(x0, x1, x2, x3);
+          } else if constexpr (EPI == EPI_RESID) {
+            float4 *dst = (float4 *)((float *)p.C + (int64_t)m * p.ldc + n);
+            const float4 r = *dst;
+            *dst = make_float4(r.x + x0, r.y + x1, r.z + x2, r.w + x3);
           } else {
             bf16_t *dst = (bf16_t *)p.C + (int64_t)m * p.ldc + n;
-            if constexpr (EPI == EPI_RESID) {
-              uint2 r = *(const uint2 *)dst;
-              x0 += bf16lo(r.x); x1 += bf16hi(r.x); x2 += bf16lo(r.y); x3 += bf16hi(r.y);
-            }
             *(uint2 *)dst = make_uint2(pack_bf16x2(x0, x1), pack_bf16x2(x2, x3));
           }
         }
@@ -194,7 +191,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmParams &p, floatx16 (&ac
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, bool GAIN>
+template <int BM, int BN, int WGM, int WGN, int EPI>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(GemmParams p) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -243,8 +240,6 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(GemmParams p) {
     n = n < p.N ? n : p.N - 1;
     w_ptr[i] = (p.wtab ? p.wtab[n >> 4] + (int64_t)(n & 15) * p.ldw : p.W + (int64_t)n * p.ldw) + lc * 8;
   }
-  const bf16_t *g_ptr = nullptr;
-  if constexpr (GAIN) g_ptr = p.gain_tab[n0 / p.gain_seg] + lc * 8;
 
   uint4 ra[A_IT], rb[B_IT];
   auto load_global = [&](int k0) {
@@ -253,16 +248,6 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(GemmParams p) {
     for (int i = 0; i < A_IT; ++i) ra[i] = kv ? *(const uint4 *)(a_ptr[i] + k0) : make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) rb[i] = kv ? *(const uint4 *)(w_ptr[i] + k0) : make_uint4(0, 0, 0, 0);
-    if constexpr (GAIN) {
-      uint4 gv = kv ? *(const uint4 *)(g_ptr + k0) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-      for (int i = 0; i < A_IT; ++i) {
-        ra[i].x = pack_bf16x2(bf16lo(ra[i].x) * bf16lo(gv.x), bf16hi(ra[i].x) * bf16hi(gv.x));
-        ra[i].y = pack_bf16x2(bf16lo(ra[i].y) * bf16lo(gv.y), bf16hi(ra[i].y) * bf16hi(gv.y));
-        ra[i].z = pack_bf16x2(bf16lo(ra[i].z) * bf16lo(gv.z), bf16hi(ra[i].z) * bf16hi(gv.z));
-        ra[i].w = pack_bf16x2(bf16lo(ra[i].w) * bf16lo(gv.w), bf16hi(ra[i].w) * bf16hi(gv.w));
-      }
-    }
   };
   auto store_lds = [&](int stage) {
     unsigned char *sa = smem + stage * STAGE_BYTES;
@@ -323,173 +308,6 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_kernel(GemmParams p) {
 }
 
 // ---------------------------------------------------------------------------
-// Main loop with direct global -> LDS loads (global_load_lds_dwordx4).  One
-// instruction moves 64 x 16 bytes into 1 KB of LDS = 8 tile rows; lane i lands
-// in (row i/8, physical chunk i%8), so it fetches the logical chunk
-// (i%8) ^ ((row >> 1) & 7) of that row, which reproduces the XOR swizzle the
-// MFMA operand reads expect.
-// No staging registers and no LDS store instructions; needs K % 64 == 0 and no
-// gain prologue.
-template <int BM, int BN, int WGM, int WGN, int EPI, bool PROF = false>
-__global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds_kernel(GemmParams p) {
-  constexpr int NW = WGM * WGN;
-  constexpr int WTM = BM / WGM, WTN = BN / WGN;
-  static_assert(WTN == 128 && WTM % 32 == 0, "wave tile");
-  constexpr int FM = WTM / 32, FN = WTN / 32;
-  constexpr int A_CH = BM / 8 / NW, B_CH = BN / 8 / NW;   // 1 KB chunks per wave per stage
-  constexpr int STAGE_BYTES = (BM + BN) * 128;
-
-  extern __shared__ __align__(16) unsigned char smem[];
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WGN, wn = wave % WGN;
-  const int l32 = lane & 31, g = lane >> 5;
-
-  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-  const int total = tiles_m * tiles_n;
-  const int per_xcd = (total + 7) / 8;
-  const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-  if (logical >= total) return;
-  constexpr int GM = 8;
-  const int group = logical / (GM * tiles_n);
-  const int first_m = group * GM;
-  const int gsz = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
-  const int in_group = logical % (GM * tiles_n);
-  const int tm = first_m + in_group % gsz, tn = in_group / gsz;
-  const int m0 = tm * BM, n0 = tn * BN;
-
-  // lane -> (row within an 8-row chunk, logical 16-byte chunk)
-  static_assert(NW % 2 == 0, "chunk parity must be a per-wave constant");
-  const int cr = lane >> 3;                                   // row inside the wave's 8-row chunk
-  const int cl = (lane & 7) ^ (((wave & 1) << 2) | (cr >> 1));  // ((8*chunk + cr) >> 1) & 7, chunk = wave + i*NW
-  const bf16_t *a_ptr[A_CH];
-  const bf16_t *w_ptr[B_CH];
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) {
-    int m = m0 + (wave + i * NW) * 8 + cr;
-    m = m < p.M ? m : p.M - 1;
-    a_ptr[i] = p.A + (int64_t)m * p.lda + cl * 8;
-  }
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) {
-    int n = n0 + (wave + i * NW) * 8 + cr;
-    n = n < p.N ? n : p.N - 1;
-    w_ptr[i] = (p.wtab ? p.wtab[n >> 4] + (int64_t)(n & 15) * p.ldw : p.W + (int64_t)n * p.ldw) + cl * 8;
-  }
-  typedef __attribute__((address_space(3))) void *lds_ptr_t;
-  typedef const __attribute__((address_space(1))) void *glb_ptr_t;
-  auto issue_loads = [&](int stage, int k0) {
-    unsigned char *sa = smem + stage * STAGE_BYTES;
-    unsigned char *sb = sa + BM * 128;
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i)
-      __builtin_amdgcn_global_load_lds((glb_ptr_t)(a_ptr[i] + k0), (lds_ptr_t)(sa + (wave + i * NW) * 1024), 16, 0, 0);
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i)
-      __builtin_amdgcn_global_load_lds((glb_ptr_t)(w_ptr[i] + k0), (lds_ptr_t)(sb + (wave + i * NW) * 1024), 16, 0, 0);
-  };
-
-  floatx16 acc[FN][FM];
-#pragma unroll
-  for (int bn = 0; bn < FN; ++bn)
-#pragma unroll
-    for (int bm = 0; bm < FM; ++bm)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[bn][bm][v] = 0.f;
-
-  // byte offsets of this lane's operand rows inside a stage (row r, chunk c at r*128 + ((c ^ ((r>>1)&7)) << 4))
-  int w_off[FN], a_off[FM], w_sw[FN], a_sw[FM];
-#pragma unroll
-  for (int bn = 0; bn < FN; ++bn) { int r = wn * WTN + bn * 32 + l32; w_off[bn] = BM * 128 + r * 128; w_sw[bn] = (r >> 1) & 7; }
-#pragma unroll
-  for (int bm = 0; bm < FM; ++bm) { int r = wm * WTM + bm * 32 + l32; a_off[bm] = r * 128; a_sw[bm] = (r >> 1) & 7; }
-
-  bf16x8 wf[2][FN], af[2][FM];
-  auto load_frags = [&](int buf, const unsigned char *st, int kk) {
-    const int cc = kk * 2 + g;
-#pragma unroll
-    for (int bn = 0; bn < FN; ++bn) wf[buf][bn] = *(const bf16x8 *)(st + w_off[bn] + ((cc ^ w_sw[bn]) << 4));
-#pragma unroll
-    for (int bm = 0; bm < FM; ++bm) af[buf][bm] = *(const bf16x8 *)(st + a_off[bm] + ((cc ^ a_sw[bm]) << 4));
-  };
-
-  const int nk = p.K / BK;
-  long long t_vm = 0, t_bar = 0, t_frag = 0, t_begin = 0;
-  if constexpr (PROF) t_begin = clock64();
-  issue_loads(0, 0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const unsigned char *st = smem + (kt & 1) * STAGE_BYTES;
-    long long tf0 = 0;
-    if constexpr (PROF) tf0 = clock64();
-    load_frags(0, st, 0);
-    if constexpr (PROF) { __builtin_amdgcn_s_waitcnt(0xC07F); t_frag += clock64() - tf0; }
-    __builtin_amdgcn_sched_barrier(0);
-    // Step 0: its MFMAs are interleaved one-to-one with the LDS-DMA loads of the
-    // next tile and with the operand reads of step 1, so that every non-MFMA
-    // instruction issues in the shadow of an MFMA that is executing.  The loads
-    // are unconditional (after the last tile they re-read it into the idle stage).
-    {
-      const int nstage = (kt + 1) & 1;
-      const int nk0 = p.dbg == 2 ? 0 : (kt + 1 < nk ? kt + 1 : kt) * BK;
-      unsigned char *nsa = smem + nstage * STAGE_BYTES;
-      unsigned char *nsb = nsa + BM * 128;
-      const int cc1 = 2 + g;
-#pragma unroll
-      for (int i = 0; i < FN * FM; ++i) {
-        const int bn = i / FM, bm = i % FM;
-        acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0][bn], af[0][bm], acc[bn][bm], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (!PROF || p.head_dim == 0) {   // (the profiling build can drop the loads: head_dim = 1 there means "no loads")
-          if (i < A_CH)
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(a_ptr[i] + nk0), (lds_ptr_t)(nsa + (wave + i * NW) * 1024), 16, 0, 0);
-          else if (i < A_CH + B_CH)
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(w_ptr[i - A_CH] + nk0), (lds_ptr_t)(nsb + (wave + (i - A_CH) * NW) * 1024), 16, 0, 0);
-        }
-        if (i < FN) wf[1][i] = *(const bf16x8 *)(st + w_off[i] + ((cc1 ^ w_sw[i]) << 4));
-        else if (i < FN + FM) af[1][i - FN] = *(const bf16x8 *)(st + a_off[i - FN] + ((cc1 ^ a_sw[i - FN]) << 4));
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-#pragma unroll
-    for (int kk = 1; kk < BK / 16; ++kk) {
-      if (kk + 1 < BK / 16) load_frags((kk + 1) & 1, st, kk + 1);
-#pragma unroll
-      for (int bn = 0; bn < FN; ++bn)
-#pragma unroll
-        for (int bm = 0; bm < FM; ++bm)
-          acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk & 1][bn], af[kk & 1][bm], acc[bn][bm], 0, 0, 0);
-      if (kk + 1 < BK / 16) {
-#pragma unroll
-        for (int i = 0; i < FN + FM; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    long long t0 = 0, t1 = 0;
-    if constexpr (PROF) t0 = clock64();
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // this wave's loads of the next tile have landed in LDS
-    if constexpr (PROF) t1 = clock64();
-    __syncthreads();
-    if constexpr (PROF) { t_vm += t1 - t0; t_bar += clock64() - t1; }
-  }
-  if constexpr (PROF) {
-    long long t_loop = clock64() - t_begin;
-    gemm_epilogue<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
-    if (lane == 0 && p.stage) {   // experiment only: `stage` doubles as the int64 output [wg][wave][5]
-      long long *o = (long long *)p.stage + ((long long)blockIdx.x * (WGM * WGN) + wave) * 5;
-      o[0] = t_loop; o[1] = t_vm; o[2] = t_bar; o[3] = t_frag; o[4] = clock64() - t_begin;
-    }
-    return;
-  }
-  gemm_epilogue<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
-}
-
-// ---------------------------------------------------------------------------
 // Epilogue that leaves through LDS.  The accumulator layout gives a lane 4
 // consecutive columns of 32 different rows, i.e. 8-byte stores into 32 different
 // cache lines per instruction.  Here each wave first applies its epilogue
@@ -497,7 +315,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds_kernel(GemmParams p) 
 // [row][column] (row stride padded by 16 bytes), and then streams it out with
 // 16-byte stores in which 16 (or 8) consecutive lanes cover one contiguous row
 // segment of 256 (128) bytes.  The residual add stages fp32 accumulators, 32 rows
-// at a time, so that h + acc is rounded to bf16 once.
+// at a time, and adds them to the fp32 residual stream in place.
 template <int EPI, int FM, int FN>
 __device__ __forceinline__ void gemm_epilogue_lds(const GemmParams &p, floatx16 (&acc)[FN][FM], const int m_base,
                                                   const int n_base, const int lane, unsigned char *slab) {
@@ -506,7 +324,7 @@ __device__ __forceinline__ void gemm_epilogue_lds(const GemmParams &p, floatx16 
   if (n_base >= p.N) return;                       // N is a multiple of 16; a wave tile past it has nothing to do
   if constexpr (EPI == EPI_RESID) {
     constexpr int RS = 128 * 4 + 16;               // fp32 row stride in bytes
-    bf16_t *cbase = (bf16_t *)p.C + n_base;
+    float *cbase = (float *)p.C + n_base;
 #pragma unroll
     for (int bm = 0; bm < FM; ++bm) {
 #pragma unroll
@@ -522,10 +340,10 @@ __device__ __forceinline__ void gemm_epilogue_lds(const GemmParams &p, floatx16 
         const int m = m_base + bm * 32 + row, n = n_base + ch * 8;
         const float4 lo = *(const float4 *)(slab + row * RS + ch * 32), hi = *(const float4 *)(slab + row * RS + ch * 32 + 16);
         if (m < p.M && n < p.N) {
-          bf16_t *dst = cbase + (int64_t)m * p.ldc + ch * 8;
-          const uint4 r = *(const uint4 *)dst;
-          *(uint4 *)dst = make_uint4(pack_bf16x2(lo.x + bf16lo(r.x), lo.y + bf16hi(r.x)), pack_bf16x2(lo.z + bf16lo(r.y), lo.w + bf16hi(r.y)),
-                                     pack_bf16x2(hi.x + bf16lo(r.z), hi.y + bf16hi(r.z)), pack_bf16x2(hi.z + bf16lo(r.w), hi.w + bf16hi(r.w)));
+          float4 *dst = (float4 *)(cbase + (int64_t)m * p.ldc + ch * 8);
+          const float4 r0 = dst[0], r1 = dst[1];
+          dst[0] = make_float4(r0.x + lo.x, r0.y + lo.y, r0.z + lo.z, r0.w + lo.w);
+          dst[1] = make_float4(r1.x + hi.x, r1.y + hi.y, r1.z + hi.z, r1.w + hi.w);
         }
       }
     }
@@ -693,26 +511,14 @@ __device__ __forceinline__ void gemm_epilogue_lds(const GemmParams &p, floatx16 
 __device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
 }
-// 4 bytes per lane (lane i lands at lds_addr + 4*i): used to pull a cache line into L2 ahead of time
-__device__ __forceinline__ void lds_dma4(const void *gptr, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
-}
-// the same with the non-temporal hint (streamed once through L2 by this workgroup)
-__device__ __forceinline__ void lds_dma16_nt(const void *gptr, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds_addr), "v"(gptr) : "memory");
-}
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int XP = 0>   // XP: 0 product; 1 cycle counters; 2/3/4 timing experiments without the in-loop LDS reads / DMA / both (results are meaningless there)
+template <int BM, int BN, int WGM, int WGN, int EPI>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p) {
-  constexpr bool PROF = XP == 1 || XP == 11;   // 11: only the per-tile totals (no timers inside the loop)
-  constexpr bool PROF_STEP = XP == 1;
-  constexpr bool DO_RD = XP != 2 && XP != 4, DO_DMA = XP != 3 && XP != 4;
   constexpr int NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   static_assert(WTN == 128 && WTM % 32 == 0, "wave tile");
   constexpr int FM = WTM / 32, FN = WTN / 32;
-  constexpr bool TOUCH = XP == 10;   // one L2 prefetch request per wave and step (see below)
-  constexpr int NS = (XP == 5 || TOUCH) ? 4 : XP == 6 ? 3 : 5, BKS = 32;   // stages (XP 5/6: timing experiments with fewer stages in flight)
+  constexpr int NS = 5, BKS = 32;                            // stages, k values per step
   constexpr int A_CH = BM / 16 / NW, B_CH = BN / 16 / NW;   // 1 KB chunks (16 rows) per wave per stage
   constexpr int LPW = A_CH + B_CH;                           // LDS-DMA loads per wave per step
   constexpr int STAGE_BYTES = (BM + BN) * 64;
@@ -757,35 +563,16 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
     n = n < p.N ? n : p.N - 1;
     w_ptr[i] = (p.wtab ? p.wtab[n >> 4] + (int64_t)(n & 15) * p.ldw : p.W + (int64_t)n * p.ldw) + cl * 8;
   }
-  // L2 prefetch: the 32 workgroups resident on an XCD are 8 m tiles x 4 n tiles; an A row is used by the
-  // 4 workgroups of its m tile, a W row by the 8 of its n tile, at about the same time, so that all of them
-  // wait for the same miss.  Each workgroup therefore touches its share of the rows (a quarter of its A
-  // tile on even steps, an eighth of its W tile on odd steps) several steps ahead of everybody's loads.
-  const bf16_t *t_a = nullptr, *t_w = nullptr;
-  if constexpr (TOUCH) {
-    int m = m0 + (tn & 3) * 64 + wave * 16 + (lane & 15);
-    m = m < p.M ? m : p.M - 1;
-    t_a = p.A + (int64_t)m * p.lda;
-    int n = n0 + ((in_group % gsz) & 7) * 32 + wave * 8 + (lane & 7);
-    n = n < p.N ? n : p.N - 1;
-    t_w = p.wtab ? p.wtab[n >> 4] + (int64_t)(n & 15) * p.ldw : p.W + (int64_t)n * p.ldw;
-  }
   typedef __attribute__((address_space(3))) void *lds_ptr_t;
   const unsigned lds_base = (unsigned)(size_t)(lds_ptr_t)smem;
   // one of the LPW loads of a step: idx < A_CH -> A chunk, else W chunk; `stage` = byte offset of the stage
   auto issue_one = [&](int idx, unsigned stage, int k0) {
 #pragma unroll
     for (int i = 0; i < A_CH; ++i)
-      if (idx == i) {
-        if constexpr (XP == 7 || XP == 8) lds_dma16_nt(a_ptr[i] + k0, lds_base + stage + (wave + i * NW) * 1024);
-        else lds_dma16(a_ptr[i] + k0, lds_base + stage + (wave + i * NW) * 1024);
-      }
+      if (idx == i) lds_dma16(a_ptr[i] + k0, lds_base + stage + (wave + i * NW) * 1024);
 #pragma unroll
     for (int i = 0; i < B_CH; ++i)
-      if (idx == A_CH + i) {
-        if constexpr (XP == 7 || XP == 9) lds_dma16_nt(w_ptr[i] + k0, lds_base + stage + BM * 64 + (wave + i * NW) * 1024);
-        else lds_dma16(w_ptr[i] + k0, lds_base + stage + BM * 64 + (wave + i * NW) * 1024);
-      }
+      if (idx == A_CH + i) lds_dma16(w_ptr[i] + k0, lds_base + stage + BM * 64 + (wave + i * NW) * 1024);
   };
 
   floatx16 acc[FN][FM];
@@ -815,8 +602,6 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
   };
 
   const int nk = p.K / BKS;
-  long long t_vm = 0, t_bar = 0, t_begin = 0;
-  if constexpr (PROF) t_begin = clock64();
   // prologue: steps 0..3 in flight, steps 0 and 1 resident
 #pragma unroll
   for (int s0 = 0; s0 < NS - 1; ++s0) {
@@ -824,9 +609,8 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
 #pragma unroll
     for (int i = 0; i < LPW; ++i) issue_one(i, s0 * STAGE_BYTES, k0);
   }
-  constexpr int VMCNT0 = (NS - 3) * LPW;                              // prologue: the NS-3 youngest groups may stay in flight
-  constexpr int VMCNT2 = TOUCH ? (NS - 3) * (LPW + 1) + 1 : VMCNT0;   // loop: those, plus the prefetch requests issued since (one per step, after the step's loads)
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (VMCNT0 & 15) | ((VMCNT0 >> 4) << 14));
+  constexpr int VMCNT = (NS - 3) * LPW;   // the NS-3 youngest groups may stay in flight
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (VMCNT & 15) | ((VMCNT >> 4) << 14));
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < FN + FM; ++i) load_frag(i, 0, smem, 0);
@@ -838,7 +622,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
     const unsigned char *st = smem + s_cur * STAGE_BYTES;
     const unsigned char *stn = smem + s_nxt * STAGE_BYTES;
     const unsigned stl = s_ld * STAGE_BYTES;
-    const int kl = (PROF && p.head_dim == 1) ? 0 : (t + NS - 1 < nk ? t + NS - 1 : nk - 1) * BKS;   // clamped: the request count per step stays constant (profiling build: head_dim 1 = always tile 0)
+    const int kl = (t + NS - 1 < nk ? t + NS - 1 : nk - 1) * BKS;   // clamped: the request count per step stays constant
     __builtin_amdgcn_sched_barrier(0);
     // sub-step 0: MFMAs on fragment buffer 0; fetch buffer 1 (sub-step 1 of this stage); first half of the loads
 #pragma unroll
@@ -846,8 +630,8 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
       const int bn = i / FM, bm = i % FM;
       acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0][bn], af[0][bm], acc[bn][bm], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      if (DO_RD && i < FN + FM) load_frag(i, 1, st, 1);
-      if (DO_DMA && (i % GSP) == GSP - 1) issue_one(i / GSP, stl, kl);              // one request every GSP MFMAs: keeps the address unit's queue short
+      if (i < FN + FM) load_frag(i, 1, st, 1);
+      if ((i % GSP) == GSP - 1) issue_one(i / GSP, stl, kl);              // one request every GSP MFMAs: keeps the address unit's queue short
       __builtin_amdgcn_sched_barrier(0);
     }
     // sub-step 1: MFMAs on buffer 1; fetch buffer 0 from the next stage (resident since the previous barrier); second half of the loads
@@ -856,21 +640,12 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
       const int bn = i / FM, bm = i % FM;
       acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1][bn], af[1][bm], acc[bn][bm], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      if (DO_RD && i < FN + FM) load_frag(i, 0, stn, 0);
-      if (DO_DMA && (i % GSP) == GSP - 1) issue_one(LPW / 2 + i / GSP, stl, kl);
+      if (i < FN + FM) load_frag(i, 0, stn, 0);
+      if ((i % GSP) == GSP - 1) issue_one(LPW / 2 + i / GSP, stl, kl);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if constexpr (TOUCH) {   // the 64-wide k chunk 4 steps beyond the one being requested now
-      int c = (t + NS - 1 + 5) >> 1;
-      c = c < (nk >> 1) ? c : (nk >> 1) - 1;
-      lds_dma4(((t & 1) ? t_w : t_a) + c * 64, lds_base + NS * STAGE_BYTES + wave * 256);
-    }
-    long long tp0 = 0, tp1 = 0;
-    if constexpr (PROF_STEP) { __builtin_amdgcn_s_waitcnt(0xC07F); tp0 = clock64(); }
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (VMCNT2 & 15) | ((VMCNT2 >> 4) << 14));   // step t+2 has landed (this wave's part)
-    if constexpr (PROF_STEP) tp1 = clock64();
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (VMCNT & 15) | ((VMCNT >> 4) << 14));   // step t+2 has landed (this wave's part)
     __syncthreads();
-    if constexpr (PROF_STEP) { t_vm += tp1 - tp0; t_bar += clock64() - tp1; }
     s_cur = s_nxt;
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped extra loads ...
@@ -878,16 +653,6 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_dlds5_kernel(GemmParams p)
   constexpr int SLAB = WTM * (128 * 2 + 16) > 32 * (128 * 4 + 16) ? WTM * (128 * 2 + 16) : 32 * (128 * 4 + 16);
   static_assert(NW * SLAB <= 5 * STAGE_BYTES, "epilogue slabs must fit in the stage memory");
   unsigned char *slab = smem + wave * SLAB;
-  if constexpr (PROF) {
-    const long long t_loop = clock64() - t_begin;
-    if constexpr (EPI == EPI_STORE_F32) gemm_epilogue<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
-    else gemm_epilogue_lds<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane, slab);
-    if (lane == 0 && p.stage) {   // experiment only: `stage` doubles as the int64 output [wg][wave][5]
-      long long *o = (long long *)p.stage + ((long long)blockIdx.x * NW + wave) * 5;
-      o[0] = t_loop; o[1] = t_vm; o[2] = t_bar; o[3] = 0; o[4] = clock64() - t_begin;
-    }
-    return;
-  }
   if constexpr (EPI == EPI_STORE_F32) gemm_epilogue<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
   else gemm_epilogue_lds<EPI, FM, FN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane, slab);
 }
@@ -896,31 +661,6 @@ template <int BM, int BN, int WGM, int WGN, int EPI>
 int launch_dlds5(const GemmParams &p, hipStream_t st) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int SMEM = 5 * (BM + BN) * 64;
-  if constexpr (EPI == EPI_STORE_BF16) {
-    if (p.dbg == 8 || p.dbg == 9) {   // timing experiment: per-wave cycle breakdown written through p.stage (9: totals only)
-      auto kp = p.dbg == 8 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 1> : gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 11>;
-      (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-      const int tl = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
-      hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(NT), SMEM, st, p);
-      return 0;
-    }
-    if constexpr (WGM == 2) {
-      if (p.dbg >= 25 && p.dbg <= 28) {   // non-temporal loads: both operands (25), A only (26), W only (27); shared L2 prefetch (28)
-        auto kp = p.dbg == 25 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 7> : p.dbg == 26 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 8> : p.dbg == 27 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 9> : gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 10>;
-        (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-        const int tl = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
-        hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(NT), SMEM, st, p);
-        return 0;
-      }
-      if (p.dbg >= 20 && p.dbg <= 24) {   // timing experiments: loop without LDS reads (20), without DMA (21), without both (22); 4 / 3 stages (23 / 24)
-        auto kp = p.dbg == 20 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 2> : p.dbg == 21 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 3> : p.dbg == 22 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 4> : p.dbg == 23 ? gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 5> : gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI, 6>;
-        (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-        const int tl = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
-        hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(NT), SMEM, st, p);
-        return 0;
-      }
-    }
-  }
   auto kern = gemm_dlds5_kernel<BM, BN, WGM, WGN, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -934,103 +674,11 @@ int launch_dlds5(const GemmParams &p, hipStream_t st) {
   return 0;
 }
 
-// Timing experiment: the memory side of gemm_dlds_kernel alone (same addresses,
-// same LDS-DMA instructions, same wait + barrier per k tile, no MFMA work).
-template <int BM, int BN, int NW>
-__global__ __launch_bounds__(NW * 64) void gemm_loadonly_kernel(GemmParams p) {
-  constexpr int A_CH = BM / 8 / NW, B_CH = BN / 8 / NW;
-  constexpr int STAGE_BYTES = (BM + BN) * 128;
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-  const int total = tiles_m * tiles_n;
-  const int per_xcd = (total + 7) / 8;
-  const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-  if (logical >= total) return;
-  constexpr int GM = 8;
-  const int group = logical / (GM * tiles_n);
-  const int first_m = group * GM;
-  const int gsz = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
-  const int in_group = logical % (GM * tiles_n);
-  const int m0 = (first_m + in_group % gsz) * BM, n0 = (in_group / gsz) * BN;
-  const int cr = lane >> 3;
-  const int cl = (lane & 7) ^ (((wave & 1) << 2) | (cr >> 1));
-  const bf16_t *a_ptr[A_CH];
-  const bf16_t *w_ptr[B_CH];
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) {
-    int m = m0 + (wave + i * NW) * 8 + cr;
-    m = m < p.M ? m : p.M - 1;
-    a_ptr[i] = p.A + (int64_t)m * p.lda + cl * 8;
-  }
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) {
-    int n = n0 + (wave + i * NW) * 8 + cr;
-    n = n < p.N ? n : p.N - 1;
-    w_ptr[i] = p.W + (int64_t)n * p.ldw + cl * 8;
-  }
-  typedef __attribute__((address_space(3))) void *lds_ptr_t;
-  typedef const __attribute__((address_space(1))) void *glb_ptr_t;
-  const int nk = p.K / BK;
-  for (int kt = 0; kt < nk; ++kt) {
-    unsigned char *sa = smem + (kt & 1) * STAGE_BYTES;
-    unsigned char *sb = sa + BM * 128;
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i)
-      __builtin_amdgcn_global_load_lds((glb_ptr_t)(a_ptr[i] + kt * BK), (lds_ptr_t)(sa + (wave + i * NW) * 1024), 16, 0, 0);
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i)
-      __builtin_amdgcn_global_load_lds((glb_ptr_t)(w_ptr[i] + kt * BK), (lds_ptr_t)(sb + (wave + i * NW) * 1024), 16, 0, 0);
-    if (p.dbg == 6 || (kt & 1)) {   // dbg 6: wait every tile; dbg 7: every second tile (two tiles in flight)
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-      __syncthreads();
-    }
-  }
-  __builtin_amdgcn_s_waitcnt(0x0F70);
-  __syncthreads();
-  if (p.dbg == 12345) ((float *)p.C)[tid] = smem[tid];
-}
-
 template <int BM, int BN, int WGM, int WGN, int EPI>
-int launch_dlds(const GemmParams &p, hipStream_t st) {
-  if (p.dbg == 6 || p.dbg == 7) {
-    constexpr int NWV = WGM * WGN;
-    constexpr int SMEMX = 2 * (BM + BN) * 128;
-    auto kx = gemm_loadonly_kernel<BM, BN, NWV>;
-    (void)hipFuncSetAttribute((const void *)kx, hipFuncAttributeMaxDynamicSharedMemorySize, SMEMX);
-    const int tilesx = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
-    hipLaunchKernelGGL(kx, dim3(((tilesx + 7) / 8) * 8), dim3(NWV * 64), SMEMX, st, p);
-    return 0;
-  }
-  constexpr int NT = WGM * WGN * 64;
-  constexpr int SMEM = 2 * (BM + BN) * 128;
-  if constexpr (EPI == EPI_STORE_BF16) {
-    if (p.dbg == 8) {   // timing experiment: per-wave cycle breakdown written through p.stage
-      auto kp = gemm_dlds_kernel<BM, BN, WGM, WGN, EPI, true>;
-      (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-      const int tl = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
-      hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(NT), SMEM, st, p);
-      return 0;
-    }
-  }
-  auto kern = gemm_dlds_kernel<BM, BN, WGM, WGN, EPI>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-    if (e != hipSuccess) return (int)e;
-    attr_set = true;
-  }
-  const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
-  const int grid = ((tiles + 7) / 8) * 8;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), SMEM, st, p);
-  return 0;
-}
-
-template <int BM, int BN, int WGM, int WGN, int EPI, bool GAIN>
 int launch_one(const GemmParams &p, hipStream_t st) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int SMEM = 2 * (BM + BN) * 128;
-  auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, GAIN>;
+  auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI>;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
@@ -1066,17 +714,29 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
   // in which consecutive lanes cover a contiguous row segment.
   const int l32 = lane & 31, g = lane >> 5;
   if constexpr (EPI == EPI_RESID) {
+    // C (fp32, the residual stream) += acc.  Optionally also the bf16 operand of the next projection,
+    // hb = bf16(C_new * gain of that projection's RMSNorm), and the sum of squares of C_new over this
+    // wave's 64 columns (the consumer's epilogue applies 1/rms as a row factor).
     constexpr int RS = 64 * 4 + 16;                // fp32 row stride in bytes
-    bf16_t *cbase = (bf16_t *)p.C + n_base;
+    float *cbase = (float *)p.C + n_base;
+    const int ch = lane & 7, r8 = lane >> 3;       // this lane's 8 columns, its row inside a group of 8
+    float gv[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
+    if (p.hb && p.hb_gain) {
+      const uint4 gq = *(const uint4 *)(p.hb_gain + n_base + ch * 8);
+      gv[0] = bf16lo(gq.x); gv[1] = bf16hi(gq.x); gv[2] = bf16lo(gq.y); gv[3] = bf16hi(gq.y);
+      gv[4] = bf16lo(gq.z); gv[5] = bf16hi(gq.z); gv[6] = bf16lo(gq.w); gv[7] = bf16hi(gq.w);
+    }
     // the residual rows of the whole wave tile are requested up front (the operand registers of the
-    // main loop are free by now), so their latency is paid once, not once per 32 rows
-    uint4 res[FM][4];
+    // main loop are free by now), so their latency is paid once and no load follows a store
+    float4 res[FM][4][2];
 #pragma unroll
     for (int bm = 0; bm < FM; ++bm)
 #pragma unroll
       for (int it = 0; it < 4; ++it) {
-        const int m = m_base + bm * 32 + it * 8 + (lane >> 3);
-        res[bm][it] = *(const uint4 *)(cbase + (int64_t)(m < p.M ? m : p.M - 1) * p.ldc + (lane & 7) * 8);
+        const int m = m_base + bm * 32 + it * 8 + r8;
+        const float4 *src = (const float4 *)(cbase + (int64_t)(m < p.M ? m : p.M - 1) * p.ldc + ch * 8);
+        res[bm][it][0] = src[0];
+        res[bm][it][1] = src[1];
       }
 #pragma unroll
     for (int bm = 0; bm < FM; ++bm) {
@@ -1089,14 +749,28 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
       // a wave's LDS operations execute in order: the reads below see the writes above
 #pragma unroll
       for (int it = 0; it < 4; ++it) {
-        const int row = it * 8 + (lane >> 3), ch = lane & 7;
+        const int row = it * 8 + r8;
         const int m = m_base + bm * 32 + row;
         const float4 lo = *(const float4 *)(slab + row * RS + ch * 32), hi = *(const float4 *)(slab + row * RS + ch * 32 + 16);
+        const float4 r0 = res[bm][it][0], r1 = res[bm][it][1];
+        const float x[8] = {r0.x + lo.x, r0.y + lo.y, r0.z + lo.z, r0.w + lo.w, r1.x + hi.x, r1.y + hi.y, r1.z + hi.z, r1.w + hi.w};
         if (m < p.M) {
-          const uint4 r = res[bm][it];
-          *(uint4 *)(cbase + (int64_t)m * p.ldc + ch * 8) =
-              make_uint4(pack_bf16x2(lo.x + bf16lo(r.x), lo.y + bf16hi(r.x)), pack_bf16x2(lo.z + bf16lo(r.y), lo.w + bf16hi(r.y)),
-                         pack_bf16x2(hi.x + bf16lo(r.z), hi.y + bf16hi(r.z)), pack_bf16x2(hi.z + bf16lo(r.w), hi.w + bf16hi(r.w)));
+          float4 *dst = (float4 *)(cbase + (int64_t)m * p.ldc + ch * 8);
+          dst[0] = make_float4(x[0], x[1], x[2], x[3]);
+          dst[1] = make_float4(x[4], x[5], x[6], x[7]);
+          if (p.hb)
+            *(uint4 *)(p.hb + (int64_t)m * p.ldc + n_base + ch * 8) =
+                make_uint4(pack_bf16x2(x[0] * gv[0], x[1] * gv[1]), pack_bf16x2(x[2] * gv[2], x[3] * gv[3]),
+                           pack_bf16x2(x[4] * gv[4], x[5] * gv[5]), pack_bf16x2(x[6] * gv[6], x[7] * gv[7]));
+        }
+        if (p.ssq) {   // fixed order: the lane's 8 columns left to right, then a butterfly over the row's 8 lanes
+          float sq = 0.f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) sq += x[e] * x[e];
+          sq += __shfl_xor(sq, 1);
+          sq += __shfl_xor(sq, 2);
+          sq += __shfl_xor(sq, 4);
+          if (ch == 0 && m < p.M) p.ssq[(int64_t)(n_base >> 6) * p.M + m] = sq;
         }
       }
     }
@@ -1280,7 +954,7 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
   }
 }
 
-template <int EPI, bool PROF = false, int XP = 0>   // PROF: cycle counters written through p.stage; XP 1 / 2 / 3 / 4: the loop without its weight requests / activation requests / LDS fragment reads / barrier (timing experiments, results meaningless)
+template <int EPI>
 __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
   constexpr int BM = 256, BN = 256, FM = 8;
   constexpr int NSA = 5, STAGE = BM * 128;   // activation stages: 256 rows x 128 bytes (one 64-wide k step)
@@ -1349,8 +1023,6 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
     dst = *(const bf16x8 *)(w_ptr[nb] + ((int64_t)step * 4 + kk) * 512);
   };
 
-  long long t_begin = 0, t_vm = 0, t_bar = 0;
-  if constexpr (PROF) t_begin = clock64();
   // prologue: steps 0, 1, 2 requested (16 requests per wave and step, activations and weights alternating)
 #pragma unroll
   for (int s0 = 0; s0 < 3; ++s0) {
@@ -1381,12 +1053,8 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
         // 14 LDS-DMA requests are younger than it (8 of step it-1, 6 of this step).  Register loads and
         // LDS-DMA do not complete in one common order, so all 14 requests that may stay in flight could
         // be LDS-DMA ones: the wait is for 14 in total, not for 14 + the 14 younger weight loads.
-        long long tp0 = 0, tp1 = 0;
-        if constexpr (PROF) { __builtin_amdgcn_s_waitcnt(0xC07F); tp0 = clock64(); }
         __builtin_amdgcn_s_waitcnt(0x0F7E);   // vmcnt(14)
-        if constexpr (PROF) tp1 = clock64();
-        if constexpr (XP != 4) __builtin_amdgcn_s_barrier();
-        if constexpr (PROF) { t_vm += tp1 - tp0; t_bar += clock64() - tp1; }
+        __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
@@ -1394,9 +1062,9 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
         const int nb = i / 8, bm = i % 8;
         acc[nb][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][kk * 2 + nb], af[kk & 1][bm], acc[nb][bm], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (i < 8 && (XP != 3 || it == 0)) af[(kk + 1) & 1][i] = *(const bf16x8 *)((kk < 3 ? st : stn) + (a_lane ^ (unsigned)(((kk + 1) & 3) * 32)) + i * 4096);
-        if (i % 8 == 3 && XP != 2) issue_a(kk * 2 + i / 8, sld, kl);
-        if (i % 8 == 7 && XP != 1) load_w(wf[lslot][kk * 2 + i / 8], i / 8, kk, kl);
+        if (i < 8) af[(kk + 1) & 1][i] = *(const bf16x8 *)((kk < 3 ? st : stn) + (a_lane ^ (unsigned)(((kk + 1) & 3) * 32)) + i * 4096);
+        if (i % 8 == 3) issue_a(kk * 2 + i / 8, sld, kl);
+        if (i % 8 == 7) load_w(wf[lslot][kk * 2 + i / 8], i / 8, kk, kl);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -1412,37 +1080,12 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
   __builtin_amdgcn_s_barrier();         // ... of every wave, before LDS is reused by the epilogue
   // per-wave slab: one 32-row block of fp32 (272-byte rows), or, for the rotating epilogues, all eight blocks of bf16 (144-byte rows)
   unsigned char *slab = smem + wave * ((EPI == EPI_QKV || EPI == EPI_KV) ? FM * 32 * (64 * 2 + 16) : 32 * (64 * 4 + 16));
-  long long t_loop = 0;
-  if constexpr (PROF) t_loop = clock64() - t_begin;
   gemm_epilogue_n64<EPI, FM>(p, acc, m0, n0, lane, slab);
-  if constexpr (PROF) {
-    if (lane == 0 && p.stage) {   // experiment only: `stage` doubles as the int64 output [wg][wave][5]
-      long long *o = (long long *)p.stage + ((long long)blockIdx.x * 4 + wave) * 5;
-      o[0] = t_loop; o[1] = t_vm; o[2] = t_bar; o[3] = 0; o[4] = clock64() - t_begin;
-    }
-  }
 }
 
 template <int EPI>
 int launch_wreg(const GemmParams &p, hipStream_t st) {
   constexpr int SMEM = 5 * 256 * 128;
-  if constexpr (EPI == EPI_STORE_BF16) {
-    if (p.dbg == 8) {   // timing experiment: per-wave cycle breakdown written through p.stage
-      auto kp = gemm_wreg_kernel<EPI, true>;
-      (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-      const int tl = ((p.M + 255) / 256) * (p.N / 256);
-      hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(256), SMEM, st, p);
-      return 0;
-    }
-    if (p.dbg >= 31 && p.dbg <= 34) {   // timing experiments: the loop without its weight requests / activation requests / LDS fragment reads / barrier
-      auto kp = p.dbg == 31 ? gemm_wreg_kernel<EPI, false, 1> : p.dbg == 32 ? gemm_wreg_kernel<EPI, false, 2>
-              : p.dbg == 33 ? gemm_wreg_kernel<EPI, false, 3> : gemm_wreg_kernel<EPI, false, 4>;
-      (void)hipFuncSetAttribute((const void *)kp, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-      const int tl = ((p.M + 255) / 256) * (p.N / 256);
-      hipLaunchKernelGGL(kp, dim3(((tl + 7) / 8) * 8), dim3(256), SMEM, st, p);
-      return 0;
-    }
-  }
   auto kern = gemm_wreg_kernel<EPI>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -1455,25 +1098,21 @@ int launch_wreg(const GemmParams &p, hipStream_t st) {
   return 0;
 }
 
-template <int EPI, bool GAIN>
+// variant: 0 = pick by shape; 1 = 256x256 tile, register-staged loads; 2 = 128x128 tile; 14 / 15 = the
+// five-stage direct-to-LDS loop with 4 / 8 waves; 27 = the packed-weight loop (needs p.wpack)
+template <int EPI>
 int launch_epi(const GemmParams &p, int variant, hipStream_t st) {
-  if (variant == 0) variant = (p.M >= 1024) ? ((!GAIN && (p.K % BK) == 0) ? g_big_variant : 1) : 2;
-  if constexpr (!GAIN && EPI != EPI_STORE_F32) {
+  if (variant == 0) variant = (p.M >= 1024) ? ((p.K % BK) == 0 ? 14 : 1) : 2;
+  if constexpr (EPI != EPI_STORE_F32) {
     // weights available in fragment order: the loop that keeps them out of LDS
-    if (p.wpack && (variant == 27 || variant == g_big_variant) && p.M >= 1024 && (p.K % 256) == 0 && (p.N % 256) == 0)
-      return launch_wreg<EPI>(p, st);
+    if ((variant == 27 || variant == 14) && gemm_uses_packed_weights(p)) return launch_wreg<EPI>(p, st);
   }
-  if (variant == 27) variant = g_big_variant;
-  if constexpr (!GAIN) {
-    if ((variant == 4 || variant == 5) && (p.K % BK) != 0) variant = 1;
-    if ((variant == 14 || variant == 15) && (p.K % BK) != 0) variant = 1;
-    if (variant == 14) return launch_dlds5<256, 256, 2, 2, EPI>(p, st);
-    if (variant == 15) return launch_dlds5<256, 256, 4, 2, EPI>(p, st);
-    if (variant == 4) return launch_dlds<256, 256, 4, 2, EPI>(p, st);
-    if (variant == 5) return launch_dlds<256, 256, 2, 2, EPI>(p, st);
-  }
-  if (variant == 1 || variant == 4 || variant == 5 || variant == 14 || variant == 15) return launch_one<256, 256, 2, 2, EPI, GAIN>(p, st);
-  return launch_one<128, 128, 4, 1, EPI, GAIN>(p, st);
+  if (variant == 27) variant = 14;
+  if ((variant == 14 || variant == 15) && (p.K % BK) != 0) variant = 1;
+  if (variant == 14) return launch_dlds5<256, 256, 2, 2, EPI>(p, st);
+  if (variant == 15) return launch_dlds5<256, 256, 4, 2, EPI>(p, st);
+  if (variant == 1) return launch_one<256, 256, 2, 2, EPI>(p, st);
+  return launch_one<128, 128, 4, 1, EPI>(p, st);
 }
 
 }  // namespace
@@ -1514,29 +1153,18 @@ int launch_mfma_rate(const bf16_t *operands, float *sink, int32_t n_workgroups, 
 // Whether launch_gemm(p, epi, 0, ...) reads the fragment-order copy p.wpack (and not p.W / p.wtab): the
 // driver needs to know, because that copy of a projection behind an RMSNorm has the norm's gain folded in.
 bool gemm_uses_packed_weights(const GemmParams &p) {
-  return p.wpack && !p.gain_tab && p.M >= 1024 && (p.K % 256) == 0 && (p.N % 256) == 0;
+  return p.wpack && p.M >= 1024 && (p.K % 256) == 0 && (p.N % 256) == 0;
 }
 
-int launch_gemm(const GemmParams &p_in, int epi, int variant, hipStream_t st) {
-  if (p_in.M <= 0 || p_in.N <= 0 || p_in.K <= 0) return 0;
-  GemmParams p = p_in;
-  static int env_gm = -1;
-  if (env_gm < 0) { const char *e = getenv("SWIFTKV_GEMM_RASTER_GM"); env_gm = e ? atoi(e) : 0; }
-  if (p.raster_gm == 0) p.raster_gm = env_gm;
-  static bool env_read = false;
-  if (!env_read) {   // SWIFTKV_GEMM_MAINLOOP=5|14|15 picks the main loop of large GEMMs (tuning aid)
-    const char *e = getenv("SWIFTKV_GEMM_MAINLOOP");
-    if (e && (atoi(e) == 5 || atoi(e) == 14 || atoi(e) == 15 || atoi(e) == 4 || atoi(e) == 1)) g_big_variant = atoi(e);
-    env_read = true;
-  }
-  const bool gain = p.gain_tab != nullptr;
+int launch_gemm(const GemmParams &p, int epi, int variant, hipStream_t st) {
+  if (p.M <= 0 || p.N <= 0 || p.K <= 0) return 0;
   switch (epi) {
-    case EPI_STORE_BF16: return launch_epi<EPI_STORE_BF16, false>(p, variant, st);
-    case EPI_STORE_F32: return launch_epi<EPI_STORE_F32, false>(p, variant, st);
-    case EPI_RESID: return launch_epi<EPI_RESID, false>(p, variant, st);
-    case EPI_SWIGLU: return gain ? launch_epi<EPI_SWIGLU, true>(p, variant, st) : launch_epi<EPI_SWIGLU, false>(p, variant, st);
-    case EPI_QKV: return gain ? launch_epi<EPI_QKV, true>(p, variant, st) : launch_epi<EPI_QKV, false>(p, variant, st);
-    case EPI_KV: return gain ? launch_epi<EPI_KV, true>(p, variant, st) : launch_epi<EPI_KV, false>(p, variant, st);
+    case EPI_STORE_BF16: return launch_epi<EPI_STORE_BF16>(p, variant, st);
+    case EPI_STORE_F32: return launch_epi<EPI_STORE_F32>(p, variant, st);
+    case EPI_RESID: return launch_epi<EPI_RESID>(p, variant, st);
+    case EPI_SWIGLU: return launch_epi<EPI_SWIGLU>(p, variant, st);
+    case EPI_QKV: return launch_epi<EPI_QKV>(p, variant, st);
+    case EPI_KV: return launch_epi<EPI_KV>(p, variant, st);
   }
   return -1;
 }

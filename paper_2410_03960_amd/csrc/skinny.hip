@@ -107,13 +107,13 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_kernel(SkinnyParams p) {
       } else if (m < p.M) {
         if constexpr (EPI == EPI_STORE_F32) {
           *(float4 *)((float *)p.C + (int64_t)m * p.N + n) = make_float4(x[0][0], x[0][1], x[0][2], x[0][3]);
+        } else if constexpr (EPI == EPI_RESID) {
+          float4 *dst = (float4 *)((float *)p.C + (int64_t)m * p.N + n);
+          const float4 r = *dst;
+          *dst = make_float4(r.x + x[0][0], r.y + x[0][1], r.z + x[0][2], r.w + x[0][3]);
         } else {
           bf16_t *dst = (bf16_t *)p.C + (int64_t)m * p.N + n;
           float o[4] = {x[0][0], x[0][1], x[0][2], x[0][3]};
-          if constexpr (EPI == EPI_RESID) {
-            uint2 r = *(const uint2 *)dst;
-            o[0] += bf16lo(r.x); o[1] += bf16hi(r.x); o[2] += bf16lo(r.y); o[3] += bf16hi(r.y);
-          }
           if constexpr (EPI == EPI_SWIGLU) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) o[v] = x[0][v] / (1.f + __expf(-x[0][v])) * x[NW - 1][v];
@@ -144,13 +144,13 @@ __global__ void skinny_reduce_kernel(SkinnyParams p, int ksplit) {
   }
   if constexpr (EPI == EPI_STORE_F32) {
     *(float4 *)((float *)p.C + i) = make_float4(x[0][0], x[0][1], x[0][2], x[0][3]);
+  } else if constexpr (EPI == EPI_RESID) {
+    float4 *dst = (float4 *)((float *)p.C + i);
+    const float4 r = *dst;
+    *dst = make_float4(r.x + x[0][0], r.y + x[0][1], r.z + x[0][2], r.w + x[0][3]);
   } else {
     bf16_t *dst = (bf16_t *)p.C + i;
     float o[4] = {x[0][0], x[0][1], x[0][2], x[0][3]};
-    if constexpr (EPI == EPI_RESID) {
-      const uint2 r = *(const uint2 *)dst;
-      o[0] += bf16lo(r.x); o[1] += bf16hi(r.x); o[2] += bf16lo(r.y); o[3] += bf16hi(r.y);
-    }
     if constexpr (EPI == EPI_SWIGLU) {
 #pragma unroll
       for (int v = 0; v < 4; ++v) o[v] = x[0][v] / (1.f + __expf(-x[0][v])) * x[NW - 1][v];
@@ -166,9 +166,9 @@ int launch_kernels(const SkinnyParams &p, hipStream_t st) {
   // split K while the column tiles leave CUs idle: up to 4 splits, each at least 16 k steps per wave pass
   int ksplit = 1;
   if (p.partial && MB >= 3 && tiles < 256) {
-    ksplit = std::min(4, 256 / tiles);
+    ksplit = std::min(SKINNY_MAX_SPLIT, 256 / tiles);
     ksplit = std::min(ksplit, std::max(1, p.K / (32 * SK_WAVES * 4)));
-    if ((size_t)ksplit * NW * p.M * p.N * 4 > SKINNY_PARTIAL_BYTES) ksplit = 1;
+    if ((size_t)ksplit * NW * p.M * p.N * 4 > p.partial_bytes) ksplit = 1;
   }
   dim3 grid(tiles, ksplit), block(SK_WAVES * 64);
   hipLaunchKernelGGL((skinny_kernel<MB, NB, EPI>), grid, block, 0, st, p);

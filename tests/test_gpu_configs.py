@@ -1,18 +1,30 @@
 """Parity at the full 8B / 70B shapes, in the launch configuration bench.py
-times.  The whole batch runs on the GPU; the oracle (float32) computes sampled
-outputs it can afford: a ragged prefix of one or two sequences.  By causality
-(checked on the oracle itself in test_oracle_model_pins) the K/V of the first n
-tokens of a prompt do not depend on the rest, so those cache rows of the
-full-size run are compared with an oracle prefill of the prefix alone; logits
-are compared on a second, small GPU call over the same prefix.
+times.  The whole batch runs on the GPU.  The oracle (float32) checks it three
+ways:
+
+  * end to end on what it can afford: one whole 2048-token sequence of the
+    headline batch, one whole ragged sequence of the variable-length batch, a
+    1024-token prefix at the 70B shape, a 512-token prefix of the 32K prompt
+    (by causality the K/V of the first n tokens of a prompt do not depend on
+    the rest; checked on the oracle itself in test_oracle_model_pins); logits
+    are compared on a second, small GPU call over the same tokens;
+  * on EVERY row of the batch where one step of the path can be isolated at
+    little cost: cache layer 1 (embedding -> RMSNorm -> W_K / W_V -> RoPE ->
+    paged slot) and the fused later-layer K/V projection of Eq. 2 recomputed
+    by the oracle from the GPU's own layer-l output;
+  * the prefill attention kernel alone at 8192 and 32768 keys.
 
 Tolerance.  The stated bar is max|diff|/max|ref| <= 2e-2 and cosine >= 0.999
-per tensor.  On these randomly initialised deep models bf16 storage of
-activations alone already moves deep layers further than that (the error grows
-with depth), so every tensor is also measured with the oracle itself rounding
-its activations to bf16 (`act_round`), and the bar for a tensor is the larger
-of the stated one and twice that bf16-storage error.
+per tensor (1e-1 / 0.995 with an FP8 cache).  bf16 matrix instructions force a
+rounding of every matrix-product input; on these deep random-init models that
+alone moves deep tensors further than 2e-2 (tests/test_oracle_rounding_floor.py).
+So every end-to-end tensor is also measured with the oracle rounding exactly
+those inputs ("floor"): the bar of a tensor is the stated one, or 1.25 x its floor
+where that is larger (so the stated bar is asserted wherever the floor leaves
+room for it, and the bar is continuous in the floor).  GPU error / floor is printed per
+tensor class.  Single-step checks keep tight bars (same inputs on both sides).
 """
+import os
 import sys
 import time
 
@@ -26,65 +38,115 @@ from tests.helpers import cosine, oracle_shape, rel_err
 
 pytestmark = pytest.mark.gpu
 
+_PROGRESS = os.path.join(os.environ.get("GRAFT_REPO_ROOT", os.path.dirname(os.path.dirname(os.path.abspath(__file__)))),
+                         "gpurun_out", "test_progress.log")
+
 
 def _say(msg):
+    """Progress line: stdout (shown with -s) and a file a watchdog can see while pytest captures output."""
     print(msg, flush=True)
-    sys.stdout.flush()
+    try:
+        os.makedirs(os.path.dirname(_PROGRESS), exist_ok=True)
+        with open(_PROGRESS, "a") as f:
+            f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
+    except OSError:
+        pass
 
 
 def _bf16_round(x):
     return x.to(torch.bfloat16).to(x.dtype)
 
 
+MFMA_INPUTS = {p: _bf16_round for p in ("a", "qkv", "p", "o", "z")}      # every rounding point but the residual stream
+SLACK = 1.25
+
+
 def _host_weight_fn(store):
+    """Oracle weight function over the device-resident store, host copies kept for the second run."""
+    host = {}
+
     def f(name, j0=None):
-        return store.get(name, j0).cpu()
+        key = (name, j0)
+        if key not in host:
+            host[key] = store.get(name, j0).cpu()
+        return host[key]
     return f
 
 
-def _oracle_prefix(wl, store, ids, n, fp8=False, scales=None, act_round=None):
+def _bars(stated, floor):
+    """(rel bar, cos bar) for one tensor from the stated bar and the measured floor."""
+    rel_bar = max(stated[0], SLACK * floor[0])
+    cos_bar = min(stated[1], 1.0 - SLACK * (1.0 - floor[1]))
+    return rel_bar, cos_bar
+
+
+class _Report:
+    """Collects (tensor, GPU error, floor, bar) and asserts at the end, so one line shows every tensor."""
+
+    def __init__(self, label):
+        self.label, self.rows = label, []
+
+    def add(self, name, got, want, floor_t, stated):
+        err = (rel_err(got, want), cosine(got, want))
+        floor = (rel_err(floor_t, want), cosine(floor_t, want))
+        self.rows.append((name, err, floor, _bars(stated, floor), stated))
+
+    def finish(self):
+        bad = [r for r in self.rows if r[1][0] > r[3][0] or r[1][1] < r[3][1]]
+        worst = max(self.rows, key=lambda r: r[1][0] / r[3][0])
+        ratio_rel = max(r[1][0] / max(r[2][0], 1e-30) for r in self.rows)
+        ratio_cos = max((1 - r[1][1]) / max(1 - r[2][1], 1e-30) for r in self.rows)
+        n_stated = sum(1 for r in self.rows if r[3][0] == r[4][0] and r[3][1] == r[4][1])
+        self.min_cos = min(r[1][1] for r in self.rows)
+        _say(f"  {self.label}: {len(self.rows)} tensors, {n_stated} under the stated bar, lowest cosine {self.min_cos:.6f}; worst {worst[0]}: rel {worst[1][0]:.3e} "
+             f"(floor {worst[2][0]:.3e}, bar {worst[3][0]:.3e}) cos {worst[1][1]:.6f} (floor {worst[2][1]:.6f}, bar {worst[3][1]:.6f}); "
+             f"max GPU/floor: rel {ratio_rel:.2f}, 1-cos {ratio_cos:.2f}")
+        for name, err, floor, bar, _ in self.rows:
+            if name.startswith("logits"):
+                _say(f"  {self.label}: {name}: rel {err[0]:.3e} (floor {floor[0]:.3e}, bar {bar[0]:.3e}) "
+                     f"cos {err[1]:.6f} (floor {floor[1]:.6f}, bar {bar[1]:.6f})")
+        assert not bad, f"{self.label}: " + "; ".join(
+            f"{n}: rel {e[0]:.3e} (bar {b[0]:.3e}) cos {e[1]:.6f} (bar {b[1]:.6f})" for n, e, _, b, _ in bad[:6])
+
+
+def _oracle_pair(wl, wfn, ids, n, n_ctx=0, prefix=None, fp8=False, scales=None):
+    """Plain oracle and the oracle with rounded matrix-product inputs on one sequence of n new
+    tokens over n_ctx cached rows (`prefix`: [C, 2, n_ctx, Hkv, hd] cache rows).  Returns per run
+    (logits, cache)."""
     sh = wl.shape
-    bt, nb = torch.arange((n + 15) // 16, dtype=torch.int32)[None], (n + 15) // 16
-    cache = O.PagedKVCache(wl.n_cache_layers, nb, sh.n_kv_heads, sh.head_dim, bt, dtype=torch.float32, fp8=fp8)
-    if scales is not None:
-        cache.scales.copy_(scales)
-    logits, _ = O.swiftkv_prefill(oracle_shape(sh), _host_weight_fn(store), ids, [n], [0], wl.l, wl.g, cache,
-                                  dtype=torch.float32, fp8_compute_scales=scales is None, act_round=act_round)
-    return logits[0], cache
+    nb = (n_ctx + n + 15) // 16
+    bt = torch.arange(nb, dtype=torch.int32)[None]
+    outs = []
+    for hook in (None, MFMA_INPUTS):
+        t0 = time.time()
+        cache = O.PagedKVCache(wl.n_cache_layers, nb, sh.n_kv_heads, sh.head_dim, bt, dtype=torch.float32, fp8=fp8)
+        if scales is not None:
+            cache.scales.copy_(scales)
+        if prefix is not None:
+            cache.data[:, :, :n_ctx] = prefix
+        logits, _ = O.swiftkv_prefill(oracle_shape(sh), wfn, ids, [n], [n_ctx], wl.l, wl.g, cache, dtype=torch.float32,
+                                      fp8_compute_scales=fp8 and scales is None, act_round=hook)
+        outs.append((logits[0], cache))
+        _say(f"    oracle ({'rounded matrix inputs' if hook else 'plain'}) on {n} tokens: {time.time() - t0:.1f}s")
+    return outs
 
 
-def _bar(stated_rel, stated_cos, emu_rel, emu_cos):
-    return max(stated_rel, 2 * emu_rel), min(stated_cos, 1 - 2 * (1 - emu_cos))
-
-
-def _check_prefix(wl, store, ctx, batch, gpu_cache, b, n, label, fp8=False, scales=None,
-                  stated=(G.BF16_REL, G.BF16_COS)):
-    """Compare rows [0, n) of sequence b in the full-size GPU cache, and the
-    logits of a small GPU call on that prefix, with the oracle."""
+def _check_sequence(wl, wfn, ctx, batch, gpu_cache, b, n, label, fp8=False, scales=None,
+                    stated=(G.BF16_REL, G.BF16_COS)):
+    """Rows [0, n) of sequence b of the full-size GPU cache, and the logits of a small GPU call on those
+    n tokens, against the oracle; bars from the stated tolerance and the matrix-input floor."""
     from paper_2410_03960_amd import binding as B
     sh = wl.shape
     cu = torch.cumsum(torch.cat([torch.zeros(1, dtype=torch.int64), batch.seq_lens.long()]), 0)
     ids = batch.token_ids[cu[b]:cu[b] + n].clone()
-    t0 = time.time()
-    ref_logits, ref = _oracle_prefix(wl, store, ids, n, fp8, scales)
-    _say(f"  {label}: oracle on {n}-token prefix of sequence {b}: {time.time() - t0:.1f}s")
-    emu_logits, emu = _oracle_prefix(wl, store, ids, n, fp8, scales, act_round=_bf16_round)
-    _say(f"  {label}: oracle with bf16-stored activations: {time.time() - t0:.1f}s total")
+    (ref_logits, ref), (flo_logits, flo) = _oracle_pair(wl, wfn, ids, n, fp8=fp8, scales=scales)
     slots = (batch.block_tables[b].long()[torch.arange(n) // 16] * 16 + torch.arange(n) % 16)
-    worst = []
+    rep = _Report(label)
     for c in range(ref.C):
         for kvsel in (0, 1):
-            want = ref.read(c, 0, n)[kvsel]
-            em = emu.read(c, 0, n)[kvsel]
-            got = G.gpu_cache_logical(gpu_cache, c, kvsel, slots).cpu()
-            r, cs = rel_err(got, want), cosine(got, want)
-            rel_bar, cos_bar = _bar(stated[0], stated[1], rel_err(em, want), cosine(em, want))
-            worst.append((r / rel_bar, c, kvsel, r, cs, rel_bar, cos_bar))
-            assert r <= rel_bar and cs >= cos_bar, \
-                f"{label} cache layer {c} {'KV'[kvsel]}: rel {r:.3e} (bar {rel_bar:.3e}) cos {cs:.6f} (bar {cos_bar:.6f})"
-    w = max(worst)
-    _say(f"  {label}: worst cache tensor layer {w[1]} {'KV'[w[2]]}: rel {w[3]:.3e} (bar {w[5]:.3e}) cos {w[4]:.6f}")
-    # logits: small GPU call on the same prefix
+            rep.add(f"cache layer {c} {'KV'[kvsel]}", G.gpu_cache_logical(gpu_cache, c, kvsel, slots).cpu(),
+                    ref.read(c, 0, n)[kvsel], flo.read(c, 0, n)[kvsel], stated)
+    # logits: small GPU call on the same tokens
     sub = WL.build_batch(wl, lens=[n], ctx=[0], shuffled=False)
     sub.token_ids = ids
     small = B.KVCache(ctx.n_cache_layers, sub.n_blocks, sh.n_kv_heads, sh.head_dim, sub.block_tables, [0], fp8=fp8,
@@ -93,13 +155,77 @@ def _check_prefix(wl, store, ctx, batch, gpu_cache, b, n, label, fp8=False, scal
         small.scales.copy_(scales)
     logits, small, ws = G.run_gpu(ctx, sub, fp8=fp8, cache=small)
     G.check_plan(ctx, ws, sub)
-    r, cs = rel_err(logits[0].cpu(), ref_logits), cosine(logits[0].cpu(), ref_logits)
-    rel_bar, cos_bar = _bar(stated[0], stated[1], rel_err(emu_logits, ref_logits), cosine(emu_logits, ref_logits))
-    _say(f"  {label}: logits rel {r:.3e} (bar {rel_bar:.3e}) cos {cs:.6f} (bar {cos_bar:.6f})")
-    assert r <= rel_bar and cs >= cos_bar, f"{label} logits rel {r:.3e} cos {cs:.6f}"
-    # the small call's cache must agree with the same rows of the full-size call (bit for bit in bf16:
-    # same kernels, same tile shapes only when M-tiling coincides, so compare with the bf16 bar)
-    return ref
+    rep.add("logits", logits[0].cpu(), ref_logits, flo_logits, stated)
+    rep.finish()
+    return rep
+
+
+def _all_slots(batch):
+    return torch.cat([batch.block_tables[b].long()[torch.arange(c, c + n) // 16] * 16 + torch.arange(c, c + n) % 16
+                      for b, (c, n) in enumerate(zip(batch.context_lens.tolist(), batch.seq_lens.tolist()))])
+
+
+def _all_positions(batch):
+    return torch.cat([torch.arange(c, c + n) for c, n in zip(batch.context_lens.tolist(), batch.seq_lens.tolist())])
+
+
+def _check_first_layer_all_rows(wl, wfn, batch, gpu_cache, label, rel=G.BF16_REL, cos=G.BF16_COS):
+    """Cache layer 1 of EVERY new row of the batch: embedding -> RMSNorm -> W_K, W_V -> RoPE at the row's
+    position -> the row's paged slot, at the stated bar (covers RoPE at every position of the batch, the
+    packing of the variable-length batch and the scatter through the block tables)."""
+    sh = wl.shape
+    t0 = time.time()
+    x = wfn("embed").float()[batch.token_ids.long()]
+    a = O.rmsnorm(x, wfn("norm1", 0).float(), sh.rms_eps)
+    pos, slots = _all_positions(batch), _all_slots(batch)
+    k = O.rope((a @ wfn("wk", 0).float().T).view(-1, sh.n_kv_heads, sh.head_dim), pos, sh.rope_theta)
+    v = (a @ wfn("wv", 0).float().T).view(-1, sh.n_kv_heads, sh.head_dim)
+    if gpu_cache.fp8:     # per-(K|V, head) absmax over all rows of the call, then what the codes decode to
+        out = []
+        for t, x_ in ((0, k), (1, v)):
+            sc = O.fp8_scale(x_.abs().amax(dim=(0, 2)))
+            assert rel_err(gpu_cache.scales[0, t].cpu(), sc) <= 1e-2, f"{label}: layer-1 {'KV'[t]} scales"
+            out.append(O.fp8_dequantize(O.fp8_quantize(x_, sc[None, :, None]), sc[None, :, None]))
+        k, v = out
+    for kvsel, want in ((0, k), (1, v)):
+        got = G.gpu_cache_logical(gpu_cache, 0, kvsel, slots).cpu()
+        r, cs = rel_err(got, want), cosine(got, want)
+        assert r <= rel and cs >= cos, f"{label}: layer-1 {'KV'[kvsel]} over all {len(slots)} rows: rel {r:.3e} cos {cs:.6f}"
+        # row by row, so that a single misplaced row cannot hide in the batch-wide figures
+        row_err = (got.double() - want.double()).abs().amax(dim=(1, 2)) / want.double().abs().amax()
+        assert float(row_err.max()) <= rel, f"{label}: row {int(row_err.argmax())} of layer-1 {'KV'[kvsel]}"
+    _say(f"  {label}: cache layer 1 of all {len(slots)} rows (positions up to {int(pos.max())}) within {rel:g} / {cos}: {time.time() - t0:.1f}s")
+
+
+def _check_fused_kv_all_rows(wl, wfn, ctx, ws, batch, gpu_cache, label, rows=None, rel=6e-3, given_scales=None):
+    """Eq. 2 at full size: the oracle's RMSNorm_j, W_K^j / W_V^j and RoPE applied to the GPU's own layer-l
+    output (exported, bf16), for every group leader j and every row (or the sampled `rows`), against the
+    rows the fused K/V GEMM scattered into cache layers l .. l+P-1."""
+    sh = wl.shape
+    t0 = time.time()
+    hid = ctx.export_hidden(ws, batch.n_tokens).float().cpu()
+    pos, slots = _all_positions(batch), _all_slots(batch)
+    if rows is not None:
+        hid, pos, slots = hid[rows], pos[rows], slots[rows]
+    worst = 0.0
+    for p, j in enumerate(O.leader_layers(sh.n_layers, wl.l, wl.g)):
+        a = O.rmsnorm(hid, wfn("norm1", j - 1).float(), sh.rms_eps)
+        k = O.rope((a @ wfn("wk", j - 1).float().T).view(-1, sh.n_kv_heads, sh.head_dim), pos, sh.rope_theta)
+        v = (a @ wfn("wv", j - 1).float().T).view(-1, sh.n_kv_heads, sh.head_dim)
+        for kvsel, want in ((0, k), (1, v)):
+            if gpu_cache.fp8:
+                if given_scales is None:      # computed scales: per-head absmax over all rows of the call
+                    assert rows is None
+                    sc = O.fp8_scale(want.abs().amax(dim=(0, 2)))
+                    assert rel_err(gpu_cache.scales[wl.l + p, kvsel].cpu(), sc) <= 1e-2, f"{label}: scales of projection {p}"
+                else:
+                    sc = given_scales[wl.l + p, kvsel]
+                want = O.fp8_dequantize(O.fp8_quantize(want, sc[None, :, None]), sc[None, :, None])
+            got = G.gpu_cache_logical(gpu_cache, wl.l + p, kvsel, slots).cpu()
+            r = rel_err(got, want)
+            worst = max(worst, r)
+            assert r <= rel, f"{label}: fused K/V projection {p} (layer {j}) {'KV'[kvsel]}: rel {r:.3e}"
+    _say(f"  {label}: Eq. 2 on {hid.shape[0]} rows x {wl.n_cache_layers - wl.l} projections: worst rel {worst:.3e} (bar {rel:g}): {time.time() - t0:.1f}s")
 
 
 def _gpu_setup(name):
@@ -115,36 +241,78 @@ def _gpu_setup(name):
 
 def test_config2_8b_l16_batch8x2048():
     wl, store, ctx = _gpu_setup("8b_l16_b8x2048")
+    wfn = _host_weight_fn(store)
     batch = WL.build_batch(wl)
     logits, cache, ws = G.run_gpu(ctx, batch)
     G.check_plan(ctx, ws, batch)
     assert torch.isfinite(logits).all()
-    _check_prefix(wl, store, ctx, batch, cache, b=3, n=300, label="cfg2")
+    # the accounting every TFLOP/s figure rests on
+    gemm_fl, attn_fl = ctx.flops(batch.seq_lens.tolist(), batch.context_lens.tolist())
+    want = O.executed_flops(oracle_shape(wl.shape), wl.l, wl.g, batch.seq_lens.tolist(), batch.context_lens.tolist())
+    assert gemm_fl == want["gemm"] and attn_fl == want["attn"]
+    _check_first_layer_all_rows(wl, wfn, batch, cache, "cfg2")
+    _check_fused_kv_all_rows(wl, wfn, ctx, ws, batch, cache, "cfg2")
+    rep = _check_sequence(wl, wfn, ctx, batch, cache, b=3, n=2048, label="cfg2/seq3")
+    assert rep.min_cos >= G.BF16_COS          # the stated cosine holds on every tensor of the 32-layer 8B shape
     # determinism: a second run gives the same bytes (no races between workgroups)
     logits2, cache2, _ = G.run_gpu(ctx, batch)
     assert torch.equal(cache.data, cache2.data) and torch.equal(logits, logits2)
 
 
+def test_prefill_returns_before_the_gpu_finishes():
+    """swiftkv_prefill only enqueues: with the stream kept busy, the host time of a call is a small
+    fraction of the call's GPU time, and calls issued back to back overlap launch with execution."""
+    wl, store, ctx = _gpu_setup("8b_l16_b8x2048")
+    batch = WL.build_batch(wl)
+    logits, cache, ws = G.run_gpu(ctx, batch)            # warm-up: first launches, attribute setting
+    ids, lens = batch.token_ids.cuda(), batch.seq_lens.tolist()
+    stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    host = []
+    e0.record(stream)
+    for _ in range(4):
+        t0 = time.perf_counter()
+        ctx.prefill(ids, lens, cache, logits, ws, stream)
+        host.append(time.perf_counter() - t0)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    gpu_ms = e0.elapsed_time(e1) / 4
+    _say(f"  async: host time per call {[f'{h * 1e3:.2f}' for h in host]} ms, GPU time per call {gpu_ms:.1f} ms")
+    assert max(host) * 1e3 < 0.25 * gpu_ms
+    assert sum(host) * 1e3 < gpu_ms                       # all four calls were enqueued while the first still ran
+
+
 def test_config3_8b_l24_acrosskv2_varlen_shuffled():
     wl, store, ctx = _gpu_setup("8b_l24_g2_varlen16")
+    wfn = _host_weight_fn(store)
     batch = WL.build_batch(wl)
     assert batch.n_seqs == 16 and ctx.n_cache_layers == 28
     logits, cache, ws = G.run_gpu(ctx, batch)
     G.check_plan(ctx, ws, batch)
     assert torch.isfinite(logits).all()
-    _check_prefix(wl, store, ctx, batch, cache, b=6, n=200, label="cfg3/seq6")
-    _check_prefix(wl, store, ctx, batch, cache, b=2, n=77, label="cfg3/seq2")
+    _check_first_layer_all_rows(wl, wfn, batch, cache, "cfg3")
+    _check_fused_kv_all_rows(wl, wfn, ctx, ws, batch, cache, "cfg3")
+    b = int(batch.seq_lens.argmin())                       # a whole sequence with a ragged last block
+    n = int(batch.seq_lens[b])
+    assert n % 16 != 0 and n % 128 != 0
+    rep = _check_sequence(wl, wfn, ctx, batch, cache, b=b, n=n, label=f"cfg3/seq{b}")
+    assert rep.min_cos >= G.BF16_COS
 
 
 def test_config4_70b_l40_batch4x8192():
     wl, store, ctx = _gpu_setup("70b_l40_b4x8192")
+    wfn = _host_weight_fn(store)
     batch = WL.build_batch(wl)
     t0 = time.time()
     logits, cache, ws = G.run_gpu(ctx, batch)
     _say(f"  cfg4: GPU prefill of {batch.n_tokens} tokens: {time.time() - t0:.1f}s (incl. first-launch setup)")
     G.check_plan(ctx, ws, batch)
     assert torch.isfinite(logits).all()
-    _check_prefix(wl, store, ctx, batch, cache, b=1, n=100, label="cfg4")
+    _check_first_layer_all_rows(wl, wfn, batch, cache, "cfg4")
+    rows = torch.cat([torch.arange(8192 * s + o, 8192 * s + o + 128) for s, o in ((0, 0), (1, 4000), (2, 8064), (3, 6543))])
+    _check_fused_kv_all_rows(wl, wfn, ctx, ws, batch, cache, "cfg4", rows=rows)
+    _check_sequence(wl, wfn, ctx, batch, cache, b=1, n=1024, label="cfg4/seq1")
 
 
 def test_config5_8b_fp8_32k_prompt_with_64_decode_tokens():
@@ -153,22 +321,31 @@ def test_config5_8b_fp8_32k_prompt_with_64_decode_tokens():
     scales (taken, with headroom, from an oracle prefill of a prompt prefix)."""
     from paper_2410_03960_amd import binding as B
     wl, store, ctx = _gpu_setup("8b_l16_g4_fp8_32k_dec64")
+    wfn = _host_weight_fn(store)
     sh = wl.shape
     batch = WL.build_batch(wl)
     assert batch.n_seqs == 65 and batch.n_tokens == 32768 + 64 and ctx.n_cache_layers == 20
-    n_pref = 200
-    _, probe = _oracle_prefix(wl, store, batch.token_ids[:n_pref].clone(), n_pref, fp8=True)
-    scales = probe.scales * 1.5
-    # (i) absmax mode on the prompt alone: every (layer, K|V, head) must use the top code, none saturate beyond it
+    n_pref = 512
+    # (i) absmax mode on the prompt alone: every (layer, K|V, head) must use the top code, none saturate beyond it;
+    #     cache layer 1 of all 32768 rows and Eq. 2 on all rows against the oracle
     solo = WL.build_batch(wl, lens=[32768], ctx=[0], shuffled=False)
     solo.token_ids = batch.token_ids[:32768].clone()
-    lg, c1, ws = G.run_gpu(ctx, solo, fp8=True, scale_mode=B.SWIFTKV_SCALE_COMPUTE_ABSMAX)
+    lg, c1, ws1 = G.run_gpu(ctx, solo, fp8=True, scale_mode=B.SWIFTKV_SCALE_COMPUTE_ABSMAX)
     assert torch.isfinite(lg).all() and (c1.scales > 0).all()
     mags = (c1.data.view(20, 2, -1, sh.n_kv_heads, sh.head_dim)[:, :, :32768] & 0x7F)
     top = mags.amax(dim=(2, 4))
     assert (top == 0x7E).all(), "absmax scaling must map each head's largest value to +-448"
-    del c1, mags
-    # (ii) contexts: seeded codes for every decode sequence, all cache layers
+    del mags
+    _check_first_layer_all_rows(wl, wfn, solo, c1, "cfg5/solo", rel=G.FP8_REL, cos=G.FP8_COS)
+    _check_fused_kv_all_rows(wl, wfn, ctx, ws1, solo, c1, "cfg5/solo", rel=G.FP8_REL)
+    del c1, ws1
+    # (ii) contexts: seeded codes for every decode sequence, all cache layers, under scales = 1.5 x those of an
+    #      oracle prefill of the prompt's first tokens
+    ids_pref = batch.token_ids[:n_pref].clone()
+    probe = O.PagedKVCache(20, n_pref // 16, sh.n_kv_heads, sh.head_dim, torch.arange(n_pref // 16, dtype=torch.int32)[None],
+                           dtype=torch.float32, fp8=True)
+    O.swiftkv_prefill(oracle_shape(sh), wfn, ids_pref, [n_pref], [0], wl.l, wl.g, probe, dtype=torch.float32)
+    scales = probe.scales * 1.5
     cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, sh.n_kv_heads, sh.head_dim, batch.block_tables,
                       batch.context_lens.tolist(), fp8=True, scale_mode=B.SWIFTKV_SCALE_USE_GIVEN)
     cache.scales.copy_(scales)
@@ -183,34 +360,48 @@ def test_config5_8b_fp8_32k_prompt_with_64_decode_tokens():
     logits, cache, ws = G.run_gpu(ctx, batch, fp8=True, cache=cache)
     G.check_plan(ctx, ws, batch)
     assert torch.isfinite(logits).all()
-    _check_prefix(wl, store, ctx, batch, cache, b=0, n=n_pref, label="cfg5/prompt", fp8=True, scales=scales,
-                  stated=(G.FP8_REL, G.FP8_COS))
+    # rows beyond the probed prefix must not pile up at the largest code (scales from a prefix could be too small)
+    p_slots = _all_slots(solo).cuda()
+    sat = ((cache.data[:, :, p_slots] & 0x7F) == 0x7E).float().mean().item()
+    _say(f"  cfg5: fraction of prompt codes at the largest magnitude under the given scales: {sat:.2e}")
+    assert sat < 1e-3
+    _check_fused_kv_all_rows(wl, wfn, ctx, ws, batch, cache, "cfg5/co-scheduled", rel=G.FP8_REL, given_scales=scales)
+    _check_sequence(wl, wfn, ctx, batch, cache, b=0, n=n_pref, label="cfg5/prompt", fp8=True, scales=scales,
+                    stated=(G.FP8_REL, G.FP8_COS))
     # decode tokens: oracle on the picked sequences (own small block pool)
+    rep = _Report("cfg5/decode")
     for b in picked:
-        nb = (wl.decode_ctx + 1 + 15) // 16
-        bt = torch.arange(nb, dtype=torch.int32)[None]
         tok = batch.token_ids[32768 + b - 1: 32768 + b]
-        outs = []
-        for rnd in (None, _bf16_round):
-            oc = O.PagedKVCache(20, nb, sh.n_kv_heads, sh.head_dim, bt, dtype=torch.float32, fp8=True)
-            oc.scales.copy_(scales)
-            oc.data[:, :, :wl.decode_ctx] = WL.seeded_fp8_codes(wl.seed, f"ctx.{b}", (20, 2, wl.decode_ctx, sh.n_kv_heads, sh.head_dim))
-            lg_o, _ = O.swiftkv_prefill(oracle_shape(sh), _host_weight_fn(store), tok, [1], [wl.decode_ctx], wl.l, wl.g,
-                                        oc, dtype=torch.float32, fp8_compute_scales=False, act_round=rnd)
-            outs.append((lg_o[0], oc))
-        (ref_l, ref_c), (emu_l, emu_c) = outs
-        r, cs = rel_err(logits[b].cpu(), ref_l), cosine(logits[b].cpu(), ref_l)
-        rel_bar, cos_bar = _bar(G.FP8_REL, G.FP8_COS, rel_err(emu_l, ref_l), cosine(emu_l, ref_l))
-        _say(f"  cfg5/decode seq {b}: logits rel {r:.3e} (bar {rel_bar:.3e}) cos {cs:.6f} (bar {cos_bar:.6f})")
-        assert r <= rel_bar and cs >= cos_bar
+        prefix = WL.seeded_fp8_codes(wl.seed, f"ctx.{b}", (20, 2, wl.decode_ctx, sh.n_kv_heads, sh.head_dim))
+        (ref_l, ref_c), (flo_l, flo_c) = _oracle_pair(wl, wfn, tok, 1, n_ctx=wl.decode_ctx, prefix=prefix, fp8=True, scales=scales)
+        rep.add(f"logits seq {b}", logits[b].cpu(), ref_l, flo_l, (G.FP8_REL, G.FP8_COS))
         slot = int(batch.block_tables[b, wl.decode_ctx // 16]) * 16 + wl.decode_ctx % 16
         for c in range(20):
             for kvsel in (0, 1):
                 got = G.gpu_cache_logical(cache, c, kvsel, torch.tensor([slot])).cpu()[0]
-                want = ref_c.read(c, 0, wl.decode_ctx + 1)[kvsel][-1]
-                em = emu_c.read(c, 0, wl.decode_ctx + 1)[kvsel][-1]
-                rel_bar, cos_bar = _bar(G.FP8_REL, G.FP8_COS, rel_err(em, want), cosine(em, want))
-                assert rel_err(got, want) <= rel_bar and cosine(got, want) >= cos_bar, (b, c, kvsel, rel_err(got, want))
+                rep.add(f"seq {b} new row cache layer {c} {'KV'[kvsel]}", got, ref_c.read(c, 0, wl.decode_ctx + 1)[kvsel][-1],
+                        flo_c.read(c, 0, wl.decode_ctx + 1)[kvsel][-1], (G.FP8_REL, G.FP8_COS))
+    rep.finish()
+
+
+@pytest.mark.parametrize("n", [8192, 32768])
+def test_prefill_attention_at_long_sequences(n):
+    """The prefill attention kernel alone on one long sequence at the 8B head shape: the last 128-query
+    block (which walks every key tile) and three sampled blocks against the brute-force softmax."""
+    from paper_2410_03960_amd import binding as B
+    Hq, Hkv, hd = 32, 8, 128
+    _say(f"attention at {n} keys")
+    q = WL.seeded_normal_bf16(11, f"q{n}", (n, Hq * hd), 0.0, 1.0)
+    k = WL.seeded_normal_bf16(12, f"k{n}", (n, Hkv * hd), 0.0, 1.0)
+    v = WL.seeded_normal_bf16(13, f"v{n}", (n, Hkv * hd), 0.0, 1.0)
+    got = B.op_attention_prefill(q.cuda(), k.cuda(), v.cuda(), [n], Hq, Hkv, hd).cpu()
+    kf, vf = k.float().view(n, Hkv, hd), v.float().view(n, Hkv, hd)
+    for q0 in (n - 128, n // 2 + 64, 3 * 128 + 1, 0):
+        rows = torch.arange(q0, min(q0 + 128, n))
+        ref = O.gqa_attention(q[rows].float().view(-1, Hq, hd), rows, kf[: int(rows[-1]) + 1], vf[: int(rows[-1]) + 1])
+        g = got[rows].view(-1, Hq, hd)
+        r, cs = rel_err(g, ref), cosine(g, ref)
+        assert r <= 1e-2 and cs >= 0.9995, (n, q0, r, cs)
 
 
 def test_chunk_workload_8b_2048_new_over_6144_cached():
@@ -222,6 +413,7 @@ def test_chunk_workload_8b_2048_new_over_6144_cached():
     with the same context and those 300 tokens, against the oracle's."""
     from paper_2410_03960_amd import binding as B
     wl, store, ctx = _gpu_setup("8b_l16_b8x2048_ctx6144")
+    wfn = _host_weight_fn(store)
     sh = wl.shape
     batch = WL.build_batch(wl)
     nctx, b, n = wl.prefix_ctx, 5, 300
@@ -238,32 +430,14 @@ def test_chunk_workload_8b_2048_new_over_6144_cached():
     assert torch.equal(cache.data[:, :, ctx_slots.cuda()].float().cpu(), prefix), "cached rows must stay untouched"
     cu = torch.cumsum(torch.cat([torch.zeros(1, dtype=torch.int64), batch.seq_lens.long()]), 0)
     ids = batch.token_ids[cu[b]:cu[b] + n].clone()
-    nb = (nctx + n + 15) // 16
-    bt = torch.arange(nb, dtype=torch.int32)[None]
-    outs = []
-    t0 = time.time()
-    for rnd in (None, _bf16_round):
-        oc = O.PagedKVCache(ctx.n_cache_layers, nb, sh.n_kv_heads, sh.head_dim, bt, dtype=torch.float32)
-        oc.data[:, :, :nctx] = prefix
-        lg_o, _ = O.swiftkv_prefill(oracle_shape(sh), _host_weight_fn(store), ids, [n], [nctx], wl.l, wl.g, oc,
-                                    dtype=torch.float32, act_round=rnd)
-        outs.append((lg_o[0], oc))
-        _say(f"  chunk: oracle ({'bf16-stored activations' if rnd else 'plain'}) done at {time.time() - t0:.1f}s")
-    (ref_l, ref), (emu_l, emu) = outs
+    (ref_l, ref), (flo_l, flo) = _oracle_pair(wl, wfn, ids, n, n_ctx=nctx, prefix=prefix)
     pos = nctx + torch.arange(n)
     new_slots = batch.block_tables[b].long()[pos // 16] * 16 + pos % 16
-    worst = (0.0,)
+    rep = _Report("chunk")
     for c in range(ref.C):
         for kvsel in (0, 1):
-            want = ref.read(c, 0, nctx + n)[kvsel][nctx:]
-            em = emu.read(c, 0, nctx + n)[kvsel][nctx:]
-            got = G.gpu_cache_logical(cache, c, kvsel, new_slots).cpu()
-            r, cs = rel_err(got, want), cosine(got, want)
-            rel_bar, cos_bar = _bar(G.BF16_REL, G.BF16_COS, rel_err(em, want), cosine(em, want))
-            worst = max(worst, (r / rel_bar, c, kvsel, r, cs, rel_bar))
-            assert r <= rel_bar and cs >= cos_bar, \
-                f"chunk cache layer {c} {'KV'[kvsel]}: rel {r:.3e} (bar {rel_bar:.3e}) cos {cs:.6f} (bar {cos_bar:.6f})"
-    _say(f"  chunk: worst cache tensor layer {worst[1]} {'KV'[worst[2]]}: rel {worst[3]:.3e} (bar {worst[5]:.3e}) cos {worst[4]:.6f}")
+            rep.add(f"cache layer {c} {'KV'[kvsel]}", G.gpu_cache_logical(cache, c, kvsel, new_slots).cpu(),
+                    ref.read(c, 0, nctx + n)[kvsel][nctx:], flo.read(c, 0, nctx + n)[kvsel][nctx:], (G.BF16_REL, G.BF16_COS))
     # logits of token n-1: a small GPU call, same context rows, the same 300 tokens
     sub = WL.build_batch(wl, lens=[n], ctx=[nctx], shuffled=False)
     sub.token_ids = ids
@@ -271,7 +445,6 @@ def test_chunk_workload_8b_2048_new_over_6144_cached():
     small.data[:, :, :nctx] = prefix.to(torch.bfloat16).cuda()
     lg, small, ws = G.run_gpu(ctx, sub, cache=small)
     G.check_plan(ctx, ws, sub)
-    r, cs = rel_err(lg[0].cpu(), ref_l), cosine(lg[0].cpu(), ref_l)
-    rel_bar, cos_bar = _bar(G.BF16_REL, G.BF16_COS, rel_err(emu_l, ref_l), cosine(emu_l, ref_l))
-    _say(f"  chunk: logits rel {r:.3e} (bar {rel_bar:.3e}) cos {cs:.6f} (bar {cos_bar:.6f})")
-    assert r <= rel_bar and cs >= cos_bar
+    rep.add("logits", lg[0].cpu(), ref_l, flo_l, (G.BF16_REL, G.BF16_COS))
+    rep.finish()
+    assert rep.min_cos >= G.BF16_COS

@@ -2,8 +2,7 @@
 multiples of 256 and whose batches have more than 1024 tokens: the smallest
 cases that take the large-GEMM paths (fragment-order weights, 64-column wave
 tiles with RoPE inside a wave tile for head_dim 128 and 64, fused KV scatter,
-FP8 staging + absmax) and, with SWIFTKV_PACKED_W=0, the LDS-staged loop."""
-import os
+FP8 staging + absmax) and, with the minimal pack buffer, the LDS-staged loop."""
 import sys
 
 import pytest
@@ -40,15 +39,9 @@ def test_mid_shapes_match_oracle(mid, packed, fp8):
     from paper_2410_03960_amd import binding as B
     wl, store, dev_w = mid
     _say(f"{wl.name} packed={packed} fp8={fp8}")
-    old = os.environ.get("SWIFTKV_PACKED_W")
-    os.environ["SWIFTKV_PACKED_W"] = "1" if packed else "0"
-    try:
-        ctx = B.Context(wl.shape, dev_w, wl.l, wl.g)
-    finally:
-        if old is None:
-            os.environ.pop("SWIFTKV_PACKED_W", None)
-        else:
-            os.environ["SWIFTKV_PACKED_W"] = old
+    ctx = B.Context(wl.shape, dev_w, wl.l, wl.g, packed_weights=packed)
+    assert (B.pack_bytes(wl.shape, wl.l, wl.g) > B.pack_bytes(wl.shape, wl.l, wl.g, minimum=True)) and \
+        ctx.pack_buf.numel() == B.pack_bytes(wl.shape, wl.l, wl.g, minimum=not packed)
     batch = WL.build_batch(wl, lens=LENS, shuffled=True)
     if fp8:
         logits, cache, ws = G.run_gpu(ctx, batch, fp8=True, scale_mode=B.SWIFTKV_SCALE_COMPUTE_ABSMAX)

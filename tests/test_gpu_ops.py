@@ -25,15 +25,11 @@ def _rand_bf16(seed, name, shape, std=1.0):
     (1, 256, 256, 64), (1, 700, 528, 456), (1, 2304, 768, 1024),
     (3, 1, 16, 8), (3, 8, 1024, 256), (3, 16, 272, 688), (3, 17, 64, 96), (3, 65, 160, 1000),
     (3, 32, 96, 264), (3, 33, 192, 520), (3, 48, 80, 1000), (3, 49, 1056, 4096), (3, 64, 4096, 688), (3, 80, 144, 72),
-    (29, 33, 192, 520), (29, 49, 1056, 4096), (29, 64, 4096, 1376), (29, 80, 1024, 4096), (29, 16, 1024, 4096),
+    ("rows", 33, 192, 520), ("rows", 49, 1056, 4096), ("rows", 64, 4096, 1376), ("rows", 80, 1024, 4096), ("rows", 16, 1024, 4096),
     (0, 2500, 512, 256),
-    (4, 256, 256, 64), (4, 700, 528, 448), (4, 2304, 768, 1024), (4, 1, 16, 128),
-    (5, 256, 256, 64), (5, 700, 528, 448), (5, 2304, 768, 1024), (5, 300, 272, 200),
     (14, 256, 256, 64), (14, 700, 528, 448), (14, 2304, 768, 1024), (14, 1, 16, 128), (14, 1031, 1040, 320),
     (15, 256, 256, 64), (15, 700, 528, 448), (15, 2304, 768, 1024), (15, 517, 272, 192),
-    (20, 700, 528, 448), (21, 700, 528, 448), (22, 700, 528, 448), (23, 2304, 768, 1024), (24, 1, 16, 128),
-    (25, 256, 256, 64), (25, 700, 528, 448), (25, 2304, 768, 1024), (25, 1031, 1040, 320),
-    (27, 1024, 256, 256), (27, 2304, 768, 1024), (27, 1031, 512, 256), (27, 3000, 1024, 2048),
+    ("packed", 1024, 256, 256), ("packed", 2304, 768, 1024), ("packed", 1031, 512, 256), ("packed", 3000, 1024, 2048),
 ])
 def test_gemm_matches_definition(variant, M, N, K):
     """C = A W^T (Sec. 3.1 projections); fp32 accumulation of bf16 inputs."""
@@ -42,11 +38,29 @@ def test_gemm_matches_definition(variant, M, N, K):
     A = _rand_bf16(1, f"A{M}{K}", (M, K))
     W = _rand_bf16(2, f"W{N}{K}", (N, K), 0.05)
     ref = A.double() @ W.double().T
-    for out_f32 in ((False,) if variant == 27 else (True, False)):
-        got = B.op_gemm(A.cuda(), W.cuda(), out_f32=out_f32, variant=variant)
+    for out_f32 in ((False,) if variant == "packed" else (True, False)):
+        if variant == "packed":
+            got = B.op_gemm_packed(A.cuda(), W.cuda())
+        elif variant == "rows":
+            got = B.op_gemm_rows(A.cuda(), W.cuda(), out_f32=out_f32)
+        else:
+            got = B.op_gemm(A.cuda(), W.cuda(), out_f32=out_f32, variant=variant)
         torch.cuda.synchronize()
         tol = 1e-5 if out_f32 else 4e-3          # fp32 sum of exact products / one bf16 rounding
         assert rel_err(got.cpu(), ref) <= tol, (out_f32, rel_err(got.cpu(), ref))
+
+
+def test_gemm_entry_points_reject_bad_arguments():
+    from paper_2410_03960_amd import binding as B
+    A = _rand_bf16(1, "A", (64, 256)).cuda()
+    W = _rand_bf16(2, "W", (256, 256)).cuda()
+    for variant in (4, 27, 29, -1):                    # no longer / never offered
+        with pytest.raises(B.SwiftKVError):
+            B.op_gemm(A, W, variant=variant)
+    with pytest.raises(B.SwiftKVError):                # packed-weight loop needs M >= 1024
+        B.op_gemm_packed(A, W)
+    with pytest.raises(B.SwiftKVError):                # weight-streaming kernel: M <= 80
+        B.op_gemm_rows(_rand_bf16(1, "A2", (81, 256)).cuda(), W)
 
 
 @pytest.mark.parametrize("hd,Hq,Hkv,lens", [

@@ -227,6 +227,33 @@ def test_error_paths(tiny):
     with pytest.raises(B.SwiftKVError) as e:
         ctx.prefill(ids, [3], ctxd, logits, ws)      # negative context
     assert e.value.code == B.SWIFTKV_EINVAL
+    # an FP8 cache whose per-head scales this call would recompute must not hold older tokens
+    stale = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim, batch.block_tables, [5],
+                      fp8=True, scale_mode=B.SWIFTKV_SCALE_COMPUTE_ABSMAX)
+    with pytest.raises(B.SwiftKVError) as e:
+        ctx.prefill(ids, [3], stale, logits, ws)
+    assert e.value.code == B.SWIFTKV_EINVAL and "scales" in str(e.value)
+    # the pack buffer is the caller's: too small a one is refused, nothing is allocated behind the caller's back
+    import ctypes as C
+    lib = B.load()
+    need_min, need_full = B.pack_bytes(TINY, 2, 1, minimum=True), B.pack_bytes(TINY, 2, 1)
+    assert 0 < need_min <= need_full and B.pack_bytes(TINY, 2, 3) == 0
+    cfg = B.ModelCfg(TINY.n_layers, TINY.hidden, TINY.n_q_heads, TINY.n_kv_heads, TINY.head_dim, TINY.ffn, TINY.vocab,
+                     TINY.rope_theta, TINY.rms_eps)
+    w = B.Weights()
+    keep = []
+    for n in ("norm1", "wq", "wk", "wv", "wo", "norm2", "wgate", "wup", "wdown"):
+        arr = (C.c_void_p * TINY.n_layers)(*[dev_w[f"{n}.{j}"].data_ptr() for j in range(TINY.n_layers)])
+        keep.append(arr)
+        setattr(w, n, C.cast(arr, C.POINTER(C.c_void_p)))
+    w.embed, w.final_norm, w.lm_head = dev_w["embed"].data_ptr(), dev_w["final_norm"].data_ptr(), dev_w["lm_head"].data_ptr()
+    buf = torch.empty(need_full + 256, dtype=torch.uint8, device="cuda")
+    h = C.c_void_p()
+    assert lib.swiftkv_create(C.byref(h), C.byref(cfg), C.byref(w), 2, 1, buf.data_ptr(), need_min - 1, None) == B.SWIFTKV_ENOSPC
+    assert lib.swiftkv_create(C.byref(h), C.byref(cfg), C.byref(w), 2, 1, None, need_full, None) == B.SWIFTKV_ENOSPC
+    assert lib.swiftkv_create(C.byref(h), C.byref(cfg), C.byref(w), 2, 1, buf.data_ptr() + 16, need_full, None) == B.SWIFTKV_EINVAL
+    assert lib.swiftkv_create(C.byref(h), C.byref(cfg), C.byref(w), 2, 1, buf.data_ptr(), need_full, None) == B.SWIFTKV_OK
+    lib.swiftkv_destroy(h)
     # a block id outside the pool is caught on the device and reported, not dereferenced
     bad = B.KVCache(ctx.n_cache_layers, batch.n_blocks, TINY.n_kv_heads, TINY.head_dim,
                     torch.full_like(batch.block_tables, 10 ** 6), [0])
