@@ -17,7 +17,8 @@
  *    pointers are ordinary host memory read before the call returns.
  *  - The library allocates no device memory, ever: weights, cache, block
  *    tables, logits, the workspace of a call and the buffer that holds the
- *    re-arranged weight copies (pack_buf of swiftkv_create) are the caller's.
+ *    re-arranged weight copies (pack_buf of swiftkv_create) are the caller's
+ *    (one static device array: see swiftkv_op_gemm_rows_static).
  *    A context owns host memory only (tables, a small pinned staging ring for
  *    the per-call plan, HIP events).
  *  - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
@@ -241,6 +242,18 @@ int swiftkv_op_gemm_packed(const void *A, const void *W, void *w_packed, void *C
 int swiftkv_op_gemm_rows(const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K,
                          int32_t out_f32, void *workspace, size_t workspace_bytes, void *stream);
 size_t swiftkv_op_gemm_rows_workspace(int32_t M, int32_t N);
+/* swiftkv_op_gemm_rows for callers that cannot allocate device memory or pass a
+ * workspace (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): the K-split partial sums live in a static device array of
+ * the library, 4 x 80 x 8192 fp32 = 10.5 MB per GPU, held until the process
+ * ends.  Same kernels, same split, same summation order: results are bit-identical
+ * to swiftkv_op_gemm_rows.  M <= 80 and N <= 8192, else SWIFTKV_EINVAL.  Calls no
+ * allocating routine.  All calls on one GPU share the array (nothing in it has
+ * to start at zero: a call writes every partial sum before it reads it), so
+ * calls that overlap on one GPU -- different streams, different threads --
+ * race; issue them on one stream or order them with events. */
+int swiftkv_op_gemm_rows_static(const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K,
+                                int32_t out_f32, void *stream);
 
 /* Measurement aid: the rate (TFLOP/s, host double) at which the chip executes
  * nothing but v_mfma_f32_32x32x16_bf16 on the caller's data -- `operands` is

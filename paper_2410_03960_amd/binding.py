@@ -27,7 +27,7 @@ EXPORTS = (
     "swiftkv_pack_bytes", "swiftkv_pack_bytes_min",
     "swiftkv_create", "swiftkv_destroy", "swiftkv_workspace_bytes", "swiftkv_workspace_bytes_prefix", "swiftkv_prefill",
     "swiftkv_kv_from_hidden", "swiftkv_set_early_exit", "swiftkv_export_exit_flags", "swiftkv_export_plan", "swiftkv_export_hidden", "swiftkv_op_gemm",
-    "swiftkv_op_gemm_packed", "swiftkv_op_gemm_rows", "swiftkv_op_gemm_rows_workspace",
+    "swiftkv_op_gemm_packed", "swiftkv_op_gemm_rows", "swiftkv_op_gemm_rows_workspace", "swiftkv_op_gemm_rows_static",
     "swiftkv_op_attention_prefill", "swiftkv_op_attention_workspace", "swiftkv_op_fp8_quantize", "swiftkv_op_mfma_rate",
     "swiftkv_flops", "swiftkv_set_timing", "swiftkv_get_timing", "swiftkv_last_error",
     "swiftkv_version",
@@ -93,6 +93,7 @@ def load() -> C.CDLL:
     lib.swiftkv_op_gemm.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp]
     lib.swiftkv_op_gemm_packed.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
     lib.swiftkv_op_gemm_rows.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, C.c_size_t, vp]
+    lib.swiftkv_op_gemm_rows_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
     lib.swiftkv_op_gemm_rows_workspace.argtypes = [i32, i32]
     lib.swiftkv_op_gemm_rows_workspace.restype = C.c_size_t
     lib.swiftkv_op_attention_prefill.argtypes = [vp, vp, vp, vp, C.POINTER(i32), i32, i32, i32, i32, vp, C.c_size_t, vp]
@@ -318,6 +319,15 @@ def op_gemm_rows(A: torch.Tensor, W: torch.Tensor, out_f32: bool = False, stream
     out = torch.empty((M, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device=A.device)
     _check(lib.swiftkv_op_gemm_rows(_dev(A, torch.bfloat16), _dev(W, torch.bfloat16), _dev(out), M, N, K, int(out_f32),
                                     _dev(ws), ws.numel(), _stream_ptr(stream)))
+    return out
+
+
+def op_gemm_rows_static(A: torch.Tensor, W: torch.Tensor, out: torch.Tensor, stream=None) -> torch.Tensor:
+    """swiftkv_op_gemm_rows_static: the caller passes inputs and the output; nothing is allocated here or there."""
+    M, K = A.shape
+    N = W.shape[0]
+    _check(load().swiftkv_op_gemm_rows_static(_dev(A, torch.bfloat16), _dev(W, torch.bfloat16), _dev(out), M, N, K,
+                                              int(out.dtype == torch.float32), _stream_ptr(stream)))
     return out
 
 

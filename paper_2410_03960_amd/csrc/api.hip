@@ -11,6 +11,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <string>
 #include <array>
 #include <vector>
@@ -980,6 +981,47 @@ int swiftkv_op_gemm_rows(const void *A, const void *W, void *C, int32_t M, int32
   SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, (float *)workspace, workspace_bytes};
   if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, (hipStream_t)stream)) return fail(SWIFTKV_EHIP, "skinny launch failed");
   return check_launch("weight-streaming gemm");
+}
+
+// ---- the same kernel for callers that cannot allocate: its scratch is a static device array ----
+// 4 splits x 80 rows x 8192 columns of fp32 partial sums.  Every GPU the library runs on holds its own
+// copy of this array at its own address until the process ends.
+constexpr int STATIC_ROWS_MAX_M = SKINNY_MAX_ROWS, STATIC_ROWS_MAX_N = 8192;
+constexpr size_t STATIC_SCRATCH_FLOATS = (size_t)SKINNY_MAX_SPLIT * STATIC_ROWS_MAX_M * STATIC_ROWS_MAX_N;
+static __device__ __align__(256) float scratch[STATIC_SCRATCH_FLOATS];
+
+// Device address of `scratch` on the current device, looked up once per device (in host code the
+// array's name is only a stand-in; kernels must be given this address).
+static int static_scratch(float **out) {
+  constexpr int MAX_DEV = 64;
+  static std::mutex mu;
+  static float *ptr[MAX_DEV] = {};
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEV) return fail(SWIFTKV_EINVAL, "device index %d out of range", dev);
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void *p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(SWIFTKV_EHIP, "hipGetSymbolAddress returned a null address");
+    ptr[dev] = (float *)p;
+  }
+  *out = ptr[dev];
+  return 0;
+}
+
+int swiftkv_op_gemm_rows_static(const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K, int32_t out_f32,
+                                void *stream) {
+  if (!A || !W || !C) return fail(SWIFTKV_EINVAL, "null argument");
+  if (M < 1 || N < 16 || K < 8 || (N % 16) || (K % 8)) return fail(SWIFTKV_EINVAL, "need M >= 1, N %% 16 == 0, K %% 8 == 0");
+  if (M > STATIC_ROWS_MAX_M || N > STATIC_ROWS_MAX_N)
+    return fail(SWIFTKV_EINVAL, "M = %d, N = %d beyond the static scratch: at most %d rows and %d columns (use swiftkv_op_gemm_rows "
+                "with a workspace for more)", M, N, STATIC_ROWS_MAX_M, STATIC_ROWS_MAX_N);
+  float *sp = nullptr;
+  if (int e = static_scratch(&sp)) return e;
+  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, sp, STATIC_SCRATCH_FLOATS * sizeof(float)};
+  if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, (hipStream_t)stream)) return fail(SWIFTKV_EHIP, "skinny launch failed");
+  return check_launch("weight-streaming gemm (static scratch)");
 }
 
 size_t swiftkv_op_attention_workspace(int64_t n_tokens, int32_t n_seqs, int32_t n_kv_heads, int32_t head_dim) {
