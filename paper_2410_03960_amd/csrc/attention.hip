@@ -41,7 +41,7 @@ __device__ __forceinline__ float cross_half_max(float x) {
 // The 32 MFMA rows of a key block are fed with the keys in the order bit2 <-> bit3 swapped, which
 // makes the 8 exponentials a lane holds per PV step belong to 8 consecutive keys -- one 16-byte
 // V^T chunk instead of two 8-byte halves.
-template <int HD, bool PROF = false>
+template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams p) {
   constexpr int KCH = HD / 8;              // 16-byte chunks per K row (16 or 8)
   constexpr int K_RPI = 64 / KCH;          // K rows per 1 KB DMA request (4 or 8)
@@ -64,8 +64,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
   const int NQ = (p.n_q_heads % 8 == 0) ? 8 : 1;
   const int qid = blockIdx.x % NQ, hpq = p.n_q_heads / NQ;
   const int n_items = p.n_qblocks * hpq;   // per queue
-  long long wg_t0 = 0, wg_in = 0, wg_n = 0;
-  if constexpr (PROF) wg_t0 = wall_clock64();
   if (threadIdx.x == 0) s_item = atomicAdd(p.sched + qid, 1);
   __syncthreads();
   for (;;) {
@@ -73,8 +71,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
   if (item >= n_items) break;
   int item_next = 0;
   if (threadIdx.x == 0) item_next = atomicAdd(p.sched + qid, 1);   // consumed after the last tile
-  long long it_t0 = 0;
-  if constexpr (PROF) it_t0 = wall_clock64();
   const int qblock = item / hpq;
   const QBlock qb = p.qblocks[qblock];
   const int hslot = (item % hpq) * NQ + qid;
@@ -156,22 +152,18 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
   const float sc = 1.4426950408889634f * rsqrtf((float)HD);   // log2(e) / sqrt(hd)
   const float inv_sc = 1.0f / sc;
 
-  long long t_begin = 0, t_wait = 0, t_qk = 0, t_sm = 0, t_pv = 0, t_iss = 0;
-  long long w_begin = 0;
-  if constexpr (PROF) { t_begin = clock64(); w_begin = wall_clock64(); }
   issue_tile(0, 0);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   __syncthreads();
   for (int t = 0; t < n_tiles; ++t) {
-    long long ti0 = 0;
-    if constexpr (PROF) ti0 = clock64(); else asm volatile("" ::: "memory");
+    asm volatile("" ::: "memory");
     // Tile t+1 goes into the stage every wave finished reading before the last barrier.  The requests
     // are spread over the MFMA phases (a burst would hold the wave at the address unit's queue).
     // After the last tile the requests simply repeat it into the idle stage (no branches in the phases).
     const int tn = t + 1 < n_tiles ? t + 1 : t, sn = (t + 1) & 1;
     const int key0 = t * BKV;
     if (key0 > wave_last) issue_tile(tn, sn);
-    if constexpr (PROF) t_iss += clock64() - ti0; else asm volatile("" ::: "memory");
+    asm volatile("" ::: "memory");
     if (key0 <= wave_last) {   // wave-uniform: tiles entirely above the diagonal are skipped
       const unsigned k_addr = (t & 1) * STAGE + k_lane, v_addr = (t & 1) * STAGE + v_lane;
       floatx16 s[2];
@@ -191,8 +183,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
       auto load_v = [&](int st, int db) {   // keys 16*st + 8*g .. +7 of dim db*32 + l32
         vfr[db] = *(const bf16x8 *)(smem + (v_addr ^ (unsigned)(st * 32)) + db * 4096);
       };
-      long long ta = 0, tb = 0, tc = 0;
-      if constexpr (PROF) ta = clock64(); else asm volatile("" ::: "memory");
+      asm volatile("" ::: "memory");
       __builtin_amdgcn_s_setprio(2);   // the MFMA phases win the issue arbitration against the other wave's softmax arithmetic
       load_k(0);
       __builtin_amdgcn_sched_barrier(0);
@@ -212,7 +203,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
       }
       __builtin_amdgcn_s_setprio(0);
       __builtin_amdgcn_sched_barrier(0);   // phase boundaries keep the scheduler from stretching live ranges across phases
-      if constexpr (PROF) { if (s[1][15] == 12345.f) t_wait = 0; tb = clock64(); t_qk += tb - ta; } else asm volatile("" ::: "memory");
+      asm volatile("" ::: "memory");
       // s[kb][v] = raw score(key = key0 + kb*32 + 16*(v>>3) + 8*g + (v&7), this lane's query)
       const bool need_mask = (key0 + BKV - 1 > qb.q0 + wave * 32) || (key0 + BKV > qb.n);
       if (need_mask) {   // wave-uniform: only tiles on the diagonal or at the end of the sequence
@@ -258,7 +249,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
 #pragma unroll
       for (int j = 0; j < 4; ++j) exp_pair(0, j);
       __builtin_amdgcn_sched_barrier(0);
-      if constexpr (PROF) { if (rs == 12345.f) t_wait = 0; tc = clock64(); t_sm += tc - tb; } else asm volatile("" ::: "memory");
+      asm volatile("" ::: "memory");
       __builtin_amdgcn_s_setprio(1);
       // O^T += V^T P^T, 16 keys per MFMA.  The exponentials of the next step are computed between
       // the MFMAs of this one, and each V^T fragment register is refilled right after its use.
@@ -279,19 +270,11 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
       }
       l_run += rs;
       __builtin_amdgcn_s_setprio(0);
-      if constexpr (PROF) { if (o[0][0] == 12345.f) t_wait = 0; t_pv += clock64() - tc; } else asm volatile("" ::: "memory");
+      asm volatile("" ::: "memory");
     }
-    long long tw0 = 0;
-    if constexpr (PROF) tw0 = clock64(); else asm volatile("" ::: "memory");
+    asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(0x0F70);   // this wave's part of tile t+1 has landed ...
     __syncthreads();                      // ... everyone's has, and everyone is done reading tile t
-    if constexpr (PROF) t_wait += clock64() - tw0;
-  }
-  if constexpr (PROF) {
-    if (lane == 0 && p.prof) {
-      long long *o4 = p.prof + ((long long)(head * p.n_qblocks + qblock) * 4 + wave) * 4;
-      o4[0] = (clock64() - t_begin) + ((wall_clock64() - w_begin) << 40); o4[1] = t_wait + (t_pv << 32); o4[2] = t_qk + (t_sm << 32); o4[3] = n_tiles + (t_iss << 32);
-    }
   }
 
   // ---- normalise and store: o[db][4*jg+e] = O[query][d = db*32 + 8*jg + 4*g + e] ----
@@ -307,7 +290,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
             make_uint2(pack_bf16x2(o[db][4 * jg] * inv, o[db][4 * jg + 1] * inv), pack_bf16x2(o[db][4 * jg + 2] * inv, o[db][4 * jg + 3] * inv));
       }
   }
-  if constexpr (PROF) { wg_in += wall_clock64() - it_t0; ++wg_n; }
   // every wave read s_item before the tile loop's barriers; the same barriers separate the last
   // tile's LDS reads from the next prologue's writes
   if (threadIdx.x == 0) s_item = item_next;
@@ -319,12 +301,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
     if (atomicAdd(p.sched + 8, 1) == (int)gridDim.x - 1) {
       for (int i = 0; i < 9; ++i) p.sched[i] = 0;
       __threadfence();
-    }
-  }
-  if constexpr (PROF) {
-    if (threadIdx.x == 0 && p.prof) {   // per workgroup, after the per-item records: first start, end, time inside items, items (100 MHz ticks)
-      long long *w4 = p.prof + (long long)p.n_qblocks * p.n_q_heads * 16 + blockIdx.x * 4;
-      w4[0] = wg_t0; w4[1] = wall_clock64(); w4[2] = wg_in; w4[3] = wg_n;
     }
   }
 }
@@ -541,11 +517,6 @@ int launch_attention_prefill(const AttnPrefillParams &p, hipStream_t st) {
       hipError_t e = hipFuncSetAttribute((const void *)attn_prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
       if (e != hipSuccess) return (int)e;
       set = true;
-    }
-    if (p.prof) {
-      (void)hipFuncSetAttribute((const void *)attn_prefill_kernel<128, true>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-      hipLaunchKernelGGL((attn_prefill_kernel<128, true>), grid, dim3(256), SMEM, st, p);
-      return 0;
     }
     hipLaunchKernelGGL(attn_prefill_kernel<128>, grid, dim3(256), SMEM, st, p);
   } else {

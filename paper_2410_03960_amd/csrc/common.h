@@ -103,7 +103,7 @@ struct GemmParams {
   uint32_t *amax;              // FP8: [n_cache_layers][2][Hkv] absmax bit patterns (atomicMax), or null
   // RESID in the packed-weight loop, optional: besides C += acc, write the operand of the next
   // projection, hb[m][n] = bf16(C_new[m][n] * hb_gain[n]) (hb_gain null = 1), and the sums of squares of
-  // C_new over each 64-column block, ssq[n / 64][m] (leading dimension M), from which 1/rms follows
+  // C_new over each 64-column block, ssq[m][n / 64] (N / 64 per row), from which 1/rms follows
   bf16_t *hb;
   const bf16_t *hb_gain;
   float *ssq;
@@ -165,7 +165,6 @@ struct AttnPrefillParams {
   const QBlock *qblocks;
   int32_t n_qblocks, n_q_heads, n_kv_heads, head_dim;
   int32_t *sched;       // nine device words, zero at launch (the kernel leaves them zero): next item of 8 queues, workgroups done
-  long long *prof;      // timing experiments only: per-wave cycle counters [wg][wave][4], or null
 };
 int launch_attention_prefill(const AttnPrefillParams &p, hipStream_t st);
 
@@ -210,7 +209,7 @@ int launch_plan(const PlanParams &p, hipStream_t st);
 int launch_embed(const int32_t *ids, const bf16_t *E, float *h, int32_t T, int32_t d, int32_t vocab, hipStream_t st);
 // rstd[t] = rsqrt(mean(h[t,:]^2) + eps) of bf16 rows (a layer-l output handed in by the caller)
 int launch_rstd(const bf16_t *h, float *rstd, int32_t T, int32_t d, float eps, hipStream_t st);
-// the same from per-block sums of squares ssq[n_blocks][T] written by the RESID epilogue, added in block order
+// the same from per-block sums of squares ssq[T][n_blocks] written by the RESID epilogue, added in block order
 int launch_rstd_from_ssq(const float *ssq, int32_t n_blocks, float *rstd, int32_t T, int32_t d, float eps, hipStream_t st);
 // RMSNorm of fp32 rows into a bf16 GEMM operand.  rstd_out == null: out = bf16(h * rstd * gain).  Otherwise
 // the row factor is left to the consumer's epilogue: out = bf16(h * gain) and rstd_out[row] = rstd.

@@ -87,16 +87,24 @@ int launch_rstd(const bf16_t *h, float *rstd, int32_t T, int32_t d, float eps, h
 }
 
 // 1/rms from the per-block sums of squares the residual epilogue of the packed-weight GEMM leaves:
-// ssq[b][t], b < n_blocks, added in block order (fixed order: results do not change from run to run).
-__global__ void rstd_from_ssq_kernel(const float *ssq, int n_blocks, float *rstd, int T, float eps, float inv_d) {
+// ssq[t][b], b < n_blocks (a multiple of 4), added in block order (fixed order: results do not change
+// from run to run).  One thread per row; its loads are independent of each other.
+__global__ void rstd_from_ssq_kernel(const float4 *ssq, int n_quads, float *rstd, int T, float eps, float inv_d) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= T) return;
+  const float4 *r = ssq + (int64_t)t * n_quads;
   float s = 0.f;
-  for (int b = 0; b < n_blocks; ++b) s += ssq[(int64_t)b * T + t];
+  for (int q0 = 0; q0 < n_quads; q0 += 8) {
+    float4 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = q0 + i < n_quads ? r[q0 + i] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { s += v[i].x; s += v[i].y; s += v[i].z; s += v[i].w; }
+  }
   rstd[t] = rsqrtf(s * inv_d + eps);
 }
 int launch_rstd_from_ssq(const float *ssq, int32_t n_blocks, float *rstd, int32_t T, int32_t d, float eps, hipStream_t st) {
-  hipLaunchKernelGGL(rstd_from_ssq_kernel, dim3((T + 255) / 256), dim3(256), 0, st, ssq, n_blocks, rstd, T, eps, 1.0f / (float)d);
+  hipLaunchKernelGGL(rstd_from_ssq_kernel, dim3((T + 63) / 64), dim3(64), 0, st, (const float4 *)ssq, n_blocks / 4, rstd, T, eps, 1.0f / (float)d);
   return 0;
 }
 

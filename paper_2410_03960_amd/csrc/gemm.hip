@@ -706,7 +706,7 @@ int launch_one(const GemmParams &p, hipStream_t st) {
 // before the last 16-wide sub-step, where the next step's activations are first
 // read.  Needs K % 256 == 0 (four register slots, statically indexed) and
 // N % 256 == 0.
-template <int EPI, int FM>
+template <int EPI, int FM, bool NORM_OUT = false>   // NORM_OUT (RESID only): also the next projection's bf16 operand and the rows' sums of squares
 __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 (&acc)[2][FM], const int m_base,
                                                   const int n_base, const int lane, unsigned char *slab) {
   // acc[bn][bm][4*jg + e] is C[m_base + bm*32 + l32][n_base + bn*32 + 8*jg + 4*g + e].  32 rows at a
@@ -721,56 +721,62 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
     float *cbase = (float *)p.C + n_base;
     const int ch = lane & 7, r8 = lane >> 3;       // this lane's 8 columns, its row inside a group of 8
     float gv[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
-    if (p.hb && p.hb_gain) {
+    if (NORM_OUT && p.hb_gain) {
       const uint4 gq = *(const uint4 *)(p.hb_gain + n_base + ch * 8);
       gv[0] = bf16lo(gq.x); gv[1] = bf16hi(gq.x); gv[2] = bf16lo(gq.y); gv[3] = bf16hi(gq.y);
       gv[4] = bf16lo(gq.z); gv[5] = bf16hi(gq.z); gv[6] = bf16lo(gq.w); gv[7] = bf16hi(gq.w);
     }
-    // the residual rows of the whole wave tile are requested up front (the operand registers of the
-    // main loop are free by now), so their latency is paid once and no load follows a store
-    float4 res[FM][4][2];
+    // The residual rows are requested for half of the wave tile at a time (128 registers; the operand
+    // registers of the main loop are free by now), all of a half before its first store: loads and stores
+    // share one counter, so a load issued between stores would wait for the stores before it.
+    constexpr int HB = FM / 2;
 #pragma unroll
-    for (int bm = 0; bm < FM; ++bm)
+    for (int half = 0; half < 2; ++half) {
+      float4 res[HB][4][2];
 #pragma unroll
-      for (int it = 0; it < 4; ++it) {
-        const int m = m_base + bm * 32 + it * 8 + r8;
-        const float4 *src = (const float4 *)(cbase + (int64_t)(m < p.M ? m : p.M - 1) * p.ldc + ch * 8);
-        res[bm][it][0] = src[0];
-        res[bm][it][1] = src[1];
-      }
+      for (int b = 0; b < HB; ++b)
 #pragma unroll
-    for (int bm = 0; bm < FM; ++bm) {
-#pragma unroll
-      for (int bn = 0; bn < 2; ++bn)
-#pragma unroll
-        for (int jg = 0; jg < 4; ++jg)
-          *(float4 *)(slab + l32 * RS + (bn * 32 + 8 * jg + 4 * g) * 4) =
-              make_float4(acc[bn][bm][4 * jg], acc[bn][bm][4 * jg + 1], acc[bn][bm][4 * jg + 2], acc[bn][bm][4 * jg + 3]);
-      // a wave's LDS operations execute in order: the reads below see the writes above
-#pragma unroll
-      for (int it = 0; it < 4; ++it) {
-        const int row = it * 8 + r8;
-        const int m = m_base + bm * 32 + row;
-        const float4 lo = *(const float4 *)(slab + row * RS + ch * 32), hi = *(const float4 *)(slab + row * RS + ch * 32 + 16);
-        const float4 r0 = res[bm][it][0], r1 = res[bm][it][1];
-        const float x[8] = {r0.x + lo.x, r0.y + lo.y, r0.z + lo.z, r0.w + lo.w, r1.x + hi.x, r1.y + hi.y, r1.z + hi.z, r1.w + hi.w};
-        if (m < p.M) {
-          float4 *dst = (float4 *)(cbase + (int64_t)m * p.ldc + ch * 8);
-          dst[0] = make_float4(x[0], x[1], x[2], x[3]);
-          dst[1] = make_float4(x[4], x[5], x[6], x[7]);
-          if (p.hb)
-            *(uint4 *)(p.hb + (int64_t)m * p.ldc + n_base + ch * 8) =
-                make_uint4(pack_bf16x2(x[0] * gv[0], x[1] * gv[1]), pack_bf16x2(x[2] * gv[2], x[3] * gv[3]),
-                           pack_bf16x2(x[4] * gv[4], x[5] * gv[5]), pack_bf16x2(x[6] * gv[6], x[7] * gv[7]));
+        for (int it = 0; it < 4; ++it) {
+          const int m = m_base + (half * HB + b) * 32 + it * 8 + r8;
+          const float4 *src = (const float4 *)(cbase + (int64_t)(m < p.M ? m : p.M - 1) * p.ldc + ch * 8);
+          res[b][it][0] = src[0];
+          res[b][it][1] = src[1];
         }
-        if (p.ssq) {   // fixed order: the lane's 8 columns left to right, then a butterfly over the row's 8 lanes
-          float sq = 0.f;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) sq += x[e] * x[e];
-          sq += __shfl_xor(sq, 1);
-          sq += __shfl_xor(sq, 2);
-          sq += __shfl_xor(sq, 4);
-          if (ch == 0 && m < p.M) p.ssq[(int64_t)(n_base >> 6) * p.M + m] = sq;
+      for (int b = 0; b < HB; ++b) {
+        const int bm = half * HB + b;
+#pragma unroll
+        for (int bn = 0; bn < 2; ++bn)
+#pragma unroll
+          for (int jg = 0; jg < 4; ++jg)
+            *(float4 *)(slab + l32 * RS + (bn * 32 + 8 * jg + 4 * g) * 4) =
+                make_float4(acc[bn][bm][4 * jg], acc[bn][bm][4 * jg + 1], acc[bn][bm][4 * jg + 2], acc[bn][bm][4 * jg + 3]);
+        // a wave's LDS operations execute in order: the reads below see the writes above
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int row = it * 8 + r8;
+          const int m = m_base + bm * 32 + row;
+          const float4 lo = *(const float4 *)(slab + row * RS + ch * 32), hi = *(const float4 *)(slab + row * RS + ch * 32 + 16);
+          const float4 r0 = res[b][it][0], r1 = res[b][it][1];
+          const float x[8] = {r0.x + lo.x, r0.y + lo.y, r0.z + lo.z, r0.w + lo.w, r1.x + hi.x, r1.y + hi.y, r1.z + hi.z, r1.w + hi.w};
+          if (m < p.M) {
+            float4 *dst = (float4 *)(cbase + (int64_t)m * p.ldc + ch * 8);
+            dst[0] = make_float4(x[0], x[1], x[2], x[3]);
+            dst[1] = make_float4(x[4], x[5], x[6], x[7]);
+            if constexpr (NORM_OUT)
+              *(uint4 *)(p.hb + (int64_t)m * p.ldc + n_base + ch * 8) =
+                  make_uint4(pack_bf16x2(x[0] * gv[0], x[1] * gv[1]), pack_bf16x2(x[2] * gv[2], x[3] * gv[3]),
+                             pack_bf16x2(x[4] * gv[4], x[5] * gv[5]), pack_bf16x2(x[6] * gv[6], x[7] * gv[7]));
+          }
+          if constexpr (NORM_OUT) {   // fixed order: the lane's 8 columns left to right, then a butterfly over the row's 8 lanes
+            float sq = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sq += x[e] * x[e];
+            sq += __shfl_xor(sq, 1);
+            sq += __shfl_xor(sq, 2);
+            sq += __shfl_xor(sq, 4);
+            if (ch == 0 && m < p.M) p.ssq[(int64_t)m * (p.N >> 6) + (n_base >> 6)] = sq;
+          }
         }
       }
     }
@@ -954,7 +960,7 @@ __device__ __forceinline__ void gemm_epilogue_n64(const GemmParams &p, floatx16 
   }
 }
 
-template <int EPI>
+template <int EPI, bool NORM_OUT = false>
 __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
   constexpr int BM = 256, BN = 256, FM = 8;
   constexpr int NSA = 5, STAGE = BM * 128;   // activation stages: 256 rows x 128 bytes (one 64-wide k step)
@@ -1080,13 +1086,13 @@ __global__ __launch_bounds__(256) void gemm_wreg_kernel(GemmParams p) {
   __builtin_amdgcn_s_barrier();         // ... of every wave, before LDS is reused by the epilogue
   // per-wave slab: one 32-row block of fp32 (272-byte rows), or, for the rotating epilogues, all eight blocks of bf16 (144-byte rows)
   unsigned char *slab = smem + wave * ((EPI == EPI_QKV || EPI == EPI_KV) ? FM * 32 * (64 * 2 + 16) : 32 * (64 * 4 + 16));
-  gemm_epilogue_n64<EPI, FM>(p, acc, m0, n0, lane, slab);
+  gemm_epilogue_n64<EPI, FM, NORM_OUT>(p, acc, m0, n0, lane, slab);
 }
 
-template <int EPI>
-int launch_wreg(const GemmParams &p, hipStream_t st) {
+template <int EPI, bool NORM_OUT>
+int launch_wreg_k(const GemmParams &p, hipStream_t st) {
   constexpr int SMEM = 5 * 256 * 128;
-  auto kern = gemm_wreg_kernel<EPI>;
+  auto kern = gemm_wreg_kernel<EPI, NORM_OUT>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
@@ -1096,6 +1102,13 @@ int launch_wreg(const GemmParams &p, hipStream_t st) {
   const int tiles = ((p.M + 255) / 256) * (p.N / 256);
   hipLaunchKernelGGL(kern, dim3(((tiles + 7) / 8) * 8), dim3(256), SMEM, st, p);
   return 0;
+}
+template <int EPI>
+int launch_wreg(const GemmParams &p, hipStream_t st) {
+  if constexpr (EPI == EPI_RESID) {
+    if (p.hb && p.ssq) return launch_wreg_k<EPI, true>(p, st);
+  }
+  return launch_wreg_k<EPI, false>(p, st);
 }
 
 // variant: 0 = pick by shape; 1 = 256x256 tile, register-staged loads; 2 = 128x128 tile; 14 / 15 = the
