@@ -277,6 +277,23 @@ int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, vo
 size_t swiftkv_op_attention_workspace(int64_t n_tokens, int32_t n_seqs, int32_t n_kv_heads,
                                       int32_t head_dim);
 
+/* Single-query attention over a paged cache (what decode tokens and the last-
+ * token tail run, Sec. 3.1 decoding phase / Sec. 3.5): row r of q (dev bf16
+ * [n_rows, Hq*hd], already rotated) attends to keys 0 .. n_keys[r]-1 (host
+ * array) of block-table row r; out dev bf16 [n_rows, Hq*hd].  cache_k / cache_v
+ * are the K and V planes of ONE cache layer ([n_blocks*16][Hkv][hd], bf16 or
+ * e4m3 codes); scale_k / scale_v are that layer's [Hkv] scales, or
+ * [n_blocks*16] with scale_mode SWIFTKV_SCALE_PER_TOKEN (FP8 only).  An e4m3
+ * cache is read by the matrix unit as codes (FP8-input MFMA).  workspace as
+ * from swiftkv_op_attention_decode_workspace.  Synchronises the stream. */
+int swiftkv_op_attention_decode(const void *q, void *out, const int32_t *n_keys, int32_t n_rows,
+                                int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                const void *cache_k, const void *cache_v, int32_t kv_dtype,
+                                int32_t scale_mode, const float *scale_k, const float *scale_v,
+                                const int32_t *block_tables, int32_t max_blocks_per_seq,
+                                int32_t n_blocks, void *workspace, size_t workspace_bytes, void *stream);
+size_t swiftkv_op_attention_decode_workspace(int32_t n_rows, int32_t n_q_heads, int32_t head_dim);
+
 /* Saturating round-to-nearest-even fp32 -> OCP e4m3fn of x[i]/scale, dev arrays
  * (the quantiser of the FP8 cache, Appendix B.1). */
 int swiftkv_op_fp8_quantize(const float *x, float scale, uint8_t *codes, int64_t n, void *stream);

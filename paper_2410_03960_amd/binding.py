@@ -28,7 +28,7 @@ EXPORTS = (
     "swiftkv_create", "swiftkv_destroy", "swiftkv_workspace_bytes", "swiftkv_workspace_bytes_prefix", "swiftkv_prefill",
     "swiftkv_kv_from_hidden", "swiftkv_set_early_exit", "swiftkv_export_exit_flags", "swiftkv_export_plan", "swiftkv_export_hidden", "swiftkv_op_gemm",
     "swiftkv_op_gemm_packed", "swiftkv_op_gemm_rows", "swiftkv_op_gemm_rows_workspace", "swiftkv_op_gemm_rows_static",
-    "swiftkv_op_attention_prefill", "swiftkv_op_attention_workspace", "swiftkv_op_fp8_quantize", "swiftkv_op_mfma_rate",
+    "swiftkv_op_attention_prefill", "swiftkv_op_attention_workspace", "swiftkv_op_attention_decode", "swiftkv_op_attention_decode_workspace", "swiftkv_op_fp8_quantize", "swiftkv_op_mfma_rate",
     "swiftkv_flops", "swiftkv_set_timing", "swiftkv_get_timing", "swiftkv_last_error",
     "swiftkv_version",
 )
@@ -99,6 +99,10 @@ def load() -> C.CDLL:
     lib.swiftkv_op_attention_prefill.argtypes = [vp, vp, vp, vp, C.POINTER(i32), i32, i32, i32, i32, vp, C.c_size_t, vp]
     lib.swiftkv_op_attention_workspace.argtypes = [i64, i32, i32, i32]
     lib.swiftkv_op_attention_workspace.restype = C.c_size_t
+    lib.swiftkv_op_attention_decode.argtypes = [vp, vp, C.POINTER(i32), i32, i32, i32, i32, vp, vp, i32, i32, vp, vp, vp, i32, i32,
+                                                vp, C.c_size_t, vp]
+    lib.swiftkv_op_attention_decode_workspace.argtypes = [i32, i32, i32]
+    lib.swiftkv_op_attention_decode_workspace.restype = C.c_size_t
     lib.swiftkv_op_fp8_quantize.argtypes = [vp, C.c_float, vp, i64, vp]
     lib.swiftkv_op_mfma_rate.argtypes = [vp, i32, vp, C.c_size_t, C.POINTER(C.c_double), vp]
     lib.swiftkv_flops.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -340,6 +344,27 @@ def op_attention_prefill(q, k, v, seq_lens, n_q_heads, n_kv_heads, head_dim, str
     _check(lib.swiftkv_op_attention_prefill(_dev(q, torch.bfloat16), _dev(k, torch.bfloat16), _dev(v, torch.bfloat16),
                                             _dev(out), _i32_array(seq_lens), len(seq_lens), n_q_heads, n_kv_heads,
                                             head_dim, _dev(ws), nbytes, _stream_ptr(stream)))
+    return out
+
+
+def op_attention_decode(q: torch.Tensor, n_keys: Sequence[int], cache_k: torch.Tensor, cache_v: torch.Tensor,
+                        block_tables: torch.Tensor, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                        scale_k: Optional[torch.Tensor] = None, scale_v: Optional[torch.Tensor] = None,
+                        per_token: bool = False, stream=None) -> torch.Tensor:
+    """Single-query attention of each row of q over its block-table row of one cache layer's K / V planes
+    ([n_blocks*16, Hkv, hd], bf16 or uint8 e4m3 codes with scales)."""
+    lib = load()
+    n_rows = q.shape[0]
+    fp8 = cache_k.dtype == torch.uint8
+    ws = torch.empty(int(lib.swiftkv_op_attention_decode_workspace(n_rows, n_q_heads, head_dim)), dtype=torch.uint8, device=q.device)
+    out = torch.empty_like(q)
+    bt = block_tables.to(device=q.device, dtype=torch.int32).contiguous()
+    _check(lib.swiftkv_op_attention_decode(
+        _dev(q, torch.bfloat16), _dev(out), _i32_array(n_keys), n_rows, n_q_heads, n_kv_heads, head_dim,
+        _dev(cache_k), _dev(cache_v), SWIFTKV_KV_FP8_E4M3 if fp8 else SWIFTKV_KV_BF16,
+        SWIFTKV_SCALE_PER_TOKEN if per_token else SWIFTKV_SCALE_USE_GIVEN,
+        _dev(scale_k, torch.float32) if fp8 else None, _dev(scale_v, torch.float32) if fp8 else None,
+        _dev(bt), bt.shape[1], cache_k.shape[0] // 16, _dev(ws), ws.numel(), _stream_ptr(stream)))
     return out
 
 

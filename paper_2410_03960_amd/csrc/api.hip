@@ -1075,6 +1075,51 @@ int swiftkv_op_attention_prefill(const void *q, const void *k, const void *v, vo
   return SWIFTKV_OK;
 }
 
+size_t swiftkv_op_attention_decode_workspace(int32_t n_rows, int32_t n_q_heads, int32_t head_dim) {
+  if (n_rows < 1 || n_q_heads < 1 || head_dim < 1) return 0;
+  return align_up((size_t)n_rows * sizeof(DecodeRow)) + align_up((size_t)n_rows * n_q_heads * MAX_SPLIT * (head_dim + 2) * 4);
+}
+
+int swiftkv_op_attention_decode(const void *q, void *out, const int32_t *n_keys, int32_t n_rows, int32_t Hq, int32_t Hkv,
+                                int32_t hd, const void *cache_k, const void *cache_v, int32_t kv_dtype, int32_t scale_mode,
+                                const float *scale_k, const float *scale_v, const int32_t *block_tables,
+                                int32_t max_blocks_per_seq, int32_t n_blocks, void *workspace, size_t workspace_bytes,
+                                void *stream) {
+  if (!q || !out || !n_keys || !cache_k || !cache_v || !block_tables || !workspace) return fail(SWIFTKV_EINVAL, "null argument");
+  if ((hd != 64 && hd != 128) || Hkv < 1 || Hq % Hkv || n_rows < 1 || n_blocks < 1 || max_blocks_per_seq < 1)
+    return fail(SWIFTKV_EINVAL, "bad shape");
+  const int R = Hq / Hkv;
+  if (R != 1 && R != 2 && R != 4 && R != 8) return fail(SWIFTKV_EINVAL, "query heads per KV head must be 1, 2, 4 or 8");
+  const bool fp8 = kv_dtype == SWIFTKV_KV_FP8_E4M3;
+  if (!fp8 && kv_dtype != SWIFTKV_KV_BF16) return fail(SWIFTKV_EINVAL, "bad kv dtype");
+  if (fp8 && (!scale_k || !scale_v)) return fail(SWIFTKV_EINVAL, "FP8 cache needs scales");
+  if (workspace_bytes < swiftkv_op_attention_decode_workspace(n_rows, Hq, hd)) return fail(SWIFTKV_ENOSPC, "workspace too small");
+  std::vector<DecodeRow> rows(n_rows);
+  int max_keys = 1;
+  for (int r = 0; r < n_rows; ++r) {
+    if (n_keys[r] < 1 || (n_keys[r] + SKV_BLOCK - 1) / SKV_BLOCK > max_blocks_per_seq) return fail(SWIFTKV_EINVAL, "n_keys[%d] out of range", r);
+    rows[r] = DecodeRow{r, r, r, n_keys[r], -1, {0, 0, 0}};
+    max_keys = std::max(max_keys, n_keys[r]);
+  }
+  hipStream_t st = (hipStream_t)stream;
+  unsigned char *ws = (unsigned char *)workspace;
+  HIP_TRY(hipMemcpyAsync(ws, rows.data(), rows.size() * sizeof(DecodeRow), hipMemcpyHostToDevice, st));
+  AttnDecodeParams dp{};
+  dp.q = (const bf16_t *)q; dp.out = (bf16_t *)out; dp.rows = (const DecodeRow *)ws; dp.n_rows = n_rows;
+  dp.n_q_heads = Hq; dp.n_kv_heads = Hkv; dp.head_dim = hd;
+  dp.cache_k = cache_k; dp.cache_v = cache_v;
+  dp.fp8 = !fp8 ? 0 : (scale_mode == SWIFTKV_SCALE_PER_TOKEN ? 2 : 1);
+  dp.scale_k = scale_k; dp.scale_v = scale_v;
+  dp.block_tables = block_tables; dp.max_blocks_per_seq = max_blocks_per_seq; dp.n_blocks = n_blocks;
+  dp.partial = (float *)(ws + align_up((size_t)n_rows * sizeof(DecodeRow)));
+  dp.n_split = pick_split(n_rows, Hkv, max_keys);
+  if (launch_attention_decode(dp, st)) return fail(SWIFTKV_EHIP, "decode attention launch failed");
+  launch_decode_combine(dp.partial, dp.out, dp.rows, n_rows, Hq, hd, dp.n_split, st);
+  if (int e = check_launch("single-query attention")) return e;
+  HIP_TRY(hipStreamSynchronize(st));   // the row table was staged from this call's own (pageable) host vector
+  return SWIFTKV_OK;
+}
+
 int swiftkv_op_mfma_rate(const void *operands, int32_t iters, void *sink, size_t sink_bytes, double *tflops_out, void *stream) {
   if (!operands || !tflops_out || !sink || iters < 1) return fail(SWIFTKV_EINVAL, "bad argument");
   hipStream_t st = (hipStream_t)stream;

@@ -8,8 +8,10 @@
 //    so one lane owns one query column: the running max / sum of the online
 //    softmax are per-lane scalars (one cross-half exchange), and the exponentials
 //    are already laid out as the second operand of O^T += V^T P^T.
-// 2. attn_decode_kernel: one query row against a paged (bf16 or FP8) cache,
-//    split over key ranges; used for the last-token tail and for decode tokens.
+// 2. attn_decode_kernel: one query row against a paged bf16 cache, split over key
+//    ranges; used for the last-token tail and for decode tokens.
+// 3. attn_decode_fp8_kernel: the same over an e4m3 cache, the codes fed to the
+//    matrix unit as they are.
 #include "common.h"
 
 namespace {
@@ -377,7 +379,6 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
   }
-  const float ks = p.fp8 == 1 ? p.scale_k[kvh] : 1.f, vs = p.fp8 == 1 ? p.scale_v[kvh] : 1.f;   // per-slot scales are read with the keys
   const int32_t *bt = p.block_tables + (int64_t)row.seq * p.max_blocks_per_seq;
 
   // Two key steps per iteration, all four loads first.  The running reference m[r] (log2 units) only
@@ -395,7 +396,6 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
     float kf[2][8], vf[2][8];
     bool valid[2];
     uint4 kraw[2], vraw[2];
-    float ksl[2] = {ks, ks}, vsl[2] = {vs, vs};
     const int blk_cur[2] = {blk_nxt[0], blk_nxt[1]};
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
@@ -412,33 +412,17 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
         blk = ((unsigned)blk < (unsigned)p.n_blocks) ? blk : 0;   // bad ids are flagged by the plan kernel; never dereference them
         const int64_t slot = (int64_t)blk * SKV_BLOCK + key % SKV_BLOCK;
         const int64_t off = (slot * p.n_kv_heads + kvh) * HD + sub * 8;
-        if (p.fp8) {
-          const uint2 kc = *(const uint2 *)((const uint8_t *)p.cache_k + off);
-          const uint2 vc = *(const uint2 *)((const uint8_t *)p.cache_v + off);
-          kraw[u].x = kc.x; kraw[u].y = kc.y; vraw[u].x = vc.x; vraw[u].y = vc.y;
-          if (p.fp8 == 2) { ksl[u] = p.scale_k[slot]; vsl[u] = p.scale_v[slot]; }
-        } else {
-          kraw[u] = *(const uint4 *)((const bf16_t *)p.cache_k + off);
-          vraw[u] = *(const uint4 *)((const bf16_t *)p.cache_v + off);
-        }
+        kraw[u] = *(const uint4 *)((const bf16_t *)p.cache_k + off);
+        vraw[u] = *(const uint4 *)((const bf16_t *)p.cache_v + off);
       }
     }
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      if (p.fp8) {
-        const uint32_t kw[2] = {kraw[u].x, kraw[u].y}, vw[2] = {vraw[u].x, vraw[u].y};
+      const uint32_t kw[4] = {kraw[u].x, kraw[u].y, kraw[u].z, kraw[u].w}, vw[4] = {vraw[u].x, vraw[u].y, vraw[u].z, vraw[u].w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          kf[u][e] = e4m3fn_to_f32((uint8_t)(kw[e >> 2] >> ((e & 3) * 8))) * ksl[u];
-          vf[u][e] = e4m3fn_to_f32((uint8_t)(vw[e >> 2] >> ((e & 3) * 8))) * vsl[u];
-        }
-      } else {
-        const uint32_t kw[4] = {kraw[u].x, kraw[u].y, kraw[u].z, kraw[u].w}, vw[4] = {vraw[u].x, vraw[u].y, vraw[u].z, vraw[u].w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          kf[u][2 * e] = bf16lo(kw[e]); kf[u][2 * e + 1] = bf16hi(kw[e]);
-          vf[u][2 * e] = bf16lo(vw[e]); vf[u][2 * e + 1] = bf16hi(vw[e]);
-        }
+      for (int e = 0; e < 4; ++e) {
+        kf[u][2 * e] = bf16lo(kw[e]); kf[u][2 * e + 1] = bf16hi(kw[e]);
+        vf[u][2 * e] = bf16lo(vw[e]); vf[u][2 * e + 1] = bf16hi(vw[e]);
       }
 #pragma unroll
       for (int r = 0; r < R; ++r) {
@@ -499,6 +483,285 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
   }
 }
 
+// ------------------------------------------------ decode, FP8 cache, MFMA ----
+// Single-query attention over an e4m3 cache with the codes fed to the matrix unit as they are
+// (v_mfma_f32_16x16x32_fp8_fp8), scales applied to the fp32 results.  grid (n_rows, n_kv_heads, n_split),
+// 4 waves, each wave walks 32 keys per step.
+//  * S^T[key][r] = sum_d K[key][d] q[r][d]: first operand = K codes straight from the cache (a lane reads
+//    HD/4 contiguous bytes of one key; within one instruction the contraction index may be assigned to
+//    (lane group, element) in any order as long as both operands agree), second operand = the R query heads
+//    of the KV head (columns R..15 are zero) as e4m3 with one scale per head.  To keep bf16-level accuracy q
+//    is split into two e4m3 terms, q = qs * (q_hi + q_lo), each with its own instruction.
+//  * O^T[d][r] += sum_key V^T[d][key] P^T[key][r]: V codes are staged row-major in LDS and read with the
+//    transposing LDS read (ds_read_b64_tr_b8: lane i of a 16-lane group receives column i of the 8 x 16 byte
+//    matrix the group's lanes address), which yields the [d][8 keys] fragments without any byte shuffles;
+//    the softmax weights are the second operand, again as two e4m3 terms.
+// The 32 keys of a step sit in the contraction slots in the order the score instruction leaves them:
+// slot (g, j) of lane group g holds key 4g + j for j < 4 and key 16 + 4g + (j - 4) for j >= 4.
+typedef long fp8x8_t;   // eight e4m3 codes
+__device__ __forceinline__ int pack4_fp8(float a, float b, float c, float d) {
+  int w = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
+  return __builtin_amdgcn_cvt_pk_fp8_f32(c, d, w, true);
+}
+__device__ __forceinline__ fp8x8_t make_fp8x8(int lo, int hi) {
+  return (fp8x8_t)(((unsigned long)(unsigned)hi << 32) | (unsigned long)(unsigned)lo);
+}
+// x[0..7] -> e4m3 term `hi` and e4m3 term `lo` of the remainder
+__device__ __forceinline__ void split_fp8x8(const float (&x)[8], fp8x8_t &hi, fp8x8_t &lo) {
+  const int h0 = pack4_fp8(x[0], x[1], x[2], x[3]), h1 = pack4_fp8(x[4], x[5], x[6], x[7]);
+  float r[8];
+  r[0] = x[0] - __builtin_amdgcn_cvt_f32_fp8(h0, 0); r[1] = x[1] - __builtin_amdgcn_cvt_f32_fp8(h0, 1);
+  r[2] = x[2] - __builtin_amdgcn_cvt_f32_fp8(h0, 2); r[3] = x[3] - __builtin_amdgcn_cvt_f32_fp8(h0, 3);
+  r[4] = x[4] - __builtin_amdgcn_cvt_f32_fp8(h1, 0); r[5] = x[5] - __builtin_amdgcn_cvt_f32_fp8(h1, 1);
+  r[6] = x[6] - __builtin_amdgcn_cvt_f32_fp8(h1, 2); r[7] = x[7] - __builtin_amdgcn_cvt_f32_fp8(h1, 3);
+  hi = make_fp8x8(h0, h1);
+  lo = make_fp8x8(pack4_fp8(r[0], r[1], r[2], r[3]), pack4_fp8(r[4], r[5], r[6], r[7]));
+}
+
+template <int HD, int R>
+__global__ __launch_bounds__(256) void attn_decode_fp8_kernel(AttnDecodeParams p) {
+  constexpr int NM = HD / 32;        // score instructions per 16-key block and q term
+  constexpr int NDB = HD / 16;       // 16-dim blocks of the output
+  constexpr int VS = HD + 16;        // LDS row stride of the V tile (keeps the transposing reads off shared banks)
+  constexpr int KB = HD / 4;         // contiguous K bytes a lane reads per key
+  constexpr int VCH = HD / 16;       // 16-byte chunks per V row
+  constexpr int V_IT = 32 * VCH / 64;  // 16-byte loads per lane for a 32-key V tile
+  __shared__ __align__(16) unsigned char v_lds[4][32 * VS];
+  __shared__ __align__(16) float q32[R][HD];
+  __shared__ __align__(16) unsigned char q8[2][16][HD];
+  __shared__ float q_scale[8];
+  __shared__ float sm[4][R][HD + 2];
+
+  const DecodeRow row = p.rows[blockIdx.x];
+  const int kvh = blockIdx.y, split = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, kq = lane >> 4;
+  const int q_dim = p.n_q_heads * HD;
+  const bool per_slot = p.fp8 == 2;
+
+  // keys of this split: whole 128-key steps, at least 256 keys per split
+  int per = (row.n_keys + p.n_split - 1) / p.n_split;
+  per = per < 256 ? 256 : per;
+  per = (per + 127) / 128 * 128;
+  const int k_lo = split * per;
+  const int k_hi = (k_lo + per) < row.n_keys ? (k_lo + per) : row.n_keys;
+
+  // ---- the R query heads: rotate (tail rows), round to bf16 like the prefill path, one scale per head, two e4m3 terms ----
+  for (int idx = tid; idx < R * (HD / 2); idx += 256) {
+    const int r = idx / (HD / 2), i = idx % (HD / 2);
+    const bf16_t *qp = p.q + (int64_t)row.q_row * q_dim + (kvh * R + r) * HD;
+    float x1 = bf16_to_f32(qp[i]), x2 = bf16_to_f32(qp[i + HD / 2]);
+    if (row.cs_row >= 0) {
+      const float2 c = p.cos_sin[(int64_t)row.cs_row * (HD / 2) + i];
+      const float y1 = x1 * c.x - x2 * c.y, y2 = x2 * c.x + x1 * c.y;
+      x1 = bf16_to_f32(f32_to_bf16(y1)); x2 = bf16_to_f32(f32_to_bf16(y2));
+    }
+    q32[r][i] = x1; q32[r][i + HD / 2] = x2;
+  }
+  __syncthreads();
+  for (int r = wave; r < R; r += 4) {
+    float a = 0.f;
+    for (int d = lane; d < HD; d += 64) a = fmaxf(a, fabsf(q32[r][d]));
+    a = wave_max(a);
+    if (lane == 0) q_scale[r] = a > 0.f ? a / 448.0f : 1.0f;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < 16 * HD; idx += 256) {
+    const int r = idx / HD, d = idx % HD;
+    unsigned char hi = 0, lo = 0;
+    if (r < R) {
+      const float v = q32[r][d] / q_scale[r];
+      const int h = __builtin_amdgcn_cvt_pk_fp8_f32(v, 0.f, 0, false);
+      const int l = __builtin_amdgcn_cvt_pk_fp8_f32(v - __builtin_amdgcn_cvt_f32_fp8(h, 0), 0.f, 0, false);
+      hi = (unsigned char)(h & 0xff); lo = (unsigned char)(l & 0xff);
+    }
+    q8[0][r][d] = hi; q8[1][r][d] = lo;
+  }
+  __syncthreads();
+  fp8x8_t qh[NM], ql[NM];   // second operand of score instruction m: q[r = l16][d = kq*KB + 8m .. +7]
+#pragma unroll
+  for (int m = 0; m < NM; ++m) {
+    qh[m] = *(const fp8x8_t *)&q8[0][l16][kq * KB + 8 * m];
+    ql[m] = *(const fp8x8_t *)&q8[1][l16][kq * KB + 8 * m];
+  }
+  const float sc = 1.4426950408889634f * rsqrtf((float)HD);
+  const float col_scale = l16 < R ? q_scale[l16 < R ? l16 : 0] * sc * (per_slot ? 1.f : p.scale_k[kvh]) : 0.f;
+  const float vs_head = per_slot ? 1.f : p.scale_v[kvh];
+
+  const int32_t *bt = p.block_tables + (int64_t)row.seq * p.max_blocks_per_seq;
+  const int64_t tok_stride = (int64_t)p.n_kv_heads * HD;   // bytes between tokens of a block
+  const uint8_t *ck = (const uint8_t *)p.cache_k + (int64_t)kvh * HD, *cv = (const uint8_t *)p.cache_v + (int64_t)kvh * HD;
+
+  floatx4 o[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;   // of column r = l16 (the four lanes of a column agree on m_run)
+
+  // this lane's part of the step that starts at key `base` (a multiple of 32): K bytes of key base + 16 kb + l16,
+  // 16-byte pieces of the V tile; keys at or past k_hi read the last visible key's data (masked below)
+  uint2 kreg[2][NM];
+  uint4 vreg[V_IT];
+  int blk_of[2];          // physical blocks of the two 16-key halves (wave-uniform)
+  auto load_step = [&](int base) __attribute__((always_inline)) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      int key0 = base + 16 * kb;
+      key0 = key0 < k_hi ? key0 : ((k_hi - 1) & ~15);
+      int blk = bt[key0 >> 4];
+      blk = ((unsigned)blk < (unsigned)p.n_blocks) ? blk : 0;   // bad ids are flagged by the plan kernel; never dereference them
+      blk_of[kb] = blk;
+      int key = key0 + l16;
+      key = key < k_hi ? key : k_hi - 1;
+      const uint8_t *src = ck + ((int64_t)blk * SKV_BLOCK + (key & 15)) * tok_stride + kq * KB;
+#pragma unroll
+      for (int m = 0; m < NM; ++m) kreg[kb][m] = *(const uint2 *)(src + 8 * m);
+    }
+#pragma unroll
+    for (int i = 0; i < V_IT; ++i) {
+      const int c = i * 64 + lane, kl = c / VCH, ch = c % VCH;   // local key, 16-byte chunk
+      int key = base + kl;
+      key = key < k_hi ? key : k_hi - 1;
+      int blk = (kl >> 4) ? blk_of[1] : blk_of[0];
+      if ((base + kl) >= k_hi) { blk = bt[key >> 4]; blk = ((unsigned)blk < (unsigned)p.n_blocks) ? blk : 0; }
+      vreg[i] = *(const uint4 *)(cv + ((int64_t)blk * SKV_BLOCK + (key & 15)) * tok_stride + ch * 16);
+    }
+  };
+
+  unsigned char *vt = v_lds[wave];
+  // transposing read of lane group kq: lanes 2j, 2j+1 address the 16 bytes (dims 16 db .. +15) of the key in slot (kq, j)
+  const int j_slot = l16 >> 1;
+  const int key_slot = j_slot < 4 ? 4 * kq + j_slot : 16 + 4 * kq + (j_slot - 4);
+  const unsigned char *vt_lane = vt + key_slot * VS + (lane & 1) * 8;
+  typedef int v2i_t __attribute__((ext_vector_type(2)));
+  typedef __attribute__((address_space(3))) v2i_t *lds_v2i_ptr;
+
+  if (k_lo + wave * 32 < k_hi) load_step(k_lo + wave * 32);
+  for (int base = k_lo + wave * 32; base < k_hi; base += 128) {
+    // V tile of this step into the wave's LDS tile (only this wave touches it; a wave's LDS operations run in order)
+#pragma unroll
+    for (int i = 0; i < V_IT; ++i) {
+      const int c = i * 64 + lane;
+      *(uint4 *)(vt + (c / VCH) * VS + (c % VCH) * 16) = vreg[i];
+    }
+    fp8x8_t kf[2][NM];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int m = 0; m < NM; ++m) kf[kb][m] = (fp8x8_t)(((unsigned long)kreg[kb][m].y << 32) | kreg[kb][m].x);
+    const int blk_cur[2] = {blk_of[0], blk_of[1]};
+    load_step(base + 128 < k_hi ? base + 128 : base);   // next step's bytes are in flight during this step's arithmetic (the last step re-reads itself)
+    asm volatile("" ::: "memory");
+
+    // scores of keys base + 16 kb + 4 kq + i against head l16
+    floatx4 s4[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      s4[kb] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+        s4[kb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(kf[kb][m], qh[m], s4[kb], 0, 0, 0);
+        s4[kb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(kf[kb][m], ql[m], s4[kb], 0, 0, 0);
+      }
+    }
+    float ksl[8], vsl[8];
+    if (per_slot) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const int64_t slot0 = (int64_t)blk_cur[kb] * SKV_BLOCK + 4 * kq;
+        const float4 a = *(const float4 *)(p.scale_k + slot0), b = *(const float4 *)(p.scale_v + slot0);
+        ksl[4 * kb] = a.x; ksl[4 * kb + 1] = a.y; ksl[4 * kb + 2] = a.z; ksl[4 * kb + 3] = a.w;
+        vsl[4 * kb] = b.x; vsl[4 * kb + 1] = b.y; vsl[4 * kb + 2] = b.z; vsl[4 * kb + 3] = b.w;
+      }
+    }
+    float sv[8], mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int key = base + 16 * (e >> 2) + 4 * kq + (e & 3);
+      float x = s4[e >> 2][e & 3] * col_scale;
+      if (per_slot) x *= ksl[e];
+      sv[e] = key < k_hi ? x : -INFINITY;
+      mx = fmaxf(mx, sv[e]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    // lazy rescaling: the reference only moves when a score exceeds it by more than 8 (log2 units)
+    if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.0f) != 0) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);   // exp2(-inf) = 0 the first time
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[db][i] *= alpha;
+    }
+    // per-slot V scales enter through the weights, relative to the largest scale of the step's keys so that
+    // the e4m3 terms keep their precision; the step's product is then added with that scale
+    float v_ref = 1.f, v_inv = 1.f;
+    if (per_slot) {
+      float vm = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vm = fmaxf(vm, sv[e] == -INFINITY ? 0.f : vsl[e]);
+      vm = fmaxf(vm, __shfl_xor(vm, 16));
+      vm = fmaxf(vm, __shfl_xor(vm, 32));
+      v_ref = vm;
+      v_inv = vm > 0.f ? 1.f / vm : 0.f;
+    }
+    float pw[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float w = (sv[e] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sv[e] - m_run);
+      l_run += w;
+      pw[e] = per_slot ? w * (vsl[e] * v_inv) : w;
+    }
+    fp8x8_t ph, pl;
+    split_fp8x8(pw, ph, pl);
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      const v2i_t t = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(vt_lane + db * 16));
+      const fp8x8_t vf = make_fp8x8(t.x, t.y);
+      if (per_slot) {
+        floatx4 acc = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(vf, ph, floatx4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(vf, pl, acc, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[db][i] += v_ref * acc[i];
+      } else {
+        o[db] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(vf, ph, o[db], 0, 0, 0);
+        o[db] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(vf, pl, o[db], 0, 0, 0);
+      }
+    }
+    asm volatile("" ::: "memory");
+  }
+
+  // ---- this wave's (o, m, l) of head l16: o[db][i] = O[d = 16 db + 4 kq + i]; then the four waves, as one split ----
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  if (l16 < R) {
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sm[wave][l16][db * 16 + 4 * kq + i] = o[db][i] * vs_head;
+    if (kq == 0) { sm[wave][l16][HD] = m_run; sm[wave][l16][HD + 1] = l_run; }
+  }
+  __syncthreads();
+  for (int i = tid; i < R * HD; i += 256) {
+    const int r = i / HD, d = i % HD;
+    const float mm = fmaxf(fmaxf(sm[0][r][HD], sm[1][r][HD]), fmaxf(sm[2][r][HD], sm[3][r][HD]));
+    float x = 0.f, ll = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float mw = sm[w][r][HD];
+      const float a = (mw == -INFINITY) ? 0.f : exp2f(mw - mm);
+      x += a * sm[w][r][d];
+      ll += a * sm[w][r][HD + 1];
+    }
+    float *dst = p.partial + (((int64_t)blockIdx.x * p.n_q_heads + kvh * R + r) * p.n_split + split) * (HD + 2);
+    dst[d] = x;
+    if (d == 0) { dst[HD] = mm; dst[HD + 1] = ll; }
+  }
+}
+
 }  // namespace
 
 int launch_attention_prefill(const AttnPrefillParams &p, hipStream_t st) {
@@ -530,6 +793,16 @@ template <int HD>
 static int launch_decode_hd(const AttnDecodeParams &p, hipStream_t st) {
   dim3 grid(p.n_rows, p.n_kv_heads, p.n_split);
   const int R = p.n_q_heads / p.n_kv_heads;
+  if (p.fp8) {   // e4m3 cache: the codes go to the matrix unit as they are
+    switch (R) {
+      case 1: hipLaunchKernelGGL((attn_decode_fp8_kernel<HD, 1>), grid, dim3(256), 0, st, p); break;
+      case 2: hipLaunchKernelGGL((attn_decode_fp8_kernel<HD, 2>), grid, dim3(256), 0, st, p); break;
+      case 4: hipLaunchKernelGGL((attn_decode_fp8_kernel<HD, 4>), grid, dim3(256), 0, st, p); break;
+      case 8: hipLaunchKernelGGL((attn_decode_fp8_kernel<HD, 8>), grid, dim3(256), 0, st, p); break;
+      default: return -1;
+    }
+    return 0;
+  }
   switch (R) {
     case 1: hipLaunchKernelGGL((attn_decode_kernel<HD, 1>), grid, dim3(256), 0, st, p); break;
     case 2: hipLaunchKernelGGL((attn_decode_kernel<HD, 2>), grid, dim3(256), 0, st, p); break;

@@ -86,6 +86,58 @@ def test_prefill_attention_matches_bruteforce_softmax(hd, Hq, Hkv, lens):
         off += n
 
 
+@pytest.mark.parametrize("hd,Hq,Hkv,mode,lens", [
+    (128, 32, 8, "bf16", [4097, 1, 300]), (128, 32, 8, "fp8_head", [4097, 1, 300, 2048, 33]),
+    (128, 32, 8, "fp8_token", [4097, 1, 300, 129]), (128, 8, 8, "fp8_head", [700, 5]), (128, 16, 2, "fp8_token", [1000, 17]),
+    (64, 8, 4, "fp8_head", [1500, 64]), (64, 4, 4, "fp8_token", [90, 256]), (64, 8, 1, "fp8_head", [31, 2500]),
+    (128, 8, 4, "fp8_head", [20000]),
+])
+def test_single_query_attention_over_paged_cache(hd, Hq, Hkv, mode, lens):
+    """One query row per sequence over a paged cache with shuffled blocks (the decode / last-token
+    attention), bf16 or e4m3 codes (per-head and per-slot scales; the e4m3 path feeds the codes to
+    the matrix unit), against the oracle's attention over the values the cache decodes to."""
+    from paper_2410_03960_amd import binding as B
+    _say(f"single-query attention hd={hd} Hq={Hq} Hkv={Hkv} {mode} lens={lens}")
+    n_rows = len(lens)
+    need = [(n + 15) // 16 for n in lens]
+    n_blocks = sum(need) + 3
+    perm = torch.from_numpy(WL.seeded_permutation(7, f"blocks{n_blocks}", n_blocks))
+    bt = torch.zeros((n_rows, max(need)), dtype=torch.int32)
+    pos = 0
+    for b, nb in enumerate(need):
+        bt[b, :nb] = perm[pos:pos + nb].to(torch.int32)
+        pos += nb
+    q = _rand_bf16(21, f"q{mode}{hd}", (n_rows, Hq * hd))
+    n_slots = n_blocks * 16
+    if mode == "bf16":
+        ck = _rand_bf16(22, f"k{hd}{n_slots}", (n_slots, Hkv, hd))
+        cv = _rand_bf16(23, f"v{hd}{n_slots}", (n_slots, Hkv, hd))
+        kf, vf = ck.double(), cv.double()
+        sk = sv = None
+    else:
+        ck = WL.seeded_fp8_codes(24, f"k{hd}{n_slots}", (n_slots, Hkv, hd), mag_lo=0x20, mag_hi=0x7E)
+        cv = WL.seeded_fp8_codes(25, f"v{hd}{n_slots}", (n_slots, Hkv, hd), mag_lo=0x01, mag_hi=0x7E)
+        tab = O.fp8_e4m3fn_decode_table()
+        if mode == "fp8_head":
+            sk = (0.002 + 0.001 * torch.arange(Hkv)).float()
+            sv = (0.004 + 0.0005 * torch.arange(Hkv)).float()
+            kf, vf = tab[ck.long()] * sk.double()[None, :, None], tab[cv.long()] * sv.double()[None, :, None]
+        else:     # per-slot scales spread over three binades
+            sk = (0.001 * 2.0 ** (3 * WL.seeded_uniform01(26, "sk", n_slots))).astype("float32")
+            sv = (0.0005 * 2.0 ** (3 * WL.seeded_uniform01(27, "sv", n_slots))).astype("float32")
+            sk, sv = torch.from_numpy(sk), torch.from_numpy(sv)
+            kf, vf = tab[ck.long()] * sk.double()[:, None, None], tab[cv.long()] * sv.double()[:, None, None]
+    got = B.op_attention_decode(q.cuda(), lens, ck.cuda(), cv.cuda(), bt, Hq, Hkv, hd,
+                                sk.cuda() if sk is not None else None, sv.cuda() if sv is not None else None,
+                                per_token=(mode == "fp8_token")).cpu()
+    for b, n in enumerate(lens):
+        slots = bt[b].long()[torch.arange(n) // 16] * 16 + torch.arange(n) % 16
+        ref = O.gqa_attention(q[b:b + 1].double().view(1, Hq, hd), torch.tensor([n - 1]), kf[slots], vf[slots])
+        g = got[b].view(1, Hq, hd)
+        r, cs = rel_err(g, ref), cosine(g, ref)
+        assert r <= 1e-2 and cs >= 0.9995, (b, n, r, cs)
+
+
 def test_fp8_quantiser_is_bit_exact():
     """Same fp32 inputs, same fp32 division: codes must agree bit for bit."""
     from paper_2410_03960_amd import binding as B
