@@ -279,18 +279,35 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
     __syncthreads();                      // ... everyone's has, and everyone is done reading tile t
   }
 
-  // ---- normalise and store: o[db][4*jg+e] = O[query][d = db*32 + 8*jg + 4*g + e] ----
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  if (qvalid) {
-    const float inv = 1.f / l_tot;
-    bf16_t *op = p.out + (int64_t)qrow * q_dim + head * HD;
+  // ---- normalise and store: o[db][4*jg+e] = O[query l32][d = db*32 + 8*jg + 4*g + e] ----
+  // The wave's 32 x HD block leaves through LDS, so that it is written as whole rows (16 lanes cover
+  // one 256-byte row); stored straight from the accumulator layout it went out as 16-byte pieces of
+  // 32 rows per instruction, which cost a third of the kernel's time on short sequences.  The slab is
+  // this wave's 8 KB of the second stage: every wave is past the last tile's barrier, and the next
+  // requests into that stage follow the next item's first barrier.  16-byte chunks are XOR-swizzled
+  // by the row.
+  {
+    const float inv = 1.f / (l_run + __shfl_xor(l_run, 32));
+    unsigned char *slab = smem + STAGE + wave * (32 * HD * 2);
+    unsigned char *wrow = slab + l32 * (HD * 2);
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int jg = 0; jg < 4; ++jg) {
-        *(uint2 *)(op + db * 32 + 8 * jg + 4 * g) =
+      for (int jg = 0; jg < 4; ++jg)
+        *(uint2 *)(wrow + (((db * 4 + jg) ^ (l32 & (KCH - 1))) << 4) + 8 * g) =
             make_uint2(pack_bf16x2(o[db][4 * jg] * inv, o[db][4 * jg + 1] * inv), pack_bf16x2(o[db][4 * jg + 2] * inv, o[db][4 * jg + 3] * inv));
-      }
+    // a wave's LDS operations execute in order: the reads below see the writes above
+    const int c = lane % KCH, r0 = lane / KCH;
+    // row j*K_RPI + r0: its swizzle is r0 | (j*K_RPI mod KCH) (disjoint bits), so j enters as an XOR with a constant
+    const unsigned roff = r0 * (HD * 2) + ((c ^ r0) << 4);
+    bf16_t *op = p.out + ((int64_t)(qb.row0 + wave * 32 + r0) * q_dim + head * HD + c * 8);
+    const int rows_left = qb.n - (qb.q0 + wave * 32) - r0;   // row j*K_RPI + r0 exists iff j*K_RPI < rows_left
+#pragma unroll
+    for (int j = 0; j < 32 / K_RPI; ++j) {
+      const int jr = j * K_RPI;
+      const uint4 val = *(const uint4 *)(slab + ((roff + jr * (HD * 2)) ^ (unsigned)((jr & (KCH - 1)) << 4)));
+      if (jr < rows_left) *(uint4 *)(op + (int64_t)jr * q_dim) = val;
+    }
   }
   // every wave read s_item before the tile loop's barriers; the same barriers separate the last
   // tile's LDS reads from the next prologue's writes
