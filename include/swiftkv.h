@@ -234,9 +234,10 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
  * does once per model.  Needs M >= 1024 and N, K multiples of 256. */
 int swiftkv_op_gemm_packed(const void *A, const void *W, void *w_packed, void *C, int32_t M,
                            int32_t N, int32_t K, void *stream);
-/* The weight-streaming kernel (M <= 80 rows: decode steps, the last-token tail)
- * with K split over up to 4 workgroups per column tile when few column tiles
- * would leave compute units idle; the splits' fp32 partial sums go through
+/* The weight-streaming kernels (M <= 80 rows: decode steps, the last-token tail)
+ * with K split over up to 16 workgroups (slices of K whose activation rows a
+ * workgroup keeps in LDS, or splits that keep all compute units streaming when
+ * there are few column tiles); the splits' fp32 partial sums go through
  * `workspace` (dev, swiftkv_op_gemm_rows_workspace(M, N) bytes) and are added in
  * a fixed order. */
 int swiftkv_op_gemm_rows(const void *A, const void *W, void *C, int32_t M, int32_t N, int32_t K,
@@ -245,9 +246,9 @@ size_t swiftkv_op_gemm_rows_workspace(int32_t M, int32_t N);
 /* swiftkv_op_gemm_rows for callers that cannot allocate device memory or pass a
  * workspace (code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc): the K-split partial sums live in a static device array of
- * the library, 4 x 80 x 8192 fp32 = 10.5 MB per GPU, held until the process
+ * the library, 16 x 80 x 4096 fp32 = 21 MB per GPU, held until the process
  * ends.  Same kernels, same split, same summation order: results are bit-identical
- * to swiftkv_op_gemm_rows.  M <= 80 and N <= 8192, else SWIFTKV_EINVAL.  Calls no
+ * to swiftkv_op_gemm_rows.  M <= 80 and N <= 4096, else SWIFTKV_EINVAL.  Calls no
  * allocating routine.  All calls on one GPU share the array (nothing in it has
  * to start at zero: a call writes every partial sum before it reads it), so
  * calls that overlap on one GPU -- different streams, different threads --

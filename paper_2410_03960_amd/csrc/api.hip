@@ -978,15 +978,16 @@ int swiftkv_op_gemm_rows(const void *A, const void *W, void *C, int32_t M, int32
     return fail(SWIFTKV_EINVAL, "need 1 <= M <= 80, N %% 16 == 0, K %% 8 == 0");
   if (workspace_bytes < swiftkv_op_gemm_rows_workspace(M, N))
     return fail(SWIFTKV_ENOSPC, "workspace has %zu bytes, %zu needed", workspace_bytes, swiftkv_op_gemm_rows_workspace(M, N));
-  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, (float *)workspace, workspace_bytes};
+  // (the declared size, not whatever more the caller brought: how K is split depends on the capacity)
+  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, (float *)workspace, swiftkv_op_gemm_rows_workspace(M, N)};
   if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, (hipStream_t)stream)) return fail(SWIFTKV_EHIP, "skinny launch failed");
   return check_launch("weight-streaming gemm");
 }
 
 // ---- the same kernel for callers that cannot allocate: its scratch is a static device array ----
-// 4 splits x 80 rows x 8192 columns of fp32 partial sums.  Every GPU the library runs on holds its own
-// copy of this array at its own address until the process ends.
-constexpr int STATIC_ROWS_MAX_M = SKINNY_MAX_ROWS, STATIC_ROWS_MAX_N = 8192;
+// 16 splits x 80 rows x 4096 columns of fp32 partial sums (21 MB).  Every GPU the library runs on holds
+// its own copy of this array at its own address until the process ends.
+constexpr int STATIC_ROWS_MAX_M = SKINNY_MAX_ROWS, STATIC_ROWS_MAX_N = 4096;
 constexpr size_t STATIC_SCRATCH_FLOATS = (size_t)SKINNY_MAX_SPLIT * STATIC_ROWS_MAX_M * STATIC_ROWS_MAX_N;
 static __device__ __align__(256) float scratch[STATIC_SCRATCH_FLOATS];
 
@@ -1019,7 +1020,9 @@ int swiftkv_op_gemm_rows_static(const void *A, const void *W, void *C, int32_t M
                 "with a workspace for more)", M, N, STATIC_ROWS_MAX_M, STATIC_ROWS_MAX_N);
   float *sp = nullptr;
   if (int e = static_scratch(&sp)) return e;
-  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, sp, STATIC_SCRATCH_FLOATS * sizeof(float)};
+  // the same scratch capacity as the workspace form declares for this shape: the two then split K alike
+  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, sp, swiftkv_op_gemm_rows_workspace(M, N)};
+  static_assert(STATIC_SCRATCH_FLOATS * sizeof(float) >= (size_t)SKINNY_MAX_SPLIT * STATIC_ROWS_MAX_M * STATIC_ROWS_MAX_N * 4, "static scratch");
   if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, (hipStream_t)stream)) return fail(SWIFTKV_EHIP, "skinny launch failed");
   return check_launch("weight-streaming gemm (static scratch)");
 }

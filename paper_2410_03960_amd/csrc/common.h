@@ -126,8 +126,8 @@ struct SkinnyParams {
   float *partial;    // scratch for K-split partial sums, or null (then K is never split)
   size_t partial_bytes;   // its size; a split whose partial sums would not fit is not taken
 };
-constexpr int SKINNY_MAX_SPLIT = 4;
-constexpr size_t SKINNY_PARTIAL_BYTES = (size_t)SKINNY_MAX_SPLIT * 80 * 8192 * 4;   // the driver's scratch: 4 splits x 80 rows x 8192 columns fp32
+constexpr int SKINNY_MAX_SPLIT = 16;
+constexpr size_t SKINNY_PARTIAL_BYTES = (size_t)SKINNY_MAX_SPLIT * 80 * 8192 * 4;   // the driver's scratch: 16 splits x 80 rows x 8192 columns fp32 (42 MB)
 int launch_skinny(const SkinnyParams &p, int epi, hipStream_t st);
 
 // Few-row batches (decode steps): the Q, K, V projections come out of the weight-streaming kernel as

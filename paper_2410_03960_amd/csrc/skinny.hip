@@ -56,11 +56,13 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_kernel(SkinnyParams p) {
   const int per_split = (all_steps + (int)gridDim.y - 1) / (int)gridDim.y;
   const int s_begin = blockIdx.y * per_split;
   const int nsteps = (s_begin + per_split) < all_steps ? (s_begin + per_split) : all_steps;
-  for (int s0 = s_begin + wave; s0 < nsteps; s0 += SK_WAVES * UN) {
+  // (a wave takes UN consecutive steps: both 64-byte halves of a 128-byte line of a weight row are then
+  // requested by the same wave back to back; with the steps dealt out one by one, two waves fetched each line)
+  for (int s0 = s_begin + wave * UN; s0 < nsteps; s0 += SK_WAVES * UN) {
     uint4 wv[UN][NJ], av[UN][MB];
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      const int s = s0 + u * SK_WAVES;
+      const int s = s0 + u;
       const int k = s * 32;
       const bool ok = (s < nsteps) && (k + kq * 8 + 8 <= p.K);
 #pragma unroll
@@ -159,6 +161,205 @@ __global__ void skinny_reduce_kernel(SkinnyParams p, int ksplit) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// The same product with the activations resident in LDS (K % 512 == 0).
+// Measured on the kernel above: the activation fragments, which every wave
+// fetches from L2 for every k step, take as many vector-memory requests as the
+// weights and cost 20-30 % of the achieved HBM rate.  Here a workgroup owns one
+// K slice; its activation slice sits in LDS in MFMA operand order (filled by
+// LDS-DMA, one 1 KB fragment per request: lane (row l16, quarter kq) lands at
+// 16 * lane), the waves split the output columns (16-column blocks, `nbw` in a
+// row per wave) and stream their weight rows through registers two groups of
+// U k steps ahead, both steps of a 128-byte line in the same wave.  No
+// cross-wave reduction and no barrier after the fill.  K slices go to
+// blockIdx.y and meet in skinny_reduce_kernel in a fixed order.
+__device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+}
+
+template <int MB, int EPI, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void skinny_lds_kernel(SkinnyParams p, int ks_steps, int nbw) {
+  constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
+  constexpr int U = (NW == 1 && MB <= 2) ? 8 : 4;   // k steps (of 32) per group of loads
+  extern __shared__ __align__(16) unsigned char a_lds[];   // [k step][MB][64 lanes][16 bytes]
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, kq = lane >> 4;
+  const int all_steps = p.K / 32;
+  const int s_begin = blockIdx.y * ks_steps;
+  const int steps = (all_steps - s_begin) < ks_steps ? (all_steps - s_begin) : ks_steps;   // a multiple of 2U
+  const int k0 = s_begin * 32;
+  const int groups = steps / U;
+
+  const int nblocks = p.N / 16;
+  const int nb0 = (blockIdx.x * WAVES + wave) * nbw;
+  const int nb_end = (nb0 + nbw) < nblocks ? (nb0 + nbw) : nblocks;
+  const int total = nb0 < nblocks ? (nb_end - nb0) * groups : 0;   // groups of this wave, an even number
+
+  // weight rows of this lane: group g of column block nb covers k steps g * U ...; the groups of a wave's
+  // blocks are walked in order, (l_nb, l_g) being the next one to request
+  int l_nb = nb0, l_g = 0;
+  auto load_group = [&](uint4 (&dst)[NW][U]) {
+    const int64_t off = (int64_t)(l_nb * 16 + l16) * p.K + k0 + l_g * (U * 32) + kq * 8;
+    if (++l_g == groups) { l_g = 0; ++l_nb; }
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const bf16_t *src = (w ? p.W2 : p.W) + off;
+#pragma unroll
+      for (int u = 0; u < U; ++u) dst[w][u] = *(const uint4 *)(src + u * 32);
+    }
+  };
+  uint4 wa[NW][U], wb[NW][U];
+  if (total > 0) load_group(wa);   // on its way while the activations arrive
+
+  // activation slice -> LDS: fragment (k step s, row block mb) at (s * MB + mb) * 1024; rows past M repeat row M-1
+  {
+    typedef __attribute__((address_space(3))) void *lds_ptr_t;
+    const unsigned lds_base = (unsigned)(size_t)(lds_ptr_t)a_lds;
+    for (int f = wave; f < steps * MB; f += WAVES) {
+      const int s = f / MB, mb = f % MB;
+      int m = mb * 16 + l16;
+      m = m < p.M ? m : p.M - 1;
+      lds_dma16(p.A + ((int64_t)m * p.K + k0 + s * 32 + kq * 8), lds_base + f * 1024);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+  }
+  if (total == 0) return;
+
+  floatx4 acc[NW][MB];
+#pragma unroll
+  for (int w = 0; w < NW; ++w)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc[w][mb] = floatx4{0.f, 0.f, 0.f, 0.f};
+  auto compute_group = [&](const uint4 (&src)[NW][U], int g) {
+    const unsigned char *fr = a_lds + (size_t)(g * U) * (MB * 1024) + lane * 16;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      bf16x8 a[MB];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) a[mb] = *(const bf16x8 *)(fr + (u * MB + mb) * 1024);
+#pragma unroll
+      for (int w = 0; w < NW; ++w)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+          acc[w][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, src[w][u]), a[mb], acc[w][mb], 0, 0, 0);
+    }
+  };
+  // acc[w][mb][v] = C[m = mb*16 + l16][n = nb*16 + 4*kq + v] (weight w), over this K slice
+  auto flush = [&](int nb) {
+    const int n = nb * 16 + 4 * kq;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int m = mb * 16 + l16;
+      if (m < p.M) {
+        if (gridDim.y > 1) {   // partial[split][w][m][n]
+#pragma unroll
+          for (int w = 0; w < NW; ++w)
+            *(float4 *)(p.partial + (((int64_t)blockIdx.y * NW + w) * p.M + m) * p.N + n) =
+                make_float4(acc[w][mb][0], acc[w][mb][1], acc[w][mb][2], acc[w][mb][3]);
+        } else if constexpr (EPI == EPI_STORE_F32) {
+          *(float4 *)((float *)p.C + (int64_t)m * p.N + n) = make_float4(acc[0][mb][0], acc[0][mb][1], acc[0][mb][2], acc[0][mb][3]);
+        } else if constexpr (EPI == EPI_RESID) {
+          float4 *dst = (float4 *)((float *)p.C + (int64_t)m * p.N + n);
+          const float4 r = *dst;
+          *dst = make_float4(r.x + acc[0][mb][0], r.y + acc[0][mb][1], r.z + acc[0][mb][2], r.w + acc[0][mb][3]);
+        } else {
+          float o[4] = {acc[0][mb][0], acc[0][mb][1], acc[0][mb][2], acc[0][mb][3]};
+          if constexpr (EPI == EPI_SWIGLU) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o[v] = o[v] / (1.f + __expf(-o[v])) * acc[NW - 1][mb][v];
+          }
+          *(uint2 *)((bf16_t *)p.C + (int64_t)m * p.N + n) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+        }
+      }
+#pragma unroll
+      for (int w = 0; w < NW; ++w) acc[w][mb] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+  };
+  // two groups per iteration, one register set in flight while the other is consumed; `groups` is even, so
+  // a block ends after the second group of an iteration
+  int c_nb = nb0, c_g = 0;
+  for (int idx = 0; idx < total; idx += 2) {
+    load_group(wb);
+    compute_group(wa, c_g);
+    if (idx + 2 < total) load_group(wa);
+    compute_group(wb, c_g + 1);
+    c_g += 2;
+    if (c_g == groups) { flush(c_nb); ++c_nb; c_g = 0; }
+  }
+}
+
+struct LdsPlan {
+  bool ok;
+  int waves, ks_steps, ksplit, nbw;
+  size_t lds_bytes, partial_bytes;
+};
+// How the LDS-resident form would run this shape; ok = false: it cannot, or the kernel above does better
+// (few column blocks: its workgroups split K among their waves and need no second pass).  Measured on
+// the 8B shapes with 8 and 64 rows: slices of 2048 (up to 16 rows) / 1024 columns of K, two column
+// blocks in a row per wave, 16 waves per workgroup when the slice leaves room for one workgroup per CU.
+LdsPlan plan_lds(int M, int N, int K, int nw, size_t partial_cap) {
+  LdsPlan pl{};
+  if (M < 1 || M > 80 || (N % 16) != 0 || (K % 512) != 0) return pl;
+  const int MB = (M + 15) / 16;
+  const int U = (nw == 1 && MB <= 2) ? 8 : 4;
+  const int all_steps = K / 32, nblocks = N / 16;
+  const int steps_cap = MB == 1 ? 64 : MB <= 4 ? 32 : 24;          // 64 KB, 64-128 KB, 120 KB of LDS
+  int ksplit = (all_steps + steps_cap - 1) / steps_cap;
+  const int ks_steps = ((all_steps + ksplit - 1) / ksplit + 2 * U - 1) / (2 * U) * (2 * U);
+  ksplit = (all_steps + ks_steps - 1) / ks_steps;
+  pl.ks_steps = ks_steps; pl.ksplit = ksplit;
+  const int64_t tasks = (int64_t)nblocks * ksplit * nw;             // (16 weight rows, K slice) streams; a wave takes nw * nbw of them
+  if (tasks < 1536) return pl;                                      // too few streams: the kernel above keeps more CUs busy
+  pl.nbw = tasks >= 3072 ? 2 : 1;
+  pl.waves = (MB >= 3 && nw == 1 && tasks >= 4096) ? 16 : 8;       // (two weight streams per wave need more than 128 registers)
+  pl.lds_bytes = (size_t)ks_steps * MB * 1024;
+  pl.partial_bytes = ksplit > 1 ? (size_t)ksplit * nw * M * N * 4 : 0;
+  pl.ok = pl.partial_bytes <= partial_cap && pl.lds_bytes <= 160 * 1024;
+  return pl;
+}
+
+template <int MB, int EPI, int WAVES>
+int launch_lds_w(const SkinnyParams &p, const LdsPlan &pl, hipStream_t st) {
+  auto kern = skinny_lds_kernel<MB, EPI, WAVES>;
+  static size_t attr = 0;
+  if (pl.lds_bytes > attr) {
+    if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes) != hipSuccess) return -1;
+    attr = pl.lds_bytes;
+  }
+  const int nblocks = p.N / 16;
+  dim3 grid((nblocks + WAVES * pl.nbw - 1) / (WAVES * pl.nbw), pl.ksplit);
+  hipLaunchKernelGGL(kern, grid, dim3(WAVES * 64), pl.lds_bytes, st, p, pl.ks_steps, pl.nbw);
+  if (pl.ksplit > 1) {
+    const int64_t quads = (int64_t)p.M * p.N / 4;
+    hipLaunchKernelGGL((skinny_reduce_kernel<EPI>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, p, pl.ksplit);
+  }
+  return 0;
+}
+template <int MB, int EPI>
+int launch_lds_e(const SkinnyParams &p, const LdsPlan &pl, hipStream_t st) {
+  return pl.waves == 16 ? launch_lds_w<MB, EPI, 16>(p, pl, st) : launch_lds_w<MB, EPI, 8>(p, pl, st);
+}
+template <int MB>
+int launch_lds_m(const SkinnyParams &p, int epi, const LdsPlan &pl, hipStream_t st) {
+  switch (epi) {
+    case EPI_STORE_BF16: return launch_lds_e<MB, EPI_STORE_BF16>(p, pl, st);
+    case EPI_STORE_F32: return launch_lds_e<MB, EPI_STORE_F32>(p, pl, st);
+    case EPI_RESID: return launch_lds_e<MB, EPI_RESID>(p, pl, st);
+    case EPI_SWIGLU: return launch_lds_e<MB, EPI_SWIGLU>(p, pl, st);
+  }
+  return -1;
+}
+int launch_lds(const SkinnyParams &p, int epi, const LdsPlan &pl, hipStream_t st) {
+  switch ((p.M + 15) / 16) {
+    case 1: return launch_lds_m<1>(p, epi, pl, st);
+    case 2: return launch_lds_m<2>(p, epi, pl, st);
+    case 3: return launch_lds_m<3>(p, epi, pl, st);
+    case 4: return launch_lds_m<4>(p, epi, pl, st);
+    default: return launch_lds_m<5>(p, epi, pl, st);
+  }
+}
+
 template <int MB, int NB, int EPI>
 int launch_kernels(const SkinnyParams &p, hipStream_t st) {
   constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
@@ -206,6 +407,10 @@ int launch_wide(const SkinnyParams &p, int epi, hipStream_t st) {
 int launch_skinny(const SkinnyParams &p, int epi, hipStream_t st) {
   if (p.M <= 0 || p.N <= 0) return 0;
   if (p.M > 80 || (p.N % 16) != 0 || (p.K % 8) != 0) return -1;
+  {
+    const LdsPlan pl = plan_lds(p.M, p.N, p.K, epi == EPI_SWIGLU ? 2 : 1, p.partial ? p.partial_bytes : 0);
+    if (pl.ok) return launch_lds(p, epi, pl, st);
+  }
   if (p.M <= 16) return launch_mb<1, 1>(p, epi, st);
   if (p.M <= 32) return (p.N % 32 == 0) ? launch_mb<2, 2>(p, epi, st) : launch_mb<2, 1>(p, epi, st);
   if (p.M <= 48) return launch_wide<3>(p, epi, st);
