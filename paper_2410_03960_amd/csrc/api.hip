@@ -409,7 +409,7 @@ int run_fused_kv(Run &r, const bf16_t *hidden, bool rstd_ready, Timer &tm) {
 int tail_gemm(const swiftkv_ctx *c, const bf16_t *A, int M, int N, int K, const bf16_t *W, const bf16_t *W2,
               const bf16_t *const *gu_tab, void *C, int epi, float *partial, hipStream_t st) {
   if (M <= 80) {
-    SkinnyParams s{A, M, N, K, W, W2, C, partial, SKINNY_PARTIAL_BYTES};
+    SkinnyParams s{A, M, N, K, W, W2, C, partial, SKINNY_PARTIAL_BYTES, nullptr};
     return launch_skinny(s, epi, st);
   }
   GemmParams g{};
@@ -721,14 +721,15 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     if (few_rows) {
       // decode steps and other few-token batches: weights stream once through the skinny kernel (fp32 out),
       // then rotation, rounding and the FP8 absmax in one small pass
-      float *q32 = r.at<float>(r.L.qkv32), *k32 = q32 + (int64_t)T * qd, *v32 = k32 + (int64_t)T * kvd;
+      // one launch for [W_Q; W_K; W_V] (through the layer's row-block table): rows of q_dim + 2 kv_dim fp32 columns
+      float *q32 = r.at<float>(r.L.qkv32), *k32 = q32 + qd, *v32 = k32 + kvd;
       tm.begin(TC_QKV);
-      if (tail_gemm(c, ab, T, qd, d, c->wq[j], nullptr, nullptr, q32, EPI_STORE_F32, skp, st) ||
-          tail_gemm(c, ab, T, kvd, d, c->wk[j], nullptr, nullptr, k32, EPI_STORE_F32, skp, st) ||
-          tail_gemm(c, ab, T, kvd, d, c->wv[j], nullptr, nullptr, v32, EPI_STORE_F32, skp, st))
-        return fail(SWIFTKV_EHIP, "QKV GEMM launch failed");
+      {
+        SkinnyParams sp{ab, T, qd + 2 * kvd, d, nullptr, nullptr, q32, skp, SKINNY_PARTIAL_BYTES, c->qkv_tab[j]};
+        if (launch_skinny(sp, EPI_STORE_F32, st)) return fail(SWIFTKV_EHIP, "QKV GEMM launch failed");
+      }
       QkvFinishParams fp{};
-      fp.q32 = q32; fp.k32 = k32; fp.v32 = v32; fp.q = qb; fp.k = kb; fp.v = vb;
+      fp.q32 = q32; fp.k32 = k32; fp.v32 = v32; fp.ld32 = qd + 2 * kvd; fp.q = qb; fp.k = kb; fp.v = vb;
       fp.T = T; fp.n_q_heads = m.n_q_heads; fp.n_kv_heads = m.n_kv_heads; fp.head_dim = m.head_dim;
       fp.cos_sin = r.at<float2>(r.L.cos_sin);
       fp.amax = compute_scale ? r.at<uint32_t>(r.L.amax) + (int64_t)j * 2 * m.n_kv_heads : nullptr;
@@ -946,7 +947,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
   hipStream_t st = (hipStream_t)stream;
   if (variant == 3) {
     if (M > SKINNY_MAX_ROWS) return fail(SWIFTKV_EINVAL, "weight-streaming kernel handles M <= 80");
-    SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, nullptr, 0};
+    SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, nullptr, 0, nullptr};
     if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, st)) return fail(SWIFTKV_EHIP, "skinny launch failed");
     return check_launch("skinny gemm");
   }
@@ -981,7 +982,7 @@ int swiftkv_op_gemm_rows(const void *A, const void *W, void *C, int32_t M, int32
   if (workspace_bytes < swiftkv_op_gemm_rows_workspace(M, N))
     return fail(SWIFTKV_ENOSPC, "workspace has %zu bytes, %zu needed", workspace_bytes, swiftkv_op_gemm_rows_workspace(M, N));
   // (the declared size, not whatever more the caller brought: how K is split depends on the capacity)
-  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, (float *)workspace, swiftkv_op_gemm_rows_workspace(M, N)};
+  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, (float *)workspace, swiftkv_op_gemm_rows_workspace(M, N), nullptr};
   if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, (hipStream_t)stream)) return fail(SWIFTKV_EHIP, "skinny launch failed");
   return check_launch("weight-streaming gemm");
 }
@@ -1023,7 +1024,7 @@ int swiftkv_op_gemm_rows_static(const void *A, const void *W, void *C, int32_t M
   float *sp = nullptr;
   if (int e = static_scratch(&sp)) return e;
   // the same scratch capacity as the workspace form declares for this shape: the two then split K alike
-  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, sp, swiftkv_op_gemm_rows_workspace(M, N)};
+  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, sp, swiftkv_op_gemm_rows_workspace(M, N), nullptr};
   static_assert(STATIC_SCRATCH_FLOATS * sizeof(float) >= (size_t)SKINNY_MAX_SPLIT * STATIC_ROWS_MAX_M * STATIC_ROWS_MAX_N * 4, "static scratch");
   if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, (hipStream_t)stream)) return fail(SWIFTKV_EHIP, "skinny launch failed");
   return check_launch("weight-streaming gemm (static scratch)");

@@ -125,6 +125,8 @@ struct SkinnyParams {
   void *C;           // bf16 [M,N] (STORE_BF16, SWIGLU) or fp32 (STORE_F32; RESID adds in place)
   float *partial;    // scratch for K-split partial sums, or null (then K is never split)
   size_t partial_bytes;   // its size; a split whose partial sums would not fit is not taken
+  const bf16_t *const *wtab;   // instead of W: device table of N/16 pointers, entry i = rows 16i .. 16i+15 (row stride K),
+                               // e.g. [W_Q; W_K; W_V] of a layer as one matrix
 };
 constexpr int SKINNY_MAX_SPLIT = 16;
 constexpr size_t SKINNY_PARTIAL_BYTES = (size_t)SKINNY_MAX_SPLIT * 80 * 8192 * 4;   // the driver's scratch: 16 splits x 80 rows x 8192 columns fp32 (42 MB)
@@ -134,7 +136,8 @@ int launch_skinny(const SkinnyParams &p, int epi, hipStream_t st);
 // fp32; this step rotates q and k (rotate-half, angles of the row's position), rounds to bf16 once and,
 // for an FP8 cache with computed scales, collects the absmax of the stored K and V values per KV head.
 struct QkvFinishParams {
-  const float *q32, *k32, *v32;   // [T, q_dim], [T, kv_dim], [T, kv_dim]
+  const float *q32, *k32, *v32;   // rows of q_dim / kv_dim / kv_dim columns, row stride ld32 elements (0: dense)
+  int32_t ld32;
   bf16_t *q, *k, *v;
   int32_t T, n_q_heads, n_kv_heads, head_dim;
   const float2 *cos_sin;          // [T][hd/2]

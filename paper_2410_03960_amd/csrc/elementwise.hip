@@ -135,7 +135,9 @@ __global__ void rmsnorm_rows_kernel(const float4 *h, const bf16_t *gain, uint2 *
   const float f = rstd_out ? 1.f : rs;
   for (int c = lane; c < chunks; c += 64) out[(int64_t)row * chunks + c] = norm4(r[c], f, gain, c);
 }
-// Single-pass variant: the row (d = 256 * CH elements) stays in registers between the reduction and the scaling.
+// Single-pass variant: the row (d = 256 * CH elements) stays in registers between the reduction and the
+// scaling; the gains are requested together with the row (asked for only after the reduction they were a
+// second memory latency, which is most of the time of the few-row launches of decode steps and the tail).
 template <int CH>
 __global__ void rmsnorm_rows_reg_kernel(const float4 *h, const bf16_t *gain, uint2 *out, int rows, float eps, float inv_d, float *rstd_out) {
   const int row = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
@@ -143,18 +145,22 @@ __global__ void rmsnorm_rows_reg_kernel(const float4 *h, const bf16_t *gain, uin
   if (row >= rows) return;
   const float4 *r = h + (int64_t)row * (CH * 64);
   float4 u[CH];
+  uint2 g[CH];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) u[i] = r[i * 64 + lane];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) g[i] = gain ? *(const uint2 *)(gain + 4 * (i * 64 + lane)) : make_uint2(0x3f803f80u, 0x3f803f80u);   // bf16 ones
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < CH; ++i) {
-    u[i] = r[i * 64 + lane];
-    s += u[i].x * u[i].x; s += u[i].y * u[i].y; s += u[i].z * u[i].z; s += u[i].w * u[i].w;
-  }
+  for (int i = 0; i < CH; ++i) { s += u[i].x * u[i].x; s += u[i].y * u[i].y; s += u[i].z * u[i].z; s += u[i].w * u[i].w; }
   s = wave_sum(s);
   const float rs = rsqrtf(s * inv_d + eps);
   if (rstd_out && lane == 0) rstd_out[row] = rs;
   const float f = rstd_out ? 1.f : rs;
 #pragma unroll
-  for (int i = 0; i < CH; ++i) out[(int64_t)row * (CH * 64) + i * 64 + lane] = norm4(u[i], f, gain, i * 64 + lane);
+  for (int i = 0; i < CH; ++i)
+    out[(int64_t)row * (CH * 64) + i * 64 + lane] =
+        make_uint2(pack_bf16x2(u[i].x * f * bf16lo(g[i].x), u[i].y * f * bf16hi(g[i].x)), pack_bf16x2(u[i].z * f * bf16lo(g[i].y), u[i].w * f * bf16hi(g[i].y)));
 }
 int launch_rmsnorm_rows(const float *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, float *rstd_out, hipStream_t st) {
   if (rows <= 0) return 0;
@@ -410,7 +416,7 @@ __global__ void qkv_finish_kernel(QkvFinishParams p) {
   const int kind = hs < p.n_q_heads ? 0 : (hs < p.n_q_heads + p.n_kv_heads ? 1 : 2);
   const int head = kind == 0 ? hs : (kind == 1 ? hs - p.n_q_heads : hs - p.n_q_heads - p.n_kv_heads);
   const int64_t dim = (int64_t)(kind == 0 ? p.n_q_heads : p.n_kv_heads) * hd;
-  const float *src = (kind == 0 ? p.q32 : kind == 1 ? p.k32 : p.v32) + row * dim + head * hd;
+  const float *src = (kind == 0 ? p.q32 : kind == 1 ? p.k32 : p.v32) + row * (p.ld32 ? (int64_t)p.ld32 : dim) + head * hd;
   bf16_t *dst = (kind == 0 ? p.q : kind == 1 ? p.k : p.v) + row * dim + head * hd;
   float x0 = src[i], x1 = src[i + half];
   if (kind != 2) {

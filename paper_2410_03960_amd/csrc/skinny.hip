@@ -34,7 +34,7 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_kernel(SkinnyParams p) {
   const bf16_t *wrow[NJ];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    wrow[nb] = p.W + (int64_t)(n0 + nb * 16 + l16) * p.K + kq * 8;
+    wrow[nb] = (p.wtab ? p.wtab[n0 / 16 + nb] + (int64_t)l16 * p.K : p.W + (int64_t)(n0 + nb * 16 + l16) * p.K) + kq * 8;
     if constexpr (EPI == EPI_SWIGLU) wrow[NB + nb] = p.W2 + (int64_t)(n0 + nb * 16 + l16) * p.K + kq * 8;
   }
   const bf16_t *arow[MB];
@@ -199,11 +199,12 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_lds_kernel(SkinnyParams p, 
   // blocks are walked in order, (l_nb, l_g) being the next one to request
   int l_nb = nb0, l_g = 0;
   auto load_group = [&](uint4 (&dst)[NW][U]) {
-    const int64_t off = (int64_t)(l_nb * 16 + l16) * p.K + k0 + l_g * (U * 32) + kq * 8;
+    const int64_t koff = k0 + l_g * (U * 32) + kq * 8, off = (int64_t)(l_nb * 16 + l16) * p.K + koff;
+    const bf16_t *tsrc = p.wtab ? p.wtab[l_nb] + ((int64_t)l16 * p.K + koff) : nullptr;   // (one weight, never SwiGLU)
     if (++l_g == groups) { l_g = 0; ++l_nb; }
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
-      const bf16_t *src = (w ? p.W2 : p.W) + off;
+      const bf16_t *src = tsrc ? tsrc : (w ? p.W2 : p.W) + off;
 #pragma unroll
       for (int u = 0; u < U; ++u) dst[w][u] = *(const uint4 *)(src + u * 32);
     }
