@@ -406,10 +406,12 @@ int run_fused_kv(Run &r, const bf16_t *hidden, bool rstd_ready, Timer &tm) {
   return 0;
 }
 
+// n_splits_out (host, may be null): see SkinnyParams -- the consumer of C adds the K splits
 int tail_gemm(const swiftkv_ctx *c, const bf16_t *A, int M, int N, int K, const bf16_t *W, const bf16_t *W2,
-              const bf16_t *const *gu_tab, void *C, int epi, float *partial, hipStream_t st) {
+              const bf16_t *const *gu_tab, void *C, int epi, float *partial, hipStream_t st, int32_t *n_splits_out = nullptr) {
+  if (n_splits_out) *n_splits_out = 1;
   if (M <= 80) {
-    SkinnyParams s{A, M, N, K, W, W2, C, partial, SKINNY_PARTIAL_BYTES, nullptr};
+    SkinnyParams s{A, M, N, K, W, W2, C, partial, SKINNY_PARTIAL_BYTES, nullptr, n_splits_out};
     return launch_skinny(s, epi, st);
   }
   GemmParams g{};
@@ -712,10 +714,14 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     launch_rmsnorm_rows(h, c->norm1[0], ab, T, d, m.rms_eps, rstd, st);
     tm.end();
   }
+  // Few-row batches: a residual GEMM that split K leaves the sum of its splits to the RMSNorm pass that
+  // reads the residual rows next (h_pend = number of splits waiting in skp; 1 = none).
+  int32_t h_pend = 1;
   for (int j = 0; j < c->l; ++j) {
     if (!packed) {
       tm.begin(TC_NORM);
-      launch_rmsnorm_rows(h, c->norm1[j], ab, T, d, m.rms_eps, nullptr, st);
+      launch_rmsnorm_rows(h, c->norm1[j], ab, T, d, m.rms_eps, nullptr, st, skp, h_pend);
+      h_pend = 1;
       tm.end();
     }
     if (few_rows) {
@@ -723,13 +729,17 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
       // then rotation, rounding and the FP8 absmax in one small pass
       // one launch for [W_Q; W_K; W_V] (through the layer's row-block table): rows of q_dim + 2 kv_dim fp32 columns
       float *q32 = r.at<float>(r.L.qkv32), *k32 = q32 + qd, *v32 = k32 + kvd;
+      int32_t fp_splits = 1;
       tm.begin(TC_QKV);
       {
-        SkinnyParams sp{ab, T, qd + 2 * kvd, d, nullptr, nullptr, q32, skp, SKINNY_PARTIAL_BYTES, c->qkv_tab[j]};
+        int32_t ns = 1;   // K splits left to the finishing pass (it reads the fp32 values anyway)
+        SkinnyParams sp{ab, T, qd + 2 * kvd, d, nullptr, nullptr, q32, skp, SKINNY_PARTIAL_BYTES, c->qkv_tab[j], &ns};
         if (launch_skinny(sp, EPI_STORE_F32, st)) return fail(SWIFTKV_EHIP, "QKV GEMM launch failed");
+        if (ns > 1) { q32 = skp; k32 = q32 + qd; v32 = k32 + kvd; }
+        fp_splits = ns;
       }
       QkvFinishParams fp{};
-      fp.q32 = q32; fp.k32 = k32; fp.v32 = v32; fp.ld32 = qd + 2 * kvd; fp.q = qb; fp.k = kb; fp.v = vb;
+      fp.q32 = q32; fp.k32 = k32; fp.v32 = v32; fp.ld32 = qd + 2 * kvd; fp.n_splits = fp_splits; fp.q = qb; fp.k = kb; fp.v = vb;
       fp.T = T; fp.n_q_heads = m.n_q_heads; fp.n_kv_heads = m.n_kv_heads; fp.head_dim = m.head_dim;
       fp.cos_sin = r.at<float2>(r.L.cos_sin);
       fp.amax = compute_scale ? r.at<uint32_t>(r.L.amax) + (int64_t)j * 2 * m.n_kv_heads : nullptr;
@@ -808,7 +818,7 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     }
     if (few_rows) {
       tm.begin(TC_O);
-      if (tail_gemm(c, ob, T, d, qd, c->wo[j], nullptr, nullptr, h, EPI_RESID, skp, st)) return fail(SWIFTKV_EHIP, "O GEMM launch failed");
+      if (tail_gemm(c, ob, T, d, qd, c->wo[j], nullptr, nullptr, h, EPI_RESID, skp, st, &h_pend)) return fail(SWIFTKV_EHIP, "O GEMM launch failed");
       tm.end();
     } else {
       GemmParams g{};
@@ -820,14 +830,16 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     }
     tm.begin(TC_NORM);
     if (packed) launch_rstd_from_ssq(ssq, n_ssq, rstd, T, d, m.rms_eps, st);
-    else launch_rmsnorm_rows(h, c->norm2[j], ab, T, d, m.rms_eps, nullptr, st);
+    else { launch_rmsnorm_rows(h, c->norm2[j], ab, T, d, m.rms_eps, nullptr, st, skp, h_pend); h_pend = 1; }
     tm.end();
     if (few_rows) {
       tm.begin(TC_GATEUP);
       if (tail_gemm(c, ab, T, m.ffn, d, c->wgate[j], c->wup[j], c->gu_tab[j], zb, EPI_SWIGLU, skp, st)) return fail(SWIFTKV_EHIP, "gate/up GEMM launch failed");
       tm.end();
       tm.begin(TC_DOWN);
-      if (tail_gemm(c, zb, T, d, m.ffn, c->wdown[j], nullptr, nullptr, h, EPI_RESID, skp, st)) return fail(SWIFTKV_EHIP, "down GEMM launch failed");
+      // (the next reader of h is a norm pass: the next layer's, or the one in front of the later layers' K/V projection)
+      if (tail_gemm(c, zb, T, d, m.ffn, c->wdown[j], nullptr, nullptr, h, EPI_RESID, skp, st, (j + 1 < c->l || c->P > 0) ? &h_pend : nullptr))
+        return fail(SWIFTKV_EHIP, "down GEMM launch failed");
       tm.end();
     } else {
       {
@@ -863,7 +875,8 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   if (c->P > 0) {
     if (!packed) {
       tm.begin(TC_NORM);
-      launch_rmsnorm_rows(h, nullptr, ab, T, d, m.rms_eps, rstd, st);
+      launch_rmsnorm_rows(h, nullptr, ab, T, d, m.rms_eps, rstd, st, skp, h_pend);
+      h_pend = 1;
       tm.end();
     }
     if (int e = run_fused_kv(r, ab, true, tm)) return e;
@@ -882,9 +895,10 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
   } else {
     launch_fill_u32(r.at<uint32_t>(r.L.ee_flags), 0, B, st);
   }
+  int32_t t_pend = 1;   // K splits of the last residual GEMM waiting for the next norm pass over th
   for (int j = c->l; j < m.n_layers; ++j) {
     const int cl = c->l + (j - c->l) / c->g;
-    launch_rmsnorm_rows(th, c->norm1[j], ta, B, d, m.rms_eps, nullptr, st);
+    launch_rmsnorm_rows(th, c->norm1[j], ta, B, d, m.rms_eps, nullptr, st, skp, t_pend);
     if (tail_gemm(c, ta, B, qd, d, c->wq[j], nullptr, nullptr, tq, EPI_STORE_BF16, skp, st)) return fail(SWIFTKV_EHIP, "tail q GEMM failed");
     AttnDecodeParams dp{};
     dp.q = tq; dp.out = to; dp.rows = (const DecodeRow *)r.meta(r.L.m_tail); dp.n_rows = B;
@@ -896,12 +910,12 @@ int swiftkv_prefill(swiftkv_ctx *c, const int32_t *token_ids, const int32_t *seq
     dp.n_split = pick_split(B, m.n_kv_heads, r.hp.max_keys_tail);
     if (launch_attention_decode(dp, st) != 0) return fail(SWIFTKV_EHIP, "tail attention launch failed");
     launch_decode_combine(dp.partial, to, dp.rows, B, m.n_q_heads, m.head_dim, dp.n_split, st);
-    if (tail_gemm(c, to, B, d, qd, c->wo[j], nullptr, nullptr, th, EPI_RESID, skp, st)) return fail(SWIFTKV_EHIP, "tail o GEMM failed");
-    launch_rmsnorm_rows(th, c->norm2[j], ta, B, d, m.rms_eps, nullptr, st);
+    if (tail_gemm(c, to, B, d, qd, c->wo[j], nullptr, nullptr, th, EPI_RESID, skp, st, &t_pend)) return fail(SWIFTKV_EHIP, "tail o GEMM failed");
+    launch_rmsnorm_rows(th, c->norm2[j], ta, B, d, m.rms_eps, nullptr, st, skp, t_pend);
     if (tail_gemm(c, ta, B, m.ffn, d, c->wgate[j], c->wup[j], c->gu_tab[j], tz, EPI_SWIGLU, skp, st)) return fail(SWIFTKV_EHIP, "tail MLP GEMM failed");
-    if (tail_gemm(c, tz, B, d, m.ffn, c->wdown[j], nullptr, nullptr, th, EPI_RESID, skp, st)) return fail(SWIFTKV_EHIP, "tail down GEMM failed");
+    if (tail_gemm(c, tz, B, d, m.ffn, c->wdown[j], nullptr, nullptr, th, EPI_RESID, skp, st, &t_pend)) return fail(SWIFTKV_EHIP, "tail down GEMM failed");
   }
-  launch_rmsnorm_rows(th, c->final_norm, ta, B, d, m.rms_eps, nullptr, st);
+  launch_rmsnorm_rows(th, c->final_norm, ta, B, d, m.rms_eps, nullptr, st, skp, t_pend);
   if (tail_gemm(c, ta, B, m.vocab, d, c->lm_head, nullptr, nullptr, logits_out, EPI_STORE_F32, skp, st)) return fail(SWIFTKV_EHIP, "LM head GEMM failed");
   if (c->ee_head) launch_early_exit_select(r.at<float>(r.L.ee_logits), r.at<int32_t>(r.L.ee_flags), logits_out, B, m.vocab, st);
   tm.end();
@@ -947,7 +961,7 @@ int swiftkv_op_gemm(const void *A, const void *W, void *C, int32_t M, int32_t N,
   hipStream_t st = (hipStream_t)stream;
   if (variant == 3) {
     if (M > SKINNY_MAX_ROWS) return fail(SWIFTKV_EINVAL, "weight-streaming kernel handles M <= 80");
-    SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, nullptr, 0, nullptr};
+    SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, nullptr, 0, nullptr, nullptr};
     if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, st)) return fail(SWIFTKV_EHIP, "skinny launch failed");
     return check_launch("skinny gemm");
   }
@@ -982,7 +996,7 @@ int swiftkv_op_gemm_rows(const void *A, const void *W, void *C, int32_t M, int32
   if (workspace_bytes < swiftkv_op_gemm_rows_workspace(M, N))
     return fail(SWIFTKV_ENOSPC, "workspace has %zu bytes, %zu needed", workspace_bytes, swiftkv_op_gemm_rows_workspace(M, N));
   // (the declared size, not whatever more the caller brought: how K is split depends on the capacity)
-  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, (float *)workspace, swiftkv_op_gemm_rows_workspace(M, N), nullptr};
+  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, (float *)workspace, swiftkv_op_gemm_rows_workspace(M, N), nullptr, nullptr};
   if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, (hipStream_t)stream)) return fail(SWIFTKV_EHIP, "skinny launch failed");
   return check_launch("weight-streaming gemm");
 }
@@ -1024,7 +1038,7 @@ int swiftkv_op_gemm_rows_static(const void *A, const void *W, void *C, int32_t M
   float *sp = nullptr;
   if (int e = static_scratch(&sp)) return e;
   // the same scratch capacity as the workspace form declares for this shape: the two then split K alike
-  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, sp, swiftkv_op_gemm_rows_workspace(M, N), nullptr};
+  SkinnyParams s{(const bf16_t *)A, M, N, K, (const bf16_t *)W, nullptr, C, sp, swiftkv_op_gemm_rows_workspace(M, N), nullptr, nullptr};
   static_assert(STATIC_SCRATCH_FLOATS * sizeof(float) >= (size_t)SKINNY_MAX_SPLIT * STATIC_ROWS_MAX_M * STATIC_ROWS_MAX_N * 4, "static scratch");
   if (launch_skinny(s, out_f32 ? EPI_STORE_F32 : EPI_STORE_BF16, (hipStream_t)stream)) return fail(SWIFTKV_EHIP, "skinny launch failed");
   return check_launch("weight-streaming gemm (static scratch)");

@@ -127,6 +127,9 @@ struct SkinnyParams {
   size_t partial_bytes;   // its size; a split whose partial sums would not fit is not taken
   const bf16_t *const *wtab;   // instead of W: device table of N/16 pointers, entry i = rows 16i .. 16i+15 (row stride K),
                                // e.g. [W_Q; W_K; W_V] of a layer as one matrix
+  int32_t *n_splits_out;       // HOST, or null.  Given (STORE_F32 / RESID only), a launch that splits K leaves the sum to its
+                               // consumer: it writes the number of splits here, the splits' sums stay in `partial` as
+                               // [split][M][N] fp32 and C is untouched; 1 = nothing left to do (C is final)
 };
 constexpr int SKINNY_MAX_SPLIT = 16;
 constexpr size_t SKINNY_PARTIAL_BYTES = (size_t)SKINNY_MAX_SPLIT * 80 * 8192 * 4;   // the driver's scratch: 16 splits x 80 rows x 8192 columns fp32 (42 MB)
@@ -138,6 +141,7 @@ int launch_skinny(const SkinnyParams &p, int epi, hipStream_t st);
 struct QkvFinishParams {
   const float *q32, *k32, *v32;   // rows of q_dim / kv_dim / kv_dim columns, row stride ld32 elements (0: dense)
   int32_t ld32;
+  int32_t n_splits;               // > 1: the inputs are that many partial sums, T * ld32 elements apart, to be added in order
   bf16_t *q, *k, *v;
   int32_t T, n_q_heads, n_kv_heads, head_dim;
   const float2 *cos_sin;          // [T][hd/2]
@@ -217,7 +221,10 @@ int launch_rstd_from_ssq(const float *ssq, int32_t n_blocks, float *rstd, int32_
 // RMSNorm of fp32 rows into a bf16 GEMM operand.  rstd_out == null: out = bf16(h * rstd * gain).  Otherwise
 // the row factor is left to the consumer's epilogue: out = bf16(h * gain) and rstd_out[row] = rstd.
 // gain == null stands for a gain of one.
-int launch_rmsnorm_rows(const float *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, float *rstd_out, hipStream_t st);
+// With n_splits > 1 the rows first take the K-split sums a weight-streaming GEMM left behind: h[row] +=
+// partial[0][row] + partial[1][row] + ... (partial: [n_splits][rows][d] fp32), written back to h.
+int launch_rmsnorm_rows(float *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, float *rstd_out, hipStream_t st,
+                        const float *partial = nullptr, int32_t n_splits = 1);
 int launch_gather_rows(const float *h, const int32_t *rows, float *out, int32_t n_rows, int32_t d, hipStream_t st);
 int launch_f32_to_bf16(const float *x, bf16_t *out, int64_t n, hipStream_t st);
 int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t st);

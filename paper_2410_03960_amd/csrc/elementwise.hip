@@ -162,10 +162,101 @@ __global__ void rmsnorm_rows_reg_kernel(const float4 *h, const bf16_t *gain, uin
     out[(int64_t)row * (CH * 64) + i * 64 + lane] =
         make_uint2(pack_bf16x2(u[i].x * f * bf16lo(g[i].x), u[i].y * f * bf16hi(g[i].x)), pack_bf16x2(u[i].z * f * bf16lo(g[i].y), u[i].w * f * bf16hi(g[i].y)));
 }
-int launch_rmsnorm_rows(const float *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, float *rstd_out, hipStream_t st) {
+// Few rows (decode steps, the tail): one workgroup of four waves per row, d = 1024 * CQ.  With n_splits > 1
+// the row first takes the sums of the K splits a weight-streaming GEMM left in `partial` ([n_splits][rows][d]
+// fp32): the splits are added in order, then to the row, which is written back.  The sum of squares is added
+// over a lane's values in order, then over the wave, then over the four waves in order.
+template <int CQ>
+__global__ __launch_bounds__(256) void rmsnorm_row_wg_kernel(float4 *h, const bf16_t *gain, uint2 *out, int rows, float eps, float inv_d,
+                                                             float *rstd_out, const float4 *partial, int n_splits) {
+  __shared__ float red[4];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  float4 *r = h + (int64_t)row * (CQ * 256);
+  float4 u[CQ];
+  uint2 g[CQ];
+#pragma unroll
+  for (int i = 0; i < CQ; ++i) u[i] = r[i * 256 + tid];
+#pragma unroll
+  for (int i = 0; i < CQ; ++i) g[i] = gain ? *(const uint2 *)(gain + 4 * (i * 256 + tid)) : make_uint2(0x3f803f80u, 0x3f803f80u);
+  if (n_splits > 1) {
+    float4 sum[CQ];
+#pragma unroll
+    for (int i = 0; i < CQ; ++i) sum[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float4 *pr = partial + (int64_t)row * (CQ * 256) + tid;
+    const int64_t step = (int64_t)rows * (CQ * 256);
+    int ks = 0;
+    for (; ks + 2 <= n_splits; ks += 2) {   // two splits' loads in flight, added in split order
+      float4 v0[CQ], v1[CQ];
+#pragma unroll
+      for (int i = 0; i < CQ; ++i) { v0[i] = pr[ks * step + i * 256]; v1[i] = pr[(ks + 1) * step + i * 256]; }
+#pragma unroll
+      for (int i = 0; i < CQ; ++i) {
+        sum[i].x += v0[i].x; sum[i].y += v0[i].y; sum[i].z += v0[i].z; sum[i].w += v0[i].w;
+        sum[i].x += v1[i].x; sum[i].y += v1[i].y; sum[i].z += v1[i].z; sum[i].w += v1[i].w;
+      }
+    }
+    if (ks < n_splits) {
+#pragma unroll
+      for (int i = 0; i < CQ; ++i) {
+        const float4 v = pr[ks * step + i * 256];
+        sum[i].x += v.x; sum[i].y += v.y; sum[i].z += v.z; sum[i].w += v.w;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < CQ; ++i) {
+      u[i].x += sum[i].x; u[i].y += sum[i].y; u[i].z += sum[i].z; u[i].w += sum[i].w;
+      r[i * 256 + tid] = u[i];
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < CQ; ++i) { s += u[i].x * u[i].x; s += u[i].y * u[i].y; s += u[i].z * u[i].z; s += u[i].w * u[i].w; }
+  s = wave_sum(s);
+  if ((tid & 63) == 0) red[tid >> 6] = s;
+  __syncthreads();
+  s = ((red[0] + red[1]) + red[2]) + red[3];
+  const float rs = rsqrtf(s * inv_d + eps);
+  if (rstd_out && tid == 0) rstd_out[row] = rs;
+  const float f = rstd_out ? 1.f : rs;
+#pragma unroll
+  for (int i = 0; i < CQ; ++i)
+    out[(int64_t)row * (CQ * 256) + i * 256 + tid] =
+        make_uint2(pack_bf16x2(u[i].x * f * bf16lo(g[i].x), u[i].y * f * bf16hi(g[i].x)), pack_bf16x2(u[i].z * f * bf16lo(g[i].y), u[i].w * f * bf16hi(g[i].y)));
+}
+// the K-split sums of a weight-streaming GEMM added into fp32 rows (for row widths the kernel above does not cover)
+__global__ void add_splits_kernel(float4 *h, const float4 *partial, int64_t n4, int n_splits) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int ks = 0; ks < n_splits; ++ks) {
+    const float4 v = partial[(int64_t)ks * n4 + i];
+    sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+  }
+  float4 u = h[i];
+  u.x += sum.x; u.y += sum.y; u.z += sum.z; u.w += sum.w;
+  h[i] = u;
+}
+int launch_rmsnorm_rows(float *h, const bf16_t *gain, bf16_t *out, int32_t rows, int32_t d, float eps, float *rstd_out, hipStream_t st,
+                        const float *partial, int32_t n_splits) {
   if (rows <= 0) return 0;
   const dim3 grid((rows + 3) / 4), block(256);
   const float inv_d = 1.0f / (float)d;
+  if (rows <= 256 && d % 1024 == 0 && d / 1024 <= 8) {   // few rows: a workgroup per row, K splits added on the way
+#define SKV_RMS_WG(CQ_)                                                                                            \
+  case CQ_:                                                                                                        \
+    hipLaunchKernelGGL(rmsnorm_row_wg_kernel<CQ_>, dim3(rows), block, 0, st, (float4 *)h, gain, (uint2 *)out, rows, eps, inv_d, rstd_out, \
+                       (const float4 *)partial, n_splits);                                                        \
+    return 0;
+    switch (d / 1024) {
+      SKV_RMS_WG(1) SKV_RMS_WG(2) SKV_RMS_WG(3) SKV_RMS_WG(4) SKV_RMS_WG(5) SKV_RMS_WG(6) SKV_RMS_WG(7) SKV_RMS_WG(8)
+      default: break;
+    }
+#undef SKV_RMS_WG
+  }
+  if (n_splits > 1) {   // otherwise: the splits in a pass of their own
+    const int64_t n4 = (int64_t)rows * d / 4;
+    hipLaunchKernelGGL(add_splits_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, (float4 *)h, (const float4 *)partial, n4, n_splits);
+  }
 #define SKV_RMS_CASE(CH_)                                                                                          \
   case CH_:                                                                                                        \
     hipLaunchKernelGGL(rmsnorm_rows_reg_kernel<CH_>, grid, block, 0, st, (const float4 *)h, gain, (uint2 *)out, rows, eps, inv_d, rstd_out); \
@@ -419,6 +510,10 @@ __global__ void qkv_finish_kernel(QkvFinishParams p) {
   const float *src = (kind == 0 ? p.q32 : kind == 1 ? p.k32 : p.v32) + row * (p.ld32 ? (int64_t)p.ld32 : dim) + head * hd;
   bf16_t *dst = (kind == 0 ? p.q : kind == 1 ? p.k : p.v) + row * dim + head * hd;
   float x0 = src[i], x1 = src[i + half];
+  if (p.n_splits > 1) {   // the K splits of the projection, added in split order
+    const int64_t step = (int64_t)p.T * p.ld32;
+    for (int ks = 1; ks < p.n_splits; ++ks) { x0 += src[ks * step + i]; x1 += src[ks * step + i + half]; }
+  }
   if (kind != 2) {
     const float2 cs = p.cos_sin[(int64_t)row * half + i];
     const float y0 = x0 * cs.x - x1 * cs.y, y1 = x1 * cs.x + x0 * cs.y;

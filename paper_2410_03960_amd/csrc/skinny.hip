@@ -331,7 +331,8 @@ int launch_lds_w(const SkinnyParams &p, const LdsPlan &pl, hipStream_t st) {
   const int nblocks = p.N / 16;
   dim3 grid((nblocks + WAVES * pl.nbw - 1) / (WAVES * pl.nbw), pl.ksplit);
   hipLaunchKernelGGL(kern, grid, dim3(WAVES * 64), pl.lds_bytes, st, p, pl.ks_steps, pl.nbw);
-  if (pl.ksplit > 1) {
+  if (pl.ksplit > 1 && p.n_splits_out) *p.n_splits_out = pl.ksplit;   // the consumer adds the splits
+  else if (pl.ksplit > 1) {
     const int64_t quads = (int64_t)p.M * p.N / 4;
     hipLaunchKernelGGL((skinny_reduce_kernel<EPI>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, p, pl.ksplit);
   }
@@ -374,7 +375,8 @@ int launch_kernels(const SkinnyParams &p, hipStream_t st) {
   }
   dim3 grid(tiles, ksplit), block(SK_WAVES * 64);
   hipLaunchKernelGGL((skinny_kernel<MB, NB, EPI>), grid, block, 0, st, p);
-  if (ksplit > 1) {
+  if (ksplit > 1 && p.n_splits_out) *p.n_splits_out = ksplit;   // the consumer adds the splits
+  else if (ksplit > 1) {
     const int64_t quads = (int64_t)p.M * p.N / 4;
     hipLaunchKernelGGL((skinny_reduce_kernel<EPI>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, p, ksplit);
   }
@@ -408,6 +410,10 @@ int launch_wide(const SkinnyParams &p, int epi, hipStream_t st) {
 int launch_skinny(const SkinnyParams &p, int epi, hipStream_t st) {
   if (p.M <= 0 || p.N <= 0) return 0;
   if (p.M > 80 || (p.N % 16) != 0 || (p.K % 8) != 0) return -1;
+  if (p.n_splits_out) {
+    if (epi != EPI_STORE_F32 && epi != EPI_RESID) return -1;
+    *p.n_splits_out = 1;
+  }
   {
     const LdsPlan pl = plan_lds(p.M, p.N, p.K, epi == EPI_SWIGLU ? 2 : 1, p.partial ? p.partial_bytes : 0);
     if (pl.ok) return launch_lds(p, epi, pl, st);
