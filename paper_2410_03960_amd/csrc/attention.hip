@@ -200,7 +200,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)   // the two accumulators alternate, so consecutive MFMAs are independent
           s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ds % 2][kb], qf[ds], s[kb], 0, 0, 0);
-        if (ds % (DS / K_IT) == DS / K_IT - 1) issue_one(ds / (DS / K_IT), tn, sn);
+        static_assert(K_IT + V_IT == DS, "one request of the next tile per d step");
+        issue_one(ds, tn, sn);   // all of the next tile is requested in this phase: the K rows first, then the V^T rows
         __builtin_amdgcn_sched_barrier(0);
       }
       __builtin_amdgcn_s_setprio(0);
@@ -216,11 +217,13 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
 #pragma unroll
           for (int v = 0; v < 16; ++v) s[kb][v] = (kb * 32 + 16 * (v >> 3) + (v & 7) > lim) ? -INFINITY : s[kb][v];
       }
-      float mx = -INFINITY;
+      // (four independent chains: a lone wave issues dependent vector instructions well below full rate)
+      float mx4[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mx = __builtin_fmaxf(mx, s[kb][v]);
+        for (int v = 0; v < 16; ++v) mx4[(kb * 16 + v) / 8] = __builtin_fmaxf(mx4[(kb * 16 + v) / 8], s[kb][v]);
+      float mx = __builtin_fmaxf(__builtin_fmaxf(mx4[0], mx4[1]), __builtin_fmaxf(mx4[2], mx4[3]));
       mx = cross_half_max(mx);   // (a shuffle through LDS would also wait for the V^T fragments just requested)
       // Lazy rescaling: the reference maximum m_run (raw score units) only moves when some query's
       // tile maximum exceeds it by more than 8/sc, i.e. when an exponential would exceed 2^8.  The
@@ -237,14 +240,14 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
           for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
       }
       const float msc = m_run * sc;
-      float rs = 0.f;
+      float rs4[4] = {0.f, 0.f, 0.f, 0.f};   // row sum in four independent chains (by PV step), added up in a fixed order
       // exponentials of PV step st (keys 16*st + 8*g .. +7), two at a time, straight into the bf16 operand
       bf16x8 pf[2];
       auto exp_pair = [&](int st, int j) {
 #pragma unroll
         for (int e = 2 * j; e < 2 * j + 2; ++e) {
           const float x = __builtin_amdgcn_exp2f(__builtin_fmaf(s[st >> 1][(st & 1) * 8 + e], sc, -msc));   // exp2 of (-inf) is 0
-          rs += x;
+          rs4[st] += x;
           pf[st & 1][e] = (__bf16)x;
         }
       };
@@ -267,10 +270,9 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
           }
           __builtin_amdgcn_sched_barrier(0);
         }
-        if (st % (4 / V_IT) == 4 / V_IT - 1) issue_one(K_IT + st / (4 / V_IT), tn, sn);
         __builtin_amdgcn_sched_barrier(0);
       }
-      l_run += rs;
+      l_run += (rs4[0] + rs4[1]) + (rs4[2] + rs4[3]);
       __builtin_amdgcn_s_setprio(0);
       asm volatile("" ::: "memory");
     }
