@@ -310,10 +310,10 @@ LdsPlan plan_lds(int M, int N, int K, int nw, size_t partial_cap) {
   const int ks_steps = ((all_steps + ksplit - 1) / ksplit + 2 * U - 1) / (2 * U) * (2 * U);
   ksplit = (all_steps + ks_steps - 1) / ks_steps;
   pl.ks_steps = ks_steps; pl.ksplit = ksplit;
-  const int64_t tasks = (int64_t)nblocks * ksplit * nw;             // (16 weight rows, K slice) streams; a wave takes nw * nbw of them
-  if (tasks < 1536) return pl;                                      // too few streams: the kernel above keeps more CUs busy
-  pl.nbw = tasks >= 3072 ? 2 : 1;
-  pl.waves = (MB >= 3 && nw == 1 && tasks >= 4096) ? 16 : 8;       // (two weight streams per wave need more than 128 registers)
+  const int64_t streams = (int64_t)nblocks * ksplit;                // (column block, K slice) pairs; a wave takes nbw of them in a row
+  if (streams < 1024) return pl;                                    // too few: the kernel above keeps more CUs busy
+  pl.nbw = streams >= 3200 ? 2 : 1;
+  pl.waves = (MB >= 3 && nw == 1 && streams >= 4096) ? 16 : 8;      // (two weight streams per wave need more than 128 registers)
   pl.lds_bytes = (size_t)ks_steps * MB * 1024;
   pl.partial_bytes = ksplit > 1 ? (size_t)ksplit * nw * M * N * 4 : 0;
   pl.ok = pl.partial_bytes <= partial_cap && pl.lds_bytes <= 160 * 1024;
