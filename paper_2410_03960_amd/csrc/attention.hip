@@ -518,6 +518,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
 // The 32 keys of a step sit in the contraction slots in the order the score instruction leaves them:
 // slot (g, j) of lane group g holds key 4g + j for j < 4 and key 16 + 4g + (j - 4) for j >= 4.
 typedef long fp8x8_t;   // eight e4m3 codes
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ int pack4_fp8(float a, float b, float c, float d) {
   int w = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
   return __builtin_amdgcn_cvt_pk_fp8_f32(c, d, w, true);
@@ -619,7 +620,7 @@ __global__ __launch_bounds__(256) void attn_decode_fp8_kernel(AttnDecodeParams p
   // this lane's part of the step that starts at key `base` (a multiple of 32): K bytes of key base + 16 kb + l16,
   // 16-byte pieces of the V tile; keys at or past k_hi read the last visible key's data (masked below)
   uint2 kreg[2][NM];
-  uint4 vreg[V_IT];
+  u32x4_t vreg[V_IT];   // (a native vector type: as an array of HIP's uint4 structs, written inside the lambda below, it stayed in scratch memory)
   int blk_of[2];          // physical blocks of the two 16-key halves (wave-uniform)
   auto load_step = [&](int base) __attribute__((always_inline)) {
 #pragma unroll
@@ -637,12 +638,13 @@ __global__ __launch_bounds__(256) void attn_decode_fp8_kernel(AttnDecodeParams p
     }
 #pragma unroll
     for (int i = 0; i < V_IT; ++i) {
-      const int c = i * 64 + lane, kl = c / VCH, ch = c % VCH;   // local key, 16-byte chunk
-      int key = base + kl;
-      key = key < k_hi ? key : k_hi - 1;
-      int blk = (kl >> 4) ? blk_of[1] : blk_of[0];
-      if ((base + kl) >= k_hi) { blk = bt[key >> 4]; blk = ((unsigned)blk < (unsigned)p.n_blocks) ? blk : 0; }
-      vreg[i] = *(const uint4 *)(cv + ((int64_t)blk * SKV_BLOCK + (key & 15)) * tok_stride + ch * 16);
+      const int c = i * 64 + lane, ch = c % VCH;   // local key c / VCH, 16-byte chunk
+      // (a key past the end reads the last visible key, which lies in one of the step's two blocks: no second
+      // table lookup, and no branch -- with one, the compiler kept this array in scratch memory and waited
+      // for every load before issuing the next)
+      const int kl = (c / VCH) < (k_hi - 1 - base) ? (c / VCH) : (k_hi - 1 - base);
+      const int blk = (kl >> 4) ? blk_of[1] : blk_of[0];
+      vreg[i] = *(const u32x4_t *)(cv + ((int64_t)blk * SKV_BLOCK + ((base + kl) & 15)) * tok_stride + ch * 16);
     }
   };
 
@@ -660,7 +662,7 @@ __global__ __launch_bounds__(256) void attn_decode_fp8_kernel(AttnDecodeParams p
 #pragma unroll
     for (int i = 0; i < V_IT; ++i) {
       const int c = i * 64 + lane;
-      *(uint4 *)(vt + (c / VCH) * VS + (c % VCH) * 16) = vreg[i];
+      *(u32x4_t *)(vt + (c / VCH) * VS + (c % VCH) * 16) = vreg[i];
     }
     fp8x8_t kf[2][NM];
 #pragma unroll
@@ -781,6 +783,204 @@ __global__ __launch_bounds__(256) void attn_decode_fp8_kernel(AttnDecodeParams p
   }
 }
 
+// ------------------------------------------------ decode, bf16 cache, MFMA ----
+// The same scheme for a bf16 cache: the vector-unit kernel above spends about 30 vector instructions per key and
+// query head (bf16 -> fp32 conversions, the dot products' fma and cross-lane sums); here the dot products are
+// matrix instructions (v_mfma_f32_16x16x32_bf16) and the vector unit only does the softmax of the R x 32
+// scores of a step, whatever R is.  Used for eight query heads per KV head.  grid (n_rows, n_kv_heads, n_split), 4 waves, 32 keys per
+// wave and step.
+//  * S^T[key][r]: first operand = K rows straight from the cache (a lane reads 64 contiguous bytes of one key,
+//    the four lanes of a key its whole 256-byte row; score instruction m takes the lane's m-th 16 bytes, the
+//    query operand is laid out to match), second operand = the R query heads in columns 0..R-1 of 16.
+//  * O^T[d][r] += V^T[d][key] P^T[key][r]: the V tile is staged row-major in LDS (row stride hd*2 + 32 bytes)
+//    and read with the transposing LDS read for 16-bit data (ds_read_b64_tr_b16: lanes 4r..4r+3 of a 16-lane
+//    group address the four 8-byte quarters of row r of a 4 x 16 matrix, lane i receives column i), two reads
+//    per fragment.  The 32 keys of a step sit in the contraction slots in the order the score instruction
+//    leaves them (slot (g, j): key 4g + j for j < 4, key 16 + 4g + j - 4 otherwise), so the softmax weights go
+//    from score registers to operand registers in place.
+template <int HD, int R>
+__global__ __launch_bounds__(256) void attn_decode_mfma_kernel(AttnDecodeParams p) {
+  constexpr int NM = HD / 32;          // score instructions per 16-key block
+  constexpr int NDB = HD / 16;         // 16-dim blocks of the output
+  constexpr int VS = HD * 2 + 32;      // LDS row stride of the V tile in bytes (rows 8 banks apart)
+  constexpr int VCH = HD / 8;          // 16-byte chunks per K / V row
+  constexpr int V_IT = 32 * VCH / 64;  // 16-byte loads per lane for a 32-key V tile
+  __shared__ __align__(16) unsigned char v_lds[4][32 * VS];
+  __shared__ __align__(16) bf16_t qs[16][HD];
+  __shared__ float sm[4][R][HD + 2];
+
+  const DecodeRow row = p.rows[blockIdx.x];
+  const int kvh = blockIdx.y, split = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, kq = lane >> 4;
+  const int q_dim = p.n_q_heads * HD;
+
+  // keys of this split: whole 128-key steps, at least 256 keys per split
+  int per = (row.n_keys + p.n_split - 1) / p.n_split;
+  per = per < 256 ? 256 : per;
+  per = (per + 127) / 128 * 128;
+  const int k_lo = split * per;
+  const int k_hi = (k_lo + per) < row.n_keys ? (k_lo + per) : row.n_keys;
+
+  // ---- the R query heads as bf16 rows 0..R-1 of a 16-row operand (the rest zero); tail rows are rotated here ----
+  for (int idx = tid; idx < 16 * (HD / 2); idx += 256) {
+    const int r = idx / (HD / 2), i = idx % (HD / 2);
+    bf16_t b1 = 0, b2 = 0;
+    if (r < R) {
+      const bf16_t *qp = p.q + (int64_t)row.q_row * q_dim + (kvh * R + r) * HD;
+      b1 = qp[i]; b2 = qp[i + HD / 2];
+      if (row.cs_row >= 0) {
+        const float x1 = bf16_to_f32(b1), x2 = bf16_to_f32(b2);
+        const float2 c = p.cos_sin[(int64_t)row.cs_row * (HD / 2) + i];
+        b1 = f32_to_bf16(x1 * c.x - x2 * c.y); b2 = f32_to_bf16(x2 * c.x + x1 * c.y);   // q is held in bf16 like the prefill path's
+      }
+    }
+    qs[r][i] = b1; qs[r][i + HD / 2] = b2;
+  }
+  __syncthreads();
+  bf16x8 qf[NM];   // second operand of score instruction m: q[r = l16][d = 32 kq + 8 m .. +7]
+#pragma unroll
+  for (int m = 0; m < NM; ++m) qf[m] = *(const bf16x8 *)&qs[l16][kq * (HD / 4) + 8 * m];
+  const float sc = 1.4426950408889634f * rsqrtf((float)HD);
+
+  const int32_t *bt = p.block_tables + (int64_t)row.seq * p.max_blocks_per_seq;
+  const int64_t tok_stride = (int64_t)p.n_kv_heads * HD * 2;   // bytes between tokens of a block
+  const unsigned char *ck = (const unsigned char *)p.cache_k + (int64_t)kvh * HD * 2, *cv = (const unsigned char *)p.cache_v + (int64_t)kvh * HD * 2;
+
+  floatx4 o[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;   // of column r = l16 (the four lanes of a column agree on m_run)
+
+  // this lane's part of the step that starts at key `base` (a multiple of 32): 64 bytes of key base + 16 kb + l16,
+  // 16-byte pieces of the V tile; keys at or past k_hi read the last visible key's data (masked below)
+  u32x4_t kreg[2][NM];
+  u32x4_t vreg[V_IT];   // (a native vector type: as an array of HIP's uint4 structs, written inside the lambda below, it stayed in scratch memory)
+  auto load_step = [&](int base) __attribute__((always_inline)) {
+    int blk_of[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      int key0 = base + 16 * kb;
+      key0 = key0 < k_hi ? key0 : ((k_hi - 1) & ~15);
+      int blk = bt[key0 >> 4];
+      blk = ((unsigned)blk < (unsigned)p.n_blocks) ? blk : 0;   // bad ids are flagged by the plan kernel; never dereference them
+      blk_of[kb] = blk;
+      int key = key0 + l16;
+      key = key < k_hi ? key : k_hi - 1;
+      const unsigned char *src = ck + ((int64_t)blk * SKV_BLOCK + (key & 15)) * tok_stride + kq * (HD / 2);
+#pragma unroll
+      for (int m = 0; m < NM; ++m) kreg[kb][m] = *(const u32x4_t *)(src + 16 * m);
+    }
+#pragma unroll
+    for (int i = 0; i < V_IT; ++i) {
+      const int c = i * 64 + lane, ch = c % VCH;   // local key c / VCH, 16-byte chunk
+      // (a key past the end reads the last visible key, which lies in one of the step's two blocks: no second
+      // table lookup, and no branch -- with one, the compiler kept this array in scratch memory and waited
+      // for every load before issuing the next)
+      const int kl = (c / VCH) < (k_hi - 1 - base) ? (c / VCH) : (k_hi - 1 - base);
+      const int blk = (kl >> 4) ? blk_of[1] : blk_of[0];
+      vreg[i] = *(const u32x4_t *)(cv + ((int64_t)blk * SKV_BLOCK + ((base + kl) & 15)) * tok_stride + ch * 16);
+    }
+  };
+
+  unsigned char *vt = v_lds[wave];
+  // transposing reads of lane group kq: lanes 4r..4r+3 address the 32 bytes (dims 16 db .. +15) of key 4 kq + r
+  // (first read) and of key 16 + 4 kq + r (second read)
+  const unsigned char *vt_lane = vt + (4 * kq + (l16 >> 2)) * VS + (l16 & 3) * 8;
+  typedef short v4s_t __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) v4s_t *lds_v4s_ptr;
+
+  if (k_lo + wave * 32 < k_hi) load_step(k_lo + wave * 32);
+  for (int base = k_lo + wave * 32; base < k_hi; base += 128) {
+    // V tile of this step into the wave's LDS tile (only this wave touches it; a wave's LDS operations run in order)
+#pragma unroll
+    for (int i = 0; i < V_IT; ++i) {
+      const int c = i * 64 + lane;
+      *(u32x4_t *)(vt + (c / VCH) * VS + (c % VCH) * 16) = vreg[i];
+    }
+    bf16x8 kf[2][NM];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int m = 0; m < NM; ++m) kf[kb][m] = __builtin_bit_cast(bf16x8, kreg[kb][m]);
+    load_step(base + 128 < k_hi ? base + 128 : base);   // next step's bytes are in flight during this step's arithmetic (the last step re-reads itself)
+    asm volatile("" ::: "memory");
+
+    // scores of keys base + 16 kb + 4 kq + i against head l16
+    floatx4 s4[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      s4[kb] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int m = 0; m < NM; ++m) s4[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][m], qf[m], s4[kb], 0, 0, 0);
+    }
+    float sv[8], mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int key = base + 16 * (e >> 2) + 4 * kq + (e & 3);
+      sv[e] = key < k_hi ? s4[e >> 2][e & 3] * sc : -INFINITY;
+      mx = fmaxf(mx, sv[e]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    // lazy rescaling: the reference only moves when a score exceeds it by more than 8 (log2 units)
+    if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.0f) != 0) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);   // exp2(-inf) = 0 the first time
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[db][i] *= alpha;
+    }
+    bf16x8 pb;   // the weights as second operand: contraction slot (kq, e)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float w = (sv[e] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sv[e] - m_run);
+      l_run += w;
+      pb[e] = (__bf16)w;
+    }
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      const v4s_t t0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(vt_lane + db * 32));
+      const v4s_t t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(vt_lane + 16 * VS + db * 32));
+      typedef short v8s_t __attribute__((ext_vector_type(8)));
+      const v8s_t t = {t0[0], t0[1], t0[2], t0[3], t1[0], t1[1], t1[2], t1[3]};
+      o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t), pb, o[db], 0, 0, 0);
+    }
+    asm volatile("" ::: "memory");
+  }
+
+  // ---- this wave's (o, m, l) of head l16: o[db][i] = O[d = 16 db + 4 kq + i]; then the four waves, as one split ----
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  if (l16 < R) {
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sm[wave][l16][db * 16 + 4 * kq + i] = o[db][i];
+    if (kq == 0) { sm[wave][l16][HD] = m_run; sm[wave][l16][HD + 1] = l_run; }
+  }
+  __syncthreads();
+  for (int i = tid; i < R * HD; i += 256) {
+    const int r = i / HD, d = i % HD;
+    const float mm = fmaxf(fmaxf(sm[0][r][HD], sm[1][r][HD]), fmaxf(sm[2][r][HD], sm[3][r][HD]));
+    float x = 0.f, ll = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float mw = sm[w][r][HD];
+      const float a = (mw == -INFINITY) ? 0.f : exp2f(mw - mm);
+      x += a * sm[w][r][d];
+      ll += a * sm[w][r][HD + 1];
+    }
+    float *dst = p.partial + (((int64_t)blockIdx.x * p.n_q_heads + kvh * R + r) * p.n_split + split) * (HD + 2);
+    dst[d] = x;
+    if (d == 0) { dst[HD] = mm; dst[HD + 1] = ll; }
+  }
+}
+
 }  // namespace
 
 int launch_attention_prefill(const AttnPrefillParams &p, hipStream_t st) {
@@ -822,11 +1022,16 @@ static int launch_decode_hd(const AttnDecodeParams &p, hipStream_t st) {
     }
     return 0;
   }
+  // eight query heads per KV head: the matrix-unit form (its cost does not grow with the number of heads; measured on
+  // 64 rows x 2048 keys 175 against 254 us per call; with four heads the vector-unit form is 7 % ahead)
+  if (R == 8) {
+    hipLaunchKernelGGL((attn_decode_mfma_kernel<HD, 8>), grid, dim3(256), 0, st, p);
+    return 0;
+  }
   switch (R) {
     case 1: hipLaunchKernelGGL((attn_decode_kernel<HD, 1>), grid, dim3(256), 0, st, p); break;
     case 2: hipLaunchKernelGGL((attn_decode_kernel<HD, 2>), grid, dim3(256), 0, st, p); break;
     case 4: hipLaunchKernelGGL((attn_decode_kernel<HD, 4>), grid, dim3(256), 0, st, p); break;
-    case 8: hipLaunchKernelGGL((attn_decode_kernel<HD, 8>), grid, dim3(256), 0, st, p); break;
     default: return -1;
   }
   return 0;
