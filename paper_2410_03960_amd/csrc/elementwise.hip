@@ -139,7 +139,7 @@ __global__ void rmsnorm_rows_kernel(const float4 *h, const bf16_t *gain, uint2 *
 // scaling; the gains are requested together with the row (asked for only after the reduction they were a
 // second memory latency, which is most of the time of the few-row launches of decode steps and the tail).
 template <int CH>
-__global__ void rmsnorm_rows_reg_kernel(const float4 *h, const bf16_t *gain, uint2 *out, int rows, float eps, float inv_d, float *rstd_out) {
+__global__ __launch_bounds__(256) void rmsnorm_rows_reg_kernel(const float4 *h, const bf16_t *gain, uint2 *out, int rows, float eps, float inv_d, float *rstd_out) {
   const int row = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
   const int lane = threadIdx.x & 63;
   if (row >= rows) return;

@@ -340,7 +340,10 @@ int launch_lds_w(const SkinnyParams &p, const LdsPlan &pl, hipStream_t st) {
 }
 template <int MB, int EPI>
 int launch_lds_e(const SkinnyParams &p, const LdsPlan &pl, hipStream_t st) {
-  return pl.waves == 16 ? launch_lds_w<MB, EPI, 16>(p, pl, st) : launch_lds_w<MB, EPI, 8>(p, pl, st);
+  if constexpr (EPI != EPI_SWIGLU) {   // (two weight streams per wave need more than the 128 registers of a 16-wave workgroup)
+    if (pl.waves == 16) return launch_lds_w<MB, EPI, 16>(p, pl, st);
+  }
+  return launch_lds_w<MB, EPI, 8>(p, pl, st);
 }
 template <int MB>
 int launch_lds_m(const SkinnyParams &p, int epi, const LdsPlan &pl, hipStream_t st) {
