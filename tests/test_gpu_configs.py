@@ -73,10 +73,10 @@ def _host_weight_fn(store):
     return f
 
 
-def _bars(stated, floor):
+def _bars(stated, floor, slack=SLACK):
     """(rel bar, cos bar) for one tensor from the stated bar and the measured floor."""
-    rel_bar = max(stated[0], SLACK * floor[0])
-    cos_bar = min(stated[1], 1.0 - SLACK * (1.0 - floor[1]))
+    rel_bar = max(stated[0], slack * floor[0])
+    cos_bar = min(stated[1], 1.0 - slack * (1.0 - floor[1]))
     return rel_bar, cos_bar
 
 
@@ -86,10 +86,10 @@ class _Report:
     def __init__(self, label):
         self.label, self.rows = label, []
 
-    def add(self, name, got, want, floor_t, stated):
+    def add(self, name, got, want, floor_t, stated, slack=SLACK):
         err = (rel_err(got, want), cosine(got, want))
         floor = (rel_err(floor_t, want), cosine(floor_t, want))
-        self.rows.append((name, err, floor, _bars(stated, floor), stated))
+        self.rows.append((name, err, floor, _bars(stated, floor, slack), stated))
 
     def finish(self):
         bad = [r for r in self.rows if r[1][0] > r[3][0] or r[1][1] < r[3][1]]
@@ -446,5 +446,63 @@ def test_chunk_workload_8b_2048_new_over_6144_cached():
     lg, small, ws = G.run_gpu(ctx, sub, cache=small)
     G.check_plan(ctx, ws, sub)
     rep.add("logits", lg[0].cpu(), ref_l, flo_l, (G.BF16_REL, G.BF16_COS))
+    rep.finish()
+    assert rep.min_cos >= G.BF16_COS
+
+
+def test_decode_step_workload_8b_64_sequences_over_2048_cached():
+    """The decode-step workload bench.py offers (64 sequences, 2048 tokens cached, one new token
+    each) at full size: with at most 80 tokens every projection runs on the weight-streaming
+    kernels (64 rows: the form with the activation slice in LDS, K slices added up by the norm
+    and QKV-finish passes), the new tokens attend through the paged cache.  The cached rows are
+    seeded bf16 values in all cache layers; the oracle gets the cached rows of 16 of the
+    sequences and their new tokens as one batch; logits and the rows the call stores are
+    compared."""
+    from paper_2410_03960_amd import binding as B
+    wl, store, ctx = _gpu_setup("8b_l16_dec64_ctx2048")
+    wfn = _host_weight_fn(store)
+    sh = wl.shape
+    batch = WL.build_batch(wl)
+    nctx = wl.decode_ctx
+    assert batch.n_seqs == 64 and batch.n_tokens == 64 and ctx.n_cache_layers == 32
+    cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, sh.n_kv_heads, sh.head_dim, batch.block_tables,
+                      batch.context_lens.tolist())
+    cache.data.normal_(0.0, 0.5, generator=torch.Generator(device="cuda").manual_seed(wl.seed))
+    ar = torch.arange(nctx)
+    picked = list(range(0, 64, 4))          # 16 of the 64 sequences, in one oracle call
+    slots_of = {b: batch.block_tables[b].long()[ar // 16] * 16 + ar % 16 for b in picked}
+    prefixes = {b: cache.data[:, :, slots_of[b].cuda()].float().cpu() for b in picked}   # [C, 2, nctx, Hkv, hd], before the call
+    logits, cache, ws = G.run_gpu(ctx, batch, cache=cache)
+    G.check_plan(ctx, ws, batch)
+    assert torch.isfinite(logits).all()
+    for b in picked:
+        assert torch.equal(cache.data[:, :, slots_of[b].cuda()].float().cpu(), prefixes[b]), "cached rows must stay untouched"
+    # the oracle, plain and with rounded matrix inputs, on the picked sequences as one batch over its own block pool
+    nb = (nctx + 1 + 15) // 16
+    bt = torch.arange(len(picked) * nb, dtype=torch.int32).view(len(picked), nb)
+    toks = batch.token_ids[torch.tensor(picked)].clone()
+    runs = []
+    for hook in (None, MFMA_INPUTS):
+        t0 = time.time()
+        oc = O.PagedKVCache(wl.n_cache_layers, len(picked) * nb, sh.n_kv_heads, sh.head_dim, bt, dtype=torch.float32)
+        for i, b in enumerate(picked):
+            oc.data[:, :, i * nb * 16: i * nb * 16 + nctx] = prefixes[b]
+        lg, _ = O.swiftkv_prefill(oracle_shape(sh), wfn, toks, [1] * len(picked), [nctx] * len(picked), wl.l, wl.g, oc,
+                                  dtype=torch.float32, act_round=hook)
+        new_rows = torch.stack([oc.data[:, :, i * nb * 16 + nctx] for i in range(len(picked))], 2)   # [C, 2, picked, Hkv, hd]
+        runs.append((lg, new_rows))
+        del oc
+        _say(f"    oracle ({'rounded matrix inputs' if hook else 'plain'}) on {len(picked)} decode tokens: {time.time() - t0:.1f}s")
+    (ref_l, ref_rows), (flo_l, flo_rows) = runs
+    rep = _Report("decode step")
+    rep.add("logits", logits[torch.tensor(picked)].cpu(), ref_l, flo_l, (G.BF16_REL, G.BF16_COS))
+    new_slots = torch.tensor([int(batch.block_tables[b, nctx // 16]) * 16 + nctx % 16 for b in picked])
+    # The 16 new rows of a cache layer are a small sample for a ratio of maxima (16 K values against the millions of
+    # the prompt tests), and the later layers' rows carry one rounding the floor does not emulate (the gains folded
+    # into the operand of Eq. 2): their max-error bar is the stated one or 1.5 x the floor; the cosine stays stated.
+    for c in range(wl.n_cache_layers):
+        for kvsel in (0, 1):
+            rep.add(f"new rows cache layer {c} {'KV'[kvsel]}", G.gpu_cache_logical(cache, c, kvsel, new_slots).cpu(),
+                    ref_rows[c, kvsel], flo_rows[c, kvsel], (G.BF16_REL, G.BF16_COS), slack=1.5)
     rep.finish()
     assert rep.min_cos >= G.BF16_COS
