@@ -306,9 +306,14 @@ int swiftkv_flops(const swiftkv_ctx *ctx, const int32_t *seq_lens, const int32_t
                   int32_t n_seqs, double *gemm_flops, double *attn_flops);
 
 /* Per-kernel-class device time of all swiftkv_prefill calls on this ctx since
- * timing was last switched on with swiftkv_set_timing(ctx, 1) (which also
- * clears the totals): HIP events are recorded on each call's stream around
- * every launch (no passage: a measurement aid).  Classes:
+ * swiftkv_set_timing last selected classes (which also clears the totals):
+ * HIP events are recorded on each call's stream around every launch of the
+ * selected classes (no passage: a measurement aid).  class_mask: bit c selects
+ * class c, 0 switches timing off, SWIFTKV_TIME_ALL selects every class; any
+ * other bit is SWIFTKV_EINVAL.  An event pair costs a few microseconds on the
+ * stream, so a call with every class selected runs about 1 ms longer (a
+ * decode step has ~450 launches); select only the class in question when the
+ * call's own duration matters.  Classes:
  * 0 = QKV GEMM, 1 = O GEMM, 2 = gate/up GEMM, 3 = down GEMM (layers 1..l),
  * 4 = fused KV GEMM (Eq. 2), 5 = prefill attention, 6 = plan / embedding /
  * single-query attention of decode rows / gather, 7 = last-token tail,
@@ -316,7 +321,8 @@ int swiftkv_flops(const swiftkv_ctx *ctx, const int32_t *seq_lens, const int32_t
  * V transpose).  ms_out / launches_out are host arrays of
  * SWIFTKV_N_TIME_CLASSES.  Reading waits for the last recorded event. */
 #define SWIFTKV_N_TIME_CLASSES 10
-int swiftkv_set_timing(swiftkv_ctx *ctx, int32_t enable);
+#define SWIFTKV_TIME_ALL ((1 << SWIFTKV_N_TIME_CLASSES) - 1)
+int swiftkv_set_timing(swiftkv_ctx *ctx, int32_t class_mask);
 int swiftkv_get_timing(swiftkv_ctx *ctx, double ms_out[SWIFTKV_N_TIME_CLASSES],
                        int32_t launches_out[SWIFTKV_N_TIME_CLASSES]);
 

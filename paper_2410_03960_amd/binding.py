@@ -245,8 +245,12 @@ class Context:
                                     C.byref(g), C.byref(a)))
         return g.value, a.value
 
-    def set_timing(self, enable: bool):
-        _check(load().swiftkv_set_timing(self._h, int(enable)))
+    def set_timing(self, enable: bool, classes: Optional[Sequence[str]] = None):
+        """Bracket launches with HIP events: every class, or only the named ones (TIME_CLASS_NAMES)."""
+        mask = 0
+        if enable:
+            mask = (1 << N_TIME_CLASSES) - 1 if classes is None else sum(1 << TIME_CLASS_NAMES.index(c) for c in classes)
+        _check(load().swiftkv_set_timing(self._h, mask))
 
     def get_timing(self):
         ms = (C.c_double * N_TIME_CLASSES)()

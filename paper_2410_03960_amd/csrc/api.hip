@@ -79,7 +79,7 @@ struct swiftkv_ctx {
   Layout last;
   bool have_last = false;
   // timing
-  bool timing = false;
+  uint32_t timing = 0;   // bit c set: launches of time class c are bracketed by events
   std::vector<hipEvent_t> ev;
   std::vector<int> ev_class;
   size_t ev_used = 0;
@@ -153,7 +153,7 @@ struct Timer {
   swiftkv_ctx *c;
   hipStream_t st;
   void begin(int cls) {
-    if (!c->timing) return;
+    if (!((c->timing >> cls) & 1u)) return;
     if (c->ev_used + 2 > c->ev.size()) {
       for (int i = 0; i < 64; ++i) {
         hipEvent_t e;
@@ -602,9 +602,10 @@ int swiftkv_export_exit_flags(swiftkv_ctx *c, const void *workspace, int32_t *fl
   return SWIFTKV_OK;
 }
 
-int swiftkv_set_timing(swiftkv_ctx *c, int32_t enable) {
+int swiftkv_set_timing(swiftkv_ctx *c, int32_t class_mask) {
   if (!c) return fail(SWIFTKV_EINVAL, "null ctx");
-  c->timing = enable != 0;
+  if (class_mask < 0 || class_mask > SWIFTKV_TIME_ALL) return fail(SWIFTKV_EINVAL, "class_mask %d names no time class", class_mask);
+  c->timing = (uint32_t)class_mask;
   c->ev_used = 0;          // (re)start accumulating
   c->ev_class.clear();
   return SWIFTKV_OK;
