@@ -328,6 +328,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnPrefillParams 
 
 // Sum over the LPK (8 or 16) consecutive lanes that share a key, result in all of them: data-parallel
 // primitives inside a row of 16 lanes (quad swaps, mirror of 8, mirror of 16), no LDS round trip.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float x) {
   return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
@@ -365,15 +366,16 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
   const int k_lo = split * per;
   const int k_hi = (k_lo + per) < row.n_keys ? (k_lo + per) : row.n_keys;
 
-  // query fragments (8 dims of each of the R heads), rotated here if asked
-  float q[R][8];
+  // query fragments (8 dims of each of the R heads), rotated here if asked; kept as the four bf16 pairs
+  // they are stored as, for the two-element bf16 dot product (the score scale is applied to the sum)
+  uint32_t q[R][4];
   const float sc = 1.4426950408889634f * rsqrtf((float)HD);
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const bf16_t *qp = p.q + (int64_t)row.q_row * q_dim + (kvh * R + r) * HD;
     uint4 u = *(const uint4 *)(qp + sub * 8);
-    float x[8] = {bf16lo(u.x), bf16hi(u.x), bf16lo(u.y), bf16hi(u.y), bf16lo(u.z), bf16hi(u.z), bf16lo(u.w), bf16hi(u.w)};
     if (row.cs_row >= 0) {
+      float x[8] = {bf16lo(u.x), bf16hi(u.x), bf16lo(u.y), bf16hi(u.y), bf16lo(u.z), bf16hi(u.z), bf16lo(u.w), bf16hi(u.w)};
       const int psub = (sub + LPK / 2) % LPK;   // chunk holding the rotary partners
       uint4 w = *(const uint4 *)(qp + psub * 8);
       float y[8] = {bf16lo(w.x), bf16hi(w.x), bf16lo(w.y), bf16hi(w.y), bf16lo(w.z), bf16hi(w.z), bf16lo(w.w), bf16hi(w.w)};
@@ -383,12 +385,12 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
       for (int e = 0; e < 8; ++e) {
         float2 c = cs[e];
         // first half: x*cos - partner*sin ; second half: x*cos + partner*sin
-        float v = first ? (x[e] * c.x - y[e] * c.y) : (x[e] * c.x + y[e] * c.y);
-        x[e] = bf16_to_f32(f32_to_bf16(v));   // q is held in bf16 like the prefill path's
+        x[e] = first ? (x[e] * c.x - y[e] * c.y) : (x[e] * c.x + y[e] * c.y);
       }
+      // q is held in bf16 like the prefill path's
+      u = make_uint4(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7]));
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) q[r][e] = x[e] * sc;
+    q[r][0] = u.x; q[r][1] = u.y; q[r][2] = u.z; q[r][3] = u.w;
   }
 
   float m[R], l[R], acc[R][8];
@@ -412,7 +414,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
     blk_nxt[u] = k_hi > 0 ? bt[(key < k_hi ? key : k_hi - 1) / SKV_BLOCK] : 0;
   }
   for (int kb = k_lo + wave * KPW; kb < k_hi; kb += 2 * KPS) {
-    float kf[2][8], vf[2][8];
+    float vf[2][8];
     bool valid[2];
     uint4 kraw[2], vraw[2];
     const int blk_cur[2] = {blk_nxt[0], blk_nxt[1]};
@@ -439,16 +441,13 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
     for (int u = 0; u < 2; ++u) {
       const uint32_t kw[4] = {kraw[u].x, kraw[u].y, kraw[u].z, kraw[u].w}, vw[4] = {vraw[u].x, vraw[u].y, vraw[u].z, vraw[u].w};
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        kf[u][2 * e] = bf16lo(kw[e]); kf[u][2 * e + 1] = bf16hi(kw[e]);
-        vf[u][2 * e] = bf16lo(vw[e]); vf[u][2 * e + 1] = bf16hi(vw[e]);
-      }
+      for (int e = 0; e < 4; ++e) { vf[u][2 * e] = bf16lo(vw[e]); vf[u][2 * e + 1] = bf16hi(vw[e]); }
 #pragma unroll
       for (int r = 0; r < R; ++r) {
         float d = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) d += q[r][e] * kf[u][e];
-        d = key_group_sum<LPK>(d);
+        for (int e = 0; e < 4; ++e) d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kw[e]), __builtin_bit_cast(bf16x2_t, q[r][e]), d, false);
+        d = key_group_sum<LPK>(d) * sc;
         if (valid[u] && d > m[r] + 8.0f) {   // uniform within the key's lanes
           const float a = __builtin_amdgcn_exp2f(m[r] - d);   // exp2(-inf) = 0 the first time
           l[r] *= a;

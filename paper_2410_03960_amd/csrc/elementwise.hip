@@ -4,42 +4,44 @@
 #include "common.h"
 
 // ---------------------------------------------------------------- plan -----
-// One thread per new token: sequence by binary search in cu_seqlens, absolute
-// position, paged slot = block_table[b][p/16]*16 + p%16, and the RoPE angle
-// table cos/sin(p * theta^(-2i/hd)) formed in double precision.
+// One thread per (new token, rotary pair): sequence by binary search in
+// cu_seqlens, absolute position, paged slot = block_table[b][p/16]*16 + p%16
+// (written by the token's first thread), and the RoPE angle table
+// cos/sin(p * theta^(-2i/hd)) formed in double precision.
 __global__ void plan_kernel(PlanParams p) {
-  int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t < p.B) p.last_rows[t] = p.cu_seqlens[t + 1] - 1;
+  const int half = p.head_dim / 2;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid < p.B) p.last_rows[gid] = p.cu_seqlens[gid + 1] - 1;
+  const int t = (int)(gid / half), i = (int)(gid % half);
   if (t >= p.T) return;
   int lo = 0, hi = p.B - 1;
   while (lo < hi) {
     int mid = (lo + hi + 1) >> 1;
     if (p.cu_seqlens[mid] <= t) lo = mid; else hi = mid - 1;
   }
-  int b = lo;
-  int pos = p.context_lens[b] + (t - p.cu_seqlens[b]);
-  int blk = p.block_tables[(int64_t)b * p.max_blocks_per_seq + pos / SKV_BLOCK];
-  if (blk < 0 || blk >= p.n_blocks) {  // never let a bad table turn into a wild store
-    atomicOr(p.err_flag, 1);
-    blk = 0;
+  const int b = lo;
+  const int pos = p.context_lens[b] + (t - p.cu_seqlens[b]);
+  if (i == 0) {
+    int blk = p.block_tables[(int64_t)b * p.max_blocks_per_seq + pos / SKV_BLOCK];
+    if (blk < 0 || blk >= p.n_blocks) {  // never let a bad table turn into a wild store
+      atomicOr(p.err_flag, 1);
+      blk = 0;
+    }
+    if (p.token_ids) {
+      int id = p.token_ids[t];
+      if (id < 0 || id >= p.vocab) atomicOr(p.err_flag, 2);
+    }
+    p.positions[t] = pos;
+    p.seq_of[t] = b;
+    p.slots[t] = (int64_t)blk * SKV_BLOCK + pos % SKV_BLOCK;
   }
-  if (p.token_ids) {
-    int id = p.token_ids[t];
-    if (id < 0 || id >= p.vocab) atomicOr(p.err_flag, 2);
-  }
-  p.positions[t] = pos;
-  p.seq_of[t] = b;
-  p.slots[t] = (int64_t)blk * SKV_BLOCK + pos % SKV_BLOCK;
-  int half = p.head_dim / 2;
-  for (int i = 0; i < half; ++i) {
-    double inv_freq = pow((double)p.rope_theta, -2.0 * (double)i / (double)p.head_dim);
-    double ang = (double)pos * inv_freq;
-    p.cos_sin[(int64_t)t * half + i] = make_float2((float)cos(ang), (float)sin(ang));
-  }
+  const double inv_freq = pow((double)p.rope_theta, -2.0 * (double)i / (double)p.head_dim);
+  const double ang = (double)pos * inv_freq;
+  p.cos_sin[(int64_t)t * half + i] = make_float2((float)cos(ang), (float)sin(ang));
 }
 int launch_plan(const PlanParams &p, hipStream_t st) {
-  int n = p.T > p.B ? p.T : p.B;
-  hipLaunchKernelGGL(plan_kernel, dim3((n + 127) / 128), dim3(128), 0, st, p);
+  const int64_t n = std::max<int64_t>((int64_t)p.T * (p.head_dim / 2), p.B);
+  hipLaunchKernelGGL(plan_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p);
   return 0;
 }
 

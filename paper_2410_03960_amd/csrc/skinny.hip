@@ -12,8 +12,13 @@
 // A CU sustains only a fraction of its share of HBM bandwidth on one such stream
 // (loads in flight / latency), so every CU has to stream: when there are fewer
 // column tiles than CUs, K is split over blockIdx.y, the splits write fp32
-// partial sums and a second small kernel adds them in a fixed order and applies
-// the epilogue (deterministic, unlike atomic accumulation).
+// partial sums and a second small kernel (or the consumer of the result) adds
+// them in a fixed order and applies the epilogue (deterministic, unlike atomic
+// accumulation).
+// Three kernels: skinny_kernel (above; any K % 8 == 0, activations from L2),
+// skinny_lds_kernel (K % 512 == 0, up to 32 rows: the activation slice of a
+// workgroup resident in LDS) and skinny_seq_kernel (K % 512 == 0, 33..80 rows:
+// slices walked in sequence behind a producer wave).
 #include "common.h"
 
 #include <algorithm>
@@ -290,30 +295,269 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_lds_kernel(SkinnyParams p, 
   }
 }
 
+// ---------------------------------------------------------------------------
+// The LDS-resident form for many rows (M > 32), where a K slice that fits LDS is
+// short (512 columns at 64 rows) and one slice per workgroup would mean many K
+// splits, i.e. fp32 partial sums of 12-25 % of the weight bytes.  Here a workgroup
+// walks several slices of its K range one after the other: the activation slice
+// is double-buffered in LDS and filled by a producer wave of its own (LDS-DMA,
+// then a wait for everything it requested, then the workgroup barrier), so the
+// consumer waves never wait for an LDS-DMA request and their weight stream runs
+// on across slice boundaries; a consumer keeps the accumulators of its NBW column
+// blocks in registers over the whole K range.  One barrier per slice.
+template <int MB, int EPI, int WAVES, int NBW>
+__global__ __launch_bounds__((WAVES + 1) * 64) void skinny_seq_kernel(SkinnyParams p, int ks_steps, int n_slices) {
+  constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
+  constexpr int U = (NBW * NW >= 4) ? 2 : 4;                                      // k steps (of 32) per group of loads
+  extern __shared__ __align__(16) unsigned char a_lds[];   // [2][k step][MB][64 lanes][16 bytes]
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, kq = lane >> 4;
+  const int all_slices = p.K / (32 * ks_steps);
+  const int sl_begin = blockIdx.y * n_slices;
+  const int my_slices = (all_slices - sl_begin) < n_slices ? (all_slices - sl_begin) : n_slices;   // >= 1 by the grid
+  const int k0 = sl_begin * ks_steps * 32;
+  const int buf_bytes = ks_steps * MB * 1024;
+
+  if (wave == WAVES) {
+    // producer: slice s -> buffer s & 1, fragment (k step j, row block mb) at (j * MB + mb) * 1024; rows past M repeat row M-1
+    typedef __attribute__((address_space(3))) void *lds_ptr_t;
+    const unsigned lds_base = (unsigned)(size_t)(lds_ptr_t)a_lds;
+    for (int s = 0; s <= my_slices; ++s) {
+      if (s < my_slices) {
+        for (int f = 0; f < ks_steps * MB; ++f) {
+          const int j = f / MB, mb = f % MB;
+          int m = mb * 16 + l16;
+          m = m < p.M ? m : p.M - 1;
+          lds_dma16(p.A + ((int64_t)m * p.K + k0 + (s * ks_steps + j) * 32 + kq * 8), lds_base + (s & 1) * buf_bytes + f * 1024);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the slice is in LDS
+      }
+      __builtin_amdgcn_s_barrier();           // slice s is ready / the consumers have left slice s - 1
+    }
+    return;
+  }
+
+  const int nblocks = p.N / 16;
+  const int gps = ks_steps / U;                                       // groups per slice, even
+  const int nb0 = (blockIdx.x * WAVES + wave) * NBW;
+  const int total = my_slices * gps;                                  // groups of this wave
+  // weight rows of this lane: a group is U k steps of all NBW column blocks (an activation fragment read from
+  // LDS then feeds NBW * NW products); groups are requested in the order they are consumed.
+  // (a column block past N re-reads the last one; its results are dropped)
+  int64_t woff[NBW];
+  const bf16_t *wt[NBW];
+#pragma unroll
+  for (int b = 0; b < NBW; ++b) {
+    int nb = nb0 + b;
+    nb = nb < nblocks ? nb : nblocks - 1;
+    woff[b] = (int64_t)(nb * 16 + l16) * p.K + k0 + kq * 8;
+    wt[b] = p.wtab ? p.wtab[nb] + ((int64_t)l16 * p.K + k0 + kq * 8) : nullptr;   // (one weight, never SwiGLU)
+  }
+  int l_idx = 0;
+  auto load_group = [&](uint4 (&dst)[NBW][NW][U]) {
+    const int koff = l_idx * (U * 32);
+    ++l_idx;
+#pragma unroll
+    for (int b = 0; b < NBW; ++b)
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const bf16_t *src = (wt[b] ? wt[b] : (w ? p.W2 : p.W) + woff[b]) + koff;
+#pragma unroll
+        for (int u = 0; u < U; ++u) dst[b][w][u] = *(const uint4 *)(src + u * 32);
+      }
+  };
+  uint4 wa[NBW][NW][U], wb[NBW][NW][U];
+  load_group(wa);   // on its way while the first slice arrives
+
+  floatx4 acc[NBW][NW][MB];
+#pragma unroll
+  for (int b = 0; b < NBW; ++b)
+#pragma unroll
+    for (int w = 0; w < NW; ++w)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) acc[b][w][mb] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  int idx = 0;
+  __builtin_amdgcn_s_barrier();   // slice 0 is in LDS
+  for (int s = 0; s < my_slices; ++s) {
+    const unsigned char *buf = a_lds + (s & 1) * buf_bytes + lane * 16;
+    for (int g = 0; g < gps; g += 2) {
+      load_group(wb);
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const unsigned char *fr = buf + (size_t)((g + half) * U) * (MB * 1024);
+        if (half == 1 && idx + 2 < total) load_group(wa);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          bf16x8 a[MB];
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) a[mb] = *(const bf16x8 *)(fr + (u * MB + mb) * 1024);
+#pragma unroll
+          for (int b = 0; b < NBW; ++b)
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+              for (int mb = 0; mb < MB; ++mb)
+                acc[b][w][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, half ? wb[b][w][u] : wa[b][w][u]), a[mb], acc[b][w][mb], 0, 0, 0);
+        }
+      }
+      idx += 2;
+    }
+    // every LDS read of this slice has returned (its values went into the products above); no wait for the
+    // weight loads in flight
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+  }
+
+  // acc[b][w][mb][v] = C[m = mb*16 + l16][n = (nb0 + b)*16 + 4*kq + v] (weight w), over this K range
+#pragma unroll
+  for (int b = 0; b < NBW; ++b) {
+    const int nb = nb0 + b;
+    if (nb >= nblocks) continue;
+    const int n = nb * 16 + 4 * kq;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int m = mb * 16 + l16;
+      if (m >= p.M) continue;
+      if (gridDim.y > 1) {   // partial[split][w][m][n]
+#pragma unroll
+        for (int w = 0; w < NW; ++w)
+          *(float4 *)(p.partial + (((int64_t)blockIdx.y * NW + w) * p.M + m) * p.N + n) =
+              make_float4(acc[b][w][mb][0], acc[b][w][mb][1], acc[b][w][mb][2], acc[b][w][mb][3]);
+      } else if constexpr (EPI == EPI_STORE_F32) {
+        *(float4 *)((float *)p.C + (int64_t)m * p.N + n) = make_float4(acc[b][0][mb][0], acc[b][0][mb][1], acc[b][0][mb][2], acc[b][0][mb][3]);
+      } else if constexpr (EPI == EPI_RESID) {
+        float4 *dst = (float4 *)((float *)p.C + (int64_t)m * p.N + n);
+        const float4 r = *dst;
+        *dst = make_float4(r.x + acc[b][0][mb][0], r.y + acc[b][0][mb][1], r.z + acc[b][0][mb][2], r.w + acc[b][0][mb][3]);
+      } else {
+        float o[4] = {acc[b][0][mb][0], acc[b][0][mb][1], acc[b][0][mb][2], acc[b][0][mb][3]};
+        if constexpr (EPI == EPI_SWIGLU) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) o[v] = o[v] / (1.f + __expf(-o[v])) * acc[b][NW - 1][mb][v];
+        }
+        *(uint2 *)((bf16_t *)p.C + (int64_t)m * p.N + n) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+      }
+    }
+  }
+}
+
+struct SeqPlan {
+  bool ok;
+  int waves, nbw, ks_steps, n_slices, ksplit;
+  size_t lds_bytes, partial_bytes;
+};
+// Shape of the launch for M > 32: column blocks per workgroup (waves x nbw) and K ranges, chosen by the
+// bytes that move besides the weights -- every workgroup fetches the activation rows of its K range from
+// L2 (n_cg * M * K * 2 bytes in total over n_cg column groups, whatever the K split), K splits write and
+// re-read fp32 partial sums (2 * ksplit * nw * M * N * 4 bytes) and, for the epilogues that cannot leave
+// the sum to their consumer, need a second launch -- scaled by how evenly the workgroups fill the 256 CUs
+// (one workgroup per CU: the two activation buffers take most of LDS).  Measured at 64 rows (us per call,
+// previous one-slice form -> this one): 128256 x 4096 296 -> 196, 28672 x 4096 64.4 -> 61.2 and no second
+// launch, 4096 x 4096 18.0 -> 16.5, 4096 x 14336 36.8 -> 36.8; at 80 rows 28672 x 4096 97.7 -> 67.1.
+SeqPlan plan_seq(int M, int N, int K, int nw, bool consumer_sums, size_t partial_cap) {
+  SeqPlan best{};
+  if (M <= 32 || M > 80 || (N % 16) != 0 || (K % 512) != 0) return best;
+  const int MB = (M + 15) / 16;
+  const int ks_steps = MB <= 4 ? 16 : 8;                      // 2 x 48-64 KB, 2 x 40 KB of LDS
+  const int all_slices = K / (32 * ks_steps), nblocks = N / 16;
+  const double w_bytes = 2.0 * nw * N * K;
+  double best_cost = 0;
+  for (int waves = 4; waves <= 8; waves += 4)
+    for (int nbw = 1; nbw <= 4; nbw *= 2) {
+      if (nw == 2 && nbw * waves > 8) continue;               // (two weights: register budget of the instantiations below)
+      const int n_cg = (nblocks + waves * nbw - 1) / (waves * nbw);
+      for (int want = 1; want <= std::min(SKINNY_MAX_SPLIT, all_slices); ++want) {
+        const int n_slices = (all_slices + want - 1) / want;
+        const int ksplit = (all_slices + n_slices - 1) / n_slices;
+        if (ksplit != want) continue;
+        const int64_t wgs = (int64_t)n_cg * ksplit;
+        const size_t partial = ksplit > 1 ? (size_t)ksplit * nw * M * N * 4 : 0;
+        if (partial > partial_cap) continue;
+        const double a_bytes = 0.75 * (double)n_cg * M * K * 2, p_bytes = 2.0 * partial;   // (L2 hits: cheaper than the partial sums' trip to memory)
+        const double second = (ksplit > 1 && !consumer_sums) ? 25e6 : 0;   // a launch, in bytes at the streaming rate
+        const int64_t n_rounds = (wgs + 255) / 256;   // every further round pays its own fill and uneven end
+        const double rounds = (double)n_rounds * 256.0 / (double)wgs * (1.0 + 0.15 * (double)(n_rounds - 1));
+        const double cost = (w_bytes + a_bytes + p_bytes + second) * rounds;
+        if (!best.ok || cost < best_cost) {
+          best_cost = cost;
+          best = SeqPlan{true, waves, nbw, ks_steps, n_slices, ksplit, (size_t)2 * ks_steps * MB * 1024, partial};
+        }
+      }
+    }
+  return best;
+}
+template <int MB, int EPI, int WAVES, int NBW>
+int launch_seq_k(const SkinnyParams &p, const SeqPlan &pl, hipStream_t st) {
+  auto kern = skinny_seq_kernel<MB, EPI, WAVES, NBW>;
+  static bool attr = false;
+  if (!attr) {
+    if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes) != hipSuccess) return -1;
+    attr = true;   // (the size depends on MB only)
+  }
+  const int nblocks = p.N / 16;
+  dim3 grid((nblocks + WAVES * NBW - 1) / (WAVES * NBW), pl.ksplit);
+  hipLaunchKernelGGL(kern, grid, dim3((WAVES + 1) * 64), pl.lds_bytes, st, p, pl.ks_steps, pl.n_slices);
+  if (pl.ksplit > 1 && p.n_splits_out) *p.n_splits_out = pl.ksplit;   // the consumer adds the splits
+  else if (pl.ksplit > 1) {
+    const int64_t quads = (int64_t)p.M * p.N / 4;
+    hipLaunchKernelGGL((skinny_reduce_kernel<EPI>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, p, pl.ksplit);
+  }
+  return 0;
+}
+template <int MB, int EPI>
+int launch_seq_e(const SkinnyParams &p, const SeqPlan &pl, hipStream_t st) {
+  if constexpr (EPI != EPI_SWIGLU) {
+    if (pl.nbw == 4) return pl.waves == 4 ? launch_seq_k<MB, EPI, 4, 4>(p, pl, st) : launch_seq_k<MB, EPI, 8, 4>(p, pl, st);
+    if (pl.waves == 8 && pl.nbw == 2) return launch_seq_k<MB, EPI, 8, 2>(p, pl, st);
+  }
+  if (pl.waves == 8 && pl.nbw == 1) return launch_seq_k<MB, EPI, 8, 1>(p, pl, st);
+  if (pl.waves == 4 && pl.nbw == 2) return launch_seq_k<MB, EPI, 4, 2>(p, pl, st);
+  if (pl.waves == 4 && pl.nbw == 1) return launch_seq_k<MB, EPI, 4, 1>(p, pl, st);
+  return -1;
+}
+template <int MB>
+int launch_seq_m(const SkinnyParams &p, int epi, const SeqPlan &pl, hipStream_t st) {
+  switch (epi) {
+    case EPI_STORE_BF16: return launch_seq_e<MB, EPI_STORE_BF16>(p, pl, st);
+    case EPI_STORE_F32: return launch_seq_e<MB, EPI_STORE_F32>(p, pl, st);
+    case EPI_RESID: return launch_seq_e<MB, EPI_RESID>(p, pl, st);
+    case EPI_SWIGLU: return launch_seq_e<MB, EPI_SWIGLU>(p, pl, st);
+  }
+  return -1;
+}
+int launch_seq(const SkinnyParams &p, int epi, const SeqPlan &pl, hipStream_t st) {
+  switch ((p.M + 15) / 16) {
+    case 3: return launch_seq_m<3>(p, epi, pl, st);
+    case 4: return launch_seq_m<4>(p, epi, pl, st);
+    default: return launch_seq_m<5>(p, epi, pl, st);
+  }
+}
+
 struct LdsPlan {
   bool ok;
   int waves, ks_steps, ksplit, nbw;
   size_t lds_bytes, partial_bytes;
 };
-// How the LDS-resident form would run this shape; ok = false: it cannot, or the kernel above does better
-// (few column blocks: its workgroups split K among their waves and need no second pass).  Measured on
-// the 8B shapes with 8 and 64 rows: slices of 2048 (up to 16 rows) / 1024 columns of K, two column
-// blocks in a row per wave, 16 waves per workgroup when the slice leaves room for one workgroup per CU.
+// How the one-slice LDS-resident form would run this shape (M <= 32); ok = false: it cannot, or the first
+// kernel does better (few column blocks: its workgroups split K among their waves and need no second
+// pass).  Measured on the 8B shapes with 8 rows: slices of 2048 (up to 16 rows) / 1024 columns of K, two
+// column blocks in a row per wave when there are many.
 LdsPlan plan_lds(int M, int N, int K, int nw, size_t partial_cap) {
   LdsPlan pl{};
-  if (M < 1 || M > 80 || (N % 16) != 0 || (K % 512) != 0) return pl;
+  if (M < 1 || M > 32 || (N % 16) != 0 || (K % 512) != 0) return pl;
   const int MB = (M + 15) / 16;
-  const int U = (nw == 1 && MB <= 2) ? 8 : 4;
+  const int U = (nw == 1) ? 8 : 4;
   const int all_steps = K / 32, nblocks = N / 16;
-  const int steps_cap = MB == 1 ? 64 : MB <= 4 ? 32 : 24;          // 64 KB, 64-128 KB, 120 KB of LDS
+  const int steps_cap = MB == 1 ? 64 : 32;                          // 64 KB of LDS
   int ksplit = (all_steps + steps_cap - 1) / steps_cap;
   const int ks_steps = ((all_steps + ksplit - 1) / ksplit + 2 * U - 1) / (2 * U) * (2 * U);
   ksplit = (all_steps + ks_steps - 1) / ks_steps;
   pl.ks_steps = ks_steps; pl.ksplit = ksplit;
   const int64_t streams = (int64_t)nblocks * ksplit;                // (column block, K slice) pairs; a wave takes nbw of them in a row
-  if (streams < 1024) return pl;                                    // too few: the kernel above keeps more CUs busy
+  if (streams < 1024) return pl;                                    // too few: the first kernel keeps more CUs busy
   pl.nbw = streams >= 3200 ? 2 : 1;
-  pl.waves = (MB >= 3 && nw == 1 && streams >= 4096) ? 16 : 8;      // (two weight streams per wave need more than 128 registers)
+  pl.waves = 8;
   pl.lds_bytes = (size_t)ks_steps * MB * 1024;
   pl.partial_bytes = ksplit > 1 ? (size_t)ksplit * nw * M * N * 4 : 0;
   pl.ok = pl.partial_bytes <= partial_cap && pl.lds_bytes <= 160 * 1024;
@@ -338,31 +582,18 @@ int launch_lds_w(const SkinnyParams &p, const LdsPlan &pl, hipStream_t st) {
   }
   return 0;
 }
-template <int MB, int EPI>
-int launch_lds_e(const SkinnyParams &p, const LdsPlan &pl, hipStream_t st) {
-  if constexpr (EPI != EPI_SWIGLU) {   // (two weight streams per wave need more than the 128 registers of a 16-wave workgroup)
-    if (pl.waves == 16) return launch_lds_w<MB, EPI, 16>(p, pl, st);
-  }
-  return launch_lds_w<MB, EPI, 8>(p, pl, st);
-}
 template <int MB>
 int launch_lds_m(const SkinnyParams &p, int epi, const LdsPlan &pl, hipStream_t st) {
   switch (epi) {
-    case EPI_STORE_BF16: return launch_lds_e<MB, EPI_STORE_BF16>(p, pl, st);
-    case EPI_STORE_F32: return launch_lds_e<MB, EPI_STORE_F32>(p, pl, st);
-    case EPI_RESID: return launch_lds_e<MB, EPI_RESID>(p, pl, st);
-    case EPI_SWIGLU: return launch_lds_e<MB, EPI_SWIGLU>(p, pl, st);
+    case EPI_STORE_BF16: return launch_lds_w<MB, EPI_STORE_BF16, 8>(p, pl, st);
+    case EPI_STORE_F32: return launch_lds_w<MB, EPI_STORE_F32, 8>(p, pl, st);
+    case EPI_RESID: return launch_lds_w<MB, EPI_RESID, 8>(p, pl, st);
+    case EPI_SWIGLU: return launch_lds_w<MB, EPI_SWIGLU, 8>(p, pl, st);
   }
   return -1;
 }
 int launch_lds(const SkinnyParams &p, int epi, const LdsPlan &pl, hipStream_t st) {
-  switch ((p.M + 15) / 16) {
-    case 1: return launch_lds_m<1>(p, epi, pl, st);
-    case 2: return launch_lds_m<2>(p, epi, pl, st);
-    case 3: return launch_lds_m<3>(p, epi, pl, st);
-    case 4: return launch_lds_m<4>(p, epi, pl, st);
-    default: return launch_lds_m<5>(p, epi, pl, st);
-  }
+  return p.M <= 16 ? launch_lds_m<1>(p, epi, pl, st) : launch_lds_m<2>(p, epi, pl, st);
 }
 
 template <int MB, int NB, int EPI>
@@ -416,6 +647,10 @@ int launch_skinny(const SkinnyParams &p, int epi, hipStream_t st) {
   if (p.n_splits_out) {
     if (epi != EPI_STORE_F32 && epi != EPI_RESID) return -1;
     *p.n_splits_out = 1;
+  }
+  {
+    const SeqPlan sq = plan_seq(p.M, p.N, p.K, epi == EPI_SWIGLU ? 2 : 1, p.n_splits_out != nullptr, p.partial ? p.partial_bytes : 0);
+    if (sq.ok) return launch_seq(p, epi, sq, st);
   }
   {
     const LdsPlan pl = plan_lds(p.M, p.N, p.K, epi == EPI_SWIGLU ? 2 : 1, p.partial ? p.partial_bytes : 0);

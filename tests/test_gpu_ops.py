@@ -26,10 +26,13 @@ def _rand_bf16(seed, name, shape, std=1.0):
     (3, 1, 16, 8), (3, 8, 1024, 256), (3, 16, 272, 688), (3, 17, 64, 96), (3, 65, 160, 1000),
     (3, 32, 96, 264), (3, 33, 192, 520), (3, 48, 80, 1000), (3, 49, 1056, 4096), (3, 64, 4096, 688), (3, 80, 144, 72),
     ("rows", 33, 192, 520), ("rows", 49, 1056, 4096), ("rows", 64, 4096, 1376), ("rows", 80, 1024, 4096), ("rows", 16, 1024, 4096),
-    # the form with the activation slice resident in LDS (K % 512 == 0, at least 1024 (column block, K slice) streams):
-    # one and several K slices, 1..5 row blocks, a ragged last workgroup, 8 and 16 waves, one and two blocks per wave
-    ("rows", 1, 8192, 4096), ("rows", 7, 16384, 2048), ("rows", 8, 8208, 4096), ("rows", 17, 4096, 4096), ("rows", 40, 16384, 1024),
-    ("rows", 64, 6144, 4096), ("rows", 64, 16384, 4096), ("rows", 80, 4096, 4096), ("rows", 16, 4096, 14336),
+    # the forms with the activation slice resident in LDS (K % 512 == 0).  Up to 32 rows (one slice per workgroup, at
+    # least 1024 (column block, K slice) streams): one and several K slices, a ragged last workgroup, one and two
+    # blocks per wave.  Beyond 32 rows (slices walked in sequence behind a producer wave): 3..5 row blocks, one and
+    # several K ranges, 4 and 8 consumer waves with 1, 2 and 4 column blocks each, a ragged last column group
+    ("rows", 1, 8192, 4096), ("rows", 7, 16384, 2048), ("rows", 8, 8208, 4096), ("rows", 17, 4096, 4096), ("rows", 16, 4096, 14336),
+    ("rows", 40, 16384, 1024), ("rows", 64, 6144, 4096), ("rows", 64, 16384, 4096), ("rows", 80, 4096, 4096),
+    ("rows", 64, 28672, 4096), ("rows", 48, 32064, 1024), ("rows", 33, 8208, 4096), ("rows", 72, 2048, 14336), ("rows", 64, 4096, 512),
     (0, 2500, 512, 256),
     (14, 256, 256, 64), (14, 700, 528, 448), (14, 2304, 768, 1024), (14, 1, 16, 128), (14, 1031, 1040, 320),
     (15, 256, 256, 64), (15, 700, 528, 448), (15, 2304, 768, 1024), (15, 517, 272, 192),
