@@ -359,10 +359,10 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeParams p) {
   const int kv_dim = p.n_kv_heads * HD;
 
   // keys of this split
-  // at least 256 keys per split: a row much shorter than the batch's longest uses fewer splits
-  // (the rest see an empty range and report a weight of zero)
+  // at least 128 keys per split (four iterations of the loop below): a row much shorter than the batch's
+  // longest uses fewer splits (the rest see an empty range and report a weight of zero)
   int per = (row.n_keys + p.n_split - 1) / p.n_split;
-  per = per < 256 ? 256 : per;
+  per = per < 128 ? 128 : per;
   const int k_lo = split * per;
   const int k_hi = (k_lo + per) < row.n_keys ? (k_lo + per) : row.n_keys;
 

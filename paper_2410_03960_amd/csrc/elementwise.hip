@@ -659,18 +659,38 @@ int launch_fp8_quantize(const float *x, float scale, uint8_t *codes, int64_t n, 
 __global__ void decode_combine_kernel(const float *partial, bf16_t *out, const DecodeRow *rows, int n_q_heads, int hd, int n_split) {
   int row = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
   if (d >= hd) return;
+  const int64_t out_row = rows[row].out_row;
   const float *base = partial + ((int64_t)(row * n_q_heads + head) * n_split) * (hd + 2);
+  // eight splits at a time, all their loads requested before the first use (one memory latency per
+  // group instead of one per split); an empty split carries m = -inf and enters with weight 0
+  constexpr int G = 8;
   float m = -INFINITY;
-  for (int s = 0; s < n_split; ++s) m = fmaxf(m, base[s * (hd + 2) + hd]);
-  float acc = 0.f, l = 0.f;
-  for (int s = 0; s < n_split; ++s) {
-    float ms = base[s * (hd + 2) + hd];
-    if (ms == -INFINITY) continue;
-    float w = exp2f(ms - m);
-    acc += w * base[s * (hd + 2) + d];
-    l += w * base[s * (hd + 2) + hd + 1];
+  for (int s0 = 0; s0 < n_split; s0 += G) {
+    float mv[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) mv[i] = s0 + i < n_split ? base[(s0 + i) * (hd + 2) + hd] : -INFINITY;
+#pragma unroll
+    for (int i = 0; i < G; ++i) m = fmaxf(m, mv[i]);
   }
-  out[(int64_t)rows[row].out_row * n_q_heads * hd + head * hd + d] = f32_to_bf16(acc / l);
+  float acc = 0.f, l = 0.f;
+  for (int s0 = 0; s0 < n_split; s0 += G) {
+    float mv[G], ov[G], lv[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+      const bool in = s0 + i < n_split;
+      const float *ps = base + (in ? s0 + i : 0) * (hd + 2);
+      mv[i] = in ? ps[hd] : -INFINITY;
+      ov[i] = ps[d];
+      lv[i] = ps[hd + 1];
+    }
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+      const float w = (mv[i] == -INFINITY) ? 0.f : exp2f(mv[i] - m);
+      acc += w * ov[i];
+      l += w * lv[i];
+    }
+  }
+  out[out_row * n_q_heads * hd + head * hd + d] = f32_to_bf16(acc / l);
 }
 int launch_decode_combine(const float *partial, bf16_t *out, const DecodeRow *rows, int32_t n_rows,
                           int32_t n_q_heads, int32_t head_dim, int32_t n_split, hipStream_t st) {
