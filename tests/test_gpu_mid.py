@@ -92,3 +92,41 @@ def test_mid_prompt_in_two_chunks(mid):
     wc = G.compare_caches(cache, ocache, full, label=wl.name)
     wlg = G.compare_logits(logits, ologits, label=wl.name)
     _say(f"  worst cache rel/cos {wc}, logits {wlg}")
+
+
+@pytest.mark.parametrize("n_seqs", [40, 72])
+def test_mid_decode_batches_of_33_to_80_rows(mid, n_seqs):
+    """One new token for each of 40 / 72 sequences over cached contexts of 1..90
+    tokens (the contexts are the oracle's own prefill of seeded prompts): a batch
+    of 3 / 5 sixteen-row blocks, so every projection of the full layers and of the
+    tail goes through the weight-streaming GEMM's form for 33..80 rows (K slices
+    in sequence; fp32 + consumer-side K-split sums for Q/K/V, residual, SwiGLU
+    and bf16 epilogues); the model with ffn 768 keeps the first form for `down`."""
+    from oracle import swiftkv_oracle as O
+    from paper_2410_03960_amd import binding as B
+    wl, store, dev_w = mid
+    sh = wl.shape
+    _say(f"{wl.name} decode batch of {n_seqs}")
+    gen = torch.Generator().manual_seed(100 + n_seqs)
+    ctx_lens = torch.randint(1, 91, (n_seqs,), generator=gen).tolist()
+    batch = WL.build_batch(wl, lens=[1] * n_seqs, ctx=ctx_lens, shuffled=True)
+    C = O.n_cache_layers(sh.n_layers, wl.l, wl.g)
+    ocache = O.PagedKVCache(C, batch.n_blocks, sh.n_kv_heads, sh.head_dim, batch.block_tables)
+    for b, cl in enumerate(ctx_lens):
+        ids = WL.seeded_token_ids(11, f"{wl.name}ctx{b}", cl, sh.vocab)
+        sub = O.PagedKVCache(C, batch.n_blocks, sh.n_kv_heads, sh.head_dim, batch.block_tables[b:b + 1])
+        O.swiftkv_prefill(G.oracle_shape(sh), G.weight_fn(store), ids, [cl], [0], wl.l, wl.g, sub)
+        s = sub.slots(0, torch.arange(cl))
+        ocache.data[:, :, s] = sub.data[:, :, s]
+    ctx = B.Context(sh, dev_w, wl.l, wl.g)
+    cache = B.KVCache(ctx.n_cache_layers, batch.n_blocks, sh.n_kv_heads, sh.head_dim, batch.block_tables, ctx_lens)
+    cache.data.copy_(ocache.data.to(torch.bfloat16))
+    ocache.data = ocache.data.to(torch.bfloat16).double()     # both sides read the same bf16 contexts
+    logits, cache, ws = G.run_gpu(ctx, batch, cache=cache)
+    G.check_plan(ctx, ws, batch)
+    ologits, ocache, _ = G.run_oracle(sh, store, batch, wl.l, wl.g, cache=ocache)
+    wc = G.compare_caches(cache, ocache, batch, label=wl.name)
+    wlg = G.compare_logits(logits, ologits, label=wl.name)
+    _say(f"  worst cache rel/cos {wc}, logits {wlg}")
+    logits2, cache2, _ = G.run_gpu(ctx, batch, cache=cache)
+    assert torch.equal(logits, logits2)
