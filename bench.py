@@ -19,7 +19,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 # HBM-side bytes per launch of the dominant kernel (gate/up GEMM): NOT measured in this run (rocprofv3 cannot run
 # inside the bench) but taken from the committed counter run of the same command, FETCH_SIZE / WRITE_SIZE scaled
 # on a 1 GiB copy: profiles/bench_8b_l16_b8x2048_hbm_traffic.txt
-PROFILED_TRAFFIC_BYTES = {("8b_l16_b8x2048", "gateup_gemm"): 5827.0 * 2 ** 20}
+PROFILED_TRAFFIC_BYTES = {("8b_l16_b8x2048", "gateup_gemm"): 5829.6 * 2 ** 20}
 PROFILED_TRAFFIC_SOURCE = "profiles/bench_8b_l16_b8x2048_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, copy-calibrated)"
 
 
