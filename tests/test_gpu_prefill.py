@@ -261,3 +261,32 @@ def test_error_paths(tiny):
     with pytest.raises(B.SwiftKVError) as e:
         ctx.export_plan(ws, 40, 1)
     assert e.value.code == B.SWIFTKV_EDATA
+
+
+def test_timing_selects_kernel_classes(tiny):
+    """swiftkv_set_timing takes a class mask: only launches of the selected
+    classes are bracketed by events, nothing else changes; a bit outside the
+    classes is refused."""
+    from paper_2410_03960_amd import binding as B
+    wl, store, dev_w = tiny
+    _say("timing classes")
+    ctx = _ctx(dev_w, wl.l, wl.g)
+    batch = WL.build_batch(wl)
+    logits0, cache0, _ = G.run_gpu(ctx, batch)
+    ctx.set_timing(True, classes=("gateup_gemm", "tail"))
+    logits1, cache1, _ = G.run_gpu(ctx, batch)
+    tim = ctx.get_timing()
+    assert tim["gateup_gemm"][1] == wl.l and tim["tail"][1] == 1
+    assert tim["gateup_gemm"][0] > 0 and tim["tail"][0] > 0
+    assert all(n == 0 and ms == 0 for k, (ms, n) in tim.items() if k not in ("gateup_gemm", "tail"))
+    ctx.set_timing(True)                                  # every class
+    G.run_gpu(ctx, batch)
+    tim = ctx.get_timing()
+    assert all(tim[k][1] > 0 for k in ("qkv_gemm", "o_gemm", "gateup_gemm", "down_gemm", "fused_kv_gemm", "tail", "kv_commit"))
+    ctx.set_timing(False)
+    G.run_gpu(ctx, batch)
+    assert all(n == 0 for _, n in ctx.get_timing().values())
+    assert torch.equal(logits0, logits1) and torch.equal(cache0.data, cache1.data)
+    with pytest.raises(B.SwiftKVError) as e:
+        B._check(B.load().swiftkv_set_timing(ctx._h, 1 << B.N_TIME_CLASSES))
+    assert e.value.code == B.SWIFTKV_EINVAL
