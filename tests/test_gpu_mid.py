@@ -94,11 +94,12 @@ def test_mid_prompt_in_two_chunks(mid):
     _say(f"  worst cache rel/cos {wc}, logits {wlg}")
 
 
-@pytest.mark.parametrize("n_seqs", [40, 72])
+@pytest.mark.parametrize("n_seqs", [33, 40, 72, 80, 81])
 def test_mid_decode_batches_of_33_to_80_rows(mid, n_seqs):
-    """One new token for each of 40 / 72 sequences over cached contexts of 1..90
+    """One new token for each of 33 .. 81 sequences over cached contexts of 1..90
     tokens (the contexts are the oracle's own prefill of seeded prompts): a batch
-    of 3 / 5 sixteen-row blocks, so every projection of the full layers and of the
+    of 3 .. 5 sixteen-row blocks (81: one row more than the weight-streaming GEMM
+    takes, the tiled GEMM runs instead), so every projection of the full layers and of the
     tail goes through the weight-streaming GEMM's form for 33..80 rows (K slices
     in sequence; fp32 + consumer-side K-split sums for Q/K/V, residual, SwiGLU
     and bf16 epilogues); the model with ffn 768 keeps the first form for `down`."""
